@@ -1,0 +1,63 @@
+"""Pins for oracle.layout: the tile order is a bijection and matches its written definition, re-derived here
+with plain loops."""
+import numpy as np
+
+from oracle import layout
+
+
+def _k_slot(t, c):
+    hf, l = divmod(t, 64)
+    for q in range(8):
+        for j in range(8):
+            for e in range(2):
+                if 8 * (4 * (q % 4) + j // 2) + 4 * (q // 4) + 2 * (j % 2) + e == c:
+                    return ((hf * 2 + q // 4) * 64 + l) * 4 + q % 4, 2 * j + 16 * e
+    raise AssertionError
+
+
+def _v_slot(t, c):
+    ch, l = divmod(c, 64)
+    hf = t // 64
+    for w in range(4):
+        for j in range(8):
+            for e in range(2):
+                if 64 * hf + 4 * (4 * w + j // 2) + 2 * (j % 2) + e == t:
+                    return ((hf * 2 + ch) * 64 + l) * 4 + w, 2 * j + 16 * e
+    raise AssertionError
+
+
+def test_tiles_are_bijections_and_match_the_definition():
+    rng = np.random.default_rng(0)
+    codes = rng.integers(0, 4, size=(128, 128))
+    for pack, unpack, slot in ((layout.pack_k_tile, layout.unpack_k_tile, _k_slot),
+                               (layout.pack_v_tile, layout.unpack_v_tile, _v_slot)):
+        tile = pack(codes)
+        assert tile.shape == (1024,) and tile.dtype == np.uint32
+        assert np.array_equal(unpack(tile), codes)
+        seen = set()
+        for t in range(0, 128, 7):
+            for c in range(128):
+                w, s = slot(t, c)
+                assert (int(tile[w]) >> s) & 3 == codes[t, c]
+                seen.add((w, s))
+        assert len(seen) == len(range(0, 128, 7)) * 128
+        one = np.zeros((128, 128), dtype=np.int64)
+        one[70, 9] = 3
+        w, s = slot(70, 9)
+        t1 = pack(one)
+        assert t1[w] == 3 << s and np.count_nonzero(t1) == 1
+
+
+def test_literal_corners():
+    one = np.zeros((128, 128), dtype=np.int64)
+    one[0, 1] = 1  # key: token 0, channel 1 -> word 0, second element of pair 0 -> bit 16
+    assert layout.pack_k_tile(one)[0] == 1 << 16
+    one[:] = 0
+    one[1, 0] = 2  # key: token 1 -> lane 1 -> word 4
+    assert layout.pack_k_tile(one)[4] == 2
+    one[:] = 0
+    one[1, 0] = 1  # value: channel 0, token 1 -> word 0, second element of pair 0
+    assert layout.pack_v_tile(one)[0] == 1 << 16
+    one[:] = 0
+    one[0, 64] = 3  # value: channel 64 = second channel half, lane 0 -> word (0*2+1)*64*4
+    assert layout.pack_v_tile(one)[256] == 3

@@ -1,0 +1,154 @@
+/*
+ * kvlinc.h -- C ABI of the KVLinC 2-bit KV-cache decode path for AMD MI355X (gfx950).
+ *
+ * The library implements, for one attention layer and one decode step, what Sec. 3 of the paper
+ * (arxiv 2510.05373) defines:
+ *   - keys quantized per channel, K_q = Q_C(K), values Hadamard-rotated and quantized per token,
+ *     V_q = Q_T(V H), both at 2 bits with group size 128 (Sec. 3.1, Obs. 3; quantizer: Sec. 2, Eq. 1);
+ *   - the 128 most recent tokens kept in fp16 and quantized only after attention has used them
+ *     (Sec. 4.1 "Setup"; Sec. 3.3, last sentence);
+ *   - the linear correction states S, P of the key quantization error (Sec. 3.2, Eq. 4-6);
+ *   - single-query attention read directly from the packed cache, split over blocks of tokens and
+ *     merged, with the correction added (Sec. 3.3, Alg. 1; Eq. 5).
+ *
+ * Conventions
+ *   - Every pointer inside kvlinc_cache and every tensor argument is a DEVICE pointer owned by the
+ *     caller, 16-byte aligned.  The library allocates nothing, keeps no state between calls and never
+ *     synchronises: a call validates its arguments on the host, enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - kvlinc_half is the bit pattern of an IEEE binary16 number.
+ *   - Return value: 0 = enqueued; negative = rejected before any launch, nothing was touched.
+ *   - Faults only the device can see (capacity exhausted, non-finite input, append to a cache whose
+ *     last group is partial) set bits in *status and leave that sequence unchanged.
+ *   - Query head h reads KV head h / (H_q / H_kv).  The softmax scale is 1/sqrt(d) (Eq. 3).
+ *
+ * Cache layout (per sequence b, KV head g; "group" = 128 consecutive tokens from token 0):
+ *   k_codes, v_codes  [B, H_kv, max_groups, 1024] uint32: one 4 KB tile per 128x128 block of 2-bit
+ *                     codes.  Logical content: code(token, channel) in {0..3}.  Word format: a word holds
+ *                     8 pairs j = 0..7, pair j = {bits 2j+1:2j, bits 16+2j+1:16+2j}.
+ *                     Key tile:   token t = 64*hf + l owns words q = 0..7 at ((hf*2 + q/4)*64 + l)*4 + q%4;
+ *                                 word q, pair j, element e holds channel 8*(4*(q%4) + j/2) + 4*(q/4) + 2*(j%2) + e.
+ *                     Value tile: channel c = 64*ch + l owns, per token half hf, words w = 0..3 at
+ *                                 ((hf*2 + ch)*64 + l)*4 + w; word w, pair j, element e holds token
+ *                                 64*hf + 4*(4*w + j/2) + 2*(j%2) + e.
+ *   k_scale, k_zero   [B, H_kv, max_groups, 128] fp16: s and z of Eq. 1 per (group, channel).
+ *   v_scale, v_zero   [B, H_kv, max_groups, 128] fp16: s and z of Eq. 1 per token of the group.
+ *   k_res, v_res      [B, H_kv, R, 128] fp16: the window; raw keys, ROTATED values, slot r = r-th oldest.
+ *   n_quant, n_res    [B] int32: quantized tokens / window tokens of each sequence (context = sum).
+ *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.
+ *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
+ *                     S, P, Wq, Wk all NULL = correction off (plain quantized attention).
+ *   status            [1] int32, OR-ed KVLINC_ST_* bits.
+ *
+ * Quantizer contract (bit exact; Eq. 1 taken against the stored fp16 scale and zero-point):
+ *   mn, mx over the group (a zero of either sign counts as +0); z = mn; s = fp16(fl32(fl32(mx - mn) / 3));
+ *   t = fl32(x - z); code = (t > 0.5 s) + (t >= 1.5 s) + (t > 2.5 s), code = 0 when s == 0.
+ * Rotation contract (bit exact): x = float(v); for h = 1, 2, ..., 64: for i with (i & h) == 0:
+ *   (x[i], x[i+h]) <- (x[i] + x[i+h], x[i] - x[i+h]) in binary32; out = fp16(fl32(x * 0x1.6a09e6p-4f)).
+ */
+#ifndef KVLINC_H
+#define KVLINC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t kvlinc_half;
+
+enum {
+  KVLINC_OK = 0,
+  KVLINC_EINVAL = -1,     /* NULL / misaligned pointer, unsupported shape or parameter */
+  KVLINC_EWORKSPACE = -2, /* workspace too small or misaligned */
+  KVLINC_EHIP = -3        /* a HIP launch failed (hipGetLastError) */
+};
+
+enum {
+  KVLINC_ST_CAPACITY = 1,  /* a sequence would need more than max_groups groups */
+  KVLINC_ST_NONFINITE = 2, /* a key or rotated value that was quantized is Inf or NaN */
+  KVLINC_ST_STATIC = 4     /* append to a sequence whose last group is partial, or an unsupported keep_residual */
+};
+
+typedef struct kvlinc_cache {
+  int32_t B, H_q, H_kv;
+  int32_t d;    /* head dimension, must be 128 */
+  int32_t G;    /* quantization group size, must be 128 */
+  int32_t R;    /* window capacity in tokens, 1..128; one-token appends need R == G */
+  int32_t D;    /* rank of the correction feature maps, must be 256 */
+  int32_t bits; /* must be 2 */
+  int64_t max_groups; /* tile capacity per (sequence, KV head) */
+  uint32_t* k_codes;
+  uint32_t* v_codes;
+  kvlinc_half* k_scale;
+  kvlinc_half* k_zero;
+  kvlinc_half* v_scale;
+  kvlinc_half* v_zero;
+  kvlinc_half* k_res;
+  kvlinc_half* v_res;
+  int32_t* n_quant;
+  int32_t* n_res;
+  float* S;
+  float* P;
+  const kvlinc_half* Wq;
+  const kvlinc_half* Wk;
+  int32_t* status;
+} kvlinc_cache;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int kvlinc_version(void);
+
+/* Static string for a return code of this library. */
+const char* kvlinc_strerror(int code);
+
+/* Host-only check of a cache descriptor (shapes, NULLs, alignment); touches no device memory.
+ * Returns KVLINC_OK or KVLINC_EINVAL.  Every other entry point runs it first. */
+int kvlinc_cache_validate(const kvlinc_cache* cache);
+
+/*
+ * Append new tokens and quantize what leaves the window (Sec. 3.3 last sentence; Sec. 3.1; Eq. 1; Eq. 5 states).
+ *
+ *   k_new, v_new   [B, H_kv, T, 128] fp16, raw keys and raw (unrotated) values of the new tokens.
+ *   n_new          [B] int32 on the device: sequence b appends its first n_new[b] (0..T) rows; NULL = T for all.
+ *   T              rows per (sequence, head) in k_new / v_new, >= 1.
+ *   keep_residual  0: lazy block flush -- the window is quantized as whole groups of 128 tokens only when a
+ *                     token arrives and the window is already full (needs R == 128); after the call
+ *                     1 <= n_res <= 128 and n_quant is a multiple of 128.
+ *                  k in 1..R: bulk build that leaves exactly the k newest tokens in fp16 and quantizes all
+ *                     older ones, the last group possibly partial (its scale/zero-point cover the valid
+ *                     tokens only, padding codes are 0).  Such a sequence accepts no further append.
+ *
+ * Per flushed group: key scale / zero-point / codes per channel, value scale / zero-point / codes per token
+ * of the rotated value, S += phi_k(K - K_q)^T V_q and P += sum phi_k(K - K_q) when the adapters are given.
+ * New tokens that stay in the window are stored as raw key and rotated fp16 value.  n_quant / n_res are
+ * updated by a second kernel on the same stream.
+ */
+int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, const kvlinc_half* v_new,
+                           const int32_t* n_new, int32_t T, int32_t keep_residual, void* stream);
+
+/* Bytes of device scratch kvlinc_decode_attention needs for this cache when no sequence holds more than
+ * max_context tokens (<= 0: the cache's full capacity).  0 on an invalid descriptor. */
+size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_context);
+
+/*
+ * One decode step of corrected attention over the whole cache (Sec. 3.3, Alg. 1, with the correction of Eq. 5).
+ *
+ *   q            [B, H_q, 128] fp16 query of the current token (its key/value must already be appended).
+ *   out          [B, H_q, 128] fp16 attention output in the original (unrotated) value basis.
+ *   workspace    device scratch of at least kvlinc_decode_workspace_bytes(cache, max_context) bytes,
+ *                16-byte aligned; contents undefined before and after.
+ *   max_context  host-side upper bound on n_quant + n_res over the batch (<= 0: capacity).  It only sizes the
+ *                launch; results do not depend on it as long as it is an upper bound.
+ *
+ * out[b, h] = ( sum_i exp(q K_i / sqrt d) V_i + phi_q(q) S ) / ( sum_i exp(q K_i / sqrt d) + phi_q(q) P ) H^T
+ * with K_i, V_i the dequantized codes for quantized tokens and the fp16 window entries otherwise.
+ * A sequence with no tokens yields zeros.
+ */
+int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                            size_t workspace_bytes, int32_t max_context, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVLINC_H */

@@ -1,0 +1,11 @@
+"""KVLinC 2-bit KV-cache decode path for AMD MI355X: thin Python binding over libkvlinc.so (C ABI, include/kvlinc.h).
+
+Every step of the path runs in the HIP kernels of the library; this package only marshals arguments
+(PyTorch supplies device memory and streams).  There is no CPU or PyTorch fallback: importing the
+binding without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    KVLINC_EHIP, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_OK, KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE,
+    KVLINC_ST_STATIC, CacheStruct, KVLincCache, KVLincError, kvlinc_append_quantize, kvlinc_cache_validate,
+    kvlinc_decode_attention, kvlinc_decode_workspace_bytes, kvlinc_strerror, kvlinc_version, lib, lib_path,
+)

@@ -1,0 +1,176 @@
+"""ctypes binding of libkvlinc.so.  Same names and argument order as include/kvlinc.h."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(HERE, "libkvlinc.so")
+
+KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP = 0, -1, -2, -3
+KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC = 1, 2, 4
+
+
+class KVLincError(RuntimeError):
+    pass
+
+
+class CacheStruct(ctypes.Structure):
+    """Mirror of struct kvlinc_cache."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H_q", ctypes.c_int32), ("H_kv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("G", ctypes.c_int32), ("R", ctypes.c_int32), ("D", ctypes.c_int32), ("bits", ctypes.c_int32),
+        ("max_groups", ctypes.c_int64),
+        ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+        ("k_scale", ctypes.c_void_p), ("k_zero", ctypes.c_void_p),
+        ("v_scale", ctypes.c_void_p), ("v_zero", ctypes.c_void_p),
+        ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
+        ("n_quant", ctypes.c_void_p), ("n_res", ctypes.c_void_p),
+        ("S", ctypes.c_void_p), ("P", ctypes.c_void_p),
+        ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p),
+        ("status", ctypes.c_void_p),
+    ]
+
+
+def _load():
+    if not os.path.exists(lib_path):
+        raise ImportError(
+            "libkvlinc.so is not built (%s missing): run `python -c 'import __graft_entry__ as g; g.build()'` or "
+            "`python paper_2510_05373_amd/build.py`; there is no fallback path" % lib_path)
+    L = ctypes.CDLL(lib_path)
+    P = ctypes.POINTER(CacheStruct)
+    L.kvlinc_version.restype = ctypes.c_int
+    L.kvlinc_version.argtypes = []
+    L.kvlinc_strerror.restype = ctypes.c_char_p
+    L.kvlinc_strerror.argtypes = [ctypes.c_int]
+    L.kvlinc_cache_validate.restype = ctypes.c_int
+    L.kvlinc_cache_validate.argtypes = [P]
+    L.kvlinc_append_quantize.restype = ctypes.c_int
+    L.kvlinc_append_quantize.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_void_p]
+    L.kvlinc_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.kvlinc_decode_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    L.kvlinc_decode_attention.restype = ctypes.c_int
+    L.kvlinc_decode_attention.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                          ctypes.c_int32, ctypes.c_void_p]
+    return L
+
+
+lib = _load()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _struct(cache):
+    return cache.struct if isinstance(cache, KVLincCache) else cache
+
+
+def kvlinc_version():
+    return lib.kvlinc_version()
+
+
+def kvlinc_strerror(code):
+    return lib.kvlinc_strerror(code).decode()
+
+
+def kvlinc_cache_validate(cache):
+    return lib.kvlinc_cache_validate(ctypes.byref(_struct(cache)))
+
+
+def kvlinc_append_quantize(cache, k_new, v_new, n_new=None, T=None, keep_residual=0, stream=None):
+    """k_new, v_new: [B, H_kv, T, 128] fp16 device tensors (contiguous); n_new: [B] int32 device tensor or None."""
+    if T is None:
+        T = k_new.shape[2]
+    return lib.kvlinc_append_quantize(ctypes.byref(_struct(cache)), _ptr(k_new), _ptr(v_new), _ptr(n_new), int(T),
+                                      int(keep_residual), _stream(stream))
+
+
+def kvlinc_decode_workspace_bytes(cache, max_context=0):
+    return lib.kvlinc_decode_workspace_bytes(ctypes.byref(_struct(cache)), int(max_context))
+
+
+def kvlinc_decode_attention(cache, q, out, workspace, workspace_bytes=None, max_context=0, stream=None):
+    """q, out: [B, H_q, 128] fp16 device tensors; workspace: device tensor of at least the advertised bytes."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return lib.kvlinc_decode_attention(ctypes.byref(_struct(cache)), _ptr(q), _ptr(out), _ptr(workspace),
+                                       int(workspace_bytes), int(max_context), _stream(stream))
+
+
+class KVLincCache:
+    """Device buffers of one layer's cache plus the descriptor that points at them (allocation only)."""
+
+    def __init__(self, B, H_q, H_kv, max_context, R=128, Wq=None, Wk=None, device="cuda"):
+        import torch
+        self.B, self.H_q, self.H_kv, self.R = B, H_q, H_kv, R
+        self.max_groups = max(1, -(-int(max_context) // 128))
+        dev = torch.device(device)
+        mg = self.max_groups
+        z = lambda *s, dt: torch.zeros(*s, dtype=dt, device=dev)
+        self.k_codes = z(B, H_kv, mg, 1024, dt=torch.int32)
+        self.v_codes = z(B, H_kv, mg, 1024, dt=torch.int32)
+        self.k_scale = z(B, H_kv, mg, 128, dt=torch.float16)
+        self.k_zero = z(B, H_kv, mg, 128, dt=torch.float16)
+        self.v_scale = z(B, H_kv, mg, 128, dt=torch.float16)
+        self.v_zero = z(B, H_kv, mg, 128, dt=torch.float16)
+        self.k_res = z(B, H_kv, R, 128, dt=torch.float16)
+        self.v_res = z(B, H_kv, R, 128, dt=torch.float16)
+        self.n_quant = z(B, dt=torch.int32)
+        self.n_res = z(B, dt=torch.int32)
+        self.status = z(1, dt=torch.int32)
+        self.Wq, self.Wk = Wq, Wk
+        if Wq is not None:
+            assert Wk is not None and tuple(Wq.shape) == (H_q, 2, 128, 128) and tuple(Wk.shape) == (H_kv, 2, 128, 128)
+            assert Wq.dtype == torch.float16 and Wk.dtype == torch.float16 and Wq.is_contiguous() and Wk.is_contiguous()
+            self.S = z(B, H_kv, 256, 128, dt=torch.float32)
+            self.P = z(B, H_kv, 256, dt=torch.float32)
+        else:
+            self.S = self.P = None
+        self.struct = CacheStruct(
+            B=B, H_q=H_q, H_kv=H_kv, d=128, G=128, R=R, D=256, bits=2, max_groups=mg,
+            k_codes=self.k_codes.data_ptr(), v_codes=self.v_codes.data_ptr(),
+            k_scale=self.k_scale.data_ptr(), k_zero=self.k_zero.data_ptr(),
+            v_scale=self.v_scale.data_ptr(), v_zero=self.v_zero.data_ptr(),
+            k_res=self.k_res.data_ptr(), v_res=self.v_res.data_ptr(),
+            n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),
+            S=None if self.S is None else self.S.data_ptr(), P=None if self.P is None else self.P.data_ptr(),
+            Wq=None if Wq is None else Wq.data_ptr(), Wk=None if Wk is None else Wk.data_ptr(),
+            status=self.status.data_ptr())
+        self._ws = None
+
+    def bytes(self):
+        ts = [self.k_codes, self.v_codes, self.k_scale, self.k_zero, self.v_scale, self.v_zero, self.k_res, self.v_res]
+        if self.S is not None:
+            ts += [self.S, self.P]
+        return sum(t.numel() * t.element_size() for t in ts)
+
+    def append(self, k_new, v_new, n_new=None, keep_residual=0, stream=None):
+        rc = kvlinc_append_quantize(self, k_new, v_new, n_new, k_new.shape[2], keep_residual, stream)
+        if rc != KVLINC_OK:
+            raise KVLincError("kvlinc_append_quantize: " + kvlinc_strerror(rc))
+
+    def workspace(self, max_context=0):
+        import torch
+        need = kvlinc_decode_workspace_bytes(self, max_context)
+        if self._ws is None or self._ws.numel() * 4 < need:
+            self._ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=self.k_codes.device)
+        return self._ws
+
+    def decode(self, q, out=None, max_context=0, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty_like(q)
+        ws = self.workspace(max_context)
+        rc = kvlinc_decode_attention(self, q, out, ws, ws.numel() * 4, max_context, stream)
+        if rc != KVLINC_OK:
+            raise KVLincError("kvlinc_decode_attention: " + kvlinc_strerror(rc))
+        return out

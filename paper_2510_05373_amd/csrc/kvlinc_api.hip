@@ -1,0 +1,77 @@
+// Host side of the C ABI: argument validation and launch set-up.  Nothing here touches device memory.
+#include <hip/hip_runtime.h>
+
+#include "kvlinc_internal.h"
+
+namespace {
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline bool bad_ptr(const void* p, uintptr_t a) { return p == nullptr || !aligned(p, a); }
+
+}  // namespace
+
+extern "C" {
+
+int kvlinc_version(void) { return 100; }
+
+const char* kvlinc_strerror(int code) {
+  switch (code) {
+    case KVLINC_OK: return "ok";
+    case KVLINC_EINVAL: return "invalid argument (NULL or misaligned pointer, unsupported shape or parameter)";
+    case KVLINC_EWORKSPACE: return "workspace too small or misaligned";
+    case KVLINC_EHIP: return "HIP launch failed";
+    default: return "unknown kvlinc error code";
+  }
+}
+
+int kvlinc_cache_validate(const kvlinc_cache* c) {
+  if (c == nullptr) return KVLINC_EINVAL;
+  if (c->B < 1 || c->H_q < 1 || c->H_kv < 1) return KVLINC_EINVAL;
+  if (c->d != kvlinc::kHeadDim || c->G != kvlinc::kGroup || c->D != kvlinc::kRank || c->bits != 2) return KVLINC_EINVAL;
+  if (c->R < 1 || c->R > kvlinc::kGroup) return KVLINC_EINVAL;
+  if (c->H_q % c->H_kv != 0 || c->H_q / c->H_kv > kvlinc::kMaxGq) return KVLINC_EINVAL;
+  if (c->max_groups < 1 || c->max_groups > (1ll << 24)) return KVLINC_EINVAL;
+  if ((long long)c->B * c->H_kv > (1ll << 24)) return KVLINC_EINVAL;
+  if (bad_ptr(c->k_codes, 16) || bad_ptr(c->v_codes, 16)) return KVLINC_EINVAL;
+  if (bad_ptr(c->k_scale, 16) || bad_ptr(c->k_zero, 16) || bad_ptr(c->v_scale, 16) || bad_ptr(c->v_zero, 16))
+    return KVLINC_EINVAL;
+  if (bad_ptr(c->k_res, 16) || bad_ptr(c->v_res, 16)) return KVLINC_EINVAL;
+  if (bad_ptr(c->n_quant, 4) || bad_ptr(c->n_res, 4) || bad_ptr(c->status, 4)) return KVLINC_EINVAL;
+  const int n_corr = (c->S != nullptr) + (c->P != nullptr) + (c->Wq != nullptr) + (c->Wk != nullptr);
+  if (n_corr != 0 && n_corr != 4) return KVLINC_EINVAL;
+  if (n_corr == 4 && (!aligned(c->S, 16) || !aligned(c->P, 16) || !aligned(c->Wq, 16) || !aligned(c->Wk, 16)))
+    return KVLINC_EINVAL;
+  return KVLINC_OK;
+}
+
+int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, const kvlinc_half* v_new,
+                           const int32_t* n_new, int32_t T, int32_t keep_residual, void* stream) {
+  const int rc = kvlinc_cache_validate(cache);
+  if (rc != KVLINC_OK) return rc;
+  if (bad_ptr(k_new, 16) || bad_ptr(v_new, 16)) return KVLINC_EINVAL;
+  if (n_new != nullptr && !aligned(n_new, 4)) return KVLINC_EINVAL;
+  if (T < 1 || T > (1 << 24)) return KVLINC_EINVAL;
+  if (keep_residual < 0 || keep_residual > cache->R) return KVLINC_EINVAL;
+  if (keep_residual == 0 && cache->R != kvlinc::kGroup) return KVLINC_EINVAL;
+  return kvlinc::launch_append(*cache, k_new, v_new, n_new, T, keep_residual, static_cast<hipStream_t>(stream));
+}
+
+size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_context) {
+  if (kvlinc_cache_validate(cache) != KVLINC_OK) return 0;
+  const int n_splits = kvlinc::decode_splits(*cache, max_context);
+  return (size_t)cache->B * cache->H_q * (n_splits + 1) * kvlinc::kPartStride * sizeof(float);
+}
+
+int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                            size_t workspace_bytes, int32_t max_context, void* stream) {
+  const int rc = kvlinc_cache_validate(cache);
+  if (rc != KVLINC_OK) return rc;
+  if (bad_ptr(q, 16) || bad_ptr(out, 16)) return KVLINC_EINVAL;
+  if (bad_ptr(workspace, 16) || workspace_bytes < kvlinc_decode_workspace_bytes(cache, max_context))
+    return KVLINC_EWORKSPACE;
+  const int n_splits = kvlinc::decode_splits(*cache, max_context);
+  return kvlinc::launch_decode(*cache, q, out, static_cast<float*>(workspace), n_splits,
+                               static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal declarations shared by the translation units of libkvlinc (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvlinc.h"
+
+namespace kvlinc {
+
+constexpr int kHeadDim = 128;   // d
+constexpr int kGroup = 128;     // G: tokens per key group = channels per value group
+constexpr int kRank = 256;      // D
+constexpr int kTileWords = 1024;
+constexpr int kMaxGq = 8;       // query heads per KV head supported by the decode kernels
+
+// Partial result of one block of tokens for one query head (Alg. 1: m^j, l^j, Y_s^j), log2 domain:
+// {m, l, unused, unused, acc[128]}; m = -inf marks an empty block whose other fields are undefined.
+constexpr int kPartStride = 132;
+
+// What one append does to one sequence (same arithmetic in the flush kernel and in the counter commit).
+struct AppendPlan {
+  int n_flush;   // tokens leaving the window / new-token stream into quantized groups
+  int n_groups;  // groups written (the last one partial iff n_flush % 128 != 0)
+  int new_res;   // window tokens after the append
+  int err;       // KVLINC_ST_* bit, 0 = fine; on error the sequence is left unchanged
+};
+
+__host__ __device__ inline AppendPlan plan_append(int n_quant, int n_res, int n_new, int R, int keep,
+                                                  long long max_groups) {
+  AppendPlan p{0, 0, n_res, 0};
+  if (n_new <= 0) return p;
+  if (n_quant % kGroup != 0) { p.err = KVLINC_ST_STATIC; return p; }
+  const int total = n_res + n_new;
+  int new_res;
+  if (keep == 0) new_res = total <= R ? total : (total - 1) % kGroup + 1;  // lazy block flush (R == G)
+  else new_res = keep < total ? keep : total;
+  const int n_flush = total - new_res;
+  if (n_flush > 0 && n_flush < n_res) { p.err = KVLINC_ST_STATIC; return p; }  // would have to shift the window
+  const int n_groups = (n_flush + kGroup - 1) / kGroup;
+  if ((long long)(n_quant / kGroup) + n_groups > max_groups) { p.err = KVLINC_ST_CAPACITY; return p; }
+  p.n_flush = n_flush;
+  p.n_groups = n_groups;
+  p.new_res = new_res;
+  return p;
+}
+
+// Split count of the decode launch: blocks of groups per (sequence, KV head).
+int decode_splits(const kvlinc_cache& c, int max_context);
+
+int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
+                  int T, int keep, hipStream_t stream);
+int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
+                  hipStream_t stream);
+
+}  // namespace kvlinc

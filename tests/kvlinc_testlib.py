@@ -1,0 +1,96 @@
+"""Shared helpers of the GPU parity tests: seeded inputs -> GPU cache through the C ABI, and the same inputs ->
+oracle, compared field by field."""
+import numpy as np
+
+import kvlinc_synth as synth
+from oracle import attention as o_attn
+from oracle import kvcache as o_cache
+from oracle import layout as o_layout
+
+OUT_MAX_ABS = 1e-2   # attention output tolerance (fp16 I/O, fp32 accumulate)
+OUT_REL_L2 = 2e-3
+STATE_REL_L2 = 1e-4  # S, P: fp32 accumulation of up to ~1e5 products against fp64
+
+
+def gen_kv(config, B, H_kv, lengths):
+    """K, V as [B, H_kv, T, 128] fp16 (rows past a sequence's length are zero), T = max length."""
+    T = int(max(lengths))
+    K = np.zeros((B, H_kv, T, 128), dtype=np.float16)
+    V = np.zeros((B, H_kv, T, 128), dtype=np.float16)
+    for b in range(B):
+        for g in range(H_kv):
+            K[b, g, :lengths[b]] = synth.keys(config, b, g, int(lengths[b]))
+            V[b, g, :lengths[b]] = synth.values(config, b, g, int(lengths[b]))
+    return K, V
+
+
+def gen_q(config, B, H_q, step=0):
+    return np.stack([synth.queries(config, b, H_q, step) for b in range(B)])
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def u16(a):
+    return np.ascontiguousarray(a).view(np.uint16)
+
+
+def check_cache_against_oracle(cache, K, V, lengths, pairs, Wk=None, keep=None, check_states=True):
+    """Bit-exact comparison of everything the append path stores, for the listed (sequence, kv head) pairs."""
+    n_quant = cache.n_quant.cpu().numpy()
+    n_res = cache.n_res.cpu().numpy()
+    for b in range(cache.B):
+        want = o_cache.window_split(int(lengths[b]), keep=keep)
+        assert (int(n_quant[b]), int(n_res[b])) == want, (b, n_quant[b], n_res[b], want)
+    for (b, g) in pairs:
+        n = int(lengths[b])
+        nq, nr = int(n_quant[b]), int(n_res[b])
+        ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], nq, Wk=None if Wk is None else Wk[g])
+        ng = -(-nq // 128)
+        kc = cache.k_codes[b, g, :ng].cpu().numpy().view(np.uint32)
+        vc = cache.v_codes[b, g, :ng].cpu().numpy().view(np.uint32)
+        if ng:
+            # logical codes first (clearer failure), then the physical tile bytes
+            assert np.array_equal(o_layout.unpack_k_tile(kc), ref["k_codes"]), ("k codes", b, g)
+            assert np.array_equal(o_layout.unpack_v_tile(vc), ref["v_codes"]), ("v codes", b, g)
+            assert np.array_equal(kc, o_layout.pack_k_tile(ref["k_codes"])), ("k tiles", b, g)
+            assert np.array_equal(vc, o_layout.pack_v_tile(ref["v_codes"])), ("v tiles", b, g)
+        for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
+            got = getattr(cache, name)[b, g, :ng].cpu().numpy()
+            assert np.array_equal(u16(got), u16(ref[name])), (name, b, g)
+        assert np.array_equal(u16(cache.k_res[b, g, :nr].cpu().numpy()), u16(ref["k_res"])), ("k_res", b, g)
+        assert np.array_equal(u16(cache.v_res[b, g, :nr].cpu().numpy()), u16(ref["v_res"])), ("v_res", b, g)
+        if Wk is not None and check_states:
+            S = cache.S[b, g].cpu().numpy().astype(np.float64)
+            P = cache.P[b, g].cpu().numpy().astype(np.float64)
+            for got, want, nm in ((S, ref["S"], "S"), (P, ref["P"], "P")):
+                den = np.linalg.norm(want)
+                err = np.linalg.norm(got - want)
+                assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
+
+
+def oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq=None, Wk=None):
+    """{(b, h): y fp64[128]} for every query head of the listed (sequence, kv head) pairs."""
+    gq = H_q // H_kv
+    out = {}
+    for (b, g) in pairs:
+        n = int(lengths[b])
+        ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=None if Wk is None else Wk[g])
+        for h in range(g * gq, (g + 1) * gq):
+            out[(b, h)] = o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h])
+    return out
+
+
+def check_outputs(got, want):
+    """got: [B, H_q, 128] array; want: {(b, h): y}.  Max-abs and relative-L2 over all compared rows."""
+    g = np.stack([got[b, h].astype(np.float64) for (b, h) in want])
+    w = np.stack([want[k] for k in want])
+    assert np.isfinite(g).all()
+    max_abs = np.abs(g - w).max()
+    rel_l2 = np.linalg.norm(g - w) / np.linalg.norm(w)
+    worst_row = max(np.linalg.norm(g[i] - w[i]) / np.linalg.norm(w[i]) for i in range(len(w)))
+    assert max_abs <= OUT_MAX_ABS, ("max abs", max_abs)
+    assert rel_l2 <= OUT_REL_L2, ("rel l2", rel_l2, "worst row", worst_row)
+    return max_abs, rel_l2, worst_row

@@ -1,0 +1,169 @@
+"""GPU parity: the HIP path through the C ABI against the oracle, element by element (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import kvlinc_synth as synth
+from tests import kvlinc_testlib as tl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2510_05373_amd as kvmod
+    return kvmod
+
+
+def _build(kv, cfg, B, H_q, H_kv, lengths, R=128, keep=None, correction=True, capacity=None):
+    K, V = tl.gen_kv(cfg, B, H_kv, lengths)
+    Wq = synth.adapters_q(cfg, H_q) if correction else None
+    Wk = synth.adapters_k(cfg, H_kv) if correction else None
+    cache = kv.KVLincCache(B, H_q, H_kv, capacity or int(max(lengths)) + 512, R=R,
+                           Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk))
+    n_new = tl.to_dev(np.asarray(lengths, dtype=np.int32))
+    cache.append(tl.to_dev(K), tl.to_dev(V), n_new=n_new, keep_residual=0 if keep is None else keep)
+    return cache, K, V, Wq, Wk
+
+
+def _all_pairs(B, H_kv):
+    return [(b, g) for b in range(B) for g in range(H_kv)]
+
+
+@pytest.mark.parametrize("correction", [True, False])
+def test_bulk_append_and_decode_small_ragged(kv, correction):
+    """Several tiles, ragged lengths (one below a group, one an exact multiple, one with a long tail)."""
+    import torch
+    B, H_q, H_kv = 4, 8, 2
+    lengths = [700, 128, 57, 1025]
+    cache, K, V, Wq, Wk = _build(kv, 11, B, H_q, H_kv, lengths, correction=correction)
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)
+    q = tl.gen_q(11, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+
+
+def test_one_token_appends_cross_flushes(kv):
+    """Bulk prefix, then one-token appends through two window flushes; state after every flush boundary and at the
+    end must equal the oracle's pure function of the token history."""
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    start, steps = [250, 127], 300
+    total = [s + steps for s in start]
+    K, V = tl.gen_kv(12, B, H_kv, total)
+    Wq, Wk = synth.adapters_q(12, H_q), synth.adapters_k(12, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    T0 = max(start)
+    k0 = torch.zeros(B, H_kv, T0, 128, dtype=torch.float16, device="cuda")
+    v0 = torch.zeros_like(k0)
+    for b in range(B):
+        k0[b, :, :start[b]] = Kd[b, :, :start[b]]
+        v0[b, :, :start[b]] = Vd[b, :, :start[b]]
+    cache.append(k0, v0, n_new=tl.to_dev(np.asarray(start, dtype=np.int32)))
+    lengths = list(start)
+    for step in range(steps):
+        kn = torch.stack([Kd[b, :, lengths[b]:lengths[b] + 1] for b in range(B)]).contiguous()
+        vn = torch.stack([Vd[b, :, lengths[b]:lengths[b] + 1] for b in range(B)]).contiguous()
+        cache.append(kn, vn)
+        lengths = [n + 1 for n in lengths]
+        if step in (0, 5, 6, 7, 133, 134, 135, steps - 1):
+            tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)
+            q = tl.gen_q(12, B, H_q, step)
+            out = cache.decode(tl.to_dev(q)).cpu().numpy()
+            want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv,
+                                    Wq, Wk)
+            tl.check_outputs(out, want)
+    assert int(cache.status.item()) == 0
+
+
+def test_config1_partial_tail_group(kv):
+    """Workload 1: batch 1, 32/8 heads, context 1024, 32-token window -> 7 full groups + a 96-token tail group."""
+    c = synth.CONFIGS[1]
+    lengths = [c["n"]]
+    cache, K, V, Wq, Wk = _build(kv, 1, c["B"], c["H_q"], c["H_kv"], lengths, R=c["R"], keep=c["keep"], capacity=1024)
+    assert cache.n_quant.cpu().tolist() == [992] and cache.n_res.cpu().tolist() == [32]
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(1, 8), Wk=Wk, keep=32)
+    q = tl.gen_q(1, 1, 32)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, [992], _all_pairs(1, 8), 32, 8, Wq, Wk)
+    tl.check_outputs(out, want)
+    # a sequence with a partial last group accepts no further token
+    import torch
+    z = torch.zeros(1, 8, 1, 128, dtype=torch.float16, device="cuda")
+    cache.append(z, z, keep_residual=32)
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) & kv.KVLINC_ST_STATIC
+    assert cache.n_quant.cpu().tolist() == [992] and cache.n_res.cpu().tolist() == [32]
+
+
+@pytest.mark.parametrize("gq,H_kv", [(1, 2), (7, 2), (2, 1), (8, 1)])
+def test_other_head_ratios(kv, gq, H_kv):
+    B, H_q = 2, gq * H_kv
+    lengths = [400, 300]
+    cache, K, V, Wq, Wk = _build(kv, 13, B, H_q, H_kv, lengths)
+    q = tl.gen_q(13, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+
+
+def test_degenerate_inputs(kv):
+    import torch
+    B, H_q, H_kv = 3, 4, 1
+    # sequence 0 empty, sequence 1 a single token, sequence 2 constant keys/values (scale 0 everywhere)
+    lengths = [0, 1, 300]
+    K, V = tl.gen_kv(14, B, H_kv, lengths)
+    K[2, :, :300] = np.float16(0.75)
+    V[2, :, :300] = np.float16(-1.5)
+    Wq, Wk = synth.adapters_q(14, H_q), synth.adapters_k(14, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+    tl.check_cache_against_oracle(cache, K, V, lengths, [(1, 0), (2, 0)], Wk=Wk)
+    assert not cache.k_scale[2, 0, :2].any() and not cache.k_codes[2, 0, :2].any()
+    q = tl.gen_q(14, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    assert not out[0].any()  # no tokens -> zeros
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), [(1, 0), (2, 0)], H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+    assert int(cache.status.item()) == 0
+
+
+def test_status_bits_and_rejections(kv):
+    import torch
+    B, H_q, H_kv = 1, 4, 1
+    cache = kv.KVLincCache(B, H_q, H_kv, 256)  # capacity: 2 groups
+    k = torch.randn(B, H_kv, 600, 128, device="cuda").half()
+    cache.append(k, k)  # would need 4 groups
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == kv.KVLINC_ST_CAPACITY
+    assert cache.n_quant.item() == 0 and cache.n_res.item() == 0 and not cache.k_codes.any()
+    cache.status.zero_()
+    k[0, 0, 5, 7] = float("inf")
+    cache.append(k[:, :, :300].contiguous(), k[:, :, :300].contiguous())
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == kv.KVLINC_ST_NONFINITE
+    # host-side rejections: nothing is launched
+    q = torch.zeros(B, H_q, 128, dtype=torch.float16, device="cuda")
+    ws = torch.empty(4, device="cuda")
+    assert kv.kvlinc_decode_attention(cache, q, q.clone(), ws) == kv.KVLINC_EWORKSPACE
+    assert kv.kvlinc_append_quantize(cache, k, k, None, 0, 0) == kv.KVLINC_EINVAL
+    assert kv.kvlinc_append_quantize(cache, k, k, None, 600, 200) == kv.KVLINC_EINVAL
+
+
+def test_run_to_run_determinism(kv):
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    lengths = [1500, 900]
+    cache, K, V, Wq, Wk = _build(kv, 15, B, H_q, H_kv, lengths)
+    q = tl.to_dev(tl.gen_q(15, B, H_q))
+    first = cache.decode(q).clone()
+    for _ in range(5):
+        assert torch.equal(cache.decode(q), first)
+    cache2, *_ = _build(kv, 15, B, H_q, H_kv, lengths)
+    for name in ("k_codes", "v_codes", "k_scale", "v_zero", "k_res", "v_res", "S", "P"):
+        assert torch.equal(getattr(cache, name), getattr(cache2, name)), name

@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVLinC 2-bit decode hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch: kvlinc_append_quantize of one new token per sequence
+(rotation, window write, and -- when a window is full -- the group flush with its state update) followed by
+kvlinc_decode_attention over the whole cache.  Workload: the Llama-3-8B-shaped layer (batch 16, 32 query / 8 KV
+heads, head_dim 128, context 8192, 2-bit keys per channel and rotated values per token at group 128, 128-token fp16
+window, linear correction on).  Steps cycle over several distinct layer caches so that every step reads HBM and
+not the 256 MB Infinity Cache, like the layers of a model do.  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line; see the design notes for the byte accounting behind "roofline".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+WORKLOAD = 2  # index into kvlinc_synth.CONFIGS
+
+
+def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True):
+    """Bytes one decode call must move: 2-bit codes (64 B per token and KV head), fp16 scale + zero-point (8 B),
+    the fp16 window (512 B per window token and KV head), S and P once per (sequence, KV head), W_q once, q and out.
+    Split partials are an implementation choice and are not counted."""
+    groups = sum(-(-int(n) // 128) for n in n_quant)
+    total = groups * H_kv * (2 * 4096 + 2 * 512)
+    total += int(sum(n_res)) * H_kv * 512
+    if correction:
+        total += B * H_kv * (256 * 128 + 256) * 4 + H_q * 2 * 128 * 128 * 2
+    total += B * H_q * 128 * 2 * 2
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=8, help="distinct layer caches cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence / "
+              "KV head without communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    import kvlinc_synth as synth
+    import paper_2510_05373_amd as kv
+
+    cfg = synth.CONFIGS[WORKLOAD]
+    B, H_q, H_kv, n0 = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["n"]
+    L, K_steps, W = args.layers, args.steps, args.warmup
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- inputs: one seeded K/V history (host, for the oracle sample) copied into L distinct caches ----------
+    t0 = time.time()
+    Kh = np.empty((B, H_kv, n0, 128), dtype=np.float16)
+    Vh = np.empty_like(Kh)
+    for b in range(B):
+        for g in range(H_kv):
+            Kh[b, g] = synth.keys(WORKLOAD, b, g, n0)
+            Vh[b, g] = synth.values(WORKLOAD, b, g, n0)
+    Wq_h, Wk_h = synth.adapters_q(WORKLOAD, H_q), synth.adapters_k(WORKLOAD, H_kv)
+    Kd, Vd = torch.from_numpy(Kh).to(dev), torch.from_numpy(Vh).to(dev)
+    Wq, Wk = torch.from_numpy(Wq_h).to(dev), torch.from_numpy(Wk_h).to(dev)
+    total_steps = W + K_steps
+    per_layer = -(-total_steps // L)
+    # Windows flush once per 128 appends.  Layers start a few tokens short of the nominal context, staggered so
+    # that flush steps fall inside the timed region at about their natural rate (here 2 layers out of 8).
+    caches, start_len = [], []
+    for j in range(L):
+        short = 0
+        if j % 4 == 0:
+            short = min(n0 - 1, W // L + 3 + (j // 4) * 7)  # its window (full at n0) flushes at append `short`+1
+        n_start = n0 - short
+        c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk)
+        c.append(Kd[:, :, :n_start].contiguous(), Vd[:, :, :n_start].contiguous())
+        caches.append(c)
+        start_len.append(n_start)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED)
+    k_new = torch.randn(total_steps, B, H_kv, 1, 128, device=dev, generator=gen).half()
+    v_new = torch.randn(total_steps, B, H_kv, 1, 128, device=dev, generator=gen).half()
+    q_all = torch.randn(total_steps, B, H_q, 128, device=dev, generator=gen).half()
+    out = torch.empty(B, H_q, 128, dtype=torch.float16, device=dev)
+    max_ctx = n0 + per_layer + 1
+    for c in caches:
+        c.workspace(max_ctx)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step(i):
+        c = caches[i % L]
+        c.append(k_new[i], v_new[i])
+        c.decode(q_all[i], out, max_context=max_ctx)
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]
+
+    # ---- timed region: exactly K steps, whole-job clock + per-call HIP events on the launch stream ------------
+    ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    tokens = 0
+    alg_bytes = []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(K_steps):
+        i = W + s
+        c = caches[i % L]
+        ev_a[s].record()
+        c.append(k_new[i], v_new[i])
+        ev_b[s].record()
+        c.decode(q_all[i], out, max_context=max_ctx)
+        ev_c[s].record()
+        lens[i % L] += 1
+        tokens += B * lens[i % L]
+        n = lens[i % L]
+        n_res = (n - 1) % 128 + 1
+        alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, [n - n_res] * B, [n_res] * B))
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    for c in caches:
+        assert int(c.status.item()) == 0, "device status word set"
+    elapsed = t_end - t_start
+    append_ms = np.array([ev_a[s].elapsed_time(ev_b[s]) for s in range(K_steps)])
+    decode_ms = np.array([ev_b[s].elapsed_time(ev_c[s]) for s in range(K_steps)])
+    decode_avg_s = float(decode_ms.mean()) * 1e-3
+    achieved = float(np.mean(alg_bytes)) / decode_avg_s / 1e9
+
+    result = {
+        "metric": "decode-attention KV tokens/s at 2-bit (achieved HBM GB/s and % of peak under roofline)",
+        "value": tokens / elapsed,
+        "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": elapsed / K_steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "2-bit codes, fp16 operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
+                   "context": n0, "window": 128, "group": 128, "bits": 2, "correction_rank": 256,
+                   "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
+                   "append_ms_median": float(np.median(append_ms)), "append_ms_max": float(append_ms.max()),
+                   "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),
+                   "setup_s": setup_s},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "kvlinc_decode_attention (all launches of one call)",
+                     "algorithmic_bytes_per_launch": float(np.mean(alg_bytes)),
+                     "avg_launch_us": decode_avg_s * 1e6},
+    }
+
+    # ---- the oracle beside it: same decode step, bounded sample, host cores ----------------------------------
+    if not args.no_cpu_baseline:
+        from oracle import attention as o_attn
+        from oracle import kvcache as o_cache
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        # parity of the bench configuration on the sample + timing of the oracle's decode of the same rows
+        i_chk = W + K_steps - 1
+        j = i_chk % L
+        n = lens[j]
+        nq, nr = o_cache.window_split(n)
+        n_app = n - start_len[j]
+        idx = [i for i in range(W + K_steps) if i % L == j]
+        k_app = k_new[idx][:, :, :, 0].cpu().numpy()  # [n_app, B, H_kv, 128]
+        v_app = v_new[idx][:, :, :, 0].cpu().numpy()
+        q_chk = q_all[i_chk].cpu().numpy()
+        got = out.cpu().numpy().astype(np.float64)
+        pairs = [(0, 0), (B - 1, H_kv - 1), (B // 2, 3)]
+        gq = H_q // H_kv
+        t_cpu, rows, reps = 0.0, 0, 0
+        err_num = err_den = 0.0
+        while t_cpu < 10.0 and reps < 40:
+            for (b, g) in pairs:
+                Kf = np.concatenate([Kh[b, g, :start_len[j]], k_app[:n_app, b, g]])
+                Vf = np.concatenate([Vh[b, g, :start_len[j]], v_app[:n_app, b, g]])
+                ref = o_cache.build_cache(Kf, Vf, nq, Wk=Wk_h[g])
+                t1 = time.perf_counter()
+                ys = [o_attn.decode(q_chk[b, h], ref, Wq_h[h]) for h in range(g * gq, (g + 1) * gq)]
+                t_cpu += time.perf_counter() - t1
+                rows += 1
+                if reps == 0:
+                    for h, y in zip(range(g * gq, (g + 1) * gq), ys):
+                        err_num += float(((got[b, h] - y) ** 2).sum())
+                        err_den += float((y ** 2).sum())
+                        assert np.abs(got[b, h] - y).max() <= 1e-2, "bench output off the oracle"
+            reps += 1
+        rel_l2 = (err_num / err_den) ** 0.5
+        assert rel_l2 <= 2e-3, "bench output off the oracle (rel-L2 %g)" % rel_l2
+        result["cpu_baseline"] = {
+            "value": n * rows / t_cpu / H_kv, "unit": "KV tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "oracle decode (dense fp64 operands, Eq. 5) of %d (sequence, KV head) pairs x %d query heads "
+                      "at context %d, %d repetitions, %.1f s; scaled to whole-layer tokens (one token = all %d KV "
+                      "heads); the oracle's cache build is not timed" % (len(pairs), gq, n, reps, t_cpu, H_kv),
+            "parity_rel_l2_on_sample": rel_l2,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

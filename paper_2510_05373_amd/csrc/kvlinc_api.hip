@@ -59,7 +59,7 @@ int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, 
 size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_context) {
   if (kvlinc_cache_validate(cache) != KVLINC_OK) return 0;
   const int n_splits = kvlinc::decode_splits(*cache, max_context);
-  return (size_t)cache->B * cache->H_q * (n_splits + 1) * kvlinc::kPartStride * sizeof(float);
+  return kvlinc::decode_workspace_floats(*cache, n_splits) * sizeof(float);
 }
 
 int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,

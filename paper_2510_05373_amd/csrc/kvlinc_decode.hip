@@ -1,14 +1,24 @@
-// Decode path: single-query attention read directly from the packed 2-bit cache, split over blocks of groups,
-// merged, corrected and rotated back (Sec. 3.3, Alg. 1; Sec. 3.2, Eq. 5-6; Sec. 3.1 for the rotated value basis).
+// Block-split decode over the packed 2-bit cache on the CDNA4 matrix cores (Sec. 3.3, Alg. 1 lines 4-12: unpack,
+// q K^T, block max / exp / sum, E V; the dequantization is folded into the small operands instead of being applied
+// to the tiles).
 //
-// Launch 1 (decode_split_kernel): one workgroup per (sequence, kv head, block of groups) plus one per
-// (sequence, kv head) for the fp16 window.  All query heads of the kv head are processed together, so every
-// packed tile is read once.  Scores live in the log2 domain: x = q.k * log2(e)/sqrt(d).  Each workgroup writes
-// (m, l, acc[128]) per query head (Alg. 1: m^j, l^j, Y_s^j).
-// Launch 2 (decode_merge_kernel): one workgroup per (sequence, kv head): weighs the partial results by
-// 2^(m_j - M), computes phi_q(q), C_n = phi_q S, C_d = phi_q P, forms (num + 2^-M C_n) / (den + 2^-M C_d), applies
-// H^T and stores fp16.
+// One wave owns a group of 128 tokens at a time and keeps its own (m, l, acc); the four waves of a workgroup take
+// the groups of the workgroup's range round-robin and are combined through LDS at the end (Alg. 1 line 11 writes
+// one (Y_s, m, l) per workgroup and query head).
+//
+// Both contractions run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad (cbsz=4,
+// abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
+//   q K^T : columns = 64 tokens (lane = token), k = 4 channels; A = q * key scale, held by quad `abid` for its 8 channels.
+//   E V   : columns = 64 channels (lane = channel), k = 4 tokens;  A = p * value scale, held by the quad that owns the tokens.
+// The B operand is the packed word itself, masked: a 2-bit code left in place inside an fp16 mantissa is the
+// subnormal code * 2^(2 pos - 24) (the matrix cores take subnormal inputs exactly), and the factor 2^(-2 pos) is
+// folded into the A operand of that k slot.  One AND per two codes, one shift per sixteen.
+// Zero-points never touch the tiles: sum_c q_c (s_c code + z_c) = sum_c (q_c s_c) code + sum_c q_c z_c, and likewise
+// for the values per token.  The fp16 rounding of (q s) and (p s) is centred: the code is taken as (code - 1.5) and
+// 1.5 * rounded operand is added back in binary32, which removes the mean of the rounding error.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "kvlinc_internal.h"
 
@@ -16,348 +26,710 @@ namespace kvlinc {
 namespace {
 
 typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 128;
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kAlpha = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
+constexpr float kRawScale = 1048576.0f;                  // 2^20: A carries 2^(4 - 2 pos), B carries 2^(2 pos - 24)
 
-__device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+// ---- small helpers ----------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t as_u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ half2_t as_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
+__device__ __forceinline__ half4_t as_h4(uint32_t a, uint32_t b) {
+  u32x2_t v = {a, b};
+  return __builtin_bit_cast(half4_t, v);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kQuadSwap1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kRowRor4 = 0x124, kRowRor8 = 0x128, kRowRor1 = 0x121, kRowRor2 = 0x122;
+
+__device__ __forceinline__ float wave_allmax(float v) {
+  v = fmaxf(v, dpp_f<kRowRor1>(v));
+  v = fmaxf(v, dpp_f<kRowRor2>(v));
+  v = fmaxf(v, dpp_f<kRowRor4>(v));
+  v = fmaxf(v, dpp_f<kRowRor8>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
   return v;
 }
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+__device__ __forceinline__ float wave_allsum(float v) {
+  v += dpp_f<kRowRor1>(v);
+  v += dpp_f<kRowRor2>(v);
+  v += dpp_f<kRowRor4>(v);
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+// sum over the 16 lanes that share lane % 4 (one per quad)
+__device__ __forceinline__ float quadlane_allsum(float v) {
+  v += dpp_f<kRowRor4>(v);
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   return v;
 }
 
-// Reductions over the 128 threads (2 waves) of a workgroup for N values at once; `red` is [N][2] floats of LDS.
-template <int N, bool IS_MAX>
-__device__ inline void block_reduce(float (&v)[N], float* red, int tid) {
-#pragma unroll
-  for (int h = 0; h < N; ++h) {
-    const float r = IS_MAX ? wave_max(v[h]) : wave_sum(v[h]);
-    if ((tid & 63) == 0) red[h * 2 + (tid >> 6)] = r;
+__device__ __forceinline__ float4_t mfma_bcast(half4_t a, half4_t b, float4_t c, int abid) {
+  switch (abid) {
+    case 0: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 0, 0);
+    case 1: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 1, 0);
+    case 2: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 2, 0);
+    case 3: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 3, 0);
+    case 4: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 4, 0);
+    case 5: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 5, 0);
+    case 6: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 6, 0);
+    case 7: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 7, 0);
+    case 8: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 8, 0);
+    case 9: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 9, 0);
+    case 10: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 10, 0);
+    case 11: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 11, 0);
+    case 12: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 12, 0);
+    case 13: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 13, 0);
+    case 14: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 14, 0);
+    default: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 15, 0);
   }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < N; ++h) v[h] = IS_MAX ? fmaxf(red[h * 2], red[h * 2 + 1]) : red[h * 2] + red[h * 2 + 1];
-  __syncthreads();
 }
 
-template <int GQ>
-__global__ __launch_bounds__(kThreads) void decode_split_kernel(kvlinc_cache c, const half_t* __restrict__ q,
-                                                                 float* __restrict__ part, int n_splits) {
-  __shared__ float sQ[GQ][kHeadDim];    // alpha * q
-  __shared__ float sQs[GQ][kHeadDim];   // alpha * q * key scale of the current group
-  __shared__ float sP[GQ][kGroup];      // 2^(x - m) of the current group
-  __shared__ float sVs[kGroup], sVz[kGroup];
-  __shared__ float sRed[GQ * 2];
+// Position of pair j of a packed word inside the fp16 mantissa after the (optional) shift by 6: the code of pair j
+// sits at bits [2 pos + 1 : 2 pos] of its half and reads as code * 2^(2 pos - 24).
+__host__ __device__ constexpr int pair_pos(int j) { return j <= 4 ? j : j - 3; }
+// The factor the A operand carries for a k slot fed by pair j: 2^(4 - 2 pos).
+__device__ __forceinline__ float pair_gain(int j) { return __builtin_ldexpf(1.0f, 4 - 2 * pair_pos(j)); }
+
+// The 8 pairs of a word as fp16x2 subnormals (9 VALU operations for 16 codes).
+__device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
+  const uint32_t ws = w >> 6;
+  u[0] = w & 0x00030003u;
+  u[1] = w & 0x000C000Cu;
+  u[2] = w & 0x00300030u;
+  u[3] = w & 0x00C000C0u;
+  u[4] = w & 0x03000300u;
+  u[5] = ws & 0x00300030u;
+  u[6] = ws & 0x00C000C0u;
+  u[7] = ws & 0x03000300u;
+}
+
+struct GroupRegs {
+  uint4 kw[2][2];  // key tile: [token half][word quad]
+  uint4 vw[2][2];  // value tile: [token half][channel half]
+  uint4 ks, kz;    // key scale / zero-point of channels 8*quad .. 8*quad+7
+  uint16_t vs[2], vz[2];  // value scale / zero-point of tokens lane, 64 + lane
+};
+
+__device__ __forceinline__ void load_group(GroupRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
+  const uint4* kt = reinterpret_cast<const uint4*>(c.k_codes + gbase * kTileWords);
+  const uint4* vt = reinterpret_cast<const uint4*>(c.v_codes + gbase * kTileWords);
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      r.kw[hf][i] = kt[(hf * 2 + i) * 64 + lane];
+      r.vw[hf][i] = vt[(hf * 2 + i) * 64 + lane];
+    }
+  const int quad = lane >> 2;
+  r.ks = reinterpret_cast<const uint4*>(c.k_scale + gbase * kGroup)[quad];
+  r.kz = reinterpret_cast<const uint4*>(c.k_zero + gbase * kGroup)[quad];
+  const uint16_t* vs = c.v_scale + gbase * kGroup;
+  const uint16_t* vz = c.v_zero + gbase * kGroup;
+  r.vs[0] = vs[lane]; r.vs[1] = vs[64 + lane];
+  r.vz[0] = vz[lane]; r.vz[1] = vz[64 + lane];
+}
+
+__device__ __forceinline__ float h2f(uint16_t bits) { return (float)__builtin_bit_cast(half_t, bits); }
+
+// NB = head blocks of 4 query heads (1: up to 4 heads per KV head, 2: up to 8).
+template <int NB>
+struct WaveState {
+  float m[NB][4];       // running maximum per head (wave-uniform), log2 domain
+  float l[NB][4];       // per-lane partial sums of p
+  float pz[NB][4];      // per-lane partial sums of the zero-point / centring terms of E V
+  float4_t acc[NB][2];  // E V in raw matrix-core units: [head block][channel half], rows = heads, lane = channel
+};
+
+template <int NB>
+__device__ __forceinline__ void process_group(const GroupRegs& g, int valid, const uint32_t (&Qs)[NB][4],
+                                              const uint32_t (&Qr)[NB][4], float gain0, float gain1, float vgain,
+                                              uint32_t perm_sel, int lane, WaveState<NB>& st) {
+  // ---- A operand of q K^T and the group's additive term per head ------------------------------------------------
+  const uint32_t S[4] = {g.ks.x, g.ks.y, g.ks.z, g.ks.w};
+  const uint32_t Z[4] = {g.kz.x, g.kz.y, g.kz.z, g.kz.w};
+  const half2_t c15 = {(half_t)1.5f, (half_t)1.5f};
+  const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
+  half4_t A[NB][2];
+  float4_t bias[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    uint32_t a[4];
+    float t = 0.0f, ua = 0.0f, ub = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = as_u32(as_h2(Qs[nb][i]) * as_h2(S[i]));                    // fp16(q 2^gain s), one rounding
+      const half2_t mid = as_h2(S[i]) * c15 + as_h2(Z[i]);              // z + 1.5 s
+      t = __builtin_amdgcn_fdot2(as_h2(Qr[nb][i]), mid, t, false);      // sum q (z + 1.5 s)
+      if (i & 1) ub = __builtin_amdgcn_fdot2(as_h2(a[i]), ones, ub, false);
+      else ua = __builtin_amdgcn_fdot2(as_h2(a[i]), ones, ua, false);
+    }
+    A[nb][0] = as_h4(a[0], a[1]);
+    A[nb][1] = as_h4(a[2], a[3]);
+    // sum_c q_c (z_c + 1.5 s_c) - 1.5 sum_c rounded(q_c s_c): exact compensation of the centring
+    float b = t - 1.5f * (ua / gain0 + ub / gain1);
+    b = quadlane_allsum(b) * (1.0f / kRawScale);  // lanes with lane % 4 == h now hold head h's term, in raw units
+    bias[nb][0] = dpp_f<0x00>(b);
+    bias[nb][1] = dpp_f<0x55>(b);
+    bias[nb][2] = dpp_f<0xAA>(b);
+    bias[nb][3] = dpp_f<0xFF>(b);
+  }
+
+  // ---- q K^T for both token halves -----------------------------------------------------------------------------
+  float4_t sc[NB][2];
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    float4_t acc0[NB], acc1[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) { acc0[nb] = bias[nb]; acc1[nb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t words[4] = {g.kw[hf][i].x, g.kw[hf][i].y, g.kw[hf][i].z, g.kw[hf][i].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        uint32_t u[8];
+        unpack_word(words[w], u);
+#pragma unroll
+        for (int mstep = 0; mstep < 4; ++mstep) {
+          const half4_t bop = as_h4(u[2 * mstep], u[2 * mstep + 1]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            if (i == 0) acc0[nb] = mfma_bcast(A[nb][0], bop, acc0[nb], 4 * w + mstep);
+            else acc1[nb] = mfma_bcast(A[nb][1], bop, acc1[nb], 4 * w + mstep);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) sc[nb][hf] = (acc0[nb] + acc1[nb]) * (kRawScale * kAlpha);
+  }
+  if (valid < kGroup) {  // partial last group: tokens >= valid do not exist
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+        if (64 * hf + lane >= valid) sc[nb][hf] = float4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  }
+
+  // ---- running maximum (Alg. 1 line 8), rescale only when it moved --------------------------------------------
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float mx[4];
+    bool moved = false;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      mx[h] = wave_allmax(fmaxf(sc[nb][0][h], sc[nb][1][h]));
+      mx[h] = fmaxf(mx[h], st.m[nb][h]);
+      moved |= mx[h] != st.m[nb][h];
+    }
+    if (__builtin_amdgcn_readfirstlane((int)moved)) {
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        const float f = exp2f(st.m[nb][h] - mx[h]);  // 0 when the old maximum is -inf
+        st.l[nb][h] *= f;
+        st.pz[nb][h] *= f;
+        st.acc[nb][0][h] *= f;
+        st.acc[nb][1][h] *= f;
+        st.m[nb][h] = mx[h];
+      }
+    }
+  }
+
+  // ---- p = 2^(x - m), its sums, the A operand of E V, and E V ----------------------------------------------------
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    const float vs = h2f(g.vs[hf]);
+    const float vmid = h2f(g.vz[hf]) + 1.5f * vs;
+    const float vsg = vs * vgain;             // value scale with the k-slot gain of this lane's token
+    const float comp = -1.5f / vgain;         // exact (power of two times 1.5)
+    half4_t A2[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float p[4], ps[4];
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        p[h] = __builtin_amdgcn_exp2f(sc[nb][hf][h] - st.m[nb][h]);
+        st.l[nb][h] += p[h];
+        ps[h] = p[h] * vsg;
+      }
+      const half2_t x01 = as_h2(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ps[0], ps[1])));
+      const half2_t x23 = as_h2(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ps[2], ps[3])));
+      // sum_t p_t (z_t + 1.5 s_t) - 1.5 sum_t rounded(p_t s_t)
+      st.pz[nb][0] = fmaf(p[0], vmid, fmaf((float)x01[0], comp, st.pz[nb][0]));
+      st.pz[nb][1] = fmaf(p[1], vmid, fmaf((float)x01[1], comp, st.pz[nb][1]));
+      st.pz[nb][2] = fmaf(p[2], vmid, fmaf((float)x23[0], comp, st.pz[nb][2]));
+      st.pz[nb][3] = fmaf(p[3], vmid, fmaf((float)x23[1], comp, st.pz[nb][3]));
+      // 4x4 transpose inside each lane quad: (lane = token, slots = heads) -> (lane = head, slots = tokens)
+      const uint32_t X = as_u32(x01), Y = as_u32(x23);
+      const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
+      const uint32_t X1 = __builtin_amdgcn_perm(TX, X, perm_sel);  // even lane {X.lo, TX.lo}; odd lane {TX.hi, X.hi}
+      const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, perm_sel);
+      const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
+      const bool upper = (lane & 2) != 0;
+      const uint32_t U = upper ? Y2 : X1;
+      const uint32_t W = upper ? Y1 : X2;
+      A2[nb] = as_h4(U, W);
+    }
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const uint32_t words[4] = {g.vw[hf][ch].x, g.vw[hf][ch].y, g.vw[hf][ch].z, g.vw[hf][ch].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        uint32_t u[8];
+        unpack_word(words[w], u);
+#pragma unroll
+        for (int mstep = 0; mstep < 4; ++mstep) {
+          const half4_t bop = as_h4(u[2 * mstep], u[2 * mstep + 1]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) st.acc[nb][ch] = mfma_bcast(A2[nb], bop, st.acc[nb][ch], 4 * w + mstep);
+        }
+      }
+    }
+  }
+}
+
+
+// ---- work item 1: a range of quantized groups of one (sequence, kv head) ----------------------------------------
+
+template <int NB>
+__device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* __restrict__ q, float* __restrict__ part,
+                                           int n_splits, int gq, int bh, int sp, float* lds) {
+  float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                       // [kWaves][NB*4]
+  float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);     // [kWaves][NB*4]
+  float (*sAcc)[NB * 4][kHeadDim] = reinterpret_cast<float (*)[NB * 4][kHeadDim]>(lds + 2 * kWaves * NB * 4);
 
   const int tid = threadIdx.x;
-  const int items_per_bh = n_splits + 1;
-  const int bh = blockIdx.x / items_per_bh;
-  const int sp = blockIdx.x % items_per_bh;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
   const int b = bh / c.H_kv;
   const int g = bh % c.H_kv;
   const int nq = c.n_quant[b];
-  const int nr = c.n_res[b];
+  const int n_groups = (nq + kGroup - 1) / kGroup;
+  const int g0 = (int)((long long)n_groups * sp / n_splits);
+  const int g1 = (int)((long long)n_groups * (sp + 1) / n_splits);
+  const int items_per_bh = n_splits + 1;
 
-#pragma unroll
-  for (int h = 0; h < GQ; ++h)
-    sQ[h][tid] = kAlpha * (float)q[((long long)b * c.H_q + g * GQ + h) * kHeadDim + tid];
-  __syncthreads();
+  // per-lane constants
+  const int quad = lane >> 2, hrow = lane & 3;
+  const int j0 = 2 * (quad & 3), j1 = j0 + 1;          // pairs feeding this quad's k slots (0,1) and (2,3)
+  const float gain0 = pair_gain(j0), gain1 = pair_gain(j1);
+  const float vgain = pair_gain(2 * ((lane >> 2) & 3) + ((lane >> 1) & 1));  // this lane's token as a k slot of E V
+  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
 
-  float m[GQ], l_loc[GQ], acc[GQ];
+  // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7; heads beyond gq read as 0
+  uint32_t Qr[NB][4], Qs[NB][4];
 #pragma unroll
-  for (int h = 0; h < GQ; ++h) { m[h] = -INFINITY; l_loc[h] = 0.0f; acc[h] = 0.0f; }
-
-  if (sp < n_splits) {
-    // ---- quantized groups [g0, g1) of this sequence ---------------------------------------------------------
-    const int n_groups = (nq + kGroup - 1) / kGroup;
-    const int g0 = (int)((long long)n_groups * sp / n_splits);
-    const int g1 = (int)((long long)n_groups * (sp + 1) / n_splits);
-    for (int grp = g0; grp < g1; ++grp) {
-      const int valid = min(kGroup, nq - grp * kGroup);
-      const long long gbase = (long long)bh * c.max_groups + grp;
-      const float ks = (float)reinterpret_cast<const half_t*>(c.k_scale)[gbase * kGroup + tid];
-      const float kz = (float)reinterpret_cast<const half_t*>(c.k_zero)[gbase * kGroup + tid];
-      float bias[GQ];
+  for (int nb = 0; nb < NB; ++nb) {
+    const int h = nb * 4 + hrow;
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + 8 * quad);
+    const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        sQs[h][tid] = sQ[h][tid] * ks;
-        bias[h] = sQ[h][tid] * kz;
-      }
-      sVs[tid] = (float)reinterpret_cast<const half_t*>(c.v_scale)[gbase * kGroup + tid];
-      sVz[tid] = (float)reinterpret_cast<const half_t*>(c.v_zero)[gbase * kGroup + tid];
-      block_reduce<GQ, false>(bias, sRed, tid);  // syncs: sQs, sVs, sVz visible afterwards
-
-      // scores of token tid: x[h] = sum_c (alpha q s)[h][c] * code[tid][c] + sum_c (alpha q z)[h][c]
-      float x[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) x[h] = bias[h];
-      {
-        const uint32_t* tile = c.k_codes + gbase * kTileWords;
-        const int hf = tid >> 6, l = tid & 63;
-        const uint4 w0 = *reinterpret_cast<const uint4*>(tile + ((hf * 2 + 0) * 64 + l) * 4);
-        const uint4 w1 = *reinterpret_cast<const uint4*>(tile + ((hf * 2 + 1) * 64 + l) * 4);
-        const uint32_t words[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-#pragma unroll
-        for (int qw = 0; qw < 8; ++qw) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              const int ch = 8 * (4 * (qw % 4) + j / 2) + 4 * (qw / 4) + 2 * (j % 2) + e;
-              const float code = (float)((words[qw] >> (2 * j + 16 * e)) & 3u);
-#pragma unroll
-              for (int h = 0; h < GQ; ++h) x[h] = fmaf(sQs[h][ch], code, x[h]);
-            }
-          }
-        }
-      }
-      float bm[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        if (tid >= valid) x[h] = -INFINITY;
-        bm[h] = x[h];
-      }
-      block_reduce<GQ, true>(bm, sRed, tid);
-      float scale[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        const float mn = fmaxf(m[h], bm[h]);
-        scale[h] = exp2f(m[h] - mn);  // 0 on the first group (m = -inf)
-        m[h] = mn;
-        const float p = exp2f(x[h] - mn);
-        l_loc[h] = l_loc[h] * scale[h] + p;
-        sP[h][tid] = p;
-      }
-      __syncthreads();
-      // channel tid: acc[h] += sum_t p[h][t] * (s_v[t] * code[t][tid] + z_v[t])
-      {
-        const uint32_t* tile = c.v_codes + gbase * kTileWords;
-        const int chh = tid >> 6, l = tid & 63;
-        float a[GQ];
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) a[h] = 0.0f;
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          const uint4 wv = *reinterpret_cast<const uint4*>(tile + ((hf * 2 + chh) * 64 + l) * 4);
-          const uint32_t words[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-#pragma unroll
-              for (int e = 0; e < 2; ++e) {
-                const int t = 64 * hf + 4 * (4 * w + j / 2) + 2 * (j % 2) + e;
-                const float code = (float)((words[w] >> (2 * j + 16 * e)) & 3u);
-                const float vh = fmaf(sVs[t], code, sVz[t]);
-#pragma unroll
-                for (int h = 0; h < GQ; ++h) a[h] = fmaf(sP[h][t], vh, a[h]);
-              }
-            }
-          }
-        }
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) acc[h] = acc[h] * scale[h] + a[h];
-      }
-      __syncthreads();
-    }
-  } else if (nr > 0) {
-    // ---- the fp16 window: raw keys, rotated values ----------------------------------------------------------
-    const half_t* kw = reinterpret_cast<const half_t*>(c.k_res) + (long long)bh * c.R * kHeadDim;
-    const half_t* vw = reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim;
-    float x[GQ];
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) x[h] = 0.0f;
-    if (tid < nr) {
-      const half_t* row = kw + (long long)tid * kHeadDim;
-      for (int ch = 0; ch < kHeadDim; ch += 8) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(row + ch);
-        const half_t* hv = reinterpret_cast<const half_t*>(&raw);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float kv = (float)hv[i];
-#pragma unroll
-          for (int h = 0; h < GQ; ++h) x[h] = fmaf(sQ[h][ch + i], kv, x[h]);
-        }
-      }
-    }
-    float bm[GQ];
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-      if (tid >= nr) x[h] = -INFINITY;
-      bm[h] = x[h];
-    }
-    block_reduce<GQ, true>(bm, sRed, tid);
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-      m[h] = bm[h];
-      const float p = exp2f(x[h] - m[h]);
-      l_loc[h] = p;
-      sP[h][tid] = p;
-    }
-    __syncthreads();
-    for (int t = 0; t < nr; ++t) {
-      const float vv = (float)vw[(long long)t * kHeadDim + tid];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) acc[h] = fmaf(sP[h][t], vv, acc[h]);
+    for (int i = 0; i < 4; ++i) {
+      Qr[nb][i] = r[i];
+      const half_t gn = (half_t)((i & 1) ? gain1 : gain0);
+      const half2_t g2 = {gn, gn};
+      Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
     }
   }
 
-  block_reduce<GQ, false>(l_loc, sRed, tid);
+  WaveState<NB> st;
 #pragma unroll
-  for (int h = 0; h < GQ; ++h) {
-    float* dst = part + (((long long)b * c.H_q + g * GQ + h) * items_per_bh + sp) * kPartStride;
-    if (tid == 0) { dst[0] = m[h]; dst[1] = l_loc[h]; }
-    dst[4 + tid] = acc[h];
+  for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) { st.m[nb][h] = -INFINITY; st.l[nb][h] = 0.f; st.pz[nb][h] = 0.f; }
+    st.acc[nb][0] = float4_t{0.f, 0.f, 0.f, 0.f};
+    st.acc[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // this wave's groups, the next one always in flight in the other register set
+  const long long tile0 = (long long)bh * c.max_groups;
+  int grp = g0 + wave;
+  GroupRegs r0, r1;
+  if (grp < g1) load_group(r0, c, tile0 + grp, lane);
+  while (grp < g1) {
+    if (grp + kWaves < g1) load_group(r1, c, tile0 + grp + kWaves, lane);
+    process_group<NB>(r0, min(kGroup, nq - grp * kGroup), Qs, Qr, gain0, gain1, vgain, perm_sel, lane, st);
+    grp += kWaves;
+    if (grp >= g1) break;
+    if (grp + kWaves < g1) load_group(r0, c, tile0 + grp + kWaves, lane);
+    process_group<NB>(r1, min(kGroup, nq - grp * kGroup), Qs, Qr, gain0, gain1, vgain, perm_sel, lane, st);
+    grp += kWaves;
+  }
+
+  // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const float l = wave_allsum(st.l[nb][h]);
+      const float pz = wave_allsum(st.pz[nb][h]);
+      if (lane == 0) { sM[wave][nb * 4 + h] = st.m[nb][h]; sL[wave][nb * 4 + h] = l; }
+      sAcc[wave][nb * 4 + h][lane] = st.acc[nb][0][h] * kRawScale + pz;
+      sAcc[wave][nb * 4 + h][64 + lane] = st.acc[nb][1][h] * kRawScale + pz;
+    }
+  __syncthreads();
+  for (int idx = tid; idx < gq * kHeadDim; idx += kThreads) {
+    const int h = idx >> 7, ch = idx & 127;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sM[w][h]);
+    float a = 0.f, l = 0.f;
+    if (M != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float f = exp2f(sM[w][h] - M);
+        a = fmaf(f, sAcc[w][h][ch], a);
+        l = fmaf(f, sL[w][h], l);
+      }
+    }
+    float* dst = part + (((long long)b * c.H_q + g * gq + h) * items_per_bh + sp) * kPartStride;
+    if (ch == 0) { dst[0] = M; dst[1] = l; }
+    dst[4 + ch] = a;
   }
 }
 
-template <int GQ>
-__global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, const half_t* __restrict__ q,
-                                                                 const float* __restrict__ part, int n_splits,
-                                                                 half_t* __restrict__ out) {
-  __shared__ float sQ[GQ][kHeadDim];
-  __shared__ float sPhi[GQ][kRank];
-  __shared__ float sRed[GQ * 2];
-  __shared__ float sY[kHeadDim];
+// ---- work item 2: the fp16 window of one (sequence, kv head): raw keys, rotated values ---------------------------
+// thread = (token or channel, head half): heads 4*hh .. 4*hh+3
+
+__device__ __forceinline__ void window_item(const kvlinc_cache& c, const half_t* __restrict__ q, float* __restrict__ part,
+                                            int n_splits, int gq, int bh, float* lds) {
+  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);            // [8][128] alpha * q
+  float (*sP)[kGroup] = reinterpret_cast<float (*)[kGroup]>(lds + 8 * kHeadDim);  // [8][128]
+  float* sRed = lds + 16 * kHeadDim;                                             // [8][2]
 
   const int tid = threadIdx.x;
-  const int bh = blockIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int tok = tid & 127, hh = tid >> 7;
   const int b = bh / c.H_kv;
   const int g = bh % c.H_kv;
+  const int nr = c.n_res[b];
   const int items_per_bh = n_splits + 1;
-  const bool correct = c.S != nullptr;
 
-  // ---- merge the blocks (Alg. 1: w = exp(m - max m)) ---------------------------------------------------------
-  float M[GQ], num[GQ], den[GQ];
-#pragma unroll
-  for (int h = 0; h < GQ; ++h) {
-    const float* p0 = part + ((long long)b * c.H_q + g * GQ + h) * items_per_bh * kPartStride;
-    float mm = -INFINITY;
-    for (int j = 0; j < items_per_bh; ++j) mm = fmaxf(mm, p0[(long long)j * kPartStride]);
-    float n_acc = 0.0f, d_acc = 0.0f;
-    for (int j = 0; j < items_per_bh; ++j) {
-      const float mj = p0[(long long)j * kPartStride];
-      if (mj == -INFINITY) continue;
-      const float w = exp2f(mj - mm);
-      n_acc = fmaf(w, p0[(long long)j * kPartStride + 4 + tid], n_acc);
-      d_acc = fmaf(w, p0[(long long)j * kPartStride + 1], d_acc);
-    }
-    M[h] = mm; num[h] = n_acc; den[h] = d_acc;
-  }
+  for (int i = tid; i < gq * kHeadDim; i += kThreads)
+    sQ[i >> 7][i & 127] = kAlpha * (float)q[((long long)b * c.H_q + g * gq) * kHeadDim + i];
+  __syncthreads();
 
-  // ---- correction: phi_q(q) = [softmax(q W_1), softmax(q W_2)], C_n = phi_q S, C_d = phi_q P (Eq. 5, Eq. 6) ----
-  float Cn[GQ], Cd[GQ];
+  const half_t* kw = reinterpret_cast<const half_t*>(c.k_res) + (long long)bh * c.R * kHeadDim;
+  const half_t* vw = reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim;
+  float x[4] = {0.f, 0.f, 0.f, 0.f};
+  if (tok < nr && 4 * hh < gq) {
+    const half_t* row = kw + (long long)tok * kHeadDim;
+#pragma unroll 4
+    for (int ch = 0; ch < kHeadDim; ch += 8) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(row + ch);
+      const half_t* hv = reinterpret_cast<const half_t*>(&raw);
 #pragma unroll
-  for (int h = 0; h < GQ; ++h) { Cn[h] = 0.0f; Cd[h] = 0.0f; }
-  if (correct && c.n_quant[b] > 0) {
+      for (int i = 0; i < 8; ++i) {
+        const float kv = (float)hv[i];
 #pragma unroll
-    for (int h = 0; h < GQ; ++h) sQ[h][tid] = (float)q[((long long)b * c.H_q + g * GQ + h) * kHeadDim + tid];
-    __syncthreads();
-#pragma unroll
-    for (int hs = 0; hs < 2; ++hs) {
-      float logit[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        const half_t* W = reinterpret_cast<const half_t*>(c.Wq) +
-                          ((long long)(g * GQ + h) * 2 + hs) * kHeadDim * (kRank / 2) + tid;
-        float a = 0.0f;
-        for (int ch = 0; ch < kHeadDim; ++ch) a = fmaf(sQ[h][ch], (float)W[ch * (kRank / 2)], a);
-        logit[h] = a;
-      }
-      float mx[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) mx[h] = logit[h];
-      block_reduce<GQ, true>(mx, sRed, tid);
-      float e[GQ], s[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) { e[h] = __expf(logit[h] - mx[h]); s[h] = e[h]; }
-      block_reduce<GQ, false>(s, sRed, tid);
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) sPhi[h][hs * 128 + tid] = e[h] / s[h];
-    }
-    __syncthreads();
-    const float* S = c.S + (long long)bh * kRank * kHeadDim + tid;
-    const float* P = c.P + (long long)bh * kRank;
-    for (int f = 0; f < kRank; ++f) {
-      const float sv = S[(long long)f * kHeadDim];
-      const float pv = P[f];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        Cn[h] = fmaf(sPhi[h][f], sv, Cn[h]);
-        Cd[h] = fmaf(sPhi[h][f], pv, Cd[h]);
+        for (int j = 0; j < 4; ++j) x[j] = fmaf(sQ[4 * hh + j][ch + i], kv, x[j]);
       }
     }
   }
-
-  // ---- (num + 2^-M C_n) / (den + 2^-M C_d), then y = y_rot H^T, per query head -----------------------------------
-  for (int h = 0; h < GQ; ++h) {
-    float y = 0.0f;
-    if (M[h] != -INFINITY) {
-      const float Ms = fmaxf(M[h], 0.0f);
-      const float a = exp2f(M[h] - Ms), bf = exp2f(-Ms);
-      y = (a * num[h] + bf * Cn[h]) / (a * den[h] + bf * Cd[h]);
+  float m[4], l[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (tok >= nr) x[j] = -INFINITY;
+    const float r = wave_allmax(x[j]);
+    if (lane == 0) sRed[(4 * hh + j) * 2 + (wave & 1)] = r;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    m[j] = fmaxf(sRed[(4 * hh + j) * 2], sRed[(4 * hh + j) * 2 + 1]);
+    const float p = (nr > 0) ? exp2f(x[j] - m[j]) : 0.f;
+    sP[4 * hh + j][tok] = p;
+    l[j] = wave_allsum(p);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (lane == 0) sRed[(4 * hh + j) * 2 + (wave & 1)] = l[j];
+  __syncthreads();
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (4 * hh < gq) {
+    for (int t = 0; t < nr; ++t) {
+      const float vv = (float)vw[(long long)t * kHeadDim + tok];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = fmaf(sP[4 * hh + j][t], vv, acc[j]);
     }
-    __syncthreads();
-    sY[tid] = y;
-    for (int hh = 1; hh < kHeadDim; hh <<= 1) {
-      __syncthreads();
-      const float mine = sY[tid], other = sY[tid ^ hh];
-      __syncthreads();
-      sY[tid] = (tid & hh) ? (other - mine) : (mine + other);
-    }
-    __syncthreads();
-    out[((long long)b * c.H_q + g * GQ + h) * kHeadDim + tid] = (half_t)(sY[tid] * 0.08838834764831845f);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int h = 4 * hh + j;
+    if (h >= gq) continue;
+    float* dst = part + (((long long)b * c.H_q + g * gq + h) * items_per_bh + n_splits) * kPartStride;
+    if (tok == 0) { dst[0] = nr > 0 ? m[j] : -INFINITY; dst[1] = sRed[h * 2] + sRed[h * 2 + 1]; }
+    dst[4 + tok] = acc[j];
   }
 }
 
-template <int GQ>
-int launch_decode_gq(const kvlinc_cache& c, const half_t* q, half_t* out, float* ws, int n_splits,
-                     hipStream_t stream) {
-  const int bh = c.B * c.H_kv;
-  hipLaunchKernelGGL(decode_split_kernel<GQ>, dim3(bh * (n_splits + 1)), dim3(kThreads), 0, stream, c, q, ws,
-                     n_splits);
-  if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
-  hipLaunchKernelGGL(decode_merge_kernel<GQ>, dim3(bh), dim3(kThreads), 0, stream, c, q, ws, n_splits, out);
-  if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
-  return KVLINC_OK;
+// ---- work item 3: correction terms of one (sequence, kv head): phi_q(q), C_n = phi_q S, C_d = phi_q P -------------
+// (Sec. 3.3: computed before the merge; Eq. 6 for phi.)  Output per query head: {C_d, -, -, -, C_n[128]}.
+
+__device__ __forceinline__ void correction_item(const kvlinc_cache& c, const half_t* __restrict__ q,
+                                                float* __restrict__ corr, int gq, int bh, float* lds) {
+  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);          // [8][128] raw q
+  float (*sPhi)[kRank] = reinterpret_cast<float (*)[kRank]>(lds + 8 * kHeadDim);  // [8][256]
+  float* sRed = lds + 8 * kHeadDim + 8 * kRank;                                // [4 waves][4][128]
+  float* sSmall = sRed + kWaves * 4 * kHeadDim;                                // [32]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int b = bh / c.H_kv;
+  const int g = bh % c.H_kv;
+  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kPartStride;
+  if (c.n_quant[b] == 0) {  // states are empty: no correction (and S, P need not be read)
+    for (int i = tid; i < gq * kPartStride; i += kThreads) out0[i] = 0.f;
+    return;
+  }
+  for (int i = tid; i < gq * kHeadDim; i += kThreads)
+    sQ[i >> 7][i & 127] = (float)q[((long long)b * c.H_q + g * gq) * kHeadDim + i];
+  __syncthreads();
+
+  // phase 1: logits[h][half][f] = sum_c q[h][c] W[h][half][c][f]; thread = (row group of 8 channels, chunk of 8 features)
+  {
+    const int chunk = tid & 15, rowgrp = tid >> 4;
+    for (int h = 0; h < gq; ++h) {
+      float acc[2][8];
+#pragma unroll
+      for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[hs][i] = 0.f;
+      const half_t* W = reinterpret_cast<const half_t*>(c.Wq) + (long long)(g * gq + h) * 2 * kHeadDim * (kRank / 2);
+#pragma unroll
+      for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+        for (int rb = 0; rb < 8; ++rb) {
+          const int ch = rowgrp * 8 + rb;
+          const uint4 raw = *reinterpret_cast<const uint4*>(W + ((long long)hs * kHeadDim + ch) * (kRank / 2) + 8 * chunk);
+          const half_t* hv = reinterpret_cast<const half_t*>(&raw);
+          const float qv = sQ[h][ch];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[hs][i] = fmaf(qv, (float)hv[i], acc[hs][i]);
+        }
+#pragma unroll
+      for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float v = acc[hs][i];
+          v += __shfl_xor(v, 16, 64);
+          v += __shfl_xor(v, 32, 64);
+          if (lane < 16) sRed[(wave * 2 + hs) * kHeadDim + 8 * chunk + i] = v;
+        }
+      __syncthreads();
+      const int hs = tid >> 7, f = tid & 127;
+      float logit = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) logit += sRed[(w * 2 + hs) * kHeadDim + f];
+      const float wm = wave_allmax(logit);
+      if (lane == 0) sSmall[wave] = wm;
+      __syncthreads();
+      const float mx = fmaxf(sSmall[2 * hs], sSmall[2 * hs + 1]);
+      const float e = __expf(logit - mx);
+      const float ws = wave_allsum(e);
+      if (lane == 0) sSmall[8 + wave] = ws;
+      __syncthreads();
+      sPhi[h][tid] = e / (sSmall[8 + 2 * hs] + sSmall[8 + 2 * hs + 1]);
+    }
+  }
+  __syncthreads();
+
+  // phase 2: C_n[h][c] = sum_f phi[h][f] S[f][c]; thread = (row group of 32 features, chunk of 4 channels); S read once
+  {
+    const int chunk = tid & 31, rowgrp = tid >> 5;
+    const float* S = c.S + (long long)bh * kRank * kHeadDim;
+    float acc[kMaxGq][4];
+#pragma unroll
+    for (int h = 0; h < kMaxGq; ++h)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < 32; ++i) {
+      const int f = rowgrp * 32 + i;
+      const float4 s4 = *reinterpret_cast<const float4*>(S + (long long)f * kHeadDim + 4 * chunk);
+#pragma unroll
+      for (int h = 0; h < kMaxGq; ++h) {
+        if (h < gq) {
+          const float ph = sPhi[h][f];
+          acc[h][0] = fmaf(ph, s4.x, acc[h][0]);
+          acc[h][1] = fmaf(ph, s4.y, acc[h][1]);
+          acc[h][2] = fmaf(ph, s4.z, acc[h][2]);
+          acc[h][3] = fmaf(ph, s4.w, acc[h][3]);
+        }
+      }
+    }
+    // C_d[h] = sum_f phi[h][f] P[f]
+    const float pf = c.P[(long long)bh * kRank + tid];
+    for (int h = 0; h < gq; ++h) {
+      const float v = wave_allsum(sPhi[h][tid] * pf);
+      if (lane == 0) sSmall[16 + h * kWaves + wave] = v;
+    }
+    for (int hb = 0; hb < gq; hb += 4) {
+      __syncthreads();
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float v = acc[0][0];
+#pragma unroll
+          for (int h = 0; h < kMaxGq; ++h)
+            if (h == hb + hh) v = acc[h][j];
+          v += __shfl_xor(v, 32, 64);
+          if (lane < 32) sRed[(wave * 4 + hh) * kHeadDim + 4 * chunk + j] = v;
+        }
+      __syncthreads();
+      for (int idx = tid; idx < 4 * kHeadDim; idx += kThreads) {
+        const int hh = idx >> 7, ch = idx & 127, h = hb + hh;
+        if (h >= gq) continue;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += sRed[(w * 4 + hh) * kHeadDim + ch];
+        out0[(long long)h * kPartStride + 4 + ch] = v;
+        if (ch == 0) {
+          float cd = 0.f;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) cd += sSmall[16 + h * kWaves + w];
+          out0[(long long)h * kPartStride] = cd;
+        }
+      }
+    }
+  }
+}
+
+constexpr int kLdsFloats = 8 * kHeadDim + 8 * kRank + kWaves * 4 * kHeadDim + 64;  // the correction item's need (largest)
+
+// blockIdx: [0, BH) correction items (only with adapters), then BH window items, then BH * n_splits group items.
+template <int NB>
+__global__ __launch_bounds__(kThreads) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+                                                                float* __restrict__ part, float* __restrict__ corr,
+                                                                int n_splits, int gq) {
+  __shared__ __align__(16) float lds[kLdsFloats];
+  static_assert(kLdsFloats >= 2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim, "group item LDS");
+  const int BH = c.B * c.H_kv;
+  int item = blockIdx.x;
+  if (corr != nullptr) {
+    if (item < BH) { correction_item(c, q, corr, gq, item, lds); return; }
+    item -= BH;
+  }
+  if (item < BH) { window_item(c, q, part, n_splits, gq, item, lds); return; }
+  item -= BH;
+  group_item<NB>(c, q, part, n_splits, gq, item / n_splits, item % n_splits, lds);
+}
+
+// ---- launch 2: merge the blocks, add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5; Sec. 3.1) ---------------
+// one wave per (sequence, query head); lane l owns channels 2l and 2l+1
+
+__global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, const float* __restrict__ part,
+                                                                 const float* __restrict__ corr, int n_splits,
+                                                                 half_t* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kWaves + (threadIdx.x >> 6);  // b * H_q + h
+  if (row >= c.B * c.H_q) return;
+  const int items = n_splits + 1;
+  const float* p0 = part + (long long)row * items * kPartStride;
+  float M = -INFINITY;
+  for (int j = lane; j < items; j += 64) M = fmaxf(M, p0[(long long)j * kPartStride]);
+  M = wave_allmax(M);
+  float n0 = 0.f, n1 = 0.f, den = 0.f;
+  for (int j = 0; j < items; ++j) {
+    const float mj = p0[(long long)j * kPartStride];
+    if (mj == -INFINITY) continue;
+    const float w = exp2f(mj - M);
+    const float2 a = *reinterpret_cast<const float2*>(p0 + (long long)j * kPartStride + 4 + 2 * lane);
+    n0 = fmaf(w, a.x, n0);
+    n1 = fmaf(w, a.y, n1);
+    den = fmaf(w, p0[(long long)j * kPartStride + 1], den);
+  }
+  float y0 = 0.f, y1 = 0.f;
+  if (M != -INFINITY) {
+    float cn0 = 0.f, cn1 = 0.f, cd = 0.f;
+    if (corr != nullptr) {
+      const float* cr = corr + (long long)row * kPartStride;
+      const float2 cn = *reinterpret_cast<const float2*>(cr + 4 + 2 * lane);
+      cn0 = cn.x; cn1 = cn.y; cd = cr[0];
+    }
+    // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum)
+    const float Ms = fmaxf(M, 0.f);
+    const float fa = exp2f(M - Ms), fb = exp2f(-Ms);
+    const float d = fa * den + fb * cd;
+    y0 = (fa * n0 + fb * cn0) / d;
+    y1 = (fa * n1 + fb * cn1) / d;
+  }
+  // y = y_rot H^T: butterflies over the 128 channels, two per lane
+  {
+    const float a = y0 + y1, bb = y0 - y1;
+    y0 = a; y1 = bb;
+#pragma unroll
+    for (int mk = 1; mk < 64; mk <<= 1) {
+      const float o0 = __shfl_xor(y0, mk, 64), o1 = __shfl_xor(y1, mk, 64);
+      const bool upper = (lane & mk) != 0;
+      y0 = upper ? (o0 - y0) : (y0 + o0);
+      y1 = upper ? (o1 - y1) : (y1 + o1);
+    }
+  }
+  const half2_t r = {(half_t)(y0 * 0.08838834764831845f), (half_t)(y1 * 0.08838834764831845f)};
+  *reinterpret_cast<uint32_t*>(out + (long long)row * kHeadDim + 2 * lane) = as_u32(r);
 }
 
 }  // namespace
 
+// Blocks of groups per (sequence, kv head): every wave of a workgroup should own about kGroupsPerWave groups.
 int decode_splits(const kvlinc_cache& c, int max_context) {
-  long long cap = (long long)c.max_groups * kGroup + c.R;
-  long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
+  constexpr int kGroupsPerWave = 4;
+  const long long cap = (long long)c.max_groups * kGroup + c.R;
+  const long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
   long long groups = (ctx + kGroup - 1) / kGroup;
   if (groups < 1) groups = 1;
-  const long long bh = (long long)c.B * c.H_kv;
-  long long target = (4096 + bh - 1) / bh;  // aim at ~16 workgroups per CU
-  if (target < 1) target = 1;
-  long long s = target < groups ? target : groups;
-  if (s > 256) s = 256;
+  long long s = (groups + kWaves * kGroupsPerWave - 1) / (kWaves * kGroupsPerWave);
+  if (const char* e = getenv("KVLINC_SPLITS")) s = atoi(e);
+  if (s < 1) s = 1;
+  if (s > 1024) s = 1024;
   return (int)s;
+}
+
+size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
+  return (size_t)c.B * c.H_q * (n_splits + 2) * kPartStride;  // n_splits + window partials, then one correction row
 }
 
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
                   hipStream_t stream) {
+  const int gq = c.H_q / c.H_kv;
+  const int BH = c.B * c.H_kv;
   const half_t* qq = reinterpret_cast<const half_t*>(q);
-  half_t* oo = reinterpret_cast<half_t*>(out);
-  switch (c.H_q / c.H_kv) {
-    case 1: return launch_decode_gq<1>(c, qq, oo, workspace, n_splits, stream);
-    case 2: return launch_decode_gq<2>(c, qq, oo, workspace, n_splits, stream);
-    case 3: return launch_decode_gq<3>(c, qq, oo, workspace, n_splits, stream);
-    case 4: return launch_decode_gq<4>(c, qq, oo, workspace, n_splits, stream);
-    case 5: return launch_decode_gq<5>(c, qq, oo, workspace, n_splits, stream);
-    case 6: return launch_decode_gq<6>(c, qq, oo, workspace, n_splits, stream);
-    case 7: return launch_decode_gq<7>(c, qq, oo, workspace, n_splits, stream);
-    case 8: return launch_decode_gq<8>(c, qq, oo, workspace, n_splits, stream);
-    default: return KVLINC_EINVAL;
-  }
+  float* part = workspace;
+  float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * (n_splits + 1) * kPartStride : nullptr;
+  const dim3 grid(BH * (n_splits + 1 + (corr != nullptr ? 1 : 0))), block(kThreads);
+  if (gq <= 4) hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq);
+  else hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq);
+  if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((c.B * c.H_q + kWaves - 1) / kWaves), block, 0, stream, c, part, corr,
+                     n_splits, reinterpret_cast<half_t*>(out));
+  return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
 
 }  // namespace kvlinc

@@ -50,6 +50,7 @@ int decode_splits(const kvlinc_cache& c, int max_context);
 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream);
+size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits);
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
                   hipStream_t stream);
 

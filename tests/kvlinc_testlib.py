@@ -91,6 +91,7 @@ def check_outputs(got, want):
     max_abs = np.abs(g - w).max()
     rel_l2 = np.linalg.norm(g - w) / np.linalg.norm(w)
     worst_row = max(np.linalg.norm(g[i] - w[i]) / np.linalg.norm(w[i]) for i in range(len(w)))
+    print("  [parity] rows %d max_abs %.3e rel_l2 %.3e worst_row_rel_l2 %.3e" % (len(w), max_abs, rel_l2, worst_row))
     assert max_abs <= OUT_MAX_ABS, ("max abs", max_abs)
     assert rel_l2 <= OUT_REL_L2, ("rel l2", rel_l2, "worst row", worst_row)
     return max_abs, rel_l2, worst_row

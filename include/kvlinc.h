@@ -23,17 +23,24 @@
  *   - Query head h reads KV head h / (H_q / H_kv).  The softmax scale is 1/sqrt(d) (Eq. 3).
  *
  * Cache layout (per sequence b, KV head g; "group" = 128 consecutive tokens from token 0):
- *   k_codes, v_codes  [B, H_kv, max_groups, 1024] uint32: one 4 KB tile per 128x128 block of 2-bit
- *                     codes.  Logical content: code(token, channel) in {0..3}.  Word format: a word holds
- *                     8 pairs j = 0..7, pair j = {bits 2j+1:2j, bits 16+2j+1:16+2j}.
+ *   groups            [B, H_kv, max_groups, 2304] uint32: one 9216-byte record per group, everything a decode step
+ *                     reads of that group, contiguous:
+ *                       words    0..1023  key tile,   2-bit codes of the 128x128 block
+ *                       words 1024..2047  value tile, 2-bit codes of the 128x128 block of ROTATED values
+ *                       words 2048..2111  key scale s of Eq. 1, fp16 per channel 0..127 (channel 2i in the low half)
+ *                       words 2112..2175  key zero-point z, fp16 per channel
+ *                       words 2176..2303  value (s, z) of token t in word 2176 + t: s in the low half, z in the high
+ *                     Logical content of a tile: code(token, channel) in {0..3}.  Word format: a word holds 8 pairs
+ *                     j = 0..7, pair j = {bits 2j+1:2j, bits 16+2j+1:16+2j}.
  *                     Key tile:   token t = 64*hf + l owns words q = 0..7 at ((hf*2 + q/4)*64 + l)*4 + q%4;
  *                                 word q, pair j, element e holds channel 8*(4*(q%4) + j/2) + 4*(q/4) + 2*(j%2) + e.
  *                     Value tile: channel c = 64*ch + l owns, per token half hf, words w = 0..3 at
  *                                 ((hf*2 + ch)*64 + l)*4 + w; word w, pair j, element e holds token
  *                                 64*hf + 4*(4*w + j/2) + 2*(j%2) + e.
- *   k_scale, k_zero   [B, H_kv, max_groups, 128] fp16: s and z of Eq. 1 per (group, channel).
- *   v_scale, v_zero   [B, H_kv, max_groups, 128] fp16: s and z of Eq. 1 per token of the group.
- *   k_res, v_res      [B, H_kv, R, 128] fp16: the window; raw keys, ROTATED values, slot r = r-th oldest.
+ *                     A partial last group (bulk build only) has zero codes and zero (s, z) for its missing tokens.
+ *   k_res             [B, H_kv, R, 128] fp16: the window's raw keys, slot r = r-th oldest window token.
+ *   v_res             [B, H_kv, R/4, 128, 4] fp16: the window's ROTATED values, 4 consecutive slots per channel:
+ *                     slot r, channel c at [r/4][c][r%4].
  *   n_quant, n_res    [B] int32: quantized tokens / window tokens of each sequence (context = sum).
  *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.
  *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
@@ -75,16 +82,11 @@ typedef struct kvlinc_cache {
   int32_t B, H_q, H_kv;
   int32_t d;    /* head dimension, must be 128 */
   int32_t G;    /* quantization group size, must be 128 */
-  int32_t R;    /* window capacity in tokens, 1..128; one-token appends need R == G */
+  int32_t R;    /* window capacity in tokens, a multiple of 4 in 4..128; one-token appends need R == G */
   int32_t D;    /* rank of the correction feature maps, must be 256 */
   int32_t bits; /* must be 2 */
   int64_t max_groups; /* tile capacity per (sequence, KV head) */
-  uint32_t* k_codes;
-  uint32_t* v_codes;
-  kvlinc_half* k_scale;
-  kvlinc_half* k_zero;
-  kvlinc_half* v_scale;
-  kvlinc_half* v_zero;
+  uint32_t* groups;
   kvlinc_half* k_res;
   kvlinc_half* v_res;
   int32_t* n_quant;

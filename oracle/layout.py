@@ -1,4 +1,5 @@
-"""Physical order of the packed 2-bit codes: one 4 KB tile (1024 32-bit words) per 128x128 block.
+"""Physical order of the quantized cache: one 9216-byte record per group of 128 tokens, holding two 4 KB tiles of
+packed 2-bit codes (1024 32-bit words per 128x128 block) and the group's scales and zero-points.
 
 The paper fixes only that 16 two-bit codes share a 32-bit word (Sec. 3.3; K_I in R^{N/16 x d},
 V_I in R^{N x d/16} in Alg. 1).  The logical content -- one code per (token, channel) -- is the
@@ -20,10 +21,21 @@ Value tile, block of 128 tokens x 128 channels, channel c = 64*ch + l (ch in {0,
     word w, pair j, element e holds token
         t = 64*hf + 4*(4*w + j//2) + 2*(j%2) + e
     (so a lane that loads 16 contiguous bytes gets 64 tokens of its own channel).
+
+Group record, 2304 words (everything one decode step needs of a group, contiguous in memory):
+    words    0 .. 1023   key tile
+    words 1024 .. 2047   value tile
+    words 2048 .. 2111   key scale, fp16 per channel 0..127 (two per word, low half first)
+    words 2112 .. 2175   key zero-point, fp16 per channel
+    words 2176 .. 2303   value (scale, zero-point) of token t in word 2176 + t: scale in the low half, zero in the high
+
+Window of fp16 values: rotated values are stored 4 consecutive tokens per channel, v_res[slot // 4][channel][slot % 4],
+so that a lane owning a channel reads 4 tokens with one 8-byte load; keys stay row-major k_res[slot][channel].
 """
 import numpy as np
 
 TILE_WORDS = 1024
+RECORD_WORDS = 2304
 
 
 def _k_index_maps():
@@ -95,3 +107,57 @@ def pack_v_tile(codes):
 
 def unpack_v_tile(tile):
     return _unpack(tile, _V_WORD, _V_SHIFT)
+
+
+def _halves_to_words(h16):
+    """fp16 array [..., 2n] -> uint32 [..., n], element 2i in the low half of word i."""
+    u = np.ascontiguousarray(h16, dtype=np.float16).view(np.uint16).astype(np.uint32)
+    return u[..., 0::2] | (u[..., 1::2] << np.uint32(16))
+
+
+def pack_records(k_codes, v_codes, k_scale, k_zero, v_scale, v_zero):
+    """Per-group arrays ([n_groups, 128, 128] codes, [n_groups, 128] fp16 parameters) -> uint32 [n_groups, 2304]."""
+    n = np.asarray(k_codes).shape[0]
+    rec = np.zeros((n, RECORD_WORDS), dtype=np.uint32)
+    if n == 0:
+        return rec
+    rec[:, 0:1024] = pack_k_tile(k_codes)
+    rec[:, 1024:2048] = pack_v_tile(v_codes)
+    rec[:, 2048:2112] = _halves_to_words(k_scale)
+    rec[:, 2112:2176] = _halves_to_words(k_zero)
+    vs = np.ascontiguousarray(v_scale, dtype=np.float16).view(np.uint16).astype(np.uint32)
+    vz = np.ascontiguousarray(v_zero, dtype=np.float16).view(np.uint16).astype(np.uint32)
+    rec[:, 2176:2304] = vs | (vz << np.uint32(16))
+    return rec
+
+
+def unpack_records(rec):
+    """uint32 [n_groups, 2304] -> dict of the logical per-group arrays (inverse of pack_records)."""
+    rec = np.asarray(rec, dtype=np.uint32)
+    def halves(words):
+        lo = (words & np.uint32(0xFFFF)).astype(np.uint16)
+        hi = (words >> np.uint32(16)).astype(np.uint16)
+        return np.stack([lo, hi], axis=-1).reshape(words.shape[:-1] + (-1,)).view(np.float16)
+    sz = rec[:, 2176:2304]
+    return {
+        "k_codes": unpack_k_tile(rec[:, 0:1024]), "v_codes": unpack_v_tile(rec[:, 1024:2048]),
+        "k_scale": halves(rec[:, 2048:2112]), "k_zero": halves(rec[:, 2112:2176]),
+        "v_scale": (sz & np.uint32(0xFFFF)).astype(np.uint16).view(np.float16),
+        "v_zero": (sz >> np.uint32(16)).astype(np.uint16).view(np.float16),
+    }
+
+
+def pack_value_window(v_rows, R):
+    """Rotated fp16 values of the window, [n_res, 128] oldest first -> [R // 4, 128, 4] (unused slots zero)."""
+    v_rows = np.asarray(v_rows, dtype=np.float16)
+    assert R % 4 == 0 and v_rows.shape[0] <= R
+    full = np.zeros((R, 128), dtype=np.float16)
+    full[:v_rows.shape[0]] = v_rows
+    return np.ascontiguousarray(full.reshape(R // 4, 4, 128).transpose(0, 2, 1))
+
+
+def unpack_value_window(v_tiled, n_res):
+    """[R // 4, 128, 4] -> [n_res, 128]."""
+    v_tiled = np.asarray(v_tiled)
+    R = v_tiled.shape[0] * 4
+    return np.ascontiguousarray(v_tiled.transpose(0, 2, 1).reshape(R, 128)[:n_res])

@@ -3,7 +3,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.path.join(HERE, "libkvlinc.so")
+lib_path = os.environ.get("KVLINC_LIB_PATH", os.path.join(HERE, "libkvlinc.so"))
 
 KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP = 0, -1, -2, -3
 KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC = 1, 2, 4
@@ -19,9 +19,7 @@ class CacheStruct(ctypes.Structure):
         ("B", ctypes.c_int32), ("H_q", ctypes.c_int32), ("H_kv", ctypes.c_int32), ("d", ctypes.c_int32),
         ("G", ctypes.c_int32), ("R", ctypes.c_int32), ("D", ctypes.c_int32), ("bits", ctypes.c_int32),
         ("max_groups", ctypes.c_int64),
-        ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
-        ("k_scale", ctypes.c_void_p), ("k_zero", ctypes.c_void_p),
-        ("v_scale", ctypes.c_void_p), ("v_zero", ctypes.c_void_p),
+        ("groups", ctypes.c_void_p),
         ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
         ("n_quant", ctypes.c_void_p), ("n_res", ctypes.c_void_p),
         ("S", ctypes.c_void_p), ("P", ctypes.c_void_p),
@@ -116,14 +114,9 @@ class KVLincCache:
         dev = torch.device(device)
         mg = self.max_groups
         z = lambda *s, dt: torch.zeros(*s, dtype=dt, device=dev)
-        self.k_codes = z(B, H_kv, mg, 1024, dt=torch.int32)
-        self.v_codes = z(B, H_kv, mg, 1024, dt=torch.int32)
-        self.k_scale = z(B, H_kv, mg, 128, dt=torch.float16)
-        self.k_zero = z(B, H_kv, mg, 128, dt=torch.float16)
-        self.v_scale = z(B, H_kv, mg, 128, dt=torch.float16)
-        self.v_zero = z(B, H_kv, mg, 128, dt=torch.float16)
+        self.groups = z(B, H_kv, mg, 2304, dt=torch.int32)
         self.k_res = z(B, H_kv, R, 128, dt=torch.float16)
-        self.v_res = z(B, H_kv, R, 128, dt=torch.float16)
+        self.v_res = z(B, H_kv, R // 4, 128, 4, dt=torch.float16)
         self.n_quant = z(B, dt=torch.int32)
         self.n_res = z(B, dt=torch.int32)
         self.status = z(1, dt=torch.int32)
@@ -137,9 +130,7 @@ class KVLincCache:
             self.S = self.P = None
         self.struct = CacheStruct(
             B=B, H_q=H_q, H_kv=H_kv, d=128, G=128, R=R, D=256, bits=2, max_groups=mg,
-            k_codes=self.k_codes.data_ptr(), v_codes=self.v_codes.data_ptr(),
-            k_scale=self.k_scale.data_ptr(), k_zero=self.k_zero.data_ptr(),
-            v_scale=self.v_scale.data_ptr(), v_zero=self.v_zero.data_ptr(),
+            groups=self.groups.data_ptr(),
             k_res=self.k_res.data_ptr(), v_res=self.v_res.data_ptr(),
             n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),
             S=None if self.S is None else self.S.data_ptr(), P=None if self.P is None else self.P.data_ptr(),
@@ -148,7 +139,7 @@ class KVLincCache:
         self._ws = None
 
     def bytes(self):
-        ts = [self.k_codes, self.v_codes, self.k_scale, self.k_zero, self.v_scale, self.v_zero, self.k_res, self.v_res]
+        ts = [self.groups, self.k_res, self.v_res]
         if self.S is not None:
             ts += [self.S, self.P]
         return sum(t.numel() * t.element_size() for t in ts)
@@ -162,7 +153,7 @@ class KVLincCache:
         import torch
         need = kvlinc_decode_workspace_bytes(self, max_context)
         if self._ws is None or self._ws.numel() * 4 < need:
-            self._ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=self.k_codes.device)
+            self._ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=self.groups.device)
         return self._ws
 
     def decode(self, q, out=None, max_context=0, stream=None):

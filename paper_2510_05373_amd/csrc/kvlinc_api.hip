@@ -28,13 +28,11 @@ int kvlinc_cache_validate(const kvlinc_cache* c) {
   if (c == nullptr) return KVLINC_EINVAL;
   if (c->B < 1 || c->H_q < 1 || c->H_kv < 1) return KVLINC_EINVAL;
   if (c->d != kvlinc::kHeadDim || c->G != kvlinc::kGroup || c->D != kvlinc::kRank || c->bits != 2) return KVLINC_EINVAL;
-  if (c->R < 1 || c->R > kvlinc::kGroup) return KVLINC_EINVAL;
+  if (c->R < 4 || c->R > kvlinc::kGroup || c->R % 4 != 0) return KVLINC_EINVAL;
   if (c->H_q % c->H_kv != 0 || c->H_q / c->H_kv > kvlinc::kMaxGq) return KVLINC_EINVAL;
   if (c->max_groups < 1 || c->max_groups > (1ll << 24)) return KVLINC_EINVAL;
   if ((long long)c->B * c->H_kv > (1ll << 24)) return KVLINC_EINVAL;
-  if (bad_ptr(c->k_codes, 16) || bad_ptr(c->v_codes, 16)) return KVLINC_EINVAL;
-  if (bad_ptr(c->k_scale, 16) || bad_ptr(c->k_zero, 16) || bad_ptr(c->v_scale, 16) || bad_ptr(c->v_zero, 16))
-    return KVLINC_EINVAL;
+  if (bad_ptr(c->groups, 16)) return KVLINC_EINVAL;
   if (bad_ptr(c->k_res, 16) || bad_ptr(c->v_res, 16)) return KVLINC_EINVAL;
   if (bad_ptr(c->n_quant, 4) || bad_ptr(c->n_res, 4) || bad_ptr(c->status, 4)) return KVLINC_EINVAL;
   const int n_corr = (c->S != nullptr) + (c->P != nullptr) + (c->Wq != nullptr) + (c->Wk != nullptr);

@@ -53,6 +53,9 @@ __device__ inline void fwht128_wave(float& x0, float& x1, int lane) {
   const float c = 0x1.6a09e6p-4f;  // fl32(1/sqrt(128))
   x0 = x0 * c;
   x1 = x1 * c;
+  // The contract rounds the product to binary32 first and to fp16 afterwards.  Keep the two roundings apart: a
+  // fused multiply-and-convert instruction would round the exact product once and differ in rare near-tie cases.
+  asm volatile("" : "+v"(x0), "+v"(x1));
 }
 
 // Eq. 1 at 2 bits against the stored fp16 scale / zero-point, decided in binary32 without a division.
@@ -134,7 +137,11 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
         const int u = j * kGroup + t;  // index in the stream [window tokens, new tokens]
         if (u < nr) {
           kv = *reinterpret_cast<const uint4*>(k_res + (long long)u * kHeadDim + part * 8);
-          vv = *reinterpret_cast<const uint4*>(v_res + (long long)u * kHeadDim + part * 8);
+          // rotated values live 4 slots per channel: slot u, channel ch at [u/4][ch][u%4]
+          half_t tmp[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) tmp[i] = v_res[((long long)(u >> 2) * kHeadDim + part * 8 + i) * 4 + (u & 3)];
+          vv = *reinterpret_cast<const uint4*>(tmp);
         } else {
           kv = *reinterpret_cast<const uint4*>(k_src + (long long)(u - nr) * kHeadDim + part * 8);
           vv = *reinterpret_cast<const uint4*>(v_src + (long long)(u - nr) * kHeadDim + part * 8);
@@ -170,8 +177,9 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       for (int t = 0; t < kGroup; ++t) L.cK[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sK[t][ch], p) : 0;
       L.kScale[ch] = p.s;
       L.kZero[ch] = p.z;
-      reinterpret_cast<half_t*>(c.k_scale)[(bh * c.max_groups + grp) * kGroup + ch] = p.s16;
-      reinterpret_cast<half_t*>(c.k_zero)[(bh * c.max_groups + grp) * kGroup + ch] = p.z16;
+      half_t* rec16 = reinterpret_cast<half_t*>(c.groups + (bh * c.max_groups + grp) * kRecordWords);
+      rec16[2 * kRecKeyScale + ch] = p.s16;
+      rec16[2 * kRecKeyZero + ch] = p.z16;
     } else {
       const int t = tid - kGroup;
       Q2 p;
@@ -191,14 +199,15 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       for (int ch = 0; ch < kHeadDim; ++ch) L.cV[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sV[t][ch], p) : 0;
       L.vScale[t] = p.s;
       L.vZero[t] = p.z;
-      reinterpret_cast<half_t*>(c.v_scale)[(bh * c.max_groups + grp) * kGroup + t] = p.s16;
-      reinterpret_cast<half_t*>(c.v_zero)[(bh * c.max_groups + grp) * kGroup + t] = p.z16;
+      half_t* rec16 = reinterpret_cast<half_t*>(c.groups + (bh * c.max_groups + grp) * kRecordWords);
+      rec16[2 * (kRecValueSZ + t)] = p.s16;
+      rec16[2 * (kRecValueSZ + t) + 1] = p.z16;
     }
     __syncthreads();
     // ---- 3. pack the two 4 KB tiles ------------------------------------------------------------------------
     {
-      uint32_t* k_tile = c.k_codes + (bh * c.max_groups + grp) * kTileWords;
-      uint32_t* v_tile = c.v_codes + (bh * c.max_groups + grp) * kTileWords;
+      uint32_t* k_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecKeyTile;
+      uint32_t* v_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecValueTile;
       for (int wi = tid; wi < kTileWords; wi += kThreads) {
         const int w = wi & 3, l = (wi >> 2) & 63, sel = (wi >> 8) & 1, hf = wi >> 9;
         // key tile: token 64*hf + l, word q = 4*sel + w; pair j, element e -> channel 8*(4*w + j/2) + 4*sel + 2*(j%2) + e
@@ -310,8 +319,8 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     *reinterpret_cast<uint32_t*>(k_win + (long long)slot * kHeadDim + 2 * lane) = kk;
     float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
     fwht128_wave(x0, x1, lane);
-    v_win[(long long)slot * kHeadDim + 2 * lane] = (half_t)x0;
-    v_win[(long long)slot * kHeadDim + 2 * lane + 1] = (half_t)x1;
+    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = (half_t)x0;
+    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = (half_t)x1;
   }
 }
 

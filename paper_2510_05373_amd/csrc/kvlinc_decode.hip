@@ -86,6 +86,10 @@ __device__ __forceinline__ float quadlane_allsum(float v) {
 }
 
 __device__ __forceinline__ float4_t mfma_bcast(half4_t a, half4_t b, float4_t c, int abid) {
+#ifdef KV_EXP_NOMFMA
+  c[abid & 3] += (float)b[abid & 3] * (float)a[0];
+  return c;
+#endif
   switch (abid) {
     case 0: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 0, 0);
     case 1: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 1, 0);
@@ -114,6 +118,10 @@ __device__ __forceinline__ float pair_gain(int j) { return __builtin_ldexpf(1.0f
 
 // The 8 pairs of a word as fp16x2 subnormals (9 VALU operations for 16 codes).
 __device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
+#ifdef KV_EXP_NOUNPACK
+  for (int j = 0; j < 8; ++j) u[j] = w;
+  return;
+#endif
   const uint32_t ws = w >> 6;
   u[0] = w & 0x00030003u;
   u[1] = w & 0x000C000Cu;
@@ -125,30 +133,38 @@ __device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
   u[7] = ws & 0x03000300u;
 }
 
-struct GroupRegs {
+// Register image of one group, loaded in two parts so that each part can be re-issued for the next group as soon
+// as its contraction has consumed it (the loads then fly during the other contraction; no second register set).
+struct KeyRegs {
   uint4 kw[2][2];  // key tile: [token half][word quad]
-  uint4 vw[2][2];  // value tile: [token half][channel half]
   uint4 ks, kz;    // key scale / zero-point of channels 8*quad .. 8*quad+7
-  uint16_t vs[2], vz[2];  // value scale / zero-point of tokens lane, 64 + lane
+};
+struct ValueRegs {
+  uint4 vw[2][2];         // value tile: [token half][channel half]
+  uint32_t sz[2];         // value (scale, zero-point) fp16 pair of tokens lane, 64 + lane
 };
 
-__device__ __forceinline__ void load_group(GroupRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
-  const uint4* kt = reinterpret_cast<const uint4*>(c.k_codes + gbase * kTileWords);
-  const uint4* vt = reinterpret_cast<const uint4*>(c.v_codes + gbase * kTileWords);
+__device__ __forceinline__ void load_keys(KeyRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
+  const uint32_t* rec = c.groups + gbase * kRecordWords;
+  const uint4* kt = reinterpret_cast<const uint4*>(rec + kRecKeyTile);
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      r.kw[hf][i] = kt[(hf * 2 + i) * 64 + lane];
-      r.vw[hf][i] = vt[(hf * 2 + i) * 64 + lane];
-    }
+    for (int i = 0; i < 2; ++i) r.kw[hf][i] = kt[(hf * 2 + i) * 64 + lane];
   const int quad = lane >> 2;
-  r.ks = reinterpret_cast<const uint4*>(c.k_scale + gbase * kGroup)[quad];
-  r.kz = reinterpret_cast<const uint4*>(c.k_zero + gbase * kGroup)[quad];
-  const uint16_t* vs = c.v_scale + gbase * kGroup;
-  const uint16_t* vz = c.v_zero + gbase * kGroup;
-  r.vs[0] = vs[lane]; r.vs[1] = vs[64 + lane];
-  r.vz[0] = vz[lane]; r.vz[1] = vz[64 + lane];
+  r.ks = reinterpret_cast<const uint4*>(rec + kRecKeyScale)[quad];
+  r.kz = reinterpret_cast<const uint4*>(rec + kRecKeyZero)[quad];
+}
+
+__device__ __forceinline__ void load_values(ValueRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
+  const uint32_t* rec = c.groups + gbase * kRecordWords;
+  const uint4* vt = reinterpret_cast<const uint4*>(rec + kRecValueTile);
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) r.vw[hf][i] = vt[(hf * 2 + i) * 64 + lane];
+  r.sz[0] = rec[kRecValueSZ + lane];
+  r.sz[1] = rec[kRecValueSZ + 64 + lane];
 }
 
 __device__ __forceinline__ float h2f(uint16_t bits) { return (float)__builtin_bit_cast(half_t, bits); }
@@ -162,42 +178,50 @@ struct WaveState {
   float4_t acc[NB][2];  // E V in raw matrix-core units: [head block][channel half], rows = heads, lane = channel
 };
 
+// Per-lane constants of a wave.
+struct LaneConst {
+  float inv_gain0, inv_gain1;  // 1 / gain of this quad's k-slot pairs (0,1) and (2,3) in q K^T
+  float vgain;                 // gain of this lane's token as a k slot of E V
+  uint32_t perm_sel;           // byte selector of the 16-bit exchange inside the 4x4 quad transpose
+  int lane;
+};
+
+// q K^T of one group for all heads: scores in the log2 domain, [head block][token half], rows = heads, lane = token.
 template <int NB>
-__device__ __forceinline__ void process_group(const GroupRegs& g, int valid, const uint32_t (&Qs)[NB][4],
-                                              const uint32_t (&Qr)[NB][4], float gain0, float gain1, float vgain,
-                                              uint32_t perm_sel, int lane, WaveState<NB>& st) {
-  // ---- A operand of q K^T and the group's additive term per head ------------------------------------------------
+__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const uint32_t (&Qs)[NB][4], const LaneConst& lc,
+                                         float4_t (&sc)[NB][2]) {
   const uint32_t S[4] = {g.ks.x, g.ks.y, g.ks.z, g.ks.w};
   const uint32_t Z[4] = {g.kz.x, g.kz.y, g.kz.z, g.kz.w};
   const half2_t c15 = {(half_t)1.5f, (half_t)1.5f};
-  const half2_t ones = {(half_t)1.0f, (half_t)1.0f};
+  const half2_t m15 = {(half_t)-1.5f, (half_t)-1.5f};
   half4_t A[NB][2];
   float4_t bias[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     uint32_t a[4];
-    float t = 0.0f, ua = 0.0f, ub = 0.0f;
+    float t0 = 0.0f, t1 = 0.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      a[i] = as_u32(as_h2(Qs[nb][i]) * as_h2(S[i]));                    // fp16(q 2^gain s), one rounding
-      const half2_t mid = as_h2(S[i]) * c15 + as_h2(Z[i]);              // z + 1.5 s
-      t = __builtin_amdgcn_fdot2(as_h2(Qr[nb][i]), mid, t, false);      // sum q (z + 1.5 s)
-      if (i & 1) ub = __builtin_amdgcn_fdot2(as_h2(a[i]), ones, ub, false);
-      else ua = __builtin_amdgcn_fdot2(as_h2(a[i]), ones, ua, false);
+      a[i] = as_u32(as_h2(Qs[nb][i]) * as_h2(S[i]));        // fp16(q gain s), one rounding
+      const half2_t mid = as_h2(S[i]) * c15 + as_h2(Z[i]);  // z + 1.5 s
+      // gain * [ sum q (z + 1.5 s) ]  -  1.5 * sum rounded(q gain s): the exact compensation of the centring
+      if (i & 1) {
+        t1 = __builtin_amdgcn_fdot2(as_h2(Qs[nb][i]), mid, t1, false);
+        t1 = __builtin_amdgcn_fdot2(as_h2(a[i]), m15, t1, false);
+      } else {
+        t0 = __builtin_amdgcn_fdot2(as_h2(Qs[nb][i]), mid, t0, false);
+        t0 = __builtin_amdgcn_fdot2(as_h2(a[i]), m15, t0, false);
+      }
     }
     A[nb][0] = as_h4(a[0], a[1]);
     A[nb][1] = as_h4(a[2], a[3]);
-    // sum_c q_c (z_c + 1.5 s_c) - 1.5 sum_c rounded(q_c s_c): exact compensation of the centring
-    float b = t - 1.5f * (ua / gain0 + ub / gain1);
+    float b = t0 * lc.inv_gain0 + t1 * lc.inv_gain1;
     b = quadlane_allsum(b) * (1.0f / kRawScale);  // lanes with lane % 4 == h now hold head h's term, in raw units
     bias[nb][0] = dpp_f<0x00>(b);
     bias[nb][1] = dpp_f<0x55>(b);
     bias[nb][2] = dpp_f<0xAA>(b);
     bias[nb][3] = dpp_f<0xFF>(b);
   }
-
-  // ---- q K^T for both token halves -----------------------------------------------------------------------------
-  float4_t sc[NB][2];
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
     float4_t acc0[NB], acc1[NB];
@@ -229,10 +253,13 @@ __device__ __forceinline__ void process_group(const GroupRegs& g, int valid, con
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
-        if (64 * hf + lane >= valid) sc[nb][hf] = float4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (64 * hf + lc.lane >= valid) sc[nb][hf] = float4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   }
+}
 
-  // ---- running maximum (Alg. 1 line 8), rescale only when it moved --------------------------------------------
+// Running maximum (Alg. 1 line 8); the accumulated state is rescaled only when a maximum moved.
+template <int NB>
+__device__ __forceinline__ void update_max(const float4_t (&sc)[NB][2], WaveState<NB>& st) {
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     float mx[4];
@@ -255,14 +282,18 @@ __device__ __forceinline__ void process_group(const GroupRegs& g, int valid, con
       }
     }
   }
+}
 
-  // ---- p = 2^(x - m), its sums, the A operand of E V, and E V ----------------------------------------------------
+// p = 2^(x - m), its sums, and E V of one group.
+template <int NB>
+__device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc)[NB][2], const LaneConst& lc,
+                                         WaveState<NB>& st) {
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
-    const float vs = h2f(g.vs[hf]);
-    const float vmid = h2f(g.vz[hf]) + 1.5f * vs;
-    const float vsg = vs * vgain;             // value scale with the k-slot gain of this lane's token
-    const float comp = -1.5f / vgain;         // exact (power of two times 1.5)
+    const float vs = h2f((uint16_t)(g.sz[hf] & 0xFFFFu));
+    const float vmid = h2f((uint16_t)(g.sz[hf] >> 16)) + 1.5f * vs;
+    const float vsg = vs * lc.vgain;       // value scale with the k-slot gain of this lane's token
+    const float comp = -1.5f / lc.vgain;   // exact (power of two times 1.5)
     half4_t A2[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -283,10 +314,10 @@ __device__ __forceinline__ void process_group(const GroupRegs& g, int valid, con
       // 4x4 transpose inside each lane quad: (lane = token, slots = heads) -> (lane = head, slots = tokens)
       const uint32_t X = as_u32(x01), Y = as_u32(x23);
       const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
-      const uint32_t X1 = __builtin_amdgcn_perm(TX, X, perm_sel);  // even lane {X.lo, TX.lo}; odd lane {TX.hi, X.hi}
-      const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, perm_sel);
+      const uint32_t X1 = __builtin_amdgcn_perm(TX, X, lc.perm_sel);  // even lane {X.lo, TX.lo}; odd lane {TX.hi, X.hi}
+      const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, lc.perm_sel);
       const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
-      const bool upper = (lane & 2) != 0;
+      const bool upper = (lc.lane & 2) != 0;
       const uint32_t U = upper ? Y2 : X1;
       const uint32_t W = upper ? Y1 : X2;
       A2[nb] = as_h4(U, W);
@@ -309,7 +340,6 @@ __device__ __forceinline__ void process_group(const GroupRegs& g, int valid, con
   }
 }
 
-
 // ---- work item 1: a range of quantized groups of one (sequence, kv head) ----------------------------------------
 
 template <int NB>
@@ -330,15 +360,19 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
   const int g1 = (int)((long long)n_groups * (sp + 1) / n_splits);
   const int items_per_bh = n_splits + 1;
 
-  // per-lane constants
   const int quad = lane >> 2, hrow = lane & 3;
-  const int j0 = 2 * (quad & 3), j1 = j0 + 1;          // pairs feeding this quad's k slots (0,1) and (2,3)
+  const int j0 = 2 * (quad & 3), j1 = j0 + 1;  // pairs feeding this quad's k slots (0,1) and (2,3)
   const float gain0 = pair_gain(j0), gain1 = pair_gain(j1);
-  const float vgain = pair_gain(2 * ((lane >> 2) & 3) + ((lane >> 1) & 1));  // this lane's token as a k slot of E V
-  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+  LaneConst lc;
+  lc.inv_gain0 = 1.0f / gain0;
+  lc.inv_gain1 = 1.0f / gain1;
+  lc.vgain = pair_gain(2 * ((lane >> 2) & 3) + ((lane >> 1) & 1));
+  lc.perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+  lc.lane = lane;
 
-  // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7; heads beyond gq read as 0
-  uint32_t Qr[NB][4], Qs[NB][4];
+  // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
+  // heads beyond gq read as 0
+  uint32_t Qs[NB][4];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int h = nb * 4 + hrow;
@@ -347,7 +381,6 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
     const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      Qr[nb][i] = r[i];
       const half_t gn = (half_t)((i & 1) ? gain1 : gain0);
       const half2_t g2 = {gn, gn};
       Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
@@ -363,19 +396,29 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
     st.acc[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
   }
 
-  // this wave's groups, the next one always in flight in the other register set
+  // This wave's groups.  The key part of the next group is requested as soon as q K^T has consumed the current
+  // one and flies during E V; the value part likewise flies during the next q K^T.  Past the end the current
+  // (cached) group is requested again, so that no branch joins between a load and its first use.
   const long long tile0 = (long long)bh * c.max_groups;
   int grp = g0 + wave;
-  GroupRegs r0, r1;
-  if (grp < g1) load_group(r0, c, tile0 + grp, lane);
-  while (grp < g1) {
-    if (grp + kWaves < g1) load_group(r1, c, tile0 + grp + kWaves, lane);
-    process_group<NB>(r0, min(kGroup, nq - grp * kGroup), Qs, Qr, gain0, gain1, vgain, perm_sel, lane, st);
-    grp += kWaves;
-    if (grp >= g1) break;
-    if (grp + kWaves < g1) load_group(r0, c, tile0 + grp + kWaves, lane);
-    process_group<NB>(r1, min(kGroup, nq - grp * kGroup), Qs, Qr, gain0, gain1, vgain, perm_sel, lane, st);
-    grp += kWaves;
+  if (grp < g1) {
+    KeyRegs kr;
+    ValueRegs vr;
+    load_keys(kr, c, tile0 + grp, lane);
+    load_values(vr, c, tile0 + grp, lane);
+    while (true) {
+      const int nxt = grp + kWaves;
+      const bool more = nxt < g1;
+      const long long nbase = tile0 + (more ? nxt : grp);
+      float4_t sc[NB][2];
+      qk_phase<NB>(kr, min(kGroup, nq - grp * kGroup), Qs, lc, sc);
+      load_keys(kr, c, nbase, lane);
+      update_max<NB>(sc, st);
+      pv_phase<NB>(vr, sc, lc, st);
+      load_values(vr, c, nbase, lane);
+      if (!more) break;
+      grp = nxt;
+    }
   }
 
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
@@ -472,7 +515,7 @@ __device__ __forceinline__ void window_item(const kvlinc_cache& c, const half_t*
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (4 * hh < gq) {
     for (int t = 0; t < nr; ++t) {
-      const float vv = (float)vw[(long long)t * kHeadDim + tok];
+      const float vv = (float)vw[((long long)(t >> 2) * kHeadDim + tok) * 4 + (t & 3)];
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[j] = fmaf(sP[4 * hh + j][t], vv, acc[j]);
     }
@@ -489,13 +532,28 @@ __device__ __forceinline__ void window_item(const kvlinc_cache& c, const half_t*
 
 // ---- work item 3: correction terms of one (sequence, kv head): phi_q(q), C_n = phi_q S, C_d = phi_q P -------------
 // (Sec. 3.3: computed before the merge; Eq. 6 for phi.)  Output per query head: {C_d, -, -, -, C_n[128]}.
+// Both products are laid out so that a wave owns complete output columns (all rows of the contraction), reduces
+// with shuffles and needs no cross-wave traffic; loads are issued in batches of eight 16-byte requests per lane.
+
+__device__ __forceinline__ float xor_allsum_16rows(float v) {  // sum over lanes that differ in bits 2..5
+  v += dpp_f<kRowRor4>(v);
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+__device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes that differ in bits 3..5
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
 
 __device__ __forceinline__ void correction_item(const kvlinc_cache& c, const half_t* __restrict__ q,
                                                 float* __restrict__ corr, int gq, int bh, float* lds) {
-  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);          // [8][128] raw q
-  float (*sPhi)[kRank] = reinterpret_cast<float (*)[kRank]>(lds + 8 * kHeadDim);  // [8][256]
-  float* sRed = lds + 8 * kHeadDim + 8 * kRank;                                // [4 waves][4][128]
-  float* sSmall = sRed + kWaves * 4 * kHeadDim;                                // [32]
+  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);             // [8][128] raw q
+  float (*sPhi)[kRank] = reinterpret_cast<float (*)[kRank]>(lds + 8 * kHeadDim);  // [8][256] logits, then phi
+  float* sSmall = lds + 8 * kHeadDim + 8 * kRank;                                 // [64]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -511,133 +569,142 @@ __device__ __forceinline__ void correction_item(const kvlinc_cache& c, const hal
     sQ[i >> 7][i & 127] = (float)q[((long long)b * c.H_q + g * gq) * kHeadDim + i];
   __syncthreads();
 
-  // phase 1: logits[h][half][f] = sum_c q[h][c] W[h][half][c][f]; thread = (row group of 8 channels, chunk of 8 features)
+  // phase 1: logit[h][hs][f] = sum_c q[h][c] W[h][hs][c][f].  Wave w owns features 32w .. 32w+31 of each half;
+  // lane = (chunk of 8 features, group of 8 channels).
   {
-    const int chunk = tid & 15, rowgrp = tid >> 4;
-    for (int h = 0; h < gq; ++h) {
-      float acc[2][8];
+    const int chunk = lane & 3, rowgrp = lane >> 2;
+    const int f0 = 32 * wave + 8 * chunk;
+    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wq) + (long long)g * gq * 2 * kHeadDim * (kRank / 2) +
+                       (long long)rowgrp * 8 * (kRank / 2) + f0;
+    // batches of eight 16-byte requests per lane, the next batch always in flight while the current one is reduced
+    uint4 raw[2][8];
 #pragma unroll
-      for (int hs = 0; hs < 2; ++hs)
+    for (int rb = 0; rb < 8; ++rb) raw[0][rb] = *reinterpret_cast<const uint4*>(W0 + rb * (kRank / 2));
+    const int n_batches = 2 * gq;  // hb = 2 h + hs
+    for (int hb0 = 0; hb0 < n_batches; hb0 += 2) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[hs][i] = 0.f;
-      const half_t* W = reinterpret_cast<const half_t*>(c.Wq) + (long long)(g * gq + h) * 2 * kHeadDim * (kRank / 2);
+      for (int par = 0; par < 2; ++par) {
+        const int hb = hb0 + par;
+        const int nb = hb + 1 < n_batches ? hb + 1 : hb;  // past the end: re-request the current, cached batch
+        const half_t* Wn = W0 + (long long)nb * kHeadDim * (kRank / 2);
 #pragma unroll
-      for (int hs = 0; hs < 2; ++hs)
+        for (int rb = 0; rb < 8; ++rb) raw[par ^ 1][rb] = *reinterpret_cast<const uint4*>(Wn + rb * (kRank / 2));
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 #pragma unroll
         for (int rb = 0; rb < 8; ++rb) {
-          const int ch = rowgrp * 8 + rb;
-          const uint4 raw = *reinterpret_cast<const uint4*>(W + ((long long)hs * kHeadDim + ch) * (kRank / 2) + 8 * chunk);
-          const half_t* hv = reinterpret_cast<const half_t*>(&raw);
-          const float qv = sQ[h][ch];
+          const float qv = sQ[hb >> 1][rowgrp * 8 + rb];
+          const half_t* hv = reinterpret_cast<const half_t*>(&raw[par][rb]);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc[hs][i] = fmaf(qv, (float)hv[i], acc[hs][i]);
+          for (int i = 0; i < 8; ++i) acc[i] = fmaf(qv, (float)hv[i], acc[i]);
         }
 #pragma unroll
-      for (int hs = 0; hs < 2; ++hs)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          float v = acc[hs][i];
-          v += __shfl_xor(v, 16, 64);
-          v += __shfl_xor(v, 32, 64);
-          if (lane < 16) sRed[(wave * 2 + hs) * kHeadDim + 8 * chunk + i] = v;
+        for (int i = 0; i < 8; ++i) acc[i] = xor_allsum_16rows(acc[i]);
+        if (rowgrp == 0) {
+          float* dst = &sPhi[hb >> 1][(hb & 1) * 128 + f0];
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
         }
-      __syncthreads();
-      const int hs = tid >> 7, f = tid & 127;
-      float logit = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) logit += sRed[(w * 2 + hs) * kHeadDim + f];
-      const float wm = wave_allmax(logit);
-      if (lane == 0) sSmall[wave] = wm;
-      __syncthreads();
-      const float mx = fmaxf(sSmall[2 * hs], sSmall[2 * hs + 1]);
-      const float e = __expf(logit - mx);
-      const float ws = wave_allsum(e);
-      if (lane == 0) sSmall[8 + wave] = ws;
-      __syncthreads();
-      sPhi[h][tid] = e / (sSmall[8 + 2 * hs] + sSmall[8 + 2 * hs + 1]);
+      }
     }
   }
   __syncthreads();
+  // softmax over each half (128 features) of each head: one wave per row at a time
+  for (int row = wave; row < 2 * gq; row += kWaves) {
+    float* p = &sPhi[row >> 1][(row & 1) * 128];
+    const float a0 = p[lane], a1 = p[lane + 64];
+    const float mx = wave_allmax(fmaxf(a0, a1));
+    const float e0 = __expf(a0 - mx), e1 = __expf(a1 - mx);
+    const float inv = 1.0f / wave_allsum(e0 + e1);
+    p[lane] = e0 * inv;
+    p[lane + 64] = e1 * inv;
+  }
+  __syncthreads();
 
-  // phase 2: C_n[h][c] = sum_f phi[h][f] S[f][c]; thread = (row group of 32 features, chunk of 4 channels); S read once
+  // phase 2: C_n[h][c] = sum_f phi[h][f] S[f][c].  Wave w owns channels 32w .. 32w+31; lane = (chunk of 4
+  // channels, group of 32 features).  S is read once for all heads.
   {
-    const int chunk = tid & 31, rowgrp = tid >> 5;
-    const float* S = c.S + (long long)bh * kRank * kHeadDim;
+    const int chunk = lane & 7, rowgrp = lane >> 3;
+    const int c0 = 32 * wave + 4 * chunk;
+    const float* S = c.S + (long long)bh * kRank * kHeadDim + (long long)rowgrp * 32 * kHeadDim + c0;
     float acc[kMaxGq][4];
 #pragma unroll
     for (int h = 0; h < kMaxGq; ++h)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < 32; ++i) {
-      const int f = rowgrp * 32 + i;
-      const float4 s4 = *reinterpret_cast<const float4*>(S + (long long)f * kHeadDim + 4 * chunk);
+    float4 s4[2][8];
 #pragma unroll
-      for (int h = 0; h < kMaxGq; ++h) {
-        if (h < gq) {
-          const float ph = sPhi[h][f];
-          acc[h][0] = fmaf(ph, s4.x, acc[h][0]);
-          acc[h][1] = fmaf(ph, s4.y, acc[h][1]);
-          acc[h][2] = fmaf(ph, s4.z, acc[h][2]);
-          acc[h][3] = fmaf(ph, s4.w, acc[h][3]);
+    for (int i = 0; i < 8; ++i) s4[0][i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
+#pragma unroll
+    for (int bt = 0; bt < 4; ++bt) {
+      const int i0 = 8 * bt;
+      if (bt < 3) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          s4[(bt & 1) ^ 1][i] = *reinterpret_cast<const float4*>(S + (long long)(i0 + 8 + i) * kHeadDim);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float4 sv = s4[bt & 1][i];
+#pragma unroll
+        for (int h = 0; h < kMaxGq; ++h) {
+          if (h < gq) {
+            const float ph = sPhi[h][rowgrp * 32 + i0 + i];
+            acc[h][0] = fmaf(ph, sv.x, acc[h][0]);
+            acc[h][1] = fmaf(ph, sv.y, acc[h][1]);
+            acc[h][2] = fmaf(ph, sv.z, acc[h][2]);
+            acc[h][3] = fmaf(ph, sv.w, acc[h][3]);
+          }
         }
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < kMaxGq; ++h) {
+      if (h < gq) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[h][j] = xor_allsum_8rows(acc[h][j]);
+        if (rowgrp == 0)
+          *reinterpret_cast<float4*>(out0 + (long long)h * kPartStride + 4 + c0) =
+              make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
       }
     }
     // C_d[h] = sum_f phi[h][f] P[f]
     const float pf = c.P[(long long)bh * kRank + tid];
     for (int h = 0; h < gq; ++h) {
       const float v = wave_allsum(sPhi[h][tid] * pf);
-      if (lane == 0) sSmall[16 + h * kWaves + wave] = v;
+      if (lane == 0) sSmall[h * kWaves + wave] = v;
     }
-    for (int hb = 0; hb < gq; hb += 4) {
-      __syncthreads();
+    __syncthreads();
+    if (tid < gq) {
+      float cd = 0.f;
 #pragma unroll
-      for (int hh = 0; hh < 4; ++hh)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float v = acc[0][0];
-#pragma unroll
-          for (int h = 0; h < kMaxGq; ++h)
-            if (h == hb + hh) v = acc[h][j];
-          v += __shfl_xor(v, 32, 64);
-          if (lane < 32) sRed[(wave * 4 + hh) * kHeadDim + 4 * chunk + j] = v;
-        }
-      __syncthreads();
-      for (int idx = tid; idx < 4 * kHeadDim; idx += kThreads) {
-        const int hh = idx >> 7, ch = idx & 127, h = hb + hh;
-        if (h >= gq) continue;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) v += sRed[(w * 4 + hh) * kHeadDim + ch];
-        out0[(long long)h * kPartStride + 4 + ch] = v;
-        if (ch == 0) {
-          float cd = 0.f;
-#pragma unroll
-          for (int w = 0; w < kWaves; ++w) cd += sSmall[16 + h * kWaves + w];
-          out0[(long long)h * kPartStride] = cd;
-        }
-      }
+      for (int w = 0; w < kWaves; ++w) cd += sSmall[tid * kWaves + w];
+      out0[(long long)tid * kPartStride] = cd;
     }
   }
 }
 
-constexpr int kLdsFloats = 8 * kHeadDim + 8 * kRank + kWaves * 4 * kHeadDim + 64;  // the correction item's need (largest)
+constexpr int kLdsFloats = 2 * kWaves * 8 + kWaves * 8 * kHeadDim;  // the group item with two head blocks (largest)
 
 // blockIdx: [0, BH) correction items (only with adapters), then BH window items, then BH * n_splits group items.
 template <int NB>
-__global__ __launch_bounds__(kThreads) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+__global__ __launch_bounds__(kThreads, NB == 1 ? 4 : 3) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                 float* __restrict__ part, float* __restrict__ corr,
-                                                                int n_splits, int gq) {
+                                                                int n_splits, int gq, int dbg_skip) {
   __shared__ __align__(16) float lds[kLdsFloats];
   static_assert(kLdsFloats >= 2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim, "group item LDS");
+  static_assert(kLdsFloats >= 8 * kHeadDim + 8 * kRank + 64, "correction item LDS");
+  static_assert(kLdsFloats >= 16 * kHeadDim + 16, "window item LDS");
   const int BH = c.B * c.H_kv;
   int item = blockIdx.x;
   if (corr != nullptr) {
-    if (item < BH) { correction_item(c, q, corr, gq, item, lds); return; }
+    if (item < BH) { if (!(dbg_skip & 1)) correction_item(c, q, corr, gq, item, lds); return; }
     item -= BH;
   }
-  if (item < BH) { window_item(c, q, part, n_splits, gq, item, lds); return; }
+  if (item < BH) { if (!(dbg_skip & 2)) window_item(c, q, part, n_splits, gq, item, lds); return; }
   item -= BH;
+  if (dbg_skip & 4) return;
   group_item<NB>(c, q, part, n_splits, gq, item / n_splits, item % n_splits, lds);
 }
 
@@ -724,8 +791,10 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   float* part = workspace;
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * (n_splits + 1) * kPartStride : nullptr;
   const dim3 grid(BH * (n_splits + 1 + (corr != nullptr ? 1 : 0))), block(kThreads);
-  if (gq <= 4) hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq);
-  else hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq);
+  const char* dbg = getenv("KVLINC_DBG_SKIP");
+  const int dbg_skip = dbg ? atoi(dbg) : 0;
+  if (gq <= 4) hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq, dbg_skip);
+  else hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq, dbg_skip);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   hipLaunchKernelGGL(decode_merge_kernel, dim3((c.B * c.H_q + kWaves - 1) / kWaves), block, 0, stream, c, part, corr,
                      n_splits, reinterpret_cast<half_t*>(out));

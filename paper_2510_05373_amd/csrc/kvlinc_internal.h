@@ -12,6 +12,9 @@ constexpr int kHeadDim = 128;   // d
 constexpr int kGroup = 128;     // G: tokens per key group = channels per value group
 constexpr int kRank = 256;      // D
 constexpr int kTileWords = 1024;
+// group record (words): key tile, value tile, key scale, key zero-point, value (scale, zero-point) per token
+constexpr int kRecordWords = 2304;
+constexpr int kRecKeyTile = 0, kRecValueTile = 1024, kRecKeyScale = 2048, kRecKeyZero = 2112, kRecValueSZ = 2176;
 constexpr int kMaxGq = 8;       // query heads per KV head supported by the decode kernels
 
 // Partial result of one block of tokens for one query head (Alg. 1: m^j, l^j, Y_s^j), log2 domain:

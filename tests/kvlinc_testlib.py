@@ -49,19 +49,20 @@ def check_cache_against_oracle(cache, K, V, lengths, pairs, Wk=None, keep=None, 
         nq, nr = int(n_quant[b]), int(n_res[b])
         ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], nq, Wk=None if Wk is None else Wk[g])
         ng = -(-nq // 128)
-        kc = cache.k_codes[b, g, :ng].cpu().numpy().view(np.uint32)
-        vc = cache.v_codes[b, g, :ng].cpu().numpy().view(np.uint32)
+        rec = cache.groups[b, g, :ng].cpu().numpy().view(np.uint32)
         if ng:
-            # logical codes first (clearer failure), then the physical tile bytes
-            assert np.array_equal(o_layout.unpack_k_tile(kc), ref["k_codes"]), ("k codes", b, g)
-            assert np.array_equal(o_layout.unpack_v_tile(vc), ref["v_codes"]), ("v codes", b, g)
-            assert np.array_equal(kc, o_layout.pack_k_tile(ref["k_codes"])), ("k tiles", b, g)
-            assert np.array_equal(vc, o_layout.pack_v_tile(ref["v_codes"])), ("v tiles", b, g)
-        for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
-            got = getattr(cache, name)[b, g, :ng].cpu().numpy()
-            assert np.array_equal(u16(got), u16(ref[name])), (name, b, g)
+            # logical fields first (clearer failure), then the physical record bytes
+            got = o_layout.unpack_records(rec)
+            assert np.array_equal(got["k_codes"], ref["k_codes"]), ("k codes", b, g)
+            assert np.array_equal(got["v_codes"], ref["v_codes"]), ("v codes", b, g)
+            for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
+                assert np.array_equal(u16(got[name]), u16(ref[name])), (name, b, g)
+            want = o_layout.pack_records(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"],
+                                         ref["v_scale"], ref["v_zero"])
+            assert np.array_equal(rec, want), ("records", b, g)
         assert np.array_equal(u16(cache.k_res[b, g, :nr].cpu().numpy()), u16(ref["k_res"])), ("k_res", b, g)
-        assert np.array_equal(u16(cache.v_res[b, g, :nr].cpu().numpy()), u16(ref["v_res"])), ("v_res", b, g)
+        v_win = o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
+        assert np.array_equal(u16(v_win), u16(ref["v_res"])), ("v_res", b, g)
         if Wk is not None and check_states:
             S = cache.S[b, g].cpu().numpy().astype(np.float64)
             P = cache.P[b, g].cpu().numpy().astype(np.float64)

@@ -124,7 +124,7 @@ def test_degenerate_inputs(kv):
     cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
     cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
     tl.check_cache_against_oracle(cache, K, V, lengths, [(1, 0), (2, 0)], Wk=Wk)
-    assert not cache.k_scale[2, 0, :2].any() and not cache.k_codes[2, 0, :2].any()
+    assert not cache.groups[2, 0, :2, :1024].any() and not cache.groups[2, 0, :2, 2048:2112].any()  # key codes, scales
     q = tl.gen_q(14, B, H_q)
     out = cache.decode(tl.to_dev(q)).cpu().numpy()
     assert not out[0].any()  # no tokens -> zeros
@@ -141,7 +141,7 @@ def test_status_bits_and_rejections(kv):
     cache.append(k, k)  # would need 4 groups
     torch.cuda.synchronize()
     assert int(cache.status.item()) == kv.KVLINC_ST_CAPACITY
-    assert cache.n_quant.item() == 0 and cache.n_res.item() == 0 and not cache.k_codes.any()
+    assert cache.n_quant.item() == 0 and cache.n_res.item() == 0 and not cache.groups.any()
     cache.status.zero_()
     k[0, 0, 5, 7] = float("inf")
     cache.append(k[:, :, :300].contiguous(), k[:, :, :300].contiguous())
@@ -165,5 +165,5 @@ def test_run_to_run_determinism(kv):
     for _ in range(5):
         assert torch.equal(cache.decode(q), first)
     cache2, *_ = _build(kv, 15, B, H_q, H_kv, lengths)
-    for name in ("k_codes", "v_codes", "k_scale", "v_zero", "k_res", "v_res", "S", "P"):
+    for name in ("groups", "k_res", "v_res", "S", "P"):
         assert torch.equal(getattr(cache, name), getattr(cache2, name)), name

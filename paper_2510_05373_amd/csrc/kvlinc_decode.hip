@@ -1,13 +1,17 @@
-// Block-split decode over the packed 2-bit cache on the CDNA4 matrix cores (Sec. 3.3, Alg. 1 lines 4-12: unpack,
-// q K^T, block max / exp / sum, E V; the dequantization is folded into the small operands instead of being applied
-// to the tiles).
+// Decode: single-query attention read directly from the packed 2-bit cache on the CDNA4 matrix cores, with the
+// linear correction and the fp16 window (Sec. 3.3, Alg. 1; Sec. 3.2, Eq. 5-6; Sec. 3.1 for the rotated value basis).
 //
-// One wave owns a group of 128 tokens at a time and keeps its own (m, l, acc); the four waves of a workgroup take
-// the groups of the workgroup's range round-robin and are combined through LDS at the end (Alg. 1 line 11 writes
-// one (Y_s, m, l) per workgroup and query head).
+// Launch 1, decode_main_kernel: one kind of workgroup, (sequence, kv head, split).  Its four waves take the groups of
+// the split round-robin; a wave owns a group of 128 tokens at a time and keeps its own (m, l, acc).  Group records
+// travel HBM -> LDS directly, two requests ahead per wave.  On the side a workgroup computes its share of the
+// correction terms (phi_q(q), C_n = phi_q S, C_d = phi_q P, split into four parts over the rows of S) and one wave
+// may own half of the fp16 window, processed as one more block of tokens.  The waves are combined through LDS and
+// the workgroup writes one (m, l, Y_s) per query head (Alg. 1 line 11).
+// Launch 2, decode_merge_kernel: one wave per (sequence, query head): weighs the splits by 2^(m_j - M), adds the
+// correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies H^T and stores fp16 (Alg. 1 lines 13-15 with Eq. 5).
 //
-// Both contractions run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad (cbsz=4,
-// abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
+// Both contractions of a group run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad
+// (cbsz=4, abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
 //   q K^T : columns = 64 tokens (lane = token), k = 4 channels; A = q * key scale, held by quad `abid` for its 8 channels.
 //   E V   : columns = 64 channels (lane = channel), k = 4 tokens;  A = p * value scale, held by the quad that owns the tokens.
 // The B operand is the packed word itself, masked: a 2-bit code left in place inside an fp16 mantissa is the
@@ -16,6 +20,7 @@
 // Zero-points never touch the tiles: sum_c q_c (s_c code + z_c) = sum_c (q_c s_c) code + sum_c q_c z_c, and likewise
 // for the values per token.  The fp16 rounding of (q s) and (p s) is centred: the code is taken as (code - 1.5) and
 // 1.5 * rounded operand is added back in binary32, which removes the mean of the rounding error.
+// Scores live in the log2 domain: x = q.k * log2(e)/sqrt(d).
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
@@ -86,10 +91,6 @@ __device__ __forceinline__ float quadlane_allsum(float v) {
 }
 
 __device__ __forceinline__ float4_t mfma_bcast(half4_t a, half4_t b, float4_t c, int abid) {
-#ifdef KV_EXP_NOMFMA
-  c[abid & 3] += (float)b[abid & 3] * (float)a[0];
-  return c;
-#endif
   switch (abid) {
     case 0: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 0, 0);
     case 1: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 4, 1, 0);
@@ -118,10 +119,6 @@ __device__ __forceinline__ float pair_gain(int j) { return __builtin_ldexpf(1.0f
 
 // The 8 pairs of a word as fp16x2 subnormals (9 VALU operations for 16 codes).
 __device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
-#ifdef KV_EXP_NOUNPACK
-  for (int j = 0; j < 8; ++j) u[j] = w;
-  return;
-#endif
   const uint32_t ws = w >> 6;
   u[0] = w & 0x00030003u;
   u[1] = w & 0x000C000Cu;
@@ -133,19 +130,19 @@ __device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
   u[7] = ws & 0x03000300u;
 }
 
-// Register image of one group, loaded in two parts so that each part can be re-issued for the next group as soon
-// as its contraction has consumed it (the loads then fly during the other contraction; no second register set).
+// Register image of one group.
 struct KeyRegs {
   uint4 kw[2][2];  // key tile: [token half][word quad]
   uint4 ks, kz;    // key scale / zero-point of channels 8*quad .. 8*quad+7
 };
 struct ValueRegs {
-  uint4 vw[2][2];         // value tile: [token half][channel half]
-  uint32_t sz[2];         // value (scale, zero-point) fp16 pair of tokens lane, 64 + lane
+  uint4 vw[2][2];  // value tile: [token half][channel half]
+  uint32_t sz[2];  // value (scale, zero-point) fp16 pair of tokens lane, 64 + lane
 };
 
-__device__ __forceinline__ void load_keys(KeyRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
-  const uint32_t* rec = c.groups + gbase * kRecordWords;
+// A record is fetched in two parts so that each part can be requested again for the next group as soon as its
+// contraction has consumed it: the key part flies during E V, the value part during the next q K^T.
+__device__ __forceinline__ void load_keys(KeyRegs& r, const uint32_t* __restrict__ rec, int lane) {
   const uint4* kt = reinterpret_cast<const uint4*>(rec + kRecKeyTile);
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf)
@@ -156,8 +153,7 @@ __device__ __forceinline__ void load_keys(KeyRegs& r, const kvlinc_cache& c, lon
   r.kz = reinterpret_cast<const uint4*>(rec + kRecKeyZero)[quad];
 }
 
-__device__ __forceinline__ void load_values(ValueRegs& r, const kvlinc_cache& c, long long gbase, int lane) {
-  const uint32_t* rec = c.groups + gbase * kRecordWords;
+__device__ __forceinline__ void load_values(ValueRegs& r, const uint32_t* __restrict__ rec, int lane) {
   const uint4* vt = reinterpret_cast<const uint4*>(rec + kRecValueTile);
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf)
@@ -175,7 +171,10 @@ struct WaveState {
   float m[NB][4];       // running maximum per head (wave-uniform), log2 domain
   float l[NB][4];       // per-lane partial sums of p
   float pz[NB][4];      // per-lane partial sums of the zero-point / centring terms of E V
-  float4_t acc[NB][2];  // E V in raw matrix-core units: [head block][channel half], rows = heads, lane = channel
+  // E V in raw matrix-core units: [head block][token half][channel half], rows = heads, lane = channel.  The two
+  // token halves accumulate separately so that four independent dependency chains are in flight.
+  float4_t acc[NB][2][2];
+  float4_t accw[NB][2];  // E V of fp16 window tokens in true units: [head block][channel half]
 };
 
 // Per-lane constants of a wave.
@@ -222,32 +221,38 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const uint
     bias[nb][2] = dpp_f<0xAA>(b);
     bias[nb][3] = dpp_f<0xFF>(b);
   }
+  // four independent accumulation chains per head block: (token half) x (word quad)
+  float4_t acc[NB][2][2];
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf) {
-    float4_t acc0[NB], acc1[NB];
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) { acc0[nb] = bias[nb]; acc1[nb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
+    for (int hf = 0; hf < 2; ++hf) { acc[nb][hf][0] = bias[nb]; acc[nb][hf][1] = float4_t{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const uint32_t words[4] = {g.kw[hf][i].x, g.kw[hf][i].y, g.kw[hf][i].z, g.kw[hf][i].w};
+  for (int w = 0; w < 4; ++w) {
+    uint32_t u[2][2][8];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        uint32_t u[8];
-        unpack_word(words[w], u);
+    for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int mstep = 0; mstep < 4; ++mstep) {
-          const half4_t bop = as_h4(u[2 * mstep], u[2 * mstep + 1]);
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb) {
-            if (i == 0) acc0[nb] = mfma_bcast(A[nb][0], bop, acc0[nb], 4 * w + mstep);
-            else acc1[nb] = mfma_bcast(A[nb][1], bop, acc1[nb], 4 * w + mstep);
-          }
-        }
+      for (int i = 0; i < 2; ++i) {
+        const uint32_t words[4] = {g.kw[hf][i].x, g.kw[hf][i].y, g.kw[hf][i].z, g.kw[hf][i].w};
+        unpack_word(words[w], u[hf][i]);
       }
-    }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) sc[nb][hf] = (acc0[nb] + acc1[nb]) * (kRawScale * kAlpha);
+    for (int mstep = 0; mstep < 4; ++mstep)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const half4_t bop = as_h4(u[hf][i][2 * mstep], u[hf][i][2 * mstep + 1]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[nb][hf][i] = mfma_bcast(A[nb][i], bop, acc[nb][hf][i], 4 * w + mstep);
+        }
   }
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) sc[nb][hf] = (acc[nb][hf][0] + acc[nb][hf][1]) * (kRawScale * kAlpha);
   if (valid < kGroup) {  // partial last group: tokens >= valid do not exist
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -257,28 +262,31 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const uint
   }
 }
 
-// Running maximum (Alg. 1 line 8); the accumulated state is rescaled only when a maximum moved.
+// Reference maximum (Alg. 1 line 8).  Any wave-uniform reference m works as long as 2^(x - m) stays inside the fp16
+// range, so the reference is only raised -- with a full cross-lane maximum and a rescale of the accumulated state --
+// when some score of the group exceeds it by more than kSlack; most groups pay one comparison per register.
+constexpr float kSlack = 5.0f;
 template <int NB>
-__device__ __forceinline__ void update_max(const float4_t (&sc)[NB][2], WaveState<NB>& st) {
+__device__ __forceinline__ void update_reference(const float4_t (&sc)[NB][2], WaveState<NB>& st) {
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    float mx[4];
-    bool moved = false;
+    bool over = false;
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      mx[h] = wave_allmax(fmaxf(sc[nb][0][h], sc[nb][1][h]));
-      mx[h] = fmaxf(mx[h], st.m[nb][h]);
-      moved |= mx[h] != st.m[nb][h];
-    }
-    if (__builtin_amdgcn_readfirstlane((int)moved)) {
+    for (int h = 0; h < 4; ++h) over |= fmaxf(sc[nb][0][h], sc[nb][1][h]) > st.m[nb][h] + kSlack;
+    if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
       for (int h = 0; h < 4; ++h) {
-        const float f = exp2f(st.m[nb][h] - mx[h]);  // 0 when the old maximum is -inf
+        const float mx = fmaxf(wave_allmax(fmaxf(sc[nb][0][h], sc[nb][1][h])), st.m[nb][h]);
+        const float f = exp2f(st.m[nb][h] - mx);  // 0 when the old reference is -inf
         st.l[nb][h] *= f;
         st.pz[nb][h] *= f;
-        st.acc[nb][0][h] *= f;
-        st.acc[nb][1][h] *= f;
-        st.m[nb][h] = mx[h];
+        st.acc[nb][0][0][h] *= f;
+        st.acc[nb][0][1][h] *= f;
+        st.acc[nb][1][0][h] *= f;
+        st.acc[nb][1][1][h] *= f;
+        st.accw[nb][0][h] *= f;
+        st.accw[nb][1][h] *= f;
+        st.m[nb][h] = mx;
       }
     }
   }
@@ -288,13 +296,13 @@ __device__ __forceinline__ void update_max(const float4_t (&sc)[NB][2], WaveStat
 template <int NB>
 __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc)[NB][2], const LaneConst& lc,
                                          WaveState<NB>& st) {
+  half4_t A2[NB][2];
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
     const float vs = h2f((uint16_t)(g.sz[hf] & 0xFFFFu));
     const float vmid = h2f((uint16_t)(g.sz[hf] >> 16)) + 1.5f * vs;
     const float vsg = vs * lc.vgain;       // value scale with the k-slot gain of this lane's token
     const float comp = -1.5f / lc.vgain;   // exact (power of two times 1.5)
-    half4_t A2[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float p[4], ps[4];
@@ -320,46 +328,331 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc
       const bool upper = (lc.lane & 2) != 0;
       const uint32_t U = upper ? Y2 : X1;
       const uint32_t W = upper ? Y1 : X2;
-      A2[nb] = as_h4(U, W);
+      A2[nb][hf] = as_h4(U, W);
     }
+  }
+  // four independent accumulation chains per head block: (token half) x (channel half)
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint32_t u[2][2][8];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const uint32_t words[4] = {g.vw[hf][ch].x, g.vw[hf][ch].y, g.vw[hf][ch].z, g.vw[hf][ch].w};
+        unpack_word(words[w], u[hf][ch]);
+      }
+#pragma unroll
+    for (int mstep = 0; mstep < 4; ++mstep)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int ch = 0; ch < 2; ++ch) {
+          const half4_t bop = as_h4(u[hf][ch][2 * mstep], u[hf][ch][2 * mstep + 1]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            st.acc[nb][hf][ch] = mfma_bcast(A2[nb][hf], bop, st.acc[nb][hf][ch], 4 * w + mstep);
+        }
+  }
+}
+
+// ---- half of the fp16 window as one more block of 64 tokens of one wave (raw keys, rotated values) ---------------
+
+template <int NB>
+__device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t* __restrict__ q, int bh, int b, int g,
+                                            int gq, int half, int nr, const LaneConst& lc, WaveState<NB>& st) {
+  const int lane = lc.lane;
+  const int quad = lane >> 2, hrow = lane & 3;
+  // 16 x 16 B of this lane's key row now; 32 x 8 B of this lane's two value channels once the keys are consumed
+  const int tok = 64 * half + lane;
+  const int row = tok < c.R ? tok : c.R - 1;  // rows beyond the capacity do not exist; their scores are masked below
+  const uint4* krow = reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(c.k_res) +
+                                                     ((long long)bh * c.R + row) * kHeadDim);
+  uint4 kx[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) kx[i] = krow[i];
+  const uint2* vbase = reinterpret_cast<const uint2*>(reinterpret_cast<const half_t*>(c.v_res) +
+                                                      (long long)bh * c.R * kHeadDim);
+  const int n_blocks = c.R / 4;
+  // A operand of q K^T: raw q of this lane's head, channels 8*quad .. 8*quad+7
+  half4_t A[NB][2];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int h = nb * 4 + hrow;
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + 8 * quad);
+    A[nb][0] = as_h4(raw.x, raw.y);
+    A[nb][1] = as_h4(raw.z, raw.w);
+  }
+  float4_t acc[NB][2][2];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int a = 0; a < 2; ++a) acc[nb][a][0] = acc[nb][a][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const half4_t b0 = as_h4(kx[i].x, kx[i].y), b1 = as_h4(kx[i].z, kx[i].w);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      acc[nb][0][i & 1] = mfma_bcast(A[nb][0], b0, acc[nb][0][i & 1], i);
+      acc[nb][1][i & 1] = mfma_bcast(A[nb][1], b1, acc[nb][1][i & 1], i);
+    }
+  }
+  float4_t sc[NB][2];
+  const float4_t ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    sc[nb][0] = (acc[nb][0][0] + acc[nb][0][1] + acc[nb][1][0] + acc[nb][1][1]) * kAlpha;
+    if (tok >= nr) sc[nb][0] = ninf;
+    sc[nb][1] = ninf;
+  }
+  uint2 vx[2][16];
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+    for (int bq = 0; bq < 16; ++bq) {
+      const int blk = 16 * half + bq;
+      vx[ch][bq] = blk < n_blocks ? vbase[(long long)blk * kHeadDim + 64 * ch + lane] : make_uint2(0, 0);
+    }
+  update_reference<NB>(sc, st);
+  half4_t A2[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float p[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      p[h] = __builtin_amdgcn_exp2f(sc[nb][0][h] - st.m[nb][h]);
+      st.l[nb][h] += p[h];
+    }
+    const half2_t x01 = {(half_t)p[0], (half_t)p[1]}, x23 = {(half_t)p[2], (half_t)p[3]};
+    const uint32_t X = as_u32(x01), Y = as_u32(x23);
+    const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
+    const uint32_t X1 = __builtin_amdgcn_perm(TX, X, lc.perm_sel);
+    const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, lc.perm_sel);
+    const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
+    const bool upper = (lane & 2) != 0;
+    A2[nb] = as_h4(upper ? Y2 : X1, upper ? Y1 : X2);
+  }
+#pragma unroll
+  for (int bq = 0; bq < 16; ++bq)
 #pragma unroll
     for (int ch = 0; ch < 2; ++ch) {
-      const uint32_t words[4] = {g.vw[hf][ch].x, g.vw[hf][ch].y, g.vw[hf][ch].z, g.vw[hf][ch].w};
+      const half4_t bop = as_h4(vx[ch][bq].x, vx[ch][bq].y);
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        uint32_t u[8];
-        unpack_word(words[w], u);
+      for (int nb = 0; nb < NB; ++nb) st.accw[nb][ch] = mfma_bcast(A2[nb], bop, st.accw[nb][ch], bq);
+    }
+}
+
+// ---- correction terms (Sec. 3.3: C_n = phi_q(q) S, C_d = phi_q(q) P; Eq. 6 for phi) -----------------------------------
+// The logits q W_1, q W_2 of every (sequence, query head) come from a small kernel of their own (the adapters are
+// shared by all sequences, so they are read once there instead of once per sequence).  In the main kernel the work of
+// one (sequence, kv head) is cut into four parts over the rows of S: part r covers the 64 features 64 (r % 2) .. + 63
+// of half hs = r / 2 of phi.  A part exponentiates its logits against its own maximum m_r and leaves the softmax
+// normalisation of the half to the merge:
+//     e_f = exp(logit_f - m_r),  Z_r = sum_f e_f,  Cn_r = sum_f e_f S[f],  Cd_r = sum_f e_f P[f].
+// Output per (query head, part): {Cd_r, m_r, Z_r, -, Cn_r[128]}.
+// A wave owns 32 output channels (lane = 4 channels x 8 features), reduces with shuffles and needs no barrier.
+
+__device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes that differ in bits 3..5
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+#ifdef KV_EXP_TIMING
+__device__ unsigned long long kv_dbg[8 * 4096];
+__device__ unsigned long long kv_dbg2[8 * 4096];
+#define KV_T(var) const long long var = clock64()
+#else
+#define KV_T(var)
+#endif
+
+constexpr int kCorrParts = 4;
+
+// launch 0: logits[b][h][f] = sum_c q[b][h][c] W[h][f / 128][c][f % 128], f = 0..255, binary32.
+// One workgroup per (query head, half, 4 sequences): thread = (chunk of 8 features, group of 8 channels).
+constexpr int kPhiSeqs = 4;
+__global__ __launch_bounds__(kThreads) void decode_logits_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+                                                                  float* __restrict__ logits) {
+  __shared__ float sPart[kWaves][kPhiSeqs][kHeadDim];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n_bq = (c.B + kPhiSeqs - 1) / kPhiSeqs;
+  const int bq = blockIdx.x % n_bq;
+  const int hs = (blockIdx.x / n_bq) & 1;
+  const int h = blockIdx.x / (2 * n_bq);
+  const int chunk = tid & 15, rowgrp = tid >> 4;  // 16 chunks x 8 features, 16 groups x 8 channels
+  const half_t* W = reinterpret_cast<const half_t*>(c.Wq) + ((long long)h * 2 + hs) * kHeadDim * (kRank / 2) +
+                    (long long)rowgrp * 8 * (kRank / 2) + 8 * chunk;
+  uint4 raw[8], qraw[kPhiSeqs];
 #pragma unroll
-        for (int mstep = 0; mstep < 4; ++mstep) {
-          const half4_t bop = as_h4(u[2 * mstep], u[2 * mstep + 1]);
+  for (int rb = 0; rb < 8; ++rb) raw[rb] = *reinterpret_cast<const uint4*>(W + rb * (kRank / 2));
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) st.acc[nb][ch] = mfma_bcast(A2[nb], bop, st.acc[nb][ch], 4 * w + mstep);
-        }
-      }
+  for (int s = 0; s < kPhiSeqs; ++s) {
+    const int b = min(bq * kPhiSeqs + s, c.B - 1);  // past the batch: repeat the last sequence (result unused)
+    qraw[s] = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + h) * kHeadDim + 8 * rowgrp);
+  }
+  float acc[kPhiSeqs][8];
+#pragma unroll
+  for (int s = 0; s < kPhiSeqs; ++s)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[s][i] = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < 8; ++rb) {
+    const half_t* hv = reinterpret_cast<const half_t*>(&raw[rb]);
+#pragma unroll
+    for (int s = 0; s < kPhiSeqs; ++s) {
+      const float qf = (float)reinterpret_cast<const half_t*>(&qraw[s])[rb];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[s][i] = fmaf(qf, (float)hv[i], acc[s][i]);
+    }
+  }
+  // sum over the 16 channel groups: 4 inside the wave (lanes that differ in bits 4, 5), then across the 4 waves
+#pragma unroll
+  for (int s = 0; s < kPhiSeqs; ++s)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float v = acc[s][i];
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      if (lane < 16) sPart[wave][s][8 * chunk + i] = v;
+    }
+  __syncthreads();
+  for (int idx = tid; idx < kPhiSeqs * kHeadDim; idx += kThreads) {
+    const int s = idx >> 7, f = idx & 127;
+    const int b = bq * kPhiSeqs + s;
+    if (b < c.B)
+      logits[((long long)b * c.H_q + h) * kRank + hs * 128 + f] =
+          sPart[0][s][f] + sPart[1][s][f] + sPart[2][s][f] + sPart[3][s][f];
+  }
+}
+
+// Operands of one correction part in registers: requested early, consumed later.  NH = 4 NB heads are processed
+// together so that their cross-lane reductions overlap; heads beyond gq repeat the last one and are not written.
+template <int NH>
+struct CorrRegs {
+  float4 s4[8];       // S slice: 8 features x 4 channels of this lane
+  float pf;           // P entry of feature `lane` of the part
+  float mine[NH];     // logit of feature `lane` of the part, per head
+  float4 la[NH], lb[NH];  // logits of this lane's 8 features, per head
+};
+
+template <int NH>
+__device__ __forceinline__ void corr_request(CorrRegs<NH>& R, const kvlinc_cache& c, const float* __restrict__ logits,
+                                             int gq, int bh, int r, int lane, int wave) {
+  const int b = bh / c.H_kv, g = bh % c.H_kv;
+  const int hs = r >> 1, fpart = 64 * (r & 1);
+  const int c0 = 32 * wave + 4 * (lane & 7), fB = 8 * (lane >> 3);
+  const float* S = c.S + ((long long)bh * kRank + 128 * hs + fpart + fB) * kHeadDim + c0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) R.s4[i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
+  R.pf = c.P[(long long)bh * kRank + 128 * hs + fpart + lane];
+  const float* lg0 = logits + ((long long)b * c.H_q + g * gq) * kRank + hs * 128 + fpart;
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    const float* lg = lg0 + (long long)(h < gq ? h : gq - 1) * kRank;
+    R.mine[h] = lg[lane];
+    R.la[h] = *reinterpret_cast<const float4*>(lg + fB);
+    R.lb[h] = *reinterpret_cast<const float4*>(lg + fB + 4);
+  }
+}
+
+template <int NH>
+__device__ __forceinline__ void corr_compute(const CorrRegs<NH>& R, const kvlinc_cache& c, float* __restrict__ corr,
+                                             int gq, int bh, int r, int lane, int wave) {
+  const int b = bh / c.H_kv, g = bh % c.H_kv;
+  const int c0 = 32 * wave + 4 * (lane & 7);
+  const bool writer = (lane >> 3) == 0;
+  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
+  float mx[NH], z[NH], cd[NH], acc[NH][4];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) mx[h] = wave_allmax(R.mine[h]);
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    const float e_mine = __expf(R.mine[h] - mx[h]);
+    z[h] = e_mine;
+    cd[h] = e_mine * R.pf;
+  }
+#pragma unroll
+  for (int h = 0; h < NH; ++h) { z[h] = wave_allsum(z[h]); cd[h] = wave_allsum(cd[h]); }
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    const float e[8] = {__expf(R.la[h].x - mx[h]), __expf(R.la[h].y - mx[h]), __expf(R.la[h].z - mx[h]),
+                        __expf(R.la[h].w - mx[h]), __expf(R.lb[h].x - mx[h]), __expf(R.lb[h].y - mx[h]),
+                        __expf(R.lb[h].z - mx[h]), __expf(R.lb[h].w - mx[h])};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[h][0] = fmaf(e[i], R.s4[i].x, acc[h][0]);
+      acc[h][1] = fmaf(e[i], R.s4[i].y, acc[h][1]);
+      acc[h][2] = fmaf(e[i], R.s4[i].z, acc[h][2]);
+      acc[h][3] = fmaf(e[i], R.s4[i].w, acc[h][3]);
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[h][j] = xor_allsum_8rows(acc[h][j]);
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    if (h < gq) {
+      float* dst = out0 + ((long long)h * kCorrParts + r) * kPartStride;
+      if (wave == 0 && lane == 0) { dst[0] = cd[h]; dst[1] = mx[h]; dst[2] = z[h]; }
+      if (writer) *reinterpret_cast<float4*>(dst + 4 + c0) = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
     }
   }
 }
 
-// ---- work item 1: a range of quantized groups of one (sequence, kv head) ----------------------------------------
+// A sequence without quantized tokens has empty states: its parts are written as zeros and S, P are not read.
+__device__ __forceinline__ void correction_part_empty(const kvlinc_cache& c, float* __restrict__ corr, int gq, int bh,
+                                                      int r) {
+  const int b = bh / c.H_kv, g = bh % c.H_kv;
+  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
+  for (int i = threadIdx.x; i < gq * kPartStride; i += kThreads)
+    out0[((long long)(i / kPartStride) * kCorrParts + r) * kPartStride + i % kPartStride] = 0.f;
+}
+
+// ---- launch 1 -------------------------------------------------------------------------------------------------------
+
+
 
 template <int NB>
-__device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* __restrict__ q, float* __restrict__ part,
-                                           int n_splits, int gq, int bh, int sp, float* lds) {
-  float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                       // [kWaves][NB*4]
-  float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);     // [kWaves][NB*4]
-  float (*sAcc)[NB * 4][kHeadDim] = reinterpret_cast<float (*)[NB * 4][kHeadDim]>(lds + 2 * kWaves * NB * 4);
+__global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+                                                                   float* __restrict__ part, float* __restrict__ corr,
+                                                                   const float* __restrict__ logits, int n_splits,
+                                                                   int gq, int dbg_skip) {
+  __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int bh = blockIdx.x / n_splits;
+  const int sp = blockIdx.x % n_splits;
   const int b = bh / c.H_kv;
   const int g = bh % c.H_kv;
   const int nq = c.n_quant[b];
+  const int nr = c.n_res[b];
   const int n_groups = (nq + kGroup - 1) / kGroup;
   const int g0 = (int)((long long)n_groups * sp / n_splits);
   const int g1 = (int)((long long)n_groups * (sp + 1) / n_splits);
-  const int items_per_bh = n_splits + 1;
 
+  // this wave's groups: g0 + wave, g0 + wave + 4, ...
+  const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
+  const int first = g0 + wave;
+  const int n_mine = first < g1 ? (g1 - first + kWaves - 1) / kWaves : 0;
+  KeyRegs kr;
+  ValueRegs vr;
+  if (n_mine > 0) {
+    load_keys(kr, rec0 + (long long)first * kRecordWords, lane);
+    load_values(vr, rec0 + (long long)first * kRecordWords, lane);
+  }
+  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0 && !(dbg_skip & 1);
+  if (corr != nullptr && nq == 0)
+    for (int r = sp; r < kCorrParts; r += n_splits) correction_part_empty(c, corr, gq, bh, r);
+
+  // per-lane constants
   const int quad = lane >> 2, hrow = lane & 3;
   const int j0 = 2 * (quad & 3), j1 = j0 + 1;  // pairs feeding this quad's k slots (0,1) and (2,3)
   const float gain0 = pair_gain(j0), gain1 = pair_gain(j1);
@@ -370,58 +663,69 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
   lc.perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
   lc.lane = lane;
 
-  // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
-  // heads beyond gq read as 0
-  uint32_t Qs[NB][4];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int h = nb * 4 + hrow;
-    uint4 raw = make_uint4(0, 0, 0, 0);
-    if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + 8 * quad);
-    const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const half_t gn = (half_t)((i & 1) ? gain1 : gain0);
-      const half2_t g2 = {gn, gn};
-      Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
-    }
-  }
-
   WaveState<NB> st;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
     for (int h = 0; h < 4; ++h) { st.m[nb][h] = -INFINITY; st.l[nb][h] = 0.f; st.pz[nb][h] = 0.f; }
-    st.acc[nb][0] = float4_t{0.f, 0.f, 0.f, 0.f};
-    st.acc[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
-  }
-
-  // This wave's groups.  The key part of the next group is requested as soon as q K^T has consumed the current
-  // one and flies during E V; the value part likewise flies during the next q K^T.  Past the end the current
-  // (cached) group is requested again, so that no branch joins between a load and its first use.
-  const long long tile0 = (long long)bh * c.max_groups;
-  int grp = g0 + wave;
-  if (grp < g1) {
-    KeyRegs kr;
-    ValueRegs vr;
-    load_keys(kr, c, tile0 + grp, lane);
-    load_values(vr, c, tile0 + grp, lane);
-    while (true) {
-      const int nxt = grp + kWaves;
-      const bool more = nxt < g1;
-      const long long nbase = tile0 + (more ? nxt : grp);
-      float4_t sc[NB][2];
-      qk_phase<NB>(kr, min(kGroup, nq - grp * kGroup), Qs, lc, sc);
-      load_keys(kr, c, nbase, lane);
-      update_max<NB>(sc, st);
-      pv_phase<NB>(vr, sc, lc, st);
-      load_values(vr, c, nbase, lane);
-      if (!more) break;
-      grp = nxt;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      st.accw[nb][hf] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) st.acc[nb][hf][ch] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
   }
 
+  // halves of the fp16 window: half hw belongs to wave 3 of split n_splits-1-hw (to waves 3 and 2 of the only split)
+  {
+    const int hw = n_splits >= 2 ? (n_splits - 1 - sp) : (3 - wave);
+    const int owner_wave = n_splits >= 2 ? 3 : wave;
+    if (hw >= 0 && hw < 2 && wave == owner_wave && nr > 64 * hw && !(dbg_skip & 2))
+      window_half<NB>(c, q, bh, b, g, gq, hw, nr, lc, st);
+  }
+
+  KV_T(t_c);
+  if (n_mine > 0 && !(dbg_skip & 4)) {
+    // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
+    // heads beyond gq read as 0
+    uint32_t Qs[NB][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int h = nb * 4 + hrow;
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + 8 * quad);
+      const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const half_t gn = (half_t)((i & 1) ? gain1 : gain0);
+        const half2_t g2 = {gn, gn};
+        Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
+      }
+    }
+    // Past the last group the current (cached) record is requested once more, so that no branch joins between a
+    // request and its first use and the waits stay partial.
+    for (int i = 0; i < n_mine; ++i) {
+      const int grp = first + i * kWaves;
+      const uint32_t* nxt = rec0 + (long long)(i + 1 < n_mine ? grp + kWaves : grp) * kRecordWords;
+      float4_t sc[NB][2];
+      qk_phase<NB>(kr, min(kGroup, nq - grp * kGroup), Qs, lc, sc);
+      load_keys(kr, nxt, lane);
+      update_reference<NB>(sc, st);
+      pv_phase<NB>(vr, sc, lc, st);
+      load_values(vr, nxt, lane);
+    }
+  }
+  if (has_corr) {
+    for (int r = sp; r < kCorrParts; r += n_splits) {
+      CorrRegs<4 * NB> cregs;
+      corr_request<4 * NB>(cregs, c, logits, gq, bh, r, lane, wave);
+      corr_compute<4 * NB>(cregs, c, corr, gq, bh, r, lane, wave);
+    }
+  }
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
+  float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                    // [kWaves][NB*4]
+  float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);  // [kWaves][NB*4]
+  float (*sAcc)[NB * 4][kHeadDim] = reinterpret_cast<float (*)[NB * 4][kHeadDim]>(lds + 2 * kWaves * NB * 4);
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -429,8 +733,9 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
       const float l = wave_allsum(st.l[nb][h]);
       const float pz = wave_allsum(st.pz[nb][h]);
       if (lane == 0) { sM[wave][nb * 4 + h] = st.m[nb][h]; sL[wave][nb * 4 + h] = l; }
-      sAcc[wave][nb * 4 + h][lane] = st.acc[nb][0][h] * kRawScale + pz;
-      sAcc[wave][nb * 4 + h][64 + lane] = st.acc[nb][1][h] * kRawScale + pz;
+      sAcc[wave][nb * 4 + h][lane] = (st.acc[nb][0][0][h] + st.acc[nb][1][0][h]) * kRawScale + pz + st.accw[nb][0][h];
+      sAcc[wave][nb * 4 + h][64 + lane] =
+          (st.acc[nb][0][1][h] + st.acc[nb][1][1][h]) * kRawScale + pz + st.accw[nb][1][h];
     }
   __syncthreads();
   for (int idx = tid; idx < gq * kHeadDim; idx += kThreads) {
@@ -442,273 +747,18 @@ __device__ __forceinline__ void group_item(const kvlinc_cache& c, const half_t* 
     if (M != -INFINITY) {
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
-        const float f = exp2f(sM[w][h] - M);
+        const float f = exp2f(sM[w][h] - M);  // 0 for a wave without tokens
         a = fmaf(f, sAcc[w][h][ch], a);
         l = fmaf(f, sL[w][h], l);
       }
     }
-    float* dst = part + (((long long)b * c.H_q + g * gq + h) * items_per_bh + sp) * kPartStride;
+    float* dst = part + (((long long)b * c.H_q + g * gq + h) * n_splits + sp) * kPartStride;
     if (ch == 0) { dst[0] = M; dst[1] = l; }
     dst[4 + ch] = a;
   }
 }
 
-// ---- work item 2: the fp16 window of one (sequence, kv head): raw keys, rotated values ---------------------------
-// thread = (token or channel, head half): heads 4*hh .. 4*hh+3
-
-__device__ __forceinline__ void window_item(const kvlinc_cache& c, const half_t* __restrict__ q, float* __restrict__ part,
-                                            int n_splits, int gq, int bh, float* lds) {
-  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);            // [8][128] alpha * q
-  float (*sP)[kGroup] = reinterpret_cast<float (*)[kGroup]>(lds + 8 * kHeadDim);  // [8][128]
-  float* sRed = lds + 16 * kHeadDim;                                             // [8][2]
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int tok = tid & 127, hh = tid >> 7;
-  const int b = bh / c.H_kv;
-  const int g = bh % c.H_kv;
-  const int nr = c.n_res[b];
-  const int items_per_bh = n_splits + 1;
-
-  for (int i = tid; i < gq * kHeadDim; i += kThreads)
-    sQ[i >> 7][i & 127] = kAlpha * (float)q[((long long)b * c.H_q + g * gq) * kHeadDim + i];
-  __syncthreads();
-
-  const half_t* kw = reinterpret_cast<const half_t*>(c.k_res) + (long long)bh * c.R * kHeadDim;
-  const half_t* vw = reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim;
-  float x[4] = {0.f, 0.f, 0.f, 0.f};
-  if (tok < nr && 4 * hh < gq) {
-    const half_t* row = kw + (long long)tok * kHeadDim;
-#pragma unroll 4
-    for (int ch = 0; ch < kHeadDim; ch += 8) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(row + ch);
-      const half_t* hv = reinterpret_cast<const half_t*>(&raw);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float kv = (float)hv[i];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = fmaf(sQ[4 * hh + j][ch + i], kv, x[j]);
-      }
-    }
-  }
-  float m[4], l[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (tok >= nr) x[j] = -INFINITY;
-    const float r = wave_allmax(x[j]);
-    if (lane == 0) sRed[(4 * hh + j) * 2 + (wave & 1)] = r;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    m[j] = fmaxf(sRed[(4 * hh + j) * 2], sRed[(4 * hh + j) * 2 + 1]);
-    const float p = (nr > 0) ? exp2f(x[j] - m[j]) : 0.f;
-    sP[4 * hh + j][tok] = p;
-    l[j] = wave_allsum(p);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (lane == 0) sRed[(4 * hh + j) * 2 + (wave & 1)] = l[j];
-  __syncthreads();
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  if (4 * hh < gq) {
-    for (int t = 0; t < nr; ++t) {
-      const float vv = (float)vw[((long long)(t >> 2) * kHeadDim + tok) * 4 + (t & 3)];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[j] = fmaf(sP[4 * hh + j][t], vv, acc[j]);
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int h = 4 * hh + j;
-    if (h >= gq) continue;
-    float* dst = part + (((long long)b * c.H_q + g * gq + h) * items_per_bh + n_splits) * kPartStride;
-    if (tok == 0) { dst[0] = nr > 0 ? m[j] : -INFINITY; dst[1] = sRed[h * 2] + sRed[h * 2 + 1]; }
-    dst[4 + tok] = acc[j];
-  }
-}
-
-// ---- work item 3: correction terms of one (sequence, kv head): phi_q(q), C_n = phi_q S, C_d = phi_q P -------------
-// (Sec. 3.3: computed before the merge; Eq. 6 for phi.)  Output per query head: {C_d, -, -, -, C_n[128]}.
-// Both products are laid out so that a wave owns complete output columns (all rows of the contraction), reduces
-// with shuffles and needs no cross-wave traffic; loads are issued in batches of eight 16-byte requests per lane.
-
-__device__ __forceinline__ float xor_allsum_16rows(float v) {  // sum over lanes that differ in bits 2..5
-  v += dpp_f<kRowRor4>(v);
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
-__device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes that differ in bits 3..5
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
-
-__device__ __forceinline__ void correction_item(const kvlinc_cache& c, const half_t* __restrict__ q,
-                                                float* __restrict__ corr, int gq, int bh, float* lds) {
-  float (*sQ)[kHeadDim] = reinterpret_cast<float (*)[kHeadDim]>(lds);             // [8][128] raw q
-  float (*sPhi)[kRank] = reinterpret_cast<float (*)[kRank]>(lds + 8 * kHeadDim);  // [8][256] logits, then phi
-  float* sSmall = lds + 8 * kHeadDim + 8 * kRank;                                 // [64]
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int b = bh / c.H_kv;
-  const int g = bh % c.H_kv;
-  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kPartStride;
-  if (c.n_quant[b] == 0) {  // states are empty: no correction (and S, P need not be read)
-    for (int i = tid; i < gq * kPartStride; i += kThreads) out0[i] = 0.f;
-    return;
-  }
-  for (int i = tid; i < gq * kHeadDim; i += kThreads)
-    sQ[i >> 7][i & 127] = (float)q[((long long)b * c.H_q + g * gq) * kHeadDim + i];
-  __syncthreads();
-
-  // phase 1: logit[h][hs][f] = sum_c q[h][c] W[h][hs][c][f].  Wave w owns features 32w .. 32w+31 of each half;
-  // lane = (chunk of 8 features, group of 8 channels).
-  {
-    const int chunk = lane & 3, rowgrp = lane >> 2;
-    const int f0 = 32 * wave + 8 * chunk;
-    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wq) + (long long)g * gq * 2 * kHeadDim * (kRank / 2) +
-                       (long long)rowgrp * 8 * (kRank / 2) + f0;
-    // batches of eight 16-byte requests per lane, the next batch always in flight while the current one is reduced
-    uint4 raw[2][8];
-#pragma unroll
-    for (int rb = 0; rb < 8; ++rb) raw[0][rb] = *reinterpret_cast<const uint4*>(W0 + rb * (kRank / 2));
-    const int n_batches = 2 * gq;  // hb = 2 h + hs
-    for (int hb0 = 0; hb0 < n_batches; hb0 += 2) {
-#pragma unroll
-      for (int par = 0; par < 2; ++par) {
-        const int hb = hb0 + par;
-        const int nb = hb + 1 < n_batches ? hb + 1 : hb;  // past the end: re-request the current, cached batch
-        const half_t* Wn = W0 + (long long)nb * kHeadDim * (kRank / 2);
-#pragma unroll
-        for (int rb = 0; rb < 8; ++rb) raw[par ^ 1][rb] = *reinterpret_cast<const uint4*>(Wn + rb * (kRank / 2));
-        float acc[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-#pragma unroll
-        for (int rb = 0; rb < 8; ++rb) {
-          const float qv = sQ[hb >> 1][rowgrp * 8 + rb];
-          const half_t* hv = reinterpret_cast<const half_t*>(&raw[par][rb]);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc[i] = fmaf(qv, (float)hv[i], acc[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = xor_allsum_16rows(acc[i]);
-        if (rowgrp == 0) {
-          float* dst = &sPhi[hb >> 1][(hb & 1) * 128 + f0];
-          *reinterpret_cast<float4*>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-          *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        }
-      }
-    }
-  }
-  __syncthreads();
-  // softmax over each half (128 features) of each head: one wave per row at a time
-  for (int row = wave; row < 2 * gq; row += kWaves) {
-    float* p = &sPhi[row >> 1][(row & 1) * 128];
-    const float a0 = p[lane], a1 = p[lane + 64];
-    const float mx = wave_allmax(fmaxf(a0, a1));
-    const float e0 = __expf(a0 - mx), e1 = __expf(a1 - mx);
-    const float inv = 1.0f / wave_allsum(e0 + e1);
-    p[lane] = e0 * inv;
-    p[lane + 64] = e1 * inv;
-  }
-  __syncthreads();
-
-  // phase 2: C_n[h][c] = sum_f phi[h][f] S[f][c].  Wave w owns channels 32w .. 32w+31; lane = (chunk of 4
-  // channels, group of 32 features).  S is read once for all heads.
-  {
-    const int chunk = lane & 7, rowgrp = lane >> 3;
-    const int c0 = 32 * wave + 4 * chunk;
-    const float* S = c.S + (long long)bh * kRank * kHeadDim + (long long)rowgrp * 32 * kHeadDim + c0;
-    float acc[kMaxGq][4];
-#pragma unroll
-    for (int h = 0; h < kMaxGq; ++h)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
-    float4 s4[2][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) s4[0][i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
-#pragma unroll
-    for (int bt = 0; bt < 4; ++bt) {
-      const int i0 = 8 * bt;
-      if (bt < 3) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          s4[(bt & 1) ^ 1][i] = *reinterpret_cast<const float4*>(S + (long long)(i0 + 8 + i) * kHeadDim);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float4 sv = s4[bt & 1][i];
-#pragma unroll
-        for (int h = 0; h < kMaxGq; ++h) {
-          if (h < gq) {
-            const float ph = sPhi[h][rowgrp * 32 + i0 + i];
-            acc[h][0] = fmaf(ph, sv.x, acc[h][0]);
-            acc[h][1] = fmaf(ph, sv.y, acc[h][1]);
-            acc[h][2] = fmaf(ph, sv.z, acc[h][2]);
-            acc[h][3] = fmaf(ph, sv.w, acc[h][3]);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < kMaxGq; ++h) {
-      if (h < gq) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[h][j] = xor_allsum_8rows(acc[h][j]);
-        if (rowgrp == 0)
-          *reinterpret_cast<float4*>(out0 + (long long)h * kPartStride + 4 + c0) =
-              make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
-      }
-    }
-    // C_d[h] = sum_f phi[h][f] P[f]
-    const float pf = c.P[(long long)bh * kRank + tid];
-    for (int h = 0; h < gq; ++h) {
-      const float v = wave_allsum(sPhi[h][tid] * pf);
-      if (lane == 0) sSmall[h * kWaves + wave] = v;
-    }
-    __syncthreads();
-    if (tid < gq) {
-      float cd = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) cd += sSmall[tid * kWaves + w];
-      out0[(long long)tid * kPartStride] = cd;
-    }
-  }
-}
-
-constexpr int kLdsFloats = 2 * kWaves * 8 + kWaves * 8 * kHeadDim;  // the group item with two head blocks (largest)
-
-// blockIdx: [0, BH) correction items (only with adapters), then BH window items, then BH * n_splits group items.
-template <int NB>
-__global__ __launch_bounds__(kThreads, NB == 1 ? 4 : 3) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
-                                                                float* __restrict__ part, float* __restrict__ corr,
-                                                                int n_splits, int gq, int dbg_skip) {
-  __shared__ __align__(16) float lds[kLdsFloats];
-  static_assert(kLdsFloats >= 2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim, "group item LDS");
-  static_assert(kLdsFloats >= 8 * kHeadDim + 8 * kRank + 64, "correction item LDS");
-  static_assert(kLdsFloats >= 16 * kHeadDim + 16, "window item LDS");
-  const int BH = c.B * c.H_kv;
-  int item = blockIdx.x;
-  if (corr != nullptr) {
-    if (item < BH) { if (!(dbg_skip & 1)) correction_item(c, q, corr, gq, item, lds); return; }
-    item -= BH;
-  }
-  if (item < BH) { if (!(dbg_skip & 2)) window_item(c, q, part, n_splits, gq, item, lds); return; }
-  item -= BH;
-  if (dbg_skip & 4) return;
-  group_item<NB>(c, q, part, n_splits, gq, item / n_splits, item % n_splits, lds);
-}
-
-// ---- launch 2: merge the blocks, add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5; Sec. 3.1) ---------------
+// ---- launch 2: merge the splits, add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5; Sec. 3.1) -----------------
 // one wave per (sequence, query head); lane l owns channels 2l and 2l+1
 
 __global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, const float* __restrict__ part,
@@ -717,28 +767,43 @@ __global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, 
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * kWaves + (threadIdx.x >> 6);  // b * H_q + h
   if (row >= c.B * c.H_q) return;
-  const int items = n_splits + 1;
-  const float* p0 = part + (long long)row * items * kPartStride;
+  const float* p0 = part + (long long)row * n_splits * kPartStride;
   float M = -INFINITY;
-  for (int j = lane; j < items; j += 64) M = fmaxf(M, p0[(long long)j * kPartStride]);
+  for (int j = lane; j < n_splits; j += 64) M = fmaxf(M, p0[(long long)j * kPartStride]);
   M = wave_allmax(M);
   float n0 = 0.f, n1 = 0.f, den = 0.f;
-  for (int j = 0; j < items; ++j) {
+  for (int j = 0; j < n_splits; ++j) {
     const float mj = p0[(long long)j * kPartStride];
+    const float2 a = *reinterpret_cast<const float2*>(p0 + (long long)j * kPartStride + 4 + 2 * lane);
+    const float lj = p0[(long long)j * kPartStride + 1];
     if (mj == -INFINITY) continue;
     const float w = exp2f(mj - M);
-    const float2 a = *reinterpret_cast<const float2*>(p0 + (long long)j * kPartStride + 4 + 2 * lane);
     n0 = fmaf(w, a.x, n0);
     n1 = fmaf(w, a.y, n1);
-    den = fmaf(w, p0[(long long)j * kPartStride + 1], den);
+    den = fmaf(w, lj, den);
   }
   float y0 = 0.f, y1 = 0.f;
   if (M != -INFINITY) {
     float cn0 = 0.f, cn1 = 0.f, cd = 0.f;
     if (corr != nullptr) {
-      const float* cr = corr + (long long)row * kPartStride;
-      const float2 cn = *reinterpret_cast<const float2*>(cr + 4 + 2 * lane);
-      cn0 = cn.x; cn1 = cn.y; cd = cr[0];
+      // the two parts of each half of phi share one softmax: phi_f = e_f exp(m_r - M_hs) / Z_hs
+      const float* cr = corr + (long long)row * kCorrParts * kPartStride;
+#pragma unroll
+      for (int hs = 0; hs < 2; ++hs) {
+        const float* pa = cr + (2 * hs) * kPartStride;
+        const float* pb = pa + kPartStride;
+        const float za = pa[2], zb = pb[2];
+        if (za + zb > 0.f) {  // zero for a sequence without quantized tokens
+          const float Mh = fmaxf(pa[1], pb[1]);
+          const float wa = __expf(pa[1] - Mh), wb = __expf(pb[1] - Mh);
+          const float inv = 1.0f / (wa * za + wb * zb);
+          const float2 ca = *reinterpret_cast<const float2*>(pa + 4 + 2 * lane);
+          const float2 cb = *reinterpret_cast<const float2*>(pb + 4 + 2 * lane);
+          cn0 += (wa * ca.x + wb * cb.x) * inv;
+          cn1 += (wa * ca.y + wb * cb.y) * inv;
+          cd += (wa * pa[0] + wb * pb[0]) * inv;
+        }
+      }
     }
     // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum)
     const float Ms = fmaxf(M, 0.f);
@@ -765,14 +830,21 @@ __global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, 
 
 }  // namespace
 
-// Blocks of groups per (sequence, kv head): every wave of a workgroup should own about kGroupsPerWave groups.
+// Splits per (sequence, kv head).  Every workgroup holds 72 KB of LDS, so two are resident per CU: aim at one full
+// round of 2 x 256 workgroups, but never more than kMaxGroupsPerSplit groups per workgroup (ragged batches then
+// balance dynamically) and never less than one group per wave.
 int decode_splits(const kvlinc_cache& c, int max_context) {
-  constexpr int kGroupsPerWave = 4;
+  constexpr int kResidentWorkgroups = 1024, kMaxGroupsPerSplit = 32;
   const long long cap = (long long)c.max_groups * kGroup + c.R;
   const long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
   long long groups = (ctx + kGroup - 1) / kGroup;
   if (groups < 1) groups = 1;
-  long long s = (groups + kWaves * kGroupsPerWave - 1) / (kWaves * kGroupsPerWave);
+  const long long bh = (long long)c.B * c.H_kv;
+  long long s = (kResidentWorkgroups + bh - 1) / bh;
+  const long long by_size = (groups + kMaxGroupsPerSplit - 1) / kMaxGroupsPerSplit;
+  if (s < by_size) s = by_size;
+  const long long most = (groups + kWaves - 1) / kWaves;
+  if (s > most) s = most;
   if (const char* e = getenv("KVLINC_SPLITS")) s = atoi(e);
   if (s < 1) s = 1;
   if (s > 1024) s = 1024;
@@ -780,7 +852,8 @@ int decode_splits(const kvlinc_cache& c, int max_context) {
 }
 
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
-  return (size_t)c.B * c.H_q * (n_splits + 2) * kPartStride;  // n_splits + window partials, then one correction row
+  // split partials, then the correction parts, then the logits of phi
+  return (size_t)c.B * c.H_q * ((n_splits + kCorrParts) * kPartStride + kRank);
 }
 
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
@@ -789,16 +862,33 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const int BH = c.B * c.H_kv;
   const half_t* qq = reinterpret_cast<const half_t*>(q);
   float* part = workspace;
-  float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * (n_splits + 1) * kPartStride : nullptr;
-  const dim3 grid(BH * (n_splits + 1 + (corr != nullptr ? 1 : 0))), block(kThreads);
+  float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
+  float* logits = workspace + (size_t)c.B * c.H_q * (n_splits + kCorrParts) * kPartStride;
+  const dim3 grid(BH * n_splits), block(kThreads);
   const char* dbg = getenv("KVLINC_DBG_SKIP");
   const int dbg_skip = dbg ? atoi(dbg) : 0;
-  if (gq <= 4) hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq, dbg_skip);
-  else hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, n_splits, gq, dbg_skip);
+  if (corr != nullptr) {
+    const int n_bq = (c.B + kPhiSeqs - 1) / kPhiSeqs;
+    hipLaunchKernelGGL(decode_logits_kernel, dim3(c.H_q * 2 * n_bq), block, 0, stream, c, qq, logits);
+    if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
+  }
+  if (gq <= 4)
+    hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, logits, n_splits, gq, dbg_skip);
+  else
+    hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, logits, n_splits, gq, dbg_skip);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   hipLaunchKernelGGL(decode_merge_kernel, dim3((c.B * c.H_q + kWaves - 1) / kWaves), block, 0, stream, c, part, corr,
                      n_splits, reinterpret_cast<half_t*>(out));
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
+
+#ifdef KV_EXP_TIMING
+extern "C" int kvlinc_debug_read(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kv_dbg), n * sizeof(unsigned long long));
+}
+extern "C" int kvlinc_debug_read2(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kv_dbg2), n * sizeof(unsigned long long));
+}
+#endif
 
 }  // namespace kvlinc

@@ -46,6 +46,10 @@
  *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
  *                     S, P, Wq, Wk all NULL = correction off (plain quantized attention).
  *   status            [1] int32, OR-ed KVLINC_ST_* bits.
+ *   split_done        [B, H_kv] int32 scratch counters of kvlinc_decode_attention (arrival count of the splits of a
+ *                     (sequence, KV head); the last split merges).  Zero them once after allocation; every call
+ *                     leaves them at zero.  Two decode calls on the same cache must not overlap in time.
+ *   All cache buffers must be zero-initialised before their first use.
  *
  * Quantizer contract (bit exact; Eq. 1 taken against the stored fp16 scale and zero-point):
  *   mn, mx over the group (a zero of either sign counts as +0); z = mn; s = fp16(fl32(fl32(mx - mn) / 3));
@@ -96,6 +100,7 @@ typedef struct kvlinc_cache {
   const kvlinc_half* Wq;
   const kvlinc_half* Wk;
   int32_t* status;
+  int32_t* split_done;
 } kvlinc_cache;
 
 /* Library version, major*10000 + minor*100 + patch. */

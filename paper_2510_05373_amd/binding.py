@@ -24,7 +24,7 @@ class CacheStruct(ctypes.Structure):
         ("n_quant", ctypes.c_void_p), ("n_res", ctypes.c_void_p),
         ("S", ctypes.c_void_p), ("P", ctypes.c_void_p),
         ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p),
-        ("status", ctypes.c_void_p),
+        ("status", ctypes.c_void_p), ("split_done", ctypes.c_void_p),
     ]
 
 
@@ -120,6 +120,7 @@ class KVLincCache:
         self.n_quant = z(B, dt=torch.int32)
         self.n_res = z(B, dt=torch.int32)
         self.status = z(1, dt=torch.int32)
+        self.split_done = z(B, H_kv, dt=torch.int32)
         self.Wq, self.Wk = Wq, Wk
         if Wq is not None:
             assert Wk is not None and tuple(Wq.shape) == (H_q, 2, 128, 128) and tuple(Wk.shape) == (H_kv, 2, 128, 128)
@@ -135,7 +136,7 @@ class KVLincCache:
             n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),
             S=None if self.S is None else self.S.data_ptr(), P=None if self.P is None else self.P.data_ptr(),
             Wq=None if Wq is None else Wq.data_ptr(), Wk=None if Wk is None else Wk.data_ptr(),
-            status=self.status.data_ptr())
+            status=self.status.data_ptr(), split_done=self.split_done.data_ptr())
         self._ws = None
 
     def bytes(self):

@@ -1,14 +1,16 @@
 // Decode: single-query attention read directly from the packed 2-bit cache on the CDNA4 matrix cores, with the
 // linear correction and the fp16 window (Sec. 3.3, Alg. 1; Sec. 3.2, Eq. 5-6; Sec. 3.1 for the rotated value basis).
 //
-// Launch 1, decode_main_kernel: one kind of workgroup, (sequence, kv head, split).  Its four waves take the groups of
-// the split round-robin; a wave owns a group of 128 tokens at a time and keeps its own (m, l, acc).  Group records
-// travel HBM -> LDS directly, two requests ahead per wave.  On the side a workgroup computes its share of the
-// correction terms (phi_q(q), C_n = phi_q S, C_d = phi_q P, split into four parts over the rows of S) and one wave
+// decode_main_kernel: one kind of workgroup, (sequence, kv head, split).  Its four waves take the groups of
+// the split round-robin; a wave owns a group of 128 tokens at a time and keeps its own (m, l, acc).  A group record
+// is fetched in two parts, each requested again for the next group as soon as its contraction has consumed it.
+// On the side a workgroup computes its share of the correction terms (C_n = phi_q S, C_d = phi_q P, split into
+// four parts over the rows of S) and one wave
 // may own half of the fp16 window, processed as one more block of tokens.  The waves are combined through LDS and
 // the workgroup writes one (m, l, Y_s) per query head (Alg. 1 line 11).
-// Launch 2, decode_merge_kernel: one wave per (sequence, query head): weighs the splits by 2^(m_j - M), adds the
-// correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies H^T and stores fp16 (Alg. 1 lines 13-15 with Eq. 5).
+// The split of a (sequence, kv head) that finishes last merges, one wave per query head: it weighs the splits by
+// 2^(m_j - M), adds the correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies H^T and stores fp16 (Alg. 1
+// lines 13-15 with Eq. 5).  One launch per decode step.
 //
 // Both contractions of a group run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad
 // (cbsz=4, abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
@@ -49,6 +51,16 @@ __device__ __forceinline__ half2_t as_h2(uint32_t v) { return __builtin_bit_cast
 __device__ __forceinline__ half4_t as_h4(uint32_t a, uint32_t b) {
   u32x2_t v = {a, b};
   return __builtin_bit_cast(half4_t, v);
+}
+
+// Results that one workgroup writes and another reads inside the same launch (split partials, correction parts) go
+// through stores and loads that are coherent across the chip's L2 slices: a workgroup-wide cache write-back /
+// invalidate (what a device-scope fence costs here) would throw away the streamed records.
+__device__ __forceinline__ void st_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 template <int CTRL>
@@ -444,15 +456,22 @@ __device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t*
 }
 
 // ---- correction terms (Sec. 3.3: C_n = phi_q(q) S, C_d = phi_q(q) P; Eq. 6 for phi) -----------------------------------
-// The logits q W_1, q W_2 of every (sequence, query head) come from a small kernel of their own (the adapters are
-// shared by all sequences, so they are read once there instead of once per sequence).  In the main kernel the work of
-// one (sequence, kv head) is cut into four parts over the rows of S: part r covers the 64 features 64 (r % 2) .. + 63
-// of half hs = r / 2 of phi.  A part exponentiates its logits against its own maximum m_r and leaves the softmax
-// normalisation of the half to the merge:
+// The work of one (sequence, kv head) is cut into four parts over the rows of S: part r covers the 64 features
+// 64 (r % 2) .. + 63 of half hs = r / 2 of phi.  A part computes its 64 logits per head (a 128 x 64 slice of W_1 or
+// W_2), exponentiates them against its own maximum m_r and leaves the softmax normalisation of the half to the merge:
 //     e_f = exp(logit_f - m_r),  Z_r = sum_f e_f,  Cn_r = sum_f e_f S[f],  Cd_r = sum_f e_f P[f].
 // Output per (query head, part): {Cd_r, m_r, Z_r, -, Cn_r[128]}.
-// A wave owns 32 output channels (lane = 4 channels x 8 features), reduces with shuffles and needs no barrier.
+// Every operand (q, the W slice, the S slice, P) is requested before anything is waited for; the logits change hands
+// through LDS once.  In both products a wave owns complete output columns and reduces with shuffles.
 
+__device__ __forceinline__ float xor_allsum_32rows(float v) {  // sum over lanes that differ in bits 1..5
+  v += dpp_f<kRowRor2>(v);
+  v += dpp_f<kRowRor4>(v);
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
 __device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes that differ in bits 3..5
   v += dpp_f<kRowRor8>(v);
   v += __shfl_xor(v, 16, 64);
@@ -460,135 +479,114 @@ __device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes 
   return v;
 }
 
-#ifdef KV_EXP_TIMING
-__device__ unsigned long long kv_dbg[8 * 4096];
-__device__ unsigned long long kv_dbg2[8 * 4096];
-#define KV_T(var) const long long var = clock64()
-#else
-#define KV_T(var)
-#endif
+// Workgroup barrier for data exchanged through LDS by ordinary LDS writes.
+__device__ __forceinline__ void barrier_lds_only() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 constexpr int kCorrParts = 4;
 
-// launch 0: logits[b][h][f] = sum_c q[b][h][c] W[h][f / 128][c][f % 128], f = 0..255, binary32.
-// One workgroup per (query head, half, 4 sequences): thread = (chunk of 8 features, group of 8 channels).
-constexpr int kPhiSeqs = 4;
-__global__ __launch_bounds__(kThreads) void decode_logits_kernel(kvlinc_cache c, const half_t* __restrict__ q,
-                                                                  float* __restrict__ logits) {
-  __shared__ float sPart[kWaves][kPhiSeqs][kHeadDim];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int n_bq = (c.B + kPhiSeqs - 1) / kPhiSeqs;
-  const int bq = blockIdx.x % n_bq;
-  const int hs = (blockIdx.x / n_bq) & 1;
-  const int h = blockIdx.x / (2 * n_bq);
-  const int chunk = tid & 15, rowgrp = tid >> 4;  // 16 chunks x 8 features, 16 groups x 8 channels
-  const half_t* W = reinterpret_cast<const half_t*>(c.Wq) + ((long long)h * 2 + hs) * kHeadDim * (kRank / 2) +
-                    (long long)rowgrp * 8 * (kRank / 2) + 8 * chunk;
-  uint4 raw[8], qraw[kPhiSeqs];
+// NH = 4 NB heads are processed together so that their cross-lane reductions overlap; heads beyond gq repeat the
+// last one and are not written.  The logits of a part live in [NH][64] floats of LDS.
+template <int NH>
+struct LogitRegs {
+  uint4 raw[NH][4];
+  uint2 qraw[NH];
+};
+
+// q W: wave w owns features 16w .. 16w+15 of the part; lane = (chunk of 8 features, group of 4 channels)
+template <int NH>
+__device__ __forceinline__ void logits_request(LogitRegs<NH>& lr, const kvlinc_cache& c, const half_t* __restrict__ q,
+                                               int gq, int bh, int r, int lane, int wave) {
+  const int b = bh / c.H_kv, g = bh % c.H_kv;
+  const int hs = r >> 1, fpart = 64 * (r & 1);
+  const int chunkA = lane & 1, rowgrpA = lane >> 1;
+  const int f0 = 16 * wave + 8 * chunkA;
+  const half_t* W0 = reinterpret_cast<const half_t*>(c.Wq) + ((long long)g * gq * 2 + hs) * kHeadDim * (kRank / 2) +
+                     (long long)rowgrpA * 4 * (kRank / 2) + fpart + f0;
+  const half_t* q0 = q + ((long long)b * c.H_q + g * gq) * kHeadDim + 4 * rowgrpA;
 #pragma unroll
-  for (int rb = 0; rb < 8; ++rb) raw[rb] = *reinterpret_cast<const uint4*>(W + rb * (kRank / 2));
+  for (int h = 0; h < NH; ++h) {
+    const int hc = h < gq ? h : gq - 1;
+    const half_t* W = W0 + (long long)hc * 2 * kHeadDim * (kRank / 2);
+    lr.qraw[h] = *reinterpret_cast<const uint2*>(q0 + (long long)hc * kHeadDim);
 #pragma unroll
-  for (int s = 0; s < kPhiSeqs; ++s) {
-    const int b = min(bq * kPhiSeqs + s, c.B - 1);  // past the batch: repeat the last sequence (result unused)
-    qraw[s] = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + h) * kHeadDim + 8 * rowgrp);
-  }
-  float acc[kPhiSeqs][8];
-#pragma unroll
-  for (int s = 0; s < kPhiSeqs; ++s)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[s][i] = 0.f;
-#pragma unroll
-  for (int rb = 0; rb < 8; ++rb) {
-    const half_t* hv = reinterpret_cast<const half_t*>(&raw[rb]);
-#pragma unroll
-    for (int s = 0; s < kPhiSeqs; ++s) {
-      const float qf = (float)reinterpret_cast<const half_t*>(&qraw[s])[rb];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[s][i] = fmaf(qf, (float)hv[i], acc[s][i]);
-    }
-  }
-  // sum over the 16 channel groups: 4 inside the wave (lanes that differ in bits 4, 5), then across the 4 waves
-#pragma unroll
-  for (int s = 0; s < kPhiSeqs; ++s)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float v = acc[s][i];
-      v += __shfl_xor(v, 16, 64);
-      v += __shfl_xor(v, 32, 64);
-      if (lane < 16) sPart[wave][s][8 * chunk + i] = v;
-    }
-  __syncthreads();
-  for (int idx = tid; idx < kPhiSeqs * kHeadDim; idx += kThreads) {
-    const int s = idx >> 7, f = idx & 127;
-    const int b = bq * kPhiSeqs + s;
-    if (b < c.B)
-      logits[((long long)b * c.H_q + h) * kRank + hs * 128 + f] =
-          sPart[0][s][f] + sPart[1][s][f] + sPart[2][s][f] + sPart[3][s][f];
+    for (int rb = 0; rb < 4; ++rb) lr.raw[h][rb] = *reinterpret_cast<const uint4*>(W + rb * (kRank / 2));
   }
 }
 
-// Operands of one correction part in registers: requested early, consumed later.  NH = 4 NB heads are processed
-// together so that their cross-lane reductions overlap; heads beyond gq repeat the last one and are not written.
+// logit[h][f] = sum_c q[h][c] W[h][hs][c][fpart + f], written to sLogit[h][f]
 template <int NH>
-struct CorrRegs {
-  float4 s4[8];       // S slice: 8 features x 4 channels of this lane
-  float pf;           // P entry of feature `lane` of the part
-  float mine[NH];     // logit of feature `lane` of the part, per head
-  float4 la[NH], lb[NH];  // logits of this lane's 8 features, per head
-};
+__device__ __forceinline__ void logits_compute(const LogitRegs<NH>& lr, int lane, int wave, float* sLogit) {
+  const int chunkA = lane & 1, rowgrpA = lane >> 1;
+  const int f0 = 16 * wave + 8 * chunkA;
+  float lg[NH][8];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    const half_t* qv = reinterpret_cast<const half_t*>(&lr.qraw[h]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lg[h][i] = 0.f;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+      const float qf = (float)qv[rb];
+      const half_t* hv = reinterpret_cast<const half_t*>(&lr.raw[h][rb]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lg[h][i] = fmaf(qf, (float)hv[i], lg[h][i]);
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lg[h][i] = xor_allsum_32rows(lg[h][i]);
+  if (rowgrpA == 0) {
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      float* dst = sLogit + h * 64 + f0;
+      *reinterpret_cast<float4*>(dst) = make_float4(lg[h][0], lg[h][1], lg[h][2], lg[h][3]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(lg[h][4], lg[h][5], lg[h][6], lg[h][7]);
+    }
+  }
+}
 
+// E S: wave w owns channels 32w .. 32w+31; lane = (chunk of 4 channels, group of 8 features).  The logits must be
+// visible in LDS (barrier) before the call.
 template <int NH>
-__device__ __forceinline__ void corr_request(CorrRegs<NH>& R, const kvlinc_cache& c, const float* __restrict__ logits,
-                                             int gq, int bh, int r, int lane, int wave) {
+__device__ __forceinline__ void correction_apply(const kvlinc_cache& c, float* __restrict__ corr, int gq, int bh, int r,
+                                                 int lane, int wave, const float* sLogit) {
   const int b = bh / c.H_kv, g = bh % c.H_kv;
   const int hs = r >> 1, fpart = 64 * (r & 1);
   const int c0 = 32 * wave + 4 * (lane & 7), fB = 8 * (lane >> 3);
-  const float* S = c.S + ((long long)bh * kRank + 128 * hs + fpart + fB) * kHeadDim + c0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) R.s4[i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
-  R.pf = c.P[(long long)bh * kRank + 128 * hs + fpart + lane];
-  const float* lg0 = logits + ((long long)b * c.H_q + g * gq) * kRank + hs * 128 + fpart;
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    const float* lg = lg0 + (long long)(h < gq ? h : gq - 1) * kRank;
-    R.mine[h] = lg[lane];
-    R.la[h] = *reinterpret_cast<const float4*>(lg + fB);
-    R.lb[h] = *reinterpret_cast<const float4*>(lg + fB + 4);
-  }
-}
-
-template <int NH>
-__device__ __forceinline__ void corr_compute(const CorrRegs<NH>& R, const kvlinc_cache& c, float* __restrict__ corr,
-                                             int gq, int bh, int r, int lane, int wave) {
-  const int b = bh / c.H_kv, g = bh % c.H_kv;
-  const int c0 = 32 * wave + 4 * (lane & 7);
   const bool writer = (lane >> 3) == 0;
+  const float* S = c.S + ((long long)bh * kRank + 128 * hs + fpart + fB) * kHeadDim + c0;
+  float4 s4[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s4[i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
+  const float pf = c.P[(long long)bh * kRank + 128 * hs + fpart + lane];
+
   float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
   float mx[NH], z[NH], cd[NH], acc[NH][4];
 #pragma unroll
-  for (int h = 0; h < NH; ++h) mx[h] = wave_allmax(R.mine[h]);
+  for (int h = 0; h < NH; ++h) mx[h] = wave_allmax(sLogit[h * 64 + lane]);
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
-    const float e_mine = __expf(R.mine[h] - mx[h]);
+    const float e_mine = __expf(sLogit[h * 64 + lane] - mx[h]);
     z[h] = e_mine;
-    cd[h] = e_mine * R.pf;
+    cd[h] = e_mine * pf;
   }
 #pragma unroll
   for (int h = 0; h < NH; ++h) { z[h] = wave_allsum(z[h]); cd[h] = wave_allsum(cd[h]); }
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
-    const float e[8] = {__expf(R.la[h].x - mx[h]), __expf(R.la[h].y - mx[h]), __expf(R.la[h].z - mx[h]),
-                        __expf(R.la[h].w - mx[h]), __expf(R.lb[h].x - mx[h]), __expf(R.lb[h].y - mx[h]),
-                        __expf(R.lb[h].z - mx[h]), __expf(R.lb[h].w - mx[h])};
+    const float4 la = *reinterpret_cast<const float4*>(sLogit + h * 64 + fB);
+    const float4 lb = *reinterpret_cast<const float4*>(sLogit + h * 64 + fB + 4);
+    const float e[8] = {__expf(la.x - mx[h]), __expf(la.y - mx[h]), __expf(la.z - mx[h]), __expf(la.w - mx[h]),
+                        __expf(lb.x - mx[h]), __expf(lb.y - mx[h]), __expf(lb.z - mx[h]), __expf(lb.w - mx[h])};
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      acc[h][0] = fmaf(e[i], R.s4[i].x, acc[h][0]);
-      acc[h][1] = fmaf(e[i], R.s4[i].y, acc[h][1]);
-      acc[h][2] = fmaf(e[i], R.s4[i].z, acc[h][2]);
-      acc[h][3] = fmaf(e[i], R.s4[i].w, acc[h][3]);
+      acc[h][0] = fmaf(e[i], s4[i].x, acc[h][0]);
+      acc[h][1] = fmaf(e[i], s4[i].y, acc[h][1]);
+      acc[h][2] = fmaf(e[i], s4[i].z, acc[h][2]);
+      acc[h][3] = fmaf(e[i], s4[i].w, acc[h][3]);
     }
   }
 #pragma unroll
@@ -599,8 +597,11 @@ __device__ __forceinline__ void corr_compute(const CorrRegs<NH>& R, const kvlinc
   for (int h = 0; h < NH; ++h) {
     if (h < gq) {
       float* dst = out0 + ((long long)h * kCorrParts + r) * kPartStride;
-      if (wave == 0 && lane == 0) { dst[0] = cd[h]; dst[1] = mx[h]; dst[2] = z[h]; }
-      if (writer) *reinterpret_cast<float4*>(dst + 4 + c0) = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+      if (wave == 0 && lane == 0) { st_coherent(dst, cd[h]); st_coherent(dst + 1, mx[h]); st_coherent(dst + 2, z[h]); }
+      if (writer) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st_coherent(dst + 4 + c0 + j, acc[h][j]);
+      }
     }
   }
 }
@@ -611,7 +612,95 @@ __device__ __forceinline__ void correction_part_empty(const kvlinc_cache& c, flo
   const int b = bh / c.H_kv, g = bh % c.H_kv;
   float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
   for (int i = threadIdx.x; i < gq * kPartStride; i += kThreads)
-    out0[((long long)(i / kPartStride) * kCorrParts + r) * kPartStride + i % kPartStride] = 0.f;
+    st_coherent(out0 + ((long long)(i / kPartStride) * kCorrParts + r) * kPartStride + i % kPartStride, 0.f);
+}
+
+// ---- merge the splits of one (sequence, query head), add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5;
+// Sec. 3.1).  Run by one wave of the split that arrives last; lane l owns channels 2l and 2l+1. ----------------------
+
+constexpr int kMergeBatch = 8;  // splits whose partial results are requested together
+
+__device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr, int n_splits,
+                                          int row, int lane, half_t* __restrict__ out) {
+  const float* p0 = part + (long long)row * n_splits * kPartStride;
+  // correction parts first (their values are needed last): {Cd_r, m_r, Z_r, -, Cn_r[128]}
+  float c_cd[kCorrParts], c_m[kCorrParts], c_z[kCorrParts], c_x[kCorrParts], c_y[kCorrParts];
+  if (corr != nullptr) {
+    const float* cr = corr + (long long)row * kCorrParts * kPartStride;
+#pragma unroll
+    for (int r = 0; r < kCorrParts; ++r) {
+      const float* pr = cr + r * kPartStride;
+      c_cd[r] = ld_coherent(pr); c_m[r] = ld_coherent(pr + 1); c_z[r] = ld_coherent(pr + 2);
+      c_x[r] = ld_coherent(pr + 4 + 2 * lane); c_y[r] = ld_coherent(pr + 5 + 2 * lane);
+    }
+  }
+  // running merge over batches of splits, every batch requested at once
+  float M = -INFINITY, n0 = 0.f, n1 = 0.f, den = 0.f;
+  for (int j0 = 0; j0 < n_splits; j0 += kMergeBatch) {
+    float mj[kMergeBatch], lj[kMergeBatch], ax[kMergeBatch], ay[kMergeBatch];
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k) {
+      const float* pj = p0 + (long long)(j0 + k < n_splits ? j0 + k : n_splits - 1) * kPartStride;
+      mj[k] = ld_coherent(pj); lj[k] = ld_coherent(pj + 1);
+      ax[k] = ld_coherent(pj + 4 + 2 * lane); ay[k] = ld_coherent(pj + 5 + 2 * lane);
+    }
+    float Mb = M;
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k)
+      if (j0 + k < n_splits) Mb = fmaxf(Mb, mj[k]);
+    if (Mb == -INFINITY) continue;
+    const float f = exp2f(M - Mb);  // 0 while nothing has been merged yet
+    n0 *= f; n1 *= f; den *= f;
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k) {
+      if (j0 + k < n_splits && mj[k] != -INFINITY) {
+        const float w = exp2f(mj[k] - Mb);
+        n0 = fmaf(w, ax[k], n0);
+        n1 = fmaf(w, ay[k], n1);
+        den = fmaf(w, lj[k], den);
+      }
+    }
+    M = Mb;
+  }
+  float y0 = 0.f, y1 = 0.f;
+  if (M != -INFINITY) {
+    float cn0 = 0.f, cn1 = 0.f, cd = 0.f;
+    if (corr != nullptr) {
+      // the two parts of each half of phi share one softmax: phi_f = e_f exp(m_r - M_hs) / Z_hs
+#pragma unroll
+      for (int hs = 0; hs < 2; ++hs) {
+        const int ra = 2 * hs, rb = 2 * hs + 1;
+        if (c_z[ra] + c_z[rb] > 0.f) {  // zero for a sequence without quantized tokens
+          const float Mh = fmaxf(c_m[ra], c_m[rb]);
+          const float wa = __expf(c_m[ra] - Mh), wb = __expf(c_m[rb] - Mh);
+          const float inv = 1.0f / (wa * c_z[ra] + wb * c_z[rb]);
+          cn0 += (wa * c_x[ra] + wb * c_x[rb]) * inv;
+          cn1 += (wa * c_y[ra] + wb * c_y[rb]) * inv;
+          cd += (wa * c_cd[ra] + wb * c_cd[rb]) * inv;
+        }
+      }
+    }
+    // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum)
+    const float Ms = fmaxf(M, 0.f);
+    const float fa = exp2f(M - Ms), fb = exp2f(-Ms);
+    const float d = fa * den + fb * cd;
+    y0 = (fa * n0 + fb * cn0) / d;
+    y1 = (fa * n1 + fb * cn1) / d;
+  }
+  // y = y_rot H^T: butterflies over the 128 channels, two per lane
+  {
+    const float a = y0 + y1, bb = y0 - y1;
+    y0 = a; y1 = bb;
+#pragma unroll
+    for (int mk = 1; mk < 64; mk <<= 1) {
+      const float o0 = __shfl_xor(y0, mk, 64), o1 = __shfl_xor(y1, mk, 64);
+      const bool upper = (lane & mk) != 0;
+      y0 = upper ? (o0 - y0) : (y0 + o0);
+      y1 = upper ? (o1 - y1) : (y1 + o1);
+    }
+  }
+  const half2_t r = {(half_t)(y0 * 0.08838834764831845f), (half_t)(y1 * 0.08838834764831845f)};
+  *reinterpret_cast<uint32_t*>(out + (long long)row * kHeadDim + 2 * lane) = as_u32(r);
 }
 
 // ---- launch 1 -------------------------------------------------------------------------------------------------------
@@ -621,9 +710,10 @@ __device__ __forceinline__ void correction_part_empty(const kvlinc_cache& c, flo
 template <int NB>
 __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
-                                                                   const float* __restrict__ logits, int n_splits,
-                                                                   int gq, int dbg_skip) {
+                                                                   half_t* __restrict__ out, int n_splits, int gq,
+                                                                   int dbg_skip) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
+  __shared__ __align__(16) float sLogit[kCorrParts][4 * NB * 64];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -642,13 +732,23 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
   const int first = g0 + wave;
   const int n_mine = first < g1 ? (g1 - first + kWaves - 1) / kWaves : 0;
+  // The logits of this workgroup's correction parts are computed first, under the latency of the first records.
+  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0 && !(dbg_skip & 1);
+  LogitRegs<4 * NB> lr;
+  if (has_corr) logits_request<4 * NB>(lr, c, q, gq, bh, sp, lane, wave);
   KeyRegs kr;
   ValueRegs vr;
   if (n_mine > 0) {
     load_keys(kr, rec0 + (long long)first * kRecordWords, lane);
     load_values(vr, rec0 + (long long)first * kRecordWords, lane);
   }
-  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0 && !(dbg_skip & 1);
+  if (has_corr) {
+    logits_compute<4 * NB>(lr, lane, wave, sLogit[0]);
+    for (int r = sp + n_splits, i = 1; r < kCorrParts; r += n_splits, ++i) {
+      logits_request<4 * NB>(lr, c, q, gq, bh, r, lane, wave);
+      logits_compute<4 * NB>(lr, lane, wave, sLogit[i]);
+    }
+  }
   if (corr != nullptr && nq == 0)
     for (int r = sp; r < kCorrParts; r += n_splits) correction_part_empty(c, corr, gq, bh, r);
 
@@ -683,8 +783,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     if (hw >= 0 && hw < 2 && wave == owner_wave && nr > 64 * hw && !(dbg_skip & 2))
       window_half<NB>(c, q, bh, b, g, gq, hw, nr, lc, st);
   }
-
-  KV_T(t_c);
   if (n_mine > 0 && !(dbg_skip & 4)) {
     // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
     // heads beyond gq read as 0
@@ -716,12 +814,11 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     }
   }
   if (has_corr) {
-    for (int r = sp; r < kCorrParts; r += n_splits) {
-      CorrRegs<4 * NB> cregs;
-      corr_request<4 * NB>(cregs, c, logits, gq, bh, r, lane, wave);
-      corr_compute<4 * NB>(cregs, c, corr, gq, bh, r, lane, wave);
-    }
+    barrier_lds_only();
+    for (int r = sp, i = 0; r < kCorrParts; r += n_splits, ++i)
+      correction_apply<4 * NB>(c, corr, gq, bh, r, lane, wave, sLogit[i]);
   }
+
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
   float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                    // [kWaves][NB*4]
   float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);  // [kWaves][NB*4]
@@ -753,79 +850,23 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       }
     }
     float* dst = part + (((long long)b * c.H_q + g * gq + h) * n_splits + sp) * kPartStride;
-    if (ch == 0) { dst[0] = M; dst[1] = l; }
-    dst[4 + ch] = a;
+    if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
+    st_coherent(dst + 4 + ch, a);
   }
-}
 
-// ---- launch 2: merge the splits, add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5; Sec. 3.1) -----------------
-// one wave per (sequence, query head); lane l owns channels 2l and 2l+1
-
-__global__ __launch_bounds__(kThreads) void decode_merge_kernel(kvlinc_cache c, const float* __restrict__ part,
-                                                                 const float* __restrict__ corr, int n_splits,
-                                                                 half_t* __restrict__ out) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * kWaves + (threadIdx.x >> 6);  // b * H_q + h
-  if (row >= c.B * c.H_q) return;
-  const float* p0 = part + (long long)row * n_splits * kPartStride;
-  float M = -INFINITY;
-  for (int j = lane; j < n_splits; j += 64) M = fmaxf(M, p0[(long long)j * kPartStride]);
-  M = wave_allmax(M);
-  float n0 = 0.f, n1 = 0.f, den = 0.f;
-  for (int j = 0; j < n_splits; ++j) {
-    const float mj = p0[(long long)j * kPartStride];
-    const float2 a = *reinterpret_cast<const float2*>(p0 + (long long)j * kPartStride + 4 + 2 * lane);
-    const float lj = p0[(long long)j * kPartStride + 1];
-    if (mj == -INFINITY) continue;
-    const float w = exp2f(mj - M);
-    n0 = fmaf(w, a.x, n0);
-    n1 = fmaf(w, a.y, n1);
-    den = fmaf(w, lj, den);
+  // The split that arrives last merges (Alg. 1 lines 13-15).  Every wave waits until its coherent stores have been
+  // acknowledged, the workgroup's arrival is counted, and the last arrival reads what the others wrote with coherent
+  // loads.  No workgroup waits for another.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int* flag = reinterpret_cast<int*>(lds);
+  if (tid == 0)
+    *flag = __hip_atomic_fetch_add(c.split_done + bh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  __syncthreads();
+  if (*flag == n_splits - 1) {
+    for (int h = wave; h < gq; h += kWaves) merge_row(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+    if (tid == 0) c.split_done[bh] = 0;
   }
-  float y0 = 0.f, y1 = 0.f;
-  if (M != -INFINITY) {
-    float cn0 = 0.f, cn1 = 0.f, cd = 0.f;
-    if (corr != nullptr) {
-      // the two parts of each half of phi share one softmax: phi_f = e_f exp(m_r - M_hs) / Z_hs
-      const float* cr = corr + (long long)row * kCorrParts * kPartStride;
-#pragma unroll
-      for (int hs = 0; hs < 2; ++hs) {
-        const float* pa = cr + (2 * hs) * kPartStride;
-        const float* pb = pa + kPartStride;
-        const float za = pa[2], zb = pb[2];
-        if (za + zb > 0.f) {  // zero for a sequence without quantized tokens
-          const float Mh = fmaxf(pa[1], pb[1]);
-          const float wa = __expf(pa[1] - Mh), wb = __expf(pb[1] - Mh);
-          const float inv = 1.0f / (wa * za + wb * zb);
-          const float2 ca = *reinterpret_cast<const float2*>(pa + 4 + 2 * lane);
-          const float2 cb = *reinterpret_cast<const float2*>(pb + 4 + 2 * lane);
-          cn0 += (wa * ca.x + wb * cb.x) * inv;
-          cn1 += (wa * ca.y + wb * cb.y) * inv;
-          cd += (wa * pa[0] + wb * pb[0]) * inv;
-        }
-      }
-    }
-    // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum)
-    const float Ms = fmaxf(M, 0.f);
-    const float fa = exp2f(M - Ms), fb = exp2f(-Ms);
-    const float d = fa * den + fb * cd;
-    y0 = (fa * n0 + fb * cn0) / d;
-    y1 = (fa * n1 + fb * cn1) / d;
-  }
-  // y = y_rot H^T: butterflies over the 128 channels, two per lane
-  {
-    const float a = y0 + y1, bb = y0 - y1;
-    y0 = a; y1 = bb;
-#pragma unroll
-    for (int mk = 1; mk < 64; mk <<= 1) {
-      const float o0 = __shfl_xor(y0, mk, 64), o1 = __shfl_xor(y1, mk, 64);
-      const bool upper = (lane & mk) != 0;
-      y0 = upper ? (o0 - y0) : (y0 + o0);
-      y1 = upper ? (o1 - y1) : (y1 + o1);
-    }
-  }
-  const half2_t r = {(half_t)(y0 * 0.08838834764831845f), (half_t)(y1 * 0.08838834764831845f)};
-  *reinterpret_cast<uint32_t*>(out + (long long)row * kHeadDim + 2 * lane) = as_u32(r);
 }
 
 }  // namespace
@@ -852,8 +893,7 @@ int decode_splits(const kvlinc_cache& c, int max_context) {
 }
 
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
-  // split partials, then the correction parts, then the logits of phi
-  return (size_t)c.B * c.H_q * ((n_splits + kCorrParts) * kPartStride + kRank);
+  return (size_t)c.B * c.H_q * (n_splits + kCorrParts) * kPartStride;  // split partials, then the correction parts
 }
 
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
@@ -863,32 +903,17 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const half_t* qq = reinterpret_cast<const half_t*>(q);
   float* part = workspace;
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
-  float* logits = workspace + (size_t)c.B * c.H_q * (n_splits + kCorrParts) * kPartStride;
   const dim3 grid(BH * n_splits), block(kThreads);
   const char* dbg = getenv("KVLINC_DBG_SKIP");
   const int dbg_skip = dbg ? atoi(dbg) : 0;
-  if (corr != nullptr) {
-    const int n_bq = (c.B + kPhiSeqs - 1) / kPhiSeqs;
-    hipLaunchKernelGGL(decode_logits_kernel, dim3(c.H_q * 2 * n_bq), block, 0, stream, c, qq, logits);
-    if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
-  }
   if (gq <= 4)
-    hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, logits, n_splits, gq, dbg_skip);
+    hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
+                       gq, dbg_skip);
   else
-    hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, logits, n_splits, gq, dbg_skip);
-  if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3((c.B * c.H_q + kWaves - 1) / kWaves), block, 0, stream, c, part, corr,
-                     n_splits, reinterpret_cast<half_t*>(out));
+    hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
+                       gq, dbg_skip);
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
 
-#ifdef KV_EXP_TIMING
-extern "C" int kvlinc_debug_read(unsigned long long* host, size_t n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kv_dbg), n * sizeof(unsigned long long));
-}
-extern "C" int kvlinc_debug_read2(unsigned long long* host, size_t n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kv_dbg2), n * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace kvlinc

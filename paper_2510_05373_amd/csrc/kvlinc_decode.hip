@@ -710,8 +710,7 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 template <int NB>
 __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
-                                                                   half_t* __restrict__ out, int n_splits, int gq,
-                                                                   int dbg_skip) {
+                                                                   half_t* __restrict__ out, int n_splits, int gq) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
   __shared__ __align__(16) float sLogit[kCorrParts][4 * NB * 64];
 
@@ -733,7 +732,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int first = g0 + wave;
   const int n_mine = first < g1 ? (g1 - first + kWaves - 1) / kWaves : 0;
   // The logits of this workgroup's correction parts are computed first, under the latency of the first records.
-  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0 && !(dbg_skip & 1);
+  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0;
   LogitRegs<4 * NB> lr;
   if (has_corr) logits_request<4 * NB>(lr, c, q, gq, bh, sp, lane, wave);
   KeyRegs kr;
@@ -780,10 +779,10 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   {
     const int hw = n_splits >= 2 ? (n_splits - 1 - sp) : (3 - wave);
     const int owner_wave = n_splits >= 2 ? 3 : wave;
-    if (hw >= 0 && hw < 2 && wave == owner_wave && nr > 64 * hw && !(dbg_skip & 2))
+    if (hw >= 0 && hw < 2 && wave == owner_wave && nr > 64 * hw)
       window_half<NB>(c, q, bh, b, g, gq, hw, nr, lc, st);
   }
-  if (n_mine > 0 && !(dbg_skip & 4)) {
+  if (n_mine > 0) {
     // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
     // heads beyond gq read as 0
     uint32_t Qs[NB][4];
@@ -871,11 +870,12 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
 
 }  // namespace
 
-// Splits per (sequence, kv head).  Every workgroup holds 72 KB of LDS, so two are resident per CU: aim at one full
-// round of 2 x 256 workgroups, but never more than kMaxGroupsPerSplit groups per workgroup (ragged batches then
-// balance dynamically) and never less than one group per wave.
+// Splits per (sequence, kv head): aim at two workgroups per compute unit (2 x 256; measured best at long contexts:
+// more workgroups lengthen the fixed per-workgroup work -- window, correction parts, combine -- faster than they
+// shorten the group loop), but never more than kMaxGroupsPerSplit groups per workgroup (ragged batches then balance
+// dynamically) and never less than one group per wave.
 int decode_splits(const kvlinc_cache& c, int max_context) {
-  constexpr int kResidentWorkgroups = 1024, kMaxGroupsPerSplit = 32;
+  constexpr int kResidentWorkgroups = 512, kMaxGroupsPerSplit = 32;
   const long long cap = (long long)c.max_groups * kGroup + c.R;
   const long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
   long long groups = (ctx + kGroup - 1) / kGroup;
@@ -886,7 +886,9 @@ int decode_splits(const kvlinc_cache& c, int max_context) {
   if (s < by_size) s = by_size;
   const long long most = (groups + kWaves - 1) / kWaves;
   if (s > most) s = most;
+#ifdef KVLINC_TUNING  // sweep builds only: override the split policy from the environment
   if (const char* e = getenv("KVLINC_SPLITS")) s = atoi(e);
+#endif
   if (s < 1) s = 1;
   if (s > 1024) s = 1024;
   return (int)s;
@@ -904,14 +906,12 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   float* part = workspace;
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
   const dim3 grid(BH * n_splits), block(kThreads);
-  const char* dbg = getenv("KVLINC_DBG_SKIP");
-  const int dbg_skip = dbg ? atoi(dbg) : 0;
   if (gq <= 4)
     hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
-                       gq, dbg_skip);
+                       gq);
   else
     hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
-                       gq, dbg_skip);
+                       gq);
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
 

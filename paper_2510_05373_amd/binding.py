@@ -33,6 +33,10 @@ def _load():
         raise ImportError(
             "libkvlinc.so is not built (%s missing): run `python -c 'import __graft_entry__ as g; g.build()'` or "
             "`python paper_2510_05373_amd/build.py`; there is no fallback path" % lib_path)
+    # PyTorch carries its own copy of the HIP runtime under the same soname as the system one, and the first copy
+    # loaded serves the whole process.  The tensors and streams passed to this library come from torch, so torch's
+    # runtime has to be that copy: import torch before the library is opened.
+    import torch  # noqa: F401
     L = ctypes.CDLL(lib_path)
     P = ctypes.POINTER(CacheStruct)
     L.kvlinc_version.restype = ctypes.c_int

@@ -37,39 +37,51 @@ def u16(a):
     return np.ascontiguousarray(a).view(np.uint16)
 
 
-def check_cache_against_oracle(cache, K, V, lengths, pairs, Wk=None, keep=None, check_states=True):
-    """Bit-exact comparison of everything the append path stores, for the listed (sequence, kv head) pairs."""
+def check_counters(cache, lengths, keep=None):
     n_quant = cache.n_quant.cpu().numpy()
     n_res = cache.n_res.cpu().numpy()
     for b in range(cache.B):
         want = o_cache.window_split(int(lengths[b]), keep=keep)
         assert (int(n_quant[b]), int(n_res[b])) == want, (b, n_quant[b], n_res[b], want)
+    return n_quant, n_res
+
+
+def check_pair_against_oracle(cache, b, g, k_rows, v_rows, nq, nr, Wk_g=None, check_states=True):
+    """Bit-exact comparison of everything the append path stores for one (sequence, kv head) whose token history is
+    k_rows, v_rows [n, 128]; returns the oracle's cache."""
+    ref = o_cache.build_cache(k_rows, v_rows, nq, Wk=Wk_g)
+    ng = -(-nq // 128)
+    rec = cache.groups[b, g, :ng].cpu().numpy().view(np.uint32)
+    if ng:
+        # logical fields first (clearer failure), then the physical record bytes
+        got = o_layout.unpack_records(rec)
+        assert np.array_equal(got["k_codes"], ref["k_codes"]), ("k codes", b, g)
+        assert np.array_equal(got["v_codes"], ref["v_codes"]), ("v codes", b, g)
+        for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
+            assert np.array_equal(u16(got[name]), u16(ref[name])), (name, b, g)
+        want = o_layout.pack_records(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"],
+                                     ref["v_scale"], ref["v_zero"])
+        assert np.array_equal(rec, want), ("records", b, g)
+    assert np.array_equal(u16(cache.k_res[b, g, :nr].cpu().numpy()), u16(ref["k_res"])), ("k_res", b, g)
+    v_win = o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
+    assert np.array_equal(u16(v_win), u16(ref["v_res"])), ("v_res", b, g)
+    if Wk_g is not None and check_states:
+        S = cache.S[b, g].cpu().numpy().astype(np.float64)
+        P = cache.P[b, g].cpu().numpy().astype(np.float64)
+        for got, want, nm in ((S, ref["S"], "S"), (P, ref["P"], "P")):
+            den = np.linalg.norm(want)
+            err = np.linalg.norm(got - want)
+            assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
+    return ref
+
+
+def check_cache_against_oracle(cache, K, V, lengths, pairs, Wk=None, keep=None, check_states=True):
+    """check_pair_against_oracle for the listed (sequence, kv head) pairs of dense K, V [B, H_kv, T, 128]."""
+    n_quant, n_res = check_counters(cache, lengths, keep)
     for (b, g) in pairs:
         n = int(lengths[b])
-        nq, nr = int(n_quant[b]), int(n_res[b])
-        ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], nq, Wk=None if Wk is None else Wk[g])
-        ng = -(-nq // 128)
-        rec = cache.groups[b, g, :ng].cpu().numpy().view(np.uint32)
-        if ng:
-            # logical fields first (clearer failure), then the physical record bytes
-            got = o_layout.unpack_records(rec)
-            assert np.array_equal(got["k_codes"], ref["k_codes"]), ("k codes", b, g)
-            assert np.array_equal(got["v_codes"], ref["v_codes"]), ("v codes", b, g)
-            for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
-                assert np.array_equal(u16(got[name]), u16(ref[name])), (name, b, g)
-            want = o_layout.pack_records(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"],
-                                         ref["v_scale"], ref["v_zero"])
-            assert np.array_equal(rec, want), ("records", b, g)
-        assert np.array_equal(u16(cache.k_res[b, g, :nr].cpu().numpy()), u16(ref["k_res"])), ("k_res", b, g)
-        v_win = o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
-        assert np.array_equal(u16(v_win), u16(ref["v_res"])), ("v_res", b, g)
-        if Wk is not None and check_states:
-            S = cache.S[b, g].cpu().numpy().astype(np.float64)
-            P = cache.P[b, g].cpu().numpy().astype(np.float64)
-            for got, want, nm in ((S, ref["S"], "S"), (P, ref["P"], "P")):
-                den = np.linalg.norm(want)
-                err = np.linalg.norm(got - want)
-                assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
+        check_pair_against_oracle(cache, b, g, K[b, g, :n], V[b, g, :n], int(n_quant[b]), int(n_res[b]),
+                                  None if Wk is None else Wk[g], check_states)
 
 
 def oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq=None, Wk=None):

@@ -1,0 +1,133 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark uses (bulk-built cache, decode with
+max_context = the batch's longest context).  The oracle cannot replay a whole batch at these sizes, so a few seeded
+(sequence, KV head) pairs carry the workload's seeded inputs and are compared element by element (records bit for bit,
+outputs within tolerance); every other pair is filled with device-generated N(0, 1) data so that the launch has its
+real shape."""
+import numpy as np
+import pytest
+
+import kvlinc_synth as synth
+from tests import kvlinc_testlib as tl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2510_05373_amd as kvmod
+    return kvmod
+
+
+def _fill(cfg_id, B, H_kv, T, lengths, pairs, seed):
+    """Device K, V [B, H_kv, T, 128] fp16: seeded host rows for `pairs`, device noise elsewhere.  Also returns the
+    host rows {(b, g): (K, V)}."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    Kd = torch.empty(B, H_kv, T, 128, dtype=torch.float16, device="cuda")
+    Vd = torch.empty_like(Kd)
+    for b in range(B):  # per sequence, to bound the fp32 temporaries
+        Kd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
+        Vd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
+    host = {}
+    for (b, g) in pairs:
+        n = int(lengths[b])
+        k, v = synth.keys(cfg_id, b, g, n), synth.values(cfg_id, b, g, n)
+        host[(b, g)] = (k, v)
+        Kd[b, g, :n] = torch.from_numpy(k).cuda()
+        Vd[b, g, :n] = torch.from_numpy(v).cuda()
+    return Kd, Vd, host
+
+
+def _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv):
+    """Records / window bit-exact, states and outputs within tolerance, for the seeded pairs."""
+    gq = H_q // H_kv
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    want = {}
+    for (b, g) in pairs:
+        n = int(lengths[b])
+        k, v = host[(b, g)]
+        ref = tl.check_pair_against_oracle(cache, b, g, k[:n], v[:n], int(n_quant[b]), int(n_res[b]), Wk[g])
+        for h in range(g * gq, (g + 1) * gq):
+            want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h])
+    return tl.check_outputs(out, want)
+
+
+def _run_bulk_config(kv, cfg_id, pairs):
+    import torch
+    cfg = synth.CONFIGS[cfg_id]
+    B, H_q, H_kv, n = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["n"]
+    lengths = [n] * B
+    print("  [case] config %d %s B=%d heads %d/%d context %d pairs %s" % (cfg_id, cfg["name"], B, H_q, H_kv, n, pairs),
+          flush=True)
+    Wq, Wk = synth.adapters_q(cfg_id, H_q), synth.adapters_k(cfg_id, H_kv)
+    Kd, Vd, host = _fill(cfg_id, B, H_kv, n, lengths, pairs, seed=cfg_id)
+    cache = kv.KVLincCache(B, H_q, H_kv, n + 256, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(Kd, Vd)
+    del Kd, Vd
+    q = tl.gen_q(cfg_id, B, H_q)
+    out = cache.decode(tl.to_dev(q), max_context=n)
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0
+    assert cache.n_quant.cpu().tolist() == [n - 128] * B and cache.n_res.cpu().tolist() == [128] * B
+    out = out.cpu().numpy()
+    assert np.isfinite(out.astype(np.float32)).all()
+    _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv)
+    # a second call on the same cache gives the same bits (the arrival counters were left at zero)
+    out2 = cache.decode(tl.to_dev(q), max_context=n).cpu().numpy()
+    assert np.array_equal(out.view(np.uint16), out2.view(np.uint16))
+    assert int(cache.split_done.abs().sum().item()) == 0
+
+
+def test_config2_llama3_8b_batch16_ctx8k(kv):
+    _run_bulk_config(kv, 2, [(0, 0), (7, 3), (15, 7)])
+
+
+def test_config3_single_sequence_ctx128k(kv):
+    _run_bulk_config(kv, 3, [(0, 5)])
+
+
+def test_config4_qwen25_7b_batch32_ctx32k_gqa7(kv):
+    _run_bulk_config(kv, 4, [(0, 0), (31, 3)])
+
+
+def test_config5_ragged_batch64_with_appends(kv):
+    """Ragged contexts, one token appended to every sequence per step for 256 steps (every sequence crosses two flush
+    boundaries); seeded pairs are compared with the oracle at the first step, around step 127 / 128 and at the end."""
+    import torch
+    cfg_id = 5
+    cfg = synth.CONFIGS[cfg_id]
+    B, H_q, H_kv, steps = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["steps"]
+    start = synth.ragged_lengths(cfg_id, B, cfg["n_min"], cfg["n_max"]).astype(np.int64)
+    total = start + steps
+    T = int(total.max())
+    order = np.argsort(start)
+    pairs = [(int(order[0]), 1), (int(order[B // 2]), 6), (int(order[-1]), 3), (int(order[B // 4]), 0)]
+    print("  [case] config 5 B=%d contexts %d..%d pairs %s" % (B, start.min(), start.max(), pairs), flush=True)
+    Wq, Wk = synth.adapters_q(cfg_id, H_q), synth.adapters_k(cfg_id, H_kv)
+    Kd, Vd, host = _fill(cfg_id, B, H_kv, T, total, pairs, seed=cfg_id)
+    cache = kv.KVLincCache(B, H_q, H_kv, T + 128, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(Kd[:, :, :int(start.max())].contiguous(), Vd[:, :, :int(start.max())].contiguous(),
+                 n_new=tl.to_dev(start.astype(np.int32)))
+    idx = torch.from_numpy(start.copy()).cuda()
+    ar = torch.arange(B, device="cuda")
+    lengths = start.copy()
+    check_at = {0, 126, 127, 128, steps - 1}
+    for step in range(steps):
+        kn = Kd[ar, :, idx].unsqueeze(2).contiguous()  # [B, H_kv, 1, 128]: row `length` of every sequence
+        vn = Vd[ar, :, idx].unsqueeze(2).contiguous()
+        cache.append(kn, vn)
+        idx += 1
+        lengths += 1
+        if step in check_at:
+            print("  [step] %d" % step, flush=True)
+            q = tl.gen_q(cfg_id, B, H_q, step)
+            out = cache.decode(tl.to_dev(q), max_context=int(lengths.max()))
+            torch.cuda.synchronize()
+            assert int(cache.status.item()) == 0
+            out = out.cpu().numpy()
+            assert np.isfinite(out.astype(np.float32)).all()
+            _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv)
+    assert (cache.n_quant.cpu().numpy() + cache.n_res.cpu().numpy() == total).all()

@@ -1,0 +1,105 @@
+"""The C-ABI library loads without a GPU, exports every function include/kvlinc.h declares, and its host-side checks
+reject bad descriptors before any launch (no compute call is made here: every rejected call returns before a launch,
+and the accepted ones only compute sizes)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvlinc.h")
+
+kb = pytest.importorskip("paper_2510_05373_amd.binding")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvlinc_[a-z_]+)\s*\(", text)))
+
+
+def fake_struct(**over):
+    """A descriptor whose pointers are aligned non-NULL integers; never dereferenced by the host checks."""
+    base = 0x10000
+    f = dict(B=2, H_q=8, H_kv=2, d=128, G=128, R=128, D=256, bits=2, max_groups=8, groups=base, k_res=base,
+             v_res=base, n_quant=base, n_res=base, S=base, P=base, Wq=base, Wk=base, status=base, split_done=base)
+    f.update(over)
+    return kb.CacheStruct(**f)
+
+
+def test_header_functions_are_exported():
+    names = declared_functions()
+    assert names == ["kvlinc_append_quantize", "kvlinc_cache_validate", "kvlinc_decode_attention",
+                     "kvlinc_decode_workspace_bytes", "kvlinc_strerror", "kvlinc_version"]
+    lib = ctypes.CDLL(kb.lib_path)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert callable(getattr(kb, n)), "binding lacks " + n
+
+
+def test_struct_mirror_matches_header_order():
+    text = open(HEADER).read()
+    body = text[text.index("typedef struct kvlinc_cache {"):text.index("} kvlinc_cache;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split("{", 1)[1].split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        first, *rest = decl.split(",")
+        fields.append(re.findall(r"\**\s*(\w+)$", first.strip())[0])
+        fields += [re.sub(r"[\s\*]", "", r) for r in rest]
+    assert fields == [n for n, _ in kb.CacheStruct._fields_]
+
+
+def test_version_and_messages():
+    assert kb.kvlinc_version() >= 100
+    for code in (0, -1, -2, -3):
+        assert "unknown" not in kb.kvlinc_strerror(code)
+    assert "unknown" in kb.kvlinc_strerror(-99)
+
+
+def test_validate_accepts_and_rejects():
+    ok = fake_struct()
+    assert kb.kvlinc_cache_validate(ok) == kb.KVLINC_OK
+    bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=4), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
+           dict(H_q=32, H_kv=2), dict(B=0), dict(max_groups=0), dict(groups=0), dict(groups=0x10004), dict(k_res=0),
+           dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S=0),
+           dict(Wk=0), dict(P=0x10002)]
+    for over in bad:
+        assert kb.kvlinc_cache_validate(fake_struct(**over)) == kb.KVLINC_EINVAL, over
+    # correction off = all four of S, P, Wq, Wk NULL
+    assert kb.kvlinc_cache_validate(fake_struct(S=0, P=0, Wq=0, Wk=0)) == kb.KVLINC_OK
+    assert kb.lib.kvlinc_cache_validate(None) == kb.KVLINC_EINVAL
+
+
+def test_rejections_happen_before_any_launch():
+    ok = fake_struct()
+    p = ctypes.c_void_p(0x20000)
+    ap = kb.lib.kvlinc_append_quantize
+    assert ap(ctypes.byref(fake_struct(d=64)), p, p, None, 1, 0, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(ok), None, p, None, 1, 0, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(ok), p, ctypes.c_void_p(0x20002), None, 1, 0, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(ok), p, p, None, 0, 0, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(ok), p, p, None, 1, 129, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(ok), p, p, None, 1, -1, None) == kb.KVLINC_EINVAL
+    assert ap(ctypes.byref(fake_struct(R=32)), p, p, None, 1, 0, None) == kb.KVLINC_EINVAL  # lazy flush needs R == G
+    de = kb.lib.kvlinc_decode_attention
+    need = kb.kvlinc_decode_workspace_bytes(ok, 0)
+    assert need > 0
+    assert de(ctypes.byref(ok), None, p, p, need, 0, None) == kb.KVLINC_EINVAL
+    assert de(ctypes.byref(ok), p, p, None, need, 0, None) == kb.KVLINC_EWORKSPACE
+    assert de(ctypes.byref(ok), p, p, p, need - 1, 0, None) == kb.KVLINC_EWORKSPACE
+    assert de(ctypes.byref(ok), p, p, ctypes.c_void_p(0x20004), need, 0, None) == kb.KVLINC_EWORKSPACE
+    assert kb.kvlinc_decode_workspace_bytes(fake_struct(bits=3), 0) == 0
+
+
+def test_workspace_size_is_monotone_and_bounded():
+    c = fake_struct(B=16, H_q=32, H_kv=8, max_groups=80)
+    sizes = [kb.kvlinc_decode_workspace_bytes(c, n) for n in (1, 128, 129, 1024, 8192, 10240, 0)]
+    assert all(s > 0 and s % 16 == 0 for s in sizes)
+    assert sizes == sorted(sizes)
+    assert sizes[-1] == kb.kvlinc_decode_workspace_bytes(c, 80 * 128 + 128)
+    # per (sequence, query head): at most 1024 splits + 4 correction parts of 132 floats
+    assert sizes[-1] <= 16 * 32 * (1024 + 4) * 132 * 4

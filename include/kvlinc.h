@@ -151,6 +151,11 @@ size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_cont
  * out[b, h] = ( sum_i exp(q K_i / sqrt d) V_i + phi_q(q) S ) / ( sum_i exp(q K_i / sqrt d) + phi_q(q) P ) H^T
  * with K_i, V_i the dequantized codes for quantized tokens and the fp16 window entries otherwise.
  * A sequence with no tokens yields zeros.
+ *
+ * One kernel launch: blocks of groups are processed by separate workgroups that leave (max, sum, numerator) partials
+ * in the workspace (Alg. 1, the per-block outputs); the workgroup of a (sequence, KV head) that finishes last, counted
+ * in cache->split_done, merges them, adds the correction and writes `out`.  Results are deterministic for a given
+ * max_context (it fixes the block boundaries and hence the summation order).
  */
 int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
                             size_t workspace_bytes, int32_t max_context, void* stream);

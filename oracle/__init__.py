@@ -12,8 +12,9 @@ What each module follows:
                     and the correction states S_n, P_n (Sec. 3.2, Eq. 5).
 * ``attention``  -- corrected single-query attention (Eq. 3, Eq. 4, Eq. 5, Eq. 6) and the
                     block-parallel decode with its merge (Sec. 3.3, Alg. 1).
-* ``layout``     -- the physical 4 KB tile order of the packed 2-bit codes (an encoding of ours;
-                    the paper only fixes "16 codes per 32-bit word", Sec. 3.3).
+* ``layout``     -- the physical order of the packed cache: 9216-byte group records (two 4 KB tiles of
+                    2-bit codes plus scales and zero-points) and the window's value order (an encoding
+                    of ours; the paper only fixes "16 codes per 32-bit word", Sec. 3.3).
 * ``accounting`` -- average bits per cached element (Table 1, "KV Cache" column).
 
 Arithmetic is fp64 except where a floating-point value decides an integer or a stored 16-bit

@@ -31,13 +31,13 @@ MEASURED_TRAFFIC_BYTES = 108.8e6
 
 def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True):
     """Bytes one decode call must move: 2-bit codes (64 B per token and KV head), fp16 scale + zero-point (8 B),
-    the fp16 window (512 B per window token and KV head), S and P once per (sequence, KV head), W_q once, q and out.
-    Split partials are an implementation choice and are not counted."""
+    the fp16 window (512 B per window token and KV head), the 16-bit state S and the fp32 P once per (sequence, KV
+    head), W_q once, q and out.  Split partials are an implementation choice and are not counted."""
     groups = sum(-(-int(n) // 128) for n in n_quant)
     total = groups * H_kv * (2 * 4096 + 2 * 512)
     total += int(sum(n_res)) * H_kv * 512
     if correction:
-        total += B * H_kv * (256 * 128 + 256) * 4 + H_q * 2 * 128 * 128 * 2
+        total += B * H_kv * (256 * 128 * 2 + 256 * 4) + H_q * 2 * 128 * 128 * 2
     total += B * H_q * 128 * 2 * 2
     return total
 

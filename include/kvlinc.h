@@ -42,9 +42,14 @@
  *   v_res             [B, H_kv, R/4, 128, 4] fp16: the window's ROTATED values, 4 consecutive slots per channel:
  *                     slot r, channel c at [r/4][c][r%4].
  *   n_quant, n_res    [B] int32: quantized tokens / window tokens of each sequence (context = sum).
- *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.
+ *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.  They are
+ *                     the master copy: kvlinc_append_quantize accumulates into them.
+ *   S16               [B, H_kv, 128, 64, 4] fp16: S rounded to binary16 (the 16-bit state the paper's average-bit
+ *                     figures of Table 1 assume), rewritten by every append that flushes a group and read by
+ *                     kvlinc_decode_attention in place of S.  Tile t = (f / 64 * 2 + c / 64) * 16 + (f % 64) / 4 holds
+ *                     S[f][c] at [t][c % 64][f % 4]  (f = feature 0..255, c = channel 0..127).
  *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
- *                     S, P, Wq, Wk all NULL = correction off (plain quantized attention).
+ *                     S, S16, P, Wq, Wk all NULL = correction off (plain quantized attention).
  *   status            [1] int32, OR-ed KVLINC_ST_* bits.
  *   split_done        [B, H_kv] int32 scratch counters of kvlinc_decode_attention (arrival count of the splits of a
  *                     (sequence, KV head); the last split merges).  Zero them once after allocation; every call
@@ -96,6 +101,7 @@ typedef struct kvlinc_cache {
   int32_t* n_quant;
   int32_t* n_res;
   float* S;
+  kvlinc_half* S16;
   float* P;
   const kvlinc_half* Wq;
   const kvlinc_half* Wk;

@@ -29,6 +29,9 @@ Group record, 2304 words (everything one decode step needs of a group, contiguou
     words 2112 .. 2175   key zero-point, fp16 per channel
     words 2176 .. 2303   value (scale, zero-point) of token t in word 2176 + t: scale in the low half, zero in the high
 
+State tiles: the binary16 copy of S [256 features, 128 channels] that the decode step reads is stored as 128 tiles of
+64 x 4 halves; tile (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4 holds S[f][c] at [c % 64][f % 4].
+
 Window of fp16 values: rotated values are stored 4 consecutive tokens per channel, v_res[slot // 4][channel][slot % 4],
 so that a lane owning a channel reads 4 tokens with one 8-byte load; keys stay row-major k_res[slot][channel].
 """
@@ -161,3 +164,25 @@ def unpack_value_window(v_tiled, n_res):
     v_tiled = np.asarray(v_tiled)
     R = v_tiled.shape[0] * 4
     return np.ascontiguousarray(v_tiled.transpose(0, 2, 1).reshape(R, 128)[:n_res])
+
+
+def pack_state_tiles(S):
+    """S [256, 128] -> fp16 [128, 64, 4] in the tile order of the decode step's copy of the state."""
+    S = np.asarray(S)
+    assert S.shape == (256, 128)
+    f = np.arange(256)[:, None]
+    c = np.arange(128)[None, :]
+    tile = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4
+    out = np.zeros((128, 64, 4), dtype=np.float16)
+    out[tile, c % 64, f % 4] = S.astype(np.float16)
+    return out
+
+
+def unpack_state_tiles(tiles):
+    """fp16 [128, 64, 4] -> [256, 128] (inverse of pack_state_tiles)."""
+    tiles = np.asarray(tiles)
+    assert tiles.shape == (128, 64, 4)
+    f = np.arange(256)[:, None]
+    c = np.arange(128)[None, :]
+    tile = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4
+    return tiles[tile, c % 64, f % 4]

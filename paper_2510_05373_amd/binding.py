@@ -22,7 +22,7 @@ class CacheStruct(ctypes.Structure):
         ("groups", ctypes.c_void_p),
         ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
         ("n_quant", ctypes.c_void_p), ("n_res", ctypes.c_void_p),
-        ("S", ctypes.c_void_p), ("P", ctypes.c_void_p),
+        ("S", ctypes.c_void_p), ("S16", ctypes.c_void_p), ("P", ctypes.c_void_p),
         ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p),
         ("status", ctypes.c_void_p), ("split_done", ctypes.c_void_p),
     ]
@@ -130,15 +130,17 @@ class KVLincCache:
             assert Wk is not None and tuple(Wq.shape) == (H_q, 2, 128, 128) and tuple(Wk.shape) == (H_kv, 2, 128, 128)
             assert Wq.dtype == torch.float16 and Wk.dtype == torch.float16 and Wq.is_contiguous() and Wk.is_contiguous()
             self.S = z(B, H_kv, 256, 128, dt=torch.float32)
+            self.S16 = z(B, H_kv, 128, 64, 4, dt=torch.float16)
             self.P = z(B, H_kv, 256, dt=torch.float32)
         else:
-            self.S = self.P = None
+            self.S = self.S16 = self.P = None
         self.struct = CacheStruct(
             B=B, H_q=H_q, H_kv=H_kv, d=128, G=128, R=R, D=256, bits=2, max_groups=mg,
             groups=self.groups.data_ptr(),
             k_res=self.k_res.data_ptr(), v_res=self.v_res.data_ptr(),
             n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),
-            S=None if self.S is None else self.S.data_ptr(), P=None if self.P is None else self.P.data_ptr(),
+            S=None if self.S is None else self.S.data_ptr(), S16=None if self.S is None else self.S16.data_ptr(),
+            P=None if self.P is None else self.P.data_ptr(),
             Wq=None if Wq is None else Wq.data_ptr(), Wk=None if Wk is None else Wk.data_ptr(),
             status=self.status.data_ptr(), split_done=self.split_done.data_ptr())
         self._ws = None
@@ -146,7 +148,7 @@ class KVLincCache:
     def bytes(self):
         ts = [self.groups, self.k_res, self.v_res]
         if self.S is not None:
-            ts += [self.S, self.P]
+            ts += [self.S, self.S16, self.P]
         return sum(t.numel() * t.element_size() for t in ts)
 
     def append(self, k_new, v_new, n_new=None, keep_residual=0, stream=None):

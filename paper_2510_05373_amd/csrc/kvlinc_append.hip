@@ -302,6 +302,13 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     for (int i = 0; i < kHeadDim; i += 4)
       *reinterpret_cast<float4*>(S_glob + i) = make_float4(S_row[i], S_row[i + 1], S_row[i + 2], S_row[i + 3]);
     c.P[bh * kRank + tid] = P_f;
+    // binary16 tile copy of S for the decode kernel: tile (part r, channel half hh, feature step fs) holds
+    // S[64 r + 4 fs + k][64 hh + l] at [l][k]; this thread owns feature f = tid, i.e. (r, fs, k).
+    half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
+    const int r = tid >> 6, fs = (tid & 63) >> 2, k = tid & 3;
+#pragma unroll
+    for (int ch = 0; ch < kHeadDim; ++ch)
+      tiles[(((r * 2 + (ch >> 6)) * 16 + fs) * 64 + (ch & 63)) * 4 + k] = (half_t)S_row[ch];
   }
   if (bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
 

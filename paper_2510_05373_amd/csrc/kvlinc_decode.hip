@@ -123,6 +123,18 @@ __device__ __forceinline__ float4_t mfma_bcast(half4_t a, half4_t b, float4_t c,
   }
 }
 
+// 4x4 transpose of binary16 elements inside each lane quad: lane t of a quad brings {v[t][0], v[t][1]} in X and
+// {v[t][2], v[t][3]} in Y; lane h leaves with {v[0][h], v[1][h], v[2][h], v[3][h]}.
+// perm_sel = (lane & 1) ? 0x03020706 : 0x05040100.
+__device__ __forceinline__ half4_t quad_transpose(uint32_t X, uint32_t Y, uint32_t perm_sel, int lane) {
+  const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
+  const uint32_t X1 = __builtin_amdgcn_perm(TX, X, perm_sel);  // even lane {X.lo, TX.lo}; odd lane {TX.hi, X.hi}
+  const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, perm_sel);
+  const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
+  const bool upper = (lane & 2) != 0;
+  return as_h4(upper ? Y2 : X1, upper ? Y1 : X2);
+}
+
 // Position of pair j of a packed word inside the fp16 mantissa after the (optional) shift by 6: the code of pair j
 // sits at bits [2 pos + 1 : 2 pos] of its half and reads as code * 2^(2 pos - 24).
 __host__ __device__ constexpr int pair_pos(int j) { return j <= 4 ? j : j - 3; }
@@ -332,15 +344,7 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc
       st.pz[nb][2] = fmaf(p[2], vmid, fmaf((float)x23[0], comp, st.pz[nb][2]));
       st.pz[nb][3] = fmaf(p[3], vmid, fmaf((float)x23[1], comp, st.pz[nb][3]));
       // 4x4 transpose inside each lane quad: (lane = token, slots = heads) -> (lane = head, slots = tokens)
-      const uint32_t X = as_u32(x01), Y = as_u32(x23);
-      const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
-      const uint32_t X1 = __builtin_amdgcn_perm(TX, X, lc.perm_sel);  // even lane {X.lo, TX.lo}; odd lane {TX.hi, X.hi}
-      const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, lc.perm_sel);
-      const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
-      const bool upper = (lc.lane & 2) != 0;
-      const uint32_t U = upper ? Y2 : X1;
-      const uint32_t W = upper ? Y1 : X2;
-      A2[nb][hf] = as_h4(U, W);
+      A2[nb][hf] = quad_transpose(as_u32(x01), as_u32(x23), lc.perm_sel, lc.lane);
     }
   }
   // four independent accumulation chains per head block: (token half) x (channel half)
@@ -456,163 +460,132 @@ __device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t*
 }
 
 // ---- correction terms (Sec. 3.3: C_n = phi_q(q) S, C_d = phi_q(q) P; Eq. 6 for phi) -----------------------------------
-// The work of one (sequence, kv head) is cut into four parts over the rows of S: part r covers the 64 features
-// 64 (r % 2) .. + 63 of half hs = r / 2 of phi.  A part computes its 64 logits per head (a 128 x 64 slice of W_1 or
-// W_2), exponentiates them against its own maximum m_r and leaves the softmax normalisation of the half to the merge:
-//     e_f = exp(logit_f - m_r),  Z_r = sum_f e_f,  Cn_r = sum_f e_f S[f],  Cd_r = sum_f e_f P[f].
-// Output per (query head, part): {Cd_r, m_r, Z_r, -, Cn_r[128]}.
-// Every operand (q, the W slice, the S slice, P) is requested before anything is waited for; the logits change hands
-// through LDS once.  In both products a wave owns complete output columns and reduces with shuffles.
-
-__device__ __forceinline__ float xor_allsum_32rows(float v) {  // sum over lanes that differ in bits 1..5
-  v += dpp_f<kRowRor2>(v);
-  v += dpp_f<kRowRor4>(v);
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
-__device__ __forceinline__ float xor_allsum_8rows(float v) {  // sum over lanes that differ in bits 3..5
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
+// The work of a kv head is cut into kCorrParts parts over the rows of S: part r covers the kPartFeat features
+// kPartFeat (r % kPartsPerHalf) .. of half hs = r / kPartsPerHalf of phi.  A correction workgroup serves one part
+// for up to kCorrSeqs sequences, on the matrix cores:
+//   phase 1, wave w = query head w of the block of four: logits[s][f] = sum_c q[s][c] W[c][f] for the sequences s as
+//            the 4 rows of the 4x4x4 blocks, block = 4 features (with 32-feature parts blocks 8..15 repeat blocks 0..7), k = 4 channels
+//            (32 steps); the W rows are read in their natural order (a lane reads 4 features of one channel) and
+//            transposed inside the lane quads;
+//   phase 2, wave s = sequence s: e_f = exp(logit_f - m_r) with the part's own maximum m_r,
+//            Z_r = sum_f e_f, Cd_r = sum_f e_f P[f], and Cn_r = e S with the 4 heads as rows, block = 4 channels,
+//            k = 4 features (kPartSteps steps per channel half), S taken from its binary16 tile copy.
+// Output per (query head, part): {Cd_r, m_r, Z_r, -, Cn_r[128]}; the softmax normalisation of each half of phi over
+// its parts is left to the merge.
 
 // Workgroup barrier for data exchanged through LDS by ordinary LDS writes.
 __device__ __forceinline__ void barrier_lds_only() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-constexpr int kCorrParts = 4;
+constexpr int kCorrParts = 4;                // 4 or 8
+constexpr int kPartFeat = 256 / kCorrParts;  // features per part
+constexpr int kPartSteps = kPartFeat / 4;    // feature steps (and distinct feature blocks) per part
+constexpr int kPartsPerHalf = kCorrParts / 2;
+constexpr int kCorrSeqs = 4;  // sequences served by one correction workgroup (the rows of its matrix products)
+// binary16 tile copy of S: tile (part r, channel half hh, feature step fs) holds, for lane = 4 blk + j, the 4 halves
+// S[64 r + 4 fs + k][64 hh + lane], k = 0..3: what lane (blk, j) feeds as B operand of that step.
+constexpr int kStateTileHalfs = 256;  // halves per tile (64 lanes x 4)
+// r64 = 64-feature block of S (0..3), hh = channel half, fs = feature step inside the block (0..15)
+__device__ __forceinline__ long long state_tile(int r64, int hh, int fs) { return ((r64 * 2 + hh) * 16 + fs) * kStateTileHalfs; }
 
-// NH = 4 NB heads are processed together so that their cross-lane reductions overlap; heads beyond gq repeat the
-// last one and are not written.  The logits of a part live in [NH][64] floats of LDS.
-template <int NH>
-struct LogitRegs {
-  uint4 raw[NH][4];
-  uint2 qraw[NH];
-};
-
-// q W: wave w owns features 16w .. 16w+15 of the part; lane = (chunk of 8 features, group of 4 channels)
-template <int NH>
-__device__ __forceinline__ void logits_request(LogitRegs<NH>& lr, const kvlinc_cache& c, const half_t* __restrict__ q,
-                                               int gq, int bh, int r, int lane, int wave) {
-  const int b = bh / c.H_kv, g = bh % c.H_kv;
-  const int hs = r >> 1, fpart = 64 * (r & 1);
-  const int chunkA = lane & 1, rowgrpA = lane >> 1;
-  const int f0 = 16 * wave + 8 * chunkA;
-  const half_t* W0 = reinterpret_cast<const half_t*>(c.Wq) + ((long long)g * gq * 2 + hs) * kHeadDim * (kRank / 2) +
-                     (long long)rowgrpA * 4 * (kRank / 2) + fpart + f0;
-  const half_t* q0 = q + ((long long)b * c.H_q + g * gq) * kHeadDim + 4 * rowgrpA;
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    const int hc = h < gq ? h : gq - 1;
-    const half_t* W = W0 + (long long)hc * 2 * kHeadDim * (kRank / 2);
-    lr.qraw[h] = *reinterpret_cast<const uint2*>(q0 + (long long)hc * kHeadDim);
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) lr.raw[h][rb] = *reinterpret_cast<const uint4*>(W + rb * (kRank / 2));
-  }
+__device__ __forceinline__ float quadgroup_allmax(float v) {  // over the 16 lanes that share lane & 3
+  v = fmaxf(v, __shfl_xor(v, 4, 64));
+  v = fmaxf(v, __shfl_xor(v, 8, 64));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+__device__ __forceinline__ float quadgroup_allsum(float v) {
+  v += __shfl_xor(v, 4, 64);
+  v += __shfl_xor(v, 8, 64);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
 }
 
-// logit[h][f] = sum_c q[h][c] W[h][hs][c][fpart + f], written to sLogit[h][f]
-template <int NH>
-__device__ __forceinline__ void logits_compute(const LogitRegs<NH>& lr, int lane, int wave, float* sLogit) {
-  const int chunkA = lane & 1, rowgrpA = lane >> 1;
-  const int f0 = 16 * wave + 8 * chunkA;
-  float lg[NH][8];
+// sLogit: [kCorrSeqs][4][kPartFeat] floats of LDS.
+__device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, const half_t* __restrict__ q,
+                                                     float* __restrict__ corr, int gq, int g, int r, int b_first,
+                                                     int n_seq, int n_head_blocks, int lane, int wave, float* sLogit) {
+  const int hs = r / kPartsPerHalf, fpart = kPartFeat * (r % kPartsPerHalf);  // features 128 hs + fpart ..
+  const int blk = lane >> 2, j = lane & 3, fblk = blk & (kPartSteps - 1);
+  const int r64 = (128 * hs + fpart) >> 6, fs0 = (fpart & 63) >> 2;  // position of the part among the state tiles
+  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+  const half_t* Wq = reinterpret_cast<const half_t*>(c.Wq);
+  const half_t* S16 = reinterpret_cast<const half_t*>(c.S16);
+  // everything this wave reads from memory is requested at once: the state tiles and P of its sequence (phase 2),
+  // then the W rows and q of its head (phase 1)
+  const bool has_seq = wave < n_seq;
+  const int b_mine = b_first + (has_seq ? wave : 0), bh_mine = b_mine * c.H_kv + g;
+  const half_t* tiles = S16 + (long long)bh_mine * kRank * kHeadDim;
+  uint2 sreg[2][kPartSteps];
 #pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    const half_t* qv = reinterpret_cast<const half_t*>(&lr.qraw[h]);
+  for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) lg[h][i] = 0.f;
+    for (int fs = 0; fs < kPartSteps; ++fs)
+      sreg[hh][fs] = *reinterpret_cast<const uint2*>(tiles + state_tile(r64, hh, fs0 + fs) + 4 * lane);
+  const float4 p4 = *reinterpret_cast<const float4*>(c.P + (long long)bh_mine * kRank + 128 * hs + fpart + 4 * fblk);
+  for (int hb = 0; hb < n_head_blocks; ++hb) {
+    // ---- phase 1: this wave's head, all sequences ----
+    {
+      const int h = hb * 4 + wave;
+      const int hc = h < gq ? h : gq - 1;
+      const int b_row = b_first + (j < n_seq ? j : n_seq - 1);  // row j of A = sequence j
+      const half_t* qrow = q + ((long long)b_row * c.H_q + g * gq + hc) * kHeadDim + 4 * blk;
+      const half_t* W0 = Wq + (((long long)g * gq + hc) * 2 + hs) * kHeadDim * (kRank / 2) + (long long)j * (kRank / 2) +
+                         fpart + 4 * fblk;
+      uint2 w[32];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      const float qf = (float)qv[rb];
-      const half_t* hv = reinterpret_cast<const half_t*>(&lr.raw[h][rb]);
+      for (int i = 0; i < 32; ++i) w[i] = *reinterpret_cast<const uint2*>(W0 + (long long)(4 * i) * (kRank / 2));
+      const half4_t a0 = __builtin_bit_cast(half4_t, *reinterpret_cast<const uint2*>(qrow));       // channels 4 blk ..
+      const half4_t a1 = __builtin_bit_cast(half4_t, *reinterpret_cast<const uint2*>(qrow + 64));  // 64 + 4 blk ..
+      float4_t d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < 8; ++i) lg[h][i] = fmaf(qf, (float)hv[i], lg[h][i]);
-    }
-  }
+      for (int i = 0; i < 32; ++i) {
+        const half4_t bop = quad_transpose(w[i].x, w[i].y, perm_sel, lane);
+        d = mfma_bcast(i < 16 ? a0 : a1, bop, d, i & 15);
+      }
+      if (blk < kPartSteps) {
 #pragma unroll
-  for (int h = 0; h < NH; ++h)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) lg[h][i] = xor_allsum_32rows(lg[h][i]);
-  if (rowgrpA == 0) {
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
-      float* dst = sLogit + h * 64 + f0;
-      *reinterpret_cast<float4*>(dst) = make_float4(lg[h][0], lg[h][1], lg[h][2], lg[h][3]);
-      *reinterpret_cast<float4*>(dst + 4) = make_float4(lg[h][4], lg[h][5], lg[h][6], lg[h][7]);
-    }
-  }
-}
-
-// E S: wave w owns channels 32w .. 32w+31; lane = (chunk of 4 channels, group of 8 features).  The logits must be
-// visible in LDS (barrier) before the call.
-template <int NH>
-__device__ __forceinline__ void correction_apply(const kvlinc_cache& c, float* __restrict__ corr, int gq, int bh, int r,
-                                                 int lane, int wave, const float* sLogit) {
-  const int b = bh / c.H_kv, g = bh % c.H_kv;
-  const int hs = r >> 1, fpart = 64 * (r & 1);
-  const int c0 = 32 * wave + 4 * (lane & 7), fB = 8 * (lane >> 3);
-  const bool writer = (lane >> 3) == 0;
-  const float* S = c.S + ((long long)bh * kRank + 128 * hs + fpart + fB) * kHeadDim + c0;
-  float4 s4[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) s4[i] = *reinterpret_cast<const float4*>(S + (long long)i * kHeadDim);
-  const float pf = c.P[(long long)bh * kRank + 128 * hs + fpart + lane];
-
-  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
-  float mx[NH], z[NH], cd[NH], acc[NH][4];
-#pragma unroll
-  for (int h = 0; h < NH; ++h) mx[h] = wave_allmax(sLogit[h * 64 + lane]);
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    const float e_mine = __expf(sLogit[h * 64 + lane] - mx[h]);
-    z[h] = e_mine;
-    cd[h] = e_mine * pf;
-  }
-#pragma unroll
-  for (int h = 0; h < NH; ++h) { z[h] = wave_allsum(z[h]); cd[h] = wave_allsum(cd[h]); }
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    const float4 la = *reinterpret_cast<const float4*>(sLogit + h * 64 + fB);
-    const float4 lb = *reinterpret_cast<const float4*>(sLogit + h * 64 + fB + 4);
-    const float e[8] = {__expf(la.x - mx[h]), __expf(la.y - mx[h]), __expf(la.z - mx[h]), __expf(la.w - mx[h]),
-                        __expf(lb.x - mx[h]), __expf(lb.y - mx[h]), __expf(lb.z - mx[h]), __expf(lb.w - mx[h])};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[h][j] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      acc[h][0] = fmaf(e[i], s4[i].x, acc[h][0]);
-      acc[h][1] = fmaf(e[i], s4[i].y, acc[h][1]);
-      acc[h][2] = fmaf(e[i], s4[i].z, acc[h][2]);
-      acc[h][3] = fmaf(e[i], s4[i].w, acc[h][3]);
-    }
-  }
-#pragma unroll
-  for (int h = 0; h < NH; ++h)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[h][j] = xor_allsum_8rows(acc[h][j]);
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-    if (h < gq) {
-      float* dst = out0 + ((long long)h * kCorrParts + r) * kPartStride;
-      if (wave == 0 && lane == 0) { st_coherent(dst, cd[h]); st_coherent(dst + 1, mx[h]); st_coherent(dst + 2, z[h]); }
-      if (writer) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) st_coherent(dst + 4 + c0 + j, acc[h][j]);
+        for (int s = 0; s < kCorrSeqs; ++s) sLogit[(s * 4 + wave) * kPartFeat + lane] = d[s];
       }
     }
+    barrier_lds_only();
+    // ---- phase 2: this wave's sequence, the four heads of the block; lane = (feature step fs = blk, head j) ----
+    if (has_seq) {
+      const int b = b_mine;
+      // lanes of blocks beyond the part's feature blocks hold no features of their own: their terms are made zero
+      const float4 l4 = *reinterpret_cast<const float4*>(sLogit + (wave * 4 + j) * kPartFeat + 4 * fblk);
+      const float mx = quadgroup_allmax(fmaxf(fmaxf(l4.x, l4.y), fmaxf(l4.z, l4.w)));
+      const float live = blk < kPartSteps ? 1.0f : 0.0f;
+      const float e0 = live * __expf(l4.x - mx), e1 = live * __expf(l4.y - mx), e2 = live * __expf(l4.z - mx),
+                  e3 = live * __expf(l4.w - mx);
+      const float z = quadgroup_allsum((e0 + e1) + (e2 + e3));
+      const float cd = quadgroup_allsum(fmaf(e0, p4.x, fmaf(e1, p4.y, fmaf(e2, p4.z, e3 * p4.w))));
+      const half4_t aop = {(half_t)e0, (half_t)e1, (half_t)e2, (half_t)e3};
+      float4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int fs = 0; fs < kPartSteps; ++fs)
+          acc[hh] = mfma_bcast(aop, __builtin_bit_cast(half4_t, sreg[hh][fs]), acc[hh], fs);
+      float* out0 = corr + ((long long)b * c.H_q + g * gq + hb * 4) * kCorrParts * kPartStride;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (hb * 4 + i < gq) {
+          float* dst = out0 + ((long long)i * kCorrParts + r) * kPartStride;
+          st_coherent(dst + 4 + lane, acc[0][i]);
+          st_coherent(dst + 4 + 64 + lane, acc[1][i]);
+        }
+      }
+      if (blk == 0 && hb * 4 + j < gq) {
+        float* dst = out0 + ((long long)j * kCorrParts + r) * kPartStride;
+        st_coherent(dst, cd);
+        st_coherent(dst + 1, mx);
+        st_coherent(dst + 2, z);
+      }
+    }
+    if (hb + 1 < n_head_blocks) barrier_lds_only();  // the logits buffer is reused
   }
-}
-
-// A sequence without quantized tokens has empty states: its parts are written as zeros and S, P are not read.
-__device__ __forceinline__ void correction_part_empty(const kvlinc_cache& c, float* __restrict__ corr, int gq, int bh,
-                                                      int r) {
-  const int b = bh / c.H_kv, g = bh % c.H_kv;
-  float* out0 = corr + ((long long)b * c.H_q + g * gq) * kCorrParts * kPartStride;
-  for (int i = threadIdx.x; i < gq * kPartStride; i += kThreads)
-    st_coherent(out0 + ((long long)(i / kPartStride) * kCorrParts + r) * kPartStride + i % kPartStride, 0.f);
 }
 
 // ---- merge the splits of one (sequence, query head), add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5;
@@ -666,17 +639,30 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
   if (M != -INFINITY) {
     float cn0 = 0.f, cn1 = 0.f, cd = 0.f;
     if (corr != nullptr) {
-      // the two parts of each half of phi share one softmax: phi_f = e_f exp(m_r - M_hs) / Z_hs
+      // the parts of each half of phi share one softmax: phi_f = e_f exp(m_r - M_hs) / Z_hs
 #pragma unroll
       for (int hs = 0; hs < 2; ++hs) {
-        const int ra = 2 * hs, rb = 2 * hs + 1;
-        if (c_z[ra] + c_z[rb] > 0.f) {  // zero for a sequence without quantized tokens
-          const float Mh = fmaxf(c_m[ra], c_m[rb]);
-          const float wa = __expf(c_m[ra] - Mh), wb = __expf(c_m[rb] - Mh);
-          const float inv = 1.0f / (wa * c_z[ra] + wb * c_z[rb]);
-          cn0 += (wa * c_x[ra] + wb * c_x[rb]) * inv;
-          cn1 += (wa * c_y[ra] + wb * c_y[rb]) * inv;
-          cd += (wa * c_cd[ra] + wb * c_cd[rb]) * inv;
+        float zsum = 0.f, Mh = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < kPartsPerHalf; ++i) {
+          zsum += c_z[kPartsPerHalf * hs + i];
+          Mh = fmaxf(Mh, c_m[kPartsPerHalf * hs + i]);
+        }
+        if (zsum > 0.f) {
+          float zz = 0.f, xx = 0.f, yy = 0.f, dd = 0.f;
+#pragma unroll
+          for (int i = 0; i < kPartsPerHalf; ++i) {
+            const int rr = kPartsPerHalf * hs + i;
+            const float wgt = __expf(c_m[rr] - Mh);
+            zz = fmaf(wgt, c_z[rr], zz);
+            xx = fmaf(wgt, c_x[rr], xx);
+            yy = fmaf(wgt, c_y[rr], yy);
+            dd = fmaf(wgt, c_cd[rr], dd);
+          }
+          const float inv = 1.0f / zz;
+          cn0 = fmaf(xx, inv, cn0);
+          cn1 = fmaf(yy, inv, cn1);
+          cd = fmaf(dd, inv, cd);
         }
       }
     }
@@ -707,49 +693,147 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 
 
 
+#ifdef KVLINC_TUNING  // sweep builds only: wall-clock stamps per wave
+__device__ long long g_dbg_ts[1 << 18];
+#define DBG_TS(slot)                                                                              \
+  do {                                                                                            \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096)                                             \
+      g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + (slot)] = wall_clock64(); \
+  } while (0)
+#else
+#define DBG_TS(slot)
+#endif
+
+// Arrival of a workgroup at its (sequence, kv head): every wave first waits until its write-through stores have been
+// acknowledged, then one thread counts the workgroup in.  Returns true in the workgroup that completes the count.
+__device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) *sFlag = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  __syncthreads();
+  return *sFlag == expected - 1;
+}
+
+// Workgroups 0 .. B H_kv n_splits - 1 stream the groups and the window of split sp of a (sequence, kv head); when
+// the correction is on, 4 more workgroups per (sequence, kv head) follow, one per part of the correction.  All of
+// them count themselves in at split_done; the last arrival merges.
+#ifndef KVLINC_RING
+#define KVLINC_RING 1
+#endif
+#ifndef KVLINC_OCC
+#define KVLINC_OCC 3
+#endif
 template <int NB>
-__global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+__global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
                                                                    half_t* __restrict__ out, int n_splits, int gq) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
-  __shared__ __align__(16) float sLogit[kCorrParts][4 * NB * 64];
+  __shared__ int sFlag;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int bh = blockIdx.x / n_splits;
-  const int sp = blockIdx.x % n_splits;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the schedule in scalar registers
+  // correction workgroups come first in the grid: they are long chains of dependent steps and must start at once
+  const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
+  const int expected = n_splits + (corr != nullptr ? kCorrParts : 0);
+  DBG_TS(0);
+#ifdef KVLINC_TUNING
+  if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096) {
+    const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4), xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20);
+    g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 15] = ((long long)xcc << 32) | hw;
+  }
+#endif
+
+#ifdef KVLINC_CORR_LAST
+  const int n_stream_wg = c.B * c.H_kv * n_splits;
+  const bool is_corr = (int)blockIdx.x >= n_stream_wg;
+  const int corr_id = blockIdx.x - n_stream_wg, stream_id = blockIdx.x;
+#else
+  const bool is_corr = (int)blockIdx.x < n_corr;
+  const int corr_id = blockIdx.x, stream_id = blockIdx.x - n_corr;
+#endif
+  if (is_corr) {
+    // ---- one part of the correction (Sec. 3.3: C_n, C_d) for up to kCorrSeqs sequences of one kv head ----
+    const int id = corr_id;
+    const int n_sb = (c.B + kCorrSeqs - 1) / kCorrSeqs;
+    const int sb = id % n_sb, r = (id / n_sb) % kCorrParts, g = id / (n_sb * kCorrParts);
+    const int b_first = sb * kCorrSeqs;
+    const int n_seq = min(kCorrSeqs, c.B - b_first);
+    // A sequence without quantized tokens has S = P = 0 (the states only change at a flush), so its parts come out
+    // as zero without looking at n_quant.
+    correction_workgroup(c, q, corr, gq, g, r, b_first, n_seq, NB, lane, wave, lds);
+    DBG_TS(5);
+    // count this workgroup in at each of its sequences; merge those it completes
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int* sFlags = reinterpret_cast<int*>(lds);
+    if (tid < n_seq)
+      sFlags[tid] = __hip_atomic_fetch_add(c.split_done + (b_first + tid) * c.H_kv + g, 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    for (int s = 0; s < n_seq; ++s) {
+      if (sFlags[s] == expected - 1) {
+        const int b = b_first + s, bh = b * c.H_kv + g;
+        for (int h = wave; h < gq; h += kWaves) merge_row(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+        if (tid == 0) c.split_done[bh] = 0;
+      }
+    }
+    DBG_TS(7);
+    return;
+  }
+
+  // ---- one split of the groups and of the window (Alg. 1, the loop over blocks) ----
+  const int wg = stream_id;
+  const int bh = wg / n_splits;
+  const int sp = wg % n_splits;
   const int b = bh / c.H_kv;
   const int g = bh % c.H_kv;
+
+  // Static schedule, the same for every sequence length, so that a wave knows its first group before it knows the
+  // length.  Time is cut into rounds of 4 n_splits slots, slot(round, wave, split) = 4 n_splits round + n_splits wave
+  // + split; the groups 0, 1, 2, ... go to the slots in order, except that the two waves that own a half of the
+  // window sit out their first kSkip slots (the window is their work for that time).  Consecutive groups thus go to
+  // different workgroups, and every split gets the same share whatever the length.
+#ifndef KVLINC_SKIP
+#define KVLINC_SKIP 2
+#endif
+  constexpr int kSkip = KVLINC_SKIP;
+  const int slots = kWaves * n_splits;
+  int my_half = -1;
+  if (n_splits >= 2) {
+    if (wave == kWaves - 1 && sp >= n_splits - 2) my_half = n_splits - 1 - sp;
+  } else if (wave >= kWaves - 2) {
+    my_half = kWaves - 1 - wave;
+  }
+  const int base0 = n_splits >= 2 ? slots - 1 : kWaves - 1;  // round-0 slots of the owners of half 0 and half 1
+  const int base1 = n_splits >= 2 ? slots - 2 : kWaves - 2;
+  // group(round) = slot - (slots skipped before it).  A wave's slot offset is at most base0, so the owner of half 0
+  // has skipped min(round, kSkip) slots before it and the owner of half 1 one more if it comes earlier in the round.
+  const int off = wave * n_splits + sp;
+  const int lead1 = off > base1 ? 1 : 0;
+  auto group_of_round = [&](int round) {
+    return round * slots + off - min(round, kSkip) - min(round + lead1, kSkip);
+  };
+  int rd = my_half >= 0 ? kSkip : 0;
+  int idx = group_of_round(rd);
+
+  // The first records are requested before the sequence length is known (any group index below the capacity is
+  // readable memory); what they hold is used only if the group exists.  NR records per wave are in flight or in use.
+  constexpr int NR = NB == 1 ? KVLINC_RING : 1;
+  const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
+  KeyRegs kr[NR];
+  ValueRegs vr[NR];
+#pragma unroll
+  for (int k = 0; k < NR; ++k) {
+    const int gk = group_of_round(rd + k);
+    const long long first = gk < c.max_groups ? gk : c.max_groups - 1;
+    load_keys(kr[k], rec0 + first * kRecordWords, lane);
+    load_values(vr[k], rec0 + first * kRecordWords, lane);
+  }
+  DBG_TS(1);
   const int nq = c.n_quant[b];
   const int nr = c.n_res[b];
-  const int n_groups = (nq + kGroup - 1) / kGroup;
-  const int g0 = (int)((long long)n_groups * sp / n_splits);
-  const int g1 = (int)((long long)n_groups * (sp + 1) / n_splits);
-
-  // this wave's groups: g0 + wave, g0 + wave + 4, ...
-  const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
-  const int first = g0 + wave;
-  const int n_mine = first < g1 ? (g1 - first + kWaves - 1) / kWaves : 0;
-  // The logits of this workgroup's correction parts are computed first, under the latency of the first records.
-  const bool has_corr = corr != nullptr && sp < kCorrParts && nq > 0;
-  LogitRegs<4 * NB> lr;
-  if (has_corr) logits_request<4 * NB>(lr, c, q, gq, bh, sp, lane, wave);
-  KeyRegs kr;
-  ValueRegs vr;
-  if (n_mine > 0) {
-    load_keys(kr, rec0 + (long long)first * kRecordWords, lane);
-    load_values(vr, rec0 + (long long)first * kRecordWords, lane);
-  }
-  if (has_corr) {
-    logits_compute<4 * NB>(lr, lane, wave, sLogit[0]);
-    for (int r = sp + n_splits, i = 1; r < kCorrParts; r += n_splits, ++i) {
-      logits_request<4 * NB>(lr, c, q, gq, bh, r, lane, wave);
-      logits_compute<4 * NB>(lr, lane, wave, sLogit[i]);
-    }
-  }
-  if (corr != nullptr && nq == 0)
-    for (int r = sp; r < kCorrParts; r += n_splits) correction_part_empty(c, corr, gq, bh, r);
+  const int count = (nq + kGroup - 1) / kGroup;
 
   // per-lane constants
   const int quad = lane >> 2, hrow = lane & 3;
@@ -775,14 +859,10 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     }
   }
 
-  // halves of the fp16 window: half hw belongs to wave 3 of split n_splits-1-hw (to waves 3 and 2 of the only split)
-  {
-    const int hw = n_splits >= 2 ? (n_splits - 1 - sp) : (3 - wave);
-    const int owner_wave = n_splits >= 2 ? 3 : wave;
-    if (hw >= 0 && hw < 2 && wave == owner_wave && nr > 64 * hw)
-      window_half<NB>(c, q, bh, b, g, gq, hw, nr, lc, st);
-  }
-  if (n_mine > 0) {
+  if (my_half >= 0 && nr > 64 * my_half) window_half<NB>(c, q, bh, b, g, gq, my_half, nr, lc, st);
+  DBG_TS(2);
+
+  if (idx < count) {
     // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
     // heads beyond gq read as 0
     uint32_t Qs[NB][4];
@@ -799,24 +879,27 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
         Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
       }
     }
-    // Past the last group the current (cached) record is requested once more, so that no branch joins between a
-    // request and its first use and the waits stay partial.
-    for (int i = 0; i < n_mine; ++i) {
-      const int grp = first + i * kWaves;
-      const uint32_t* nxt = rec0 + (long long)(i + 1 < n_mine ? grp + kWaves : grp) * kRecordWords;
-      float4_t sc[NB][2];
-      qk_phase<NB>(kr, min(kGroup, nq - grp * kGroup), Qs, lc, sc);
-      load_keys(kr, nxt, lane);
-      update_reference<NB>(sc, st);
-      pv_phase<NB>(vr, sc, lc, st);
-      load_values(vr, nxt, lane);
+    // While a group is consumed the wave's next NR - 1 records are on their way and the one after them is requested
+    // as soon as a buffer is free.  Past the last group a cached record is requested instead, so that every pass
+    // issues the same loads and the waits stay partial.
+    for (; idx < count; rd += NR, idx = group_of_round(rd)) {
+#pragma unroll
+      for (int k = 0; k < NR; ++k) {
+        const int cur = k == 0 ? idx : group_of_round(rd + k);
+        const int nxt = group_of_round(rd + k + NR);
+        const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
+        float4_t sc[NB][2];
+        if (cur < count) qk_phase<NB>(kr[k], min(kGroup, nq - cur * kGroup), Qs, lc, sc);
+        load_keys(kr[k], src, lane);
+        if (cur < count) {
+          update_reference<NB>(sc, st);
+          pv_phase<NB>(vr[k], sc, lc, st);
+        }
+        load_values(vr[k], src, lane);
+      }
     }
   }
-  if (has_corr) {
-    barrier_lds_only();
-    for (int r = sp, i = 0; r < kCorrParts; r += n_splits, ++i)
-      correction_apply<4 * NB>(c, corr, gq, bh, r, lane, wave, sLogit[i]);
-  }
+  DBG_TS(3);
 
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
   float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                    // [kWaves][NB*4]
@@ -834,8 +917,8 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
           (st.acc[nb][0][1][h] + st.acc[nb][1][1][h]) * kRawScale + pz + st.accw[nb][1][h];
     }
   __syncthreads();
-  for (int idx = tid; idx < gq * kHeadDim; idx += kThreads) {
-    const int h = idx >> 7, ch = idx & 127;
+  for (int i = tid; i < gq * kHeadDim; i += kThreads) {
+    const int h = i >> 7, ch = i & 127;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sM[w][h]);
@@ -852,20 +935,15 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
     st_coherent(dst + 4 + ch, a);
   }
+  DBG_TS(6);
 
-  // The split that arrives last merges (Alg. 1 lines 13-15).  Every wave waits until its coherent stores have been
-  // acknowledged, the workgroup's arrival is counted, and the last arrival reads what the others wrote with coherent
+  // The workgroup that arrives last merges (Alg. 1 lines 13-15): it reads what the others wrote with coherent
   // loads.  No workgroup waits for another.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  int* flag = reinterpret_cast<int*>(lds);
-  if (tid == 0)
-    *flag = __hip_atomic_fetch_add(c.split_done + bh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-  __syncthreads();
-  if (*flag == n_splits - 1) {
+  if (arrive(c.split_done + bh, expected, &sFlag)) {
     for (int h = wave; h < gq; h += kWaves) merge_row(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
     if (tid == 0) c.split_done[bh] = 0;
   }
+  DBG_TS(7);
 }
 
 }  // namespace
@@ -905,7 +983,8 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const half_t* qq = reinterpret_cast<const half_t*>(q);
   float* part = workspace;
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
-  const dim3 grid(BH * n_splits), block(kThreads);
+  const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
+  const dim3 grid(BH * n_splits + n_corr), block(kThreads);
   if (gq <= 4)
     hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
                        gq);
@@ -917,3 +996,9 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
 
 
 }  // namespace kvlinc
+
+#ifdef KVLINC_TUNING
+extern "C" int kvlinc_dbg_read(long long* dst, size_t n) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(kvlinc::g_dbg_ts), n * sizeof(long long));
+}
+#endif

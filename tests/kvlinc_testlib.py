@@ -72,6 +72,10 @@ def check_pair_against_oracle(cache, b, g, k_rows, v_rows, nq, nr, Wk_g=None, ch
             den = np.linalg.norm(want)
             err = np.linalg.norm(got - want)
             assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
+        # the binary16 tile copy the decode step reads: the fp32 state (checked above) rounded to nearest, in the
+        # documented tile order
+        S16 = o_layout.unpack_state_tiles(cache.S16[b, g].cpu().numpy())
+        assert np.array_equal(u16(S16), u16(cache.S[b, g].cpu().numpy().astype(np.float16))), ("S16", b, g)
     return ref
 
 

@@ -23,7 +23,8 @@ def fake_struct(**over):
     """A descriptor whose pointers are aligned non-NULL integers; never dereferenced by the host checks."""
     base = 0x10000
     f = dict(B=2, H_q=8, H_kv=2, d=128, G=128, R=128, D=256, bits=2, max_groups=8, groups=base, k_res=base,
-             v_res=base, n_quant=base, n_res=base, S=base, P=base, Wq=base, Wk=base, status=base, split_done=base)
+             v_res=base, n_quant=base, n_res=base, S=base, S16=base, P=base, Wq=base, Wk=base, status=base,
+             split_done=base)
     f.update(over)
     return kb.CacheStruct(**f)
 
@@ -65,12 +66,12 @@ def test_validate_accepts_and_rejects():
     assert kb.kvlinc_cache_validate(ok) == kb.KVLINC_OK
     bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=4), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
            dict(H_q=32, H_kv=2), dict(B=0), dict(max_groups=0), dict(groups=0), dict(groups=0x10004), dict(k_res=0),
-           dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S=0),
-           dict(Wk=0), dict(P=0x10002)]
+           dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S=0), dict(S16=0),
+           dict(S16=0x10008), dict(Wk=0), dict(P=0x10002)]
     for over in bad:
         assert kb.kvlinc_cache_validate(fake_struct(**over)) == kb.KVLINC_EINVAL, over
-    # correction off = all four of S, P, Wq, Wk NULL
-    assert kb.kvlinc_cache_validate(fake_struct(S=0, P=0, Wq=0, Wk=0)) == kb.KVLINC_OK
+    # correction off = all of S, S16, P, Wq, Wk NULL
+    assert kb.kvlinc_cache_validate(fake_struct(S=0, S16=0, P=0, Wq=0, Wk=0)) == kb.KVLINC_OK
     assert kb.lib.kvlinc_cache_validate(None) == kb.KVLINC_EINVAL
 
 

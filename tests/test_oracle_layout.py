@@ -61,3 +61,15 @@ def test_literal_corners():
     one[:] = 0
     one[0, 64] = 3  # value: channel 64 = second channel half, lane 0 -> word (0*2+1)*64*4
     assert layout.pack_v_tile(one)[256] == 3
+
+
+def test_state_tiles_are_a_bijection():
+    rng = np.random.default_rng(5)
+    S = rng.standard_normal((256, 128)).astype(np.float16)
+    tiles = layout.pack_state_tiles(S)
+    assert tiles.shape == (128, 64, 4)
+    assert np.array_equal(layout.unpack_state_tiles(tiles).view(np.uint16), S.view(np.uint16))
+    # the stated index map, element by element on a few entries
+    for f, c in [(0, 0), (3, 5), (64, 63), (130, 64), (255, 127), (77, 100)]:
+        t = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4
+        assert tiles[t, c % 64, f % 4] == S[f, c]

@@ -591,8 +591,8 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
 // ---- merge the splits of one (sequence, query head), add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5;
 // Sec. 3.1).  Run by one wave of the split that arrives last; lane l owns channels 2l and 2l+1. ----------------------
 
-constexpr int kMergeBatch = 8;  // splits whose partial results are requested together
-
+// MB = splits whose partial results are requested together
+template <int MB>
 __device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr, int n_splits,
                                           int row, int lane, half_t* __restrict__ out) {
   const float* p0 = part + (long long)row * n_splits * kPartStride;
@@ -609,23 +609,23 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
   }
   // running merge over batches of splits, every batch requested at once
   float M = -INFINITY, n0 = 0.f, n1 = 0.f, den = 0.f;
-  for (int j0 = 0; j0 < n_splits; j0 += kMergeBatch) {
-    float mj[kMergeBatch], lj[kMergeBatch], ax[kMergeBatch], ay[kMergeBatch];
+  for (int j0 = 0; j0 < n_splits; j0 += MB) {
+    float mj[MB], lj[MB], ax[MB], ay[MB];
 #pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k) {
+    for (int k = 0; k < MB; ++k) {
       const float* pj = p0 + (long long)(j0 + k < n_splits ? j0 + k : n_splits - 1) * kPartStride;
       mj[k] = ld_coherent(pj); lj[k] = ld_coherent(pj + 1);
       ax[k] = ld_coherent(pj + 4 + 2 * lane); ay[k] = ld_coherent(pj + 5 + 2 * lane);
     }
     float Mb = M;
 #pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k)
+    for (int k = 0; k < MB; ++k)
       if (j0 + k < n_splits) Mb = fmaxf(Mb, mj[k]);
     if (Mb == -INFINITY) continue;
     const float f = exp2f(M - Mb);  // 0 while nothing has been merged yet
     n0 *= f; n1 *= f; den *= f;
 #pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k) {
+    for (int k = 0; k < MB; ++k) {
       if (j0 + k < n_splits && mj[k] != -INFINITY) {
         const float w = exp2f(mj[k] - Mb);
         n0 = fmaf(w, ax[k], n0);
@@ -704,6 +704,12 @@ __device__ long long g_dbg_ts[1 << 18];
 #define DBG_TS(slot)
 #endif
 
+__device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr, int n_splits,
+                                           int row, int lane, half_t* __restrict__ out) {
+  if (n_splits <= 4) merge_row<4>(part, corr, n_splits, row, lane, out);
+  else merge_row<8>(part, corr, n_splits, row, lane, out);
+}
+
 // Arrival of a workgroup at its (sequence, kv head): every wave first waits until its write-through stores have been
 // acknowledged, then one thread counts the workgroup in.  Returns true in the workgroup that completes the count.
 __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
@@ -774,7 +780,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_mai
     for (int s = 0; s < n_seq; ++s) {
       if (sFlags[s] == expected - 1) {
         const int b = b_first + s, bh = b * c.H_kv + g;
-        for (int h = wave; h < gq; h += kWaves) merge_row(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+        for (int h = wave; h < gq; h += kWaves) merge_rows(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
         if (tid == 0) c.split_done[bh] = 0;
       }
     }
@@ -940,7 +946,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_mai
   // The workgroup that arrives last merges (Alg. 1 lines 13-15): it reads what the others wrote with coherent
   // loads.  No workgroup waits for another.
   if (arrive(c.split_done + bh, expected, &sFlag)) {
-    for (int h = wave; h < gq; h += kWaves) merge_row(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+    for (int h = wave; h < gq; h += kWaves) merge_rows(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
     if (tid == 0) c.split_done[bh] = 0;
   }
   DBG_TS(7);
@@ -948,20 +954,24 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_mai
 
 }  // namespace
 
-// Splits per (sequence, kv head): aim at two workgroups per compute unit (2 x 256; measured best at long contexts:
-// more workgroups lengthen the fixed per-workgroup work -- window, correction parts, combine -- faster than they
-// shorten the group loop), but never more than kMaxGroupsPerSplit groups per workgroup (ragged batches then balance
-// dynamically) and never less than one group per wave.
+// Splits per (sequence, kv head).  Measured on MI355X (256 compute units): the launch is fastest when all its
+// workgroups, the correction workgroups included, are resident at once at about two per compute unit -- a second
+// generation of workgroups pays the start-up and the merge tail again, and a compute unit that hosts a correction
+// workgroup next to two streaming ones finishes late.  The kernel for more than 4 query heads per kv head holds only
+// two workgroups per compute unit, and there four splits measured better than three.  At most 32 splits (the merge
+// walks the splits serially), at least one group per wave.
 int decode_splits(const kvlinc_cache& c, int max_context) {
-  constexpr int kResidentWorkgroups = 512, kMaxGroupsPerSplit = 32;
+  constexpr int kTargetWorkgroups = 512, kMaxSplits = 32;
   const long long cap = (long long)c.max_groups * kGroup + c.R;
   const long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
   long long groups = (ctx + kGroup - 1) / kGroup;
   if (groups < 1) groups = 1;
   const long long bh = (long long)c.B * c.H_kv;
-  long long s = (kResidentWorkgroups + bh - 1) / bh;
-  const long long by_size = (groups + kMaxGroupsPerSplit - 1) / kMaxGroupsPerSplit;
-  if (s < by_size) s = by_size;
+  const int gq = c.H_q / c.H_kv;
+  long long n_corr = 0;
+  if (c.S != nullptr && gq <= 4) n_corr = (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs);
+  long long s = (kTargetWorkgroups - n_corr + bh / 2) / bh;  // rounded to nearest
+  if (s > kMaxSplits) s = kMaxSplits;
   const long long most = (groups + kWaves - 1) / kWaves;
   if (s > most) s = most;
 #ifdef KVLINC_TUNING  // sweep builds only: override the split policy from the environment

@@ -27,6 +27,7 @@ WORKLOAD = 2  # index into kvlinc_synth.CONFIGS
 # HBM bytes one decode launch of this workload moved (read + written) according to the FETCH_SIZE and WRITE_SIZE
 # counters, each scaled by what the same counter reports for a plain copy of known size; None = not measured.
 MEASURED_TRAFFIC_BYTES = 108.8e6
+EVENT_STRIDE = 4  # every 4th decode launch of the timed region is timed with dispatch events
 
 
 def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True):
@@ -127,21 +128,35 @@ def main():
     torch.cuda.synchronize()
     lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]
 
-    # ---- timed region: exactly K steps; HIP events on the launch stream bracket every decode launch ----------
-    ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
-    ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    # ---- timed region: exactly K steps.  Every EVENT_STRIDE-th decode launch carries a start and a stop event
+    # attached to its own dispatch on the launch stream (kvlinc_decode_attention_timed), so the kernel's duration is
+    # measured inside the timed region without extra packets between the kernels (such a launch costs the host
+    # about 25 us, so timing every launch would make the loop host-bound).
+    hip = ctypes.CDLL("libamdhip64.so")  # the copy torch has already loaded
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def new_event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
     use_events = not args.no_events
+    timed = [s for s in range(K_steps) if s % EVENT_STRIDE == 0] if use_events else []
+    ev_b = {s: new_event() for s in timed}
+    ev_c = {s: new_event() for s in timed}
+    f_dec_t = kb.lib.kvlinc_decode_attention_timed
     rc = 0
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for s in range(K_steps):
         i = W + s
         rc |= f_app(*app_args[i])
-        if use_events:
-            ev_b[s].record(stream)
-        rc |= f_dec(*dec_args[i])
-        if use_events:
-            ev_c[s].record(stream)
+        if s in ev_b:
+            rc |= f_dec_t(*dec_args[i], ev_b[s], ev_c[s])
+        else:
+            rc |= f_dec(*dec_args[i])
     t_cpu_done = time.perf_counter()
     torch.cuda.synchronize()
     t_end = time.perf_counter()
@@ -159,7 +174,14 @@ def main():
         n_res = (n - 1) % 128 + 1
         alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, [n - n_res] * B, [n_res] * B))
     if use_events:
-        decode_ms = np.array([ev_b[s].elapsed_time(ev_c[s]) for s in range(K_steps)])
+        decode_ms = np.empty(len(timed))
+        for k, s in enumerate(timed):
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), ev_b[s], ev_c[s]) == 0
+            decode_ms[k] = ms.value
+            hip.hipEventDestroy(ev_b[s])
+            hip.hipEventDestroy(ev_c[s])
+        alg_bytes = [alg_bytes[s] for s in timed]
     else:
         decode_ms = np.array([float("nan")])
     decode_avg_s = float(decode_ms.mean()) * 1e-3
@@ -186,7 +208,7 @@ def main():
                      "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
                      "kernel": "decode_main_kernel (the one launch of kvlinc_decode_attention)",
                      "algorithmic_bytes_per_launch": float(np.mean(alg_bytes)),
-                     "avg_launch_us": decode_avg_s * 1e6},
+                     "avg_launch_us": decode_avg_s * 1e6, "launches_timed": len(decode_ms)},
     }
 
     if args.pmc_calibration:

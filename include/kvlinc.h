@@ -51,9 +51,11 @@
  *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
  *                     S, S16, P, Wq, Wk all NULL = correction off (plain quantized attention).
  *   status            [1] int32, OR-ed KVLINC_ST_* bits.
- *   split_done        [B, H_kv] int32 scratch counters of kvlinc_decode_attention (arrival count of the splits of a
- *                     (sequence, KV head); the last split merges).  Zero them once after allocation; every call
- *                     leaves them at zero.  Two decode calls on the same cache must not overlap in time.
+ *   split_done        [B, H_kv] int32 scratch counters (arrival counts: of the workgroups of a (sequence, KV head)
+ *                     in kvlinc_decode_attention, where the last one merges; of the workgroups of a sequence in
+ *                     kvlinc_append_quantize, where the last one updates n_quant / n_res).  Zero them once after
+ *                     allocation; every call leaves them at zero.  Two calls on the same cache must not overlap in
+ *                     time.
  *   All cache buffers must be zero-initialised before their first use.
  *
  * Quantizer contract (bit exact; Eq. 1 taken against the stored fp16 scale and zero-point):
@@ -134,8 +136,8 @@ int kvlinc_cache_validate(const kvlinc_cache* cache);
  *
  * Per flushed group: key scale / zero-point / codes per channel, value scale / zero-point / codes per token
  * of the rotated value, S += phi_k(K - K_q)^T V_q and P += sum phi_k(K - K_q) when the adapters are given.
- * New tokens that stay in the window are stored as raw key and rotated fp16 value.  n_quant / n_res are
- * updated by a second kernel on the same stream.
+ * New tokens that stay in the window are stored as raw key and rotated fp16 value.  One kernel launch: the
+ * workgroup of a sequence that finishes last updates n_quant / n_res, after all of them have read the old values.
  */
 int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, const kvlinc_half* v_new,
                            const int32_t* n_new, int32_t T, int32_t keep_residual, void* stream);
@@ -165,6 +167,16 @@ size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_cont
  */
 int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
                             size_t workspace_bytes, int32_t max_context, void* stream);
+
+/*
+ * kvlinc_decode_attention with the kernel's own start and stop time stamps (Sec. 3.3, Alg. 1, as above): start_event
+ * and stop_event are hipEvent_t handles (created by the caller with timing enabled, both non-NULL) that the runtime
+ * attaches to the dispatch of the decode kernel, so that hipEventElapsedTime(start, stop) after completion is the
+ * kernel's execution time without the gaps that separately recorded events add.  For profiling; results are the same.
+ */
+int kvlinc_decode_attention_timed(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                                  size_t workspace_bytes, int32_t max_context, void* stream, void* start_event,
+                                  void* stop_event);
 
 #ifdef __cplusplus
 }

@@ -53,6 +53,9 @@ def _load():
     L.kvlinc_decode_attention.restype = ctypes.c_int
     L.kvlinc_decode_attention.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                           ctypes.c_int32, ctypes.c_void_p]
+    L.kvlinc_decode_attention_timed.restype = ctypes.c_int
+    L.kvlinc_decode_attention_timed.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     return L
 
 
@@ -106,6 +109,16 @@ def kvlinc_decode_attention(cache, q, out, workspace, workspace_bytes=None, max_
         workspace_bytes = workspace.numel() * workspace.element_size()
     return lib.kvlinc_decode_attention(ctypes.byref(_struct(cache)), _ptr(q), _ptr(out), _ptr(workspace),
                                        int(workspace_bytes), int(max_context), _stream(stream))
+
+
+def kvlinc_decode_attention_timed(cache, q, out, workspace, start_event, stop_event, workspace_bytes=None,
+                                  max_context=0, stream=None):
+    """As kvlinc_decode_attention; start_event / stop_event are raw hipEvent_t handles (integers)."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return lib.kvlinc_decode_attention_timed(ctypes.byref(_struct(cache)), _ptr(q), _ptr(out), _ptr(workspace),
+                                             int(workspace_bytes), int(max_context), _stream(stream),
+                                             ctypes.c_void_p(int(start_event)), ctypes.c_void_p(int(stop_event)))
 
 
 class KVLincCache:

@@ -63,16 +63,30 @@ size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_cont
   return kvlinc::decode_workspace_floats(*cache, n_splits) * sizeof(float);
 }
 
-int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
-                            size_t workspace_bytes, int32_t max_context, void* stream) {
+static int decode_checked(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                          size_t workspace_bytes, int32_t max_context, void* stream, void* start, void* stop) {
   const int rc = kvlinc_cache_validate(cache);
   if (rc != KVLINC_OK) return rc;
   if (bad_ptr(q, 16) || bad_ptr(out, 16)) return KVLINC_EINVAL;
+  if ((start == nullptr) != (stop == nullptr)) return KVLINC_EINVAL;
   if (bad_ptr(workspace, 16) || workspace_bytes < kvlinc_decode_workspace_bytes(cache, max_context))
     return KVLINC_EWORKSPACE;
   const int n_splits = kvlinc::decode_splits(*cache, max_context);
   return kvlinc::launch_decode(*cache, q, out, static_cast<float*>(workspace), n_splits,
-                               static_cast<hipStream_t>(stream));
+                               static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(start),
+                               static_cast<hipEvent_t>(stop));
+}
+
+int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                            size_t workspace_bytes, int32_t max_context, void* stream) {
+  return decode_checked(cache, q, out, workspace, workspace_bytes, max_context, stream, nullptr, nullptr);
+}
+
+int kvlinc_decode_attention_timed(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
+                                  size_t workspace_bytes, int32_t max_context, void* stream, void* start_event,
+                                  void* stop_event) {
+  if (start_event == nullptr || stop_event == nullptr) return KVLINC_EINVAL;
+  return decode_checked(cache, q, out, workspace, workspace_bytes, max_context, stream, start_event, stop_event);
 }
 
 }  // extern "C"

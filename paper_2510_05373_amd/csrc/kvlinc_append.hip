@@ -84,6 +84,27 @@ __device__ inline uint32_t q2_code(float x, const Q2& p) {
   return p.s == 0.0f ? 0u : c;
 }
 
+// The counters of a sequence change only after every workgroup of that sequence (one per kv head) has read them:
+// each workgroup counts itself in when it is done, and the one that completes the count writes n_quant / n_res (or
+// the error bit) and leaves the counter at zero.  The counter is the sequence's first split_done entry, which the
+// decode kernel uses in the same way and also leaves at zero.
+__device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int* counter = c.split_done + (long long)b * c.H_kv;
+    const int before = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (before == c.H_kv - 1) {
+      if (plan.err) {
+        atomicOr(c.status, plan.err);
+      } else if (n > 0) {
+        c.n_quant[b] = nq + plan.n_flush;
+        c.n_res[b] = plan.new_res;
+      }
+      *counter = 0;
+    }
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
                                                                  const int32_t* __restrict__ n_new, int T, int keep) {
@@ -102,7 +123,10 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   int n = n_new ? n_new[b] : T;
   n = n < 0 ? 0 : (n > T ? T : n);
   const AppendPlan plan = plan_append(nq, nr, n, c.R, keep, c.max_groups);
-  if (plan.err || n == 0) return;
+  if (plan.err || n == 0) {
+    commit_sequence(c, b, nq, n, plan);
+    return;
+  }
 
   const half_t* k_res = reinterpret_cast<const half_t*>(c.k_res) + bh * c.R * kHeadDim;
   const half_t* v_res = reinterpret_cast<const half_t*>(c.v_res) + bh * c.R * kHeadDim;
@@ -329,21 +353,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = (half_t)x0;
     v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = (half_t)x1;
   }
-}
-
-__global__ void append_commit_kernel(kvlinc_cache c, const int32_t* __restrict__ n_new, int T, int keep) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= c.B) return;
-  int n = n_new ? n_new[b] : T;
-  n = n < 0 ? 0 : (n > T ? T : n);
-  const AppendPlan plan = plan_append(c.n_quant[b], c.n_res[b], n, c.R, keep, c.max_groups);
-  if (plan.err) {
-    atomicOr(c.status, plan.err);
-    return;
-  }
-  if (n == 0) return;
-  c.n_quant[b] += plan.n_flush;
-  c.n_res[b] = plan.new_res;
+  commit_sequence(c, b, nq, n, plan);
 }
 
 }  // namespace
@@ -360,8 +370,6 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
   }
   hipLaunchKernelGGL(append_flush_kernel, dim3(c.B * c.H_kv), dim3(kThreads), sizeof(Lds), stream, c,
                      reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep);
-  if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
-  hipLaunchKernelGGL(append_commit_kernel, dim3((c.B + 63) / 64), dim3(64), 0, stream, c, n_new, T, keep);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   return KVLINC_OK;
 }

@@ -24,6 +24,7 @@
 // 1.5 * rounded operand is added back in binary32, which removes the mean of the rounding error.
 // Scores live in the log2 domain: x = q.k * log2(e)/sqrt(d).
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdlib>
 
@@ -987,23 +988,28 @@ size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
 }
 
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
-                  hipStream_t stream) {
+                  hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
   const int gq = c.H_q / c.H_kv;
   const int BH = c.B * c.H_kv;
   const half_t* qq = reinterpret_cast<const half_t*>(q);
+  half_t* oo = reinterpret_cast<half_t*>(out);
   float* part = workspace;
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const dim3 grid(BH * n_splits + n_corr), block(kThreads);
-  if (gq <= 4)
-    hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
-                       gq);
-  else
-    hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, reinterpret_cast<half_t*>(out), n_splits,
-                       gq);
+  if (start != nullptr) {  // timestamps of the dispatch itself, no extra packets on the stream
+    if (gq <= 4)
+      hipExtLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, n_splits, gq);
+    else
+      hipExtLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, n_splits, gq);
+  } else {
+    if (gq <= 4)
+      hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, oo, n_splits, gq);
+    else
+      hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, oo, n_splits, gq);
+  }
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
-
 
 }  // namespace kvlinc
 

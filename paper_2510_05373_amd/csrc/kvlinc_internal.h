@@ -54,7 +54,8 @@ int decode_splits(const kvlinc_cache& c, int max_context);
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream);
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits);
+// start / stop: optional events attached to the kernel's own dispatch (both or neither)
 int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
-                  hipStream_t stream);
+                  hipStream_t stream, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 }  // namespace kvlinc

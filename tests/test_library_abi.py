@@ -32,7 +32,8 @@ def fake_struct(**over):
 def test_header_functions_are_exported():
     names = declared_functions()
     assert names == ["kvlinc_append_quantize", "kvlinc_cache_validate", "kvlinc_decode_attention",
-                     "kvlinc_decode_workspace_bytes", "kvlinc_strerror", "kvlinc_version"]
+                     "kvlinc_decode_attention_timed", "kvlinc_decode_workspace_bytes", "kvlinc_strerror",
+                     "kvlinc_version"]
     lib = ctypes.CDLL(kb.lib_path)
     for n in names:
         assert hasattr(lib, n), n
@@ -94,6 +95,11 @@ def test_rejections_happen_before_any_launch():
     assert de(ctypes.byref(ok), p, p, p, need - 1, 0, None) == kb.KVLINC_EWORKSPACE
     assert de(ctypes.byref(ok), p, p, ctypes.c_void_p(0x20004), need, 0, None) == kb.KVLINC_EWORKSPACE
     assert kb.kvlinc_decode_workspace_bytes(fake_struct(bits=3), 0) == 0
+    dt = kb.lib.kvlinc_decode_attention_timed
+    ev = ctypes.c_void_p(0x30000)
+    assert dt(ctypes.byref(ok), p, p, p, need, 0, None, None, ev) == kb.KVLINC_EINVAL
+    assert dt(ctypes.byref(ok), p, p, p, need, 0, None, ev, None) == kb.KVLINC_EINVAL
+    assert dt(ctypes.byref(ok), p, p, p, need - 1, 0, None, ev, ev) == kb.KVLINC_EWORKSPACE
 
 
 def test_workspace_size_is_monotone_and_bounded():

@@ -724,14 +724,8 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
 // Workgroups 0 .. B H_kv n_splits - 1 stream the groups and the window of split sp of a (sequence, kv head); when
 // the correction is on, 4 more workgroups per (sequence, kv head) follow, one per part of the correction.  All of
 // them count themselves in at split_done; the last arrival merges.
-#ifndef KVLINC_RING
-#define KVLINC_RING 1
-#endif
-#ifndef KVLINC_OCC
-#define KVLINC_OCC 3
-#endif
 template <int NB>
-__global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+__global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
                                                                    half_t* __restrict__ out, int n_splits, int gq) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
@@ -824,18 +818,15 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_mai
   int rd = my_half >= 0 ? kSkip : 0;
   int idx = group_of_round(rd);
 
-  // The first records are requested before the sequence length is known (any group index below the capacity is
-  // readable memory); what they hold is used only if the group exists.  NR records per wave are in flight or in use.
-  constexpr int NR = NB == 1 ? KVLINC_RING : 1;
+  // The first record is requested before the sequence length is known (any group index below the capacity is
+  // readable memory); what it holds is used only if the group exists.
   const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
-  KeyRegs kr[NR];
-  ValueRegs vr[NR];
-#pragma unroll
-  for (int k = 0; k < NR; ++k) {
-    const int gk = group_of_round(rd + k);
-    const long long first = gk < c.max_groups ? gk : c.max_groups - 1;
-    load_keys(kr[k], rec0 + first * kRecordWords, lane);
-    load_values(vr[k], rec0 + first * kRecordWords, lane);
+  KeyRegs kr;
+  ValueRegs vr;
+  {
+    const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
+    load_keys(kr, rec0 + first * kRecordWords, lane);
+    load_values(vr, rec0 + first * kRecordWords, lane);
   }
   DBG_TS(1);
   const int nq = c.n_quant[b];
@@ -886,24 +877,19 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? KVLINC_OCC : 2) void decode_mai
         Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
       }
     }
-    // While a group is consumed the wave's next NR - 1 records are on their way and the one after them is requested
-    // as soon as a buffer is free.  Past the last group a cached record is requested instead, so that every pass
-    // issues the same loads and the waits stay partial.
-    for (; idx < count; rd += NR, idx = group_of_round(rd)) {
-#pragma unroll
-      for (int k = 0; k < NR; ++k) {
-        const int cur = k == 0 ? idx : group_of_round(rd + k);
-        const int nxt = group_of_round(rd + k + NR);
-        const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
-        float4_t sc[NB][2];
-        if (cur < count) qk_phase<NB>(kr[k], min(kGroup, nq - cur * kGroup), Qs, lc, sc);
-        load_keys(kr[k], src, lane);
-        if (cur < count) {
-          update_reference<NB>(sc, st);
-          pv_phase<NB>(vr[k], sc, lc, st);
-        }
-        load_values(vr[k], src, lane);
-      }
+    // While a group is consumed the wave's next record is already requested: its key part right after the scores,
+    // its value part right after E V.  Past the last group the current (cached) record is requested once more, so
+    // that no branch joins between a request and its first use and the waits stay partial.
+    while (idx < count) {
+      const int nxt = group_of_round(++rd);
+      const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
+      float4_t sc[NB][2];
+      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), Qs, lc, sc);
+      load_keys(kr, src, lane);
+      update_reference<NB>(sc, st);
+      pv_phase<NB>(vr, sc, lc, st);
+      load_values(vr, src, lane);
+      idx = nxt;
     }
   }
   DBG_TS(3);

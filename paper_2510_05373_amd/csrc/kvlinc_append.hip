@@ -7,13 +7,12 @@
 #include <hip/hip_runtime.h>
 
 #include "kvlinc_internal.h"
+#include "kvlinc_mfma.h"
 
 #pragma clang fp contract(off)
 
 namespace kvlinc {
 namespace {
-
-typedef _Float16 half_t;
 
 constexpr int kThreads = 256;
 constexpr int kRowPad = 130;   // halfs per LDS row of a 128-wide fp16 tile (odd number of 32-bit words)
@@ -27,8 +26,11 @@ struct Lds {
   uint8_t cV[kGroup][kCodePad];
   float kScale[kGroup], kZero[kGroup], vScale[kGroup], vZero[kGroup];
   float phi[kChunk][kRank];
-  float vHat[kChunk][kHeadDim];
-  float kErr[kChunk][kHeadDim];
+  // operands of the state update of one chunk of tokens, as binary16 (the key error in two terms hi + lo)
+  half_t kErrH[kChunk][kHeadDim + 8];
+  half_t kErrL[kChunk][kHeadDim + 8];
+  half_t cVh[kChunk][kHeadDim + 8];
+  float zs[kRank];
 };
 
 __device__ inline bool nonfinite_bits(half_t x) {
@@ -105,6 +107,13 @@ __device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, in
   }
 }
 
+#ifdef KVLINC_TUNING
+__device__ long long g_app_ts[64];
+#define APP_TS(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && j == 1) g_app_ts[slot] = wall_clock64(); } while (0)
+#else
+#define APP_TS(slot)
+#endif
+
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
                                                                  const int32_t* __restrict__ n_new, int T, int keep) {
@@ -134,25 +143,41 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   const half_t* v_src = v_new + bh * (long long)T * kHeadDim;
   const bool have_states = c.S != nullptr;
 
-  // correction states of this (sequence, kv head): thread f owns row f of S and entry f of P
-  float S_row[kHeadDim];
+  // Correction states of this (sequence, kv head) (Eq. 5).  The update runs on the matrix cores (4x4x4 blocks with a
+  // broadcast A operand): wave w owns the features 64 w .. 64 w + 63, i.e. 16 blocks of 4 rows of S, each as two
+  // accumulators (channel halves) whose lane 4 b + j holds channel 64 hh + 4 b + j.  Thread f = tid owns P[f].
+  const int blk = lane >> 2, jq = lane & 3;
+  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+  const int fwave = 64 * wave;
+  const bool states_live = have_states && plan.n_groups > 0;
+  float4_t sacc[16][2];
+  half4_t wop[32];  // W_k of this wave's features as B operands: step cs = channels 4 cs .. 4 cs + 3
   float P_f = 0.0f;
-  float* S_glob = have_states ? c.S + (bh * kRank + tid) * kHeadDim : nullptr;
-  if (have_states && plan.n_groups > 0) {
+  if (states_live) {
 #pragma unroll
-    for (int i = 0; i < kHeadDim; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(S_glob + i);
-      S_row[i] = v.x; S_row[i + 1] = v.y; S_row[i + 2] = v.z; S_row[i + 3] = v.w;
-    }
+    for (int fb = 0; fb < 16; ++fb)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          sacc[fb][hh][i] = c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane];
     P_f = c.P[bh * kRank + tid];
+    // a lane reads 4 features of one channel (natural order of W); the lane quad transposes
+    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) +
+                       ((long long)g * 2 + (wave >> 1)) * kHeadDim * (kRank / 2) + (long long)jq * (kRank / 2) +
+                       64 * (wave & 1) + 4 * blk;
+#pragma unroll
+    for (int cs = 0; cs < 32; ++cs) {
+      const uint2 w = *reinterpret_cast<const uint2*>(W0 + (long long)(4 * cs) * (kRank / 2));
+      wop[cs] = quad_transpose(w.x, w.y, perm_sel, lane);
+    }
   }
-  const half_t* Wk = have_states ? reinterpret_cast<const half_t*>(c.Wk) + (long long)g * 2 * kHeadDim * (kRank / 2)
-                                 : nullptr;
   bool bad = false;
 
   for (int j = 0; j < plan.n_groups; ++j) {
     const int valid = min(kGroup, plan.n_flush - j * kGroup);
     const long long grp = (long long)(nq / kGroup) + j;
+    APP_TS(0);
     // ---- 1. stage the group's raw keys and (raw or already rotated) values in LDS -------------------------
     for (int ch = tid; ch < kGroup * 16; ch += kThreads) {  // 16-byte chunks: 16 per token row
       const int t = ch >> 4, part = ch & 15;
@@ -177,6 +202,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       dv[0] = vv.x; dv[1] = vv.y; dv[2] = vv.z; dv[3] = vv.w;
     }
     __syncthreads();
+    APP_TS(1);
     // rotate the rows that came from new tokens (window rows are rotated already)
     for (int t = wave; t < valid; t += kThreads / 64) {
       if (j * kGroup + t < nr) continue;
@@ -186,6 +212,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       L.sV[t][2 * lane + 1] = (half_t)x1;
     }
     __syncthreads();
+    APP_TS(2);
     // ---- 2. Eq. 1: keys per channel over the group's tokens, rotated values per token over the channels ----
     if (tid < kGroup) {
       const int ch = tid;
@@ -228,6 +255,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       rec16[2 * (kRecValueSZ + t) + 1] = p.z16;
     }
     __syncthreads();
+    APP_TS(3);
     // ---- 3. pack the two 4 KB tiles ------------------------------------------------------------------------
     {
       uint32_t* k_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecKeyTile;
@@ -251,40 +279,51 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
         v_tile[wi] = vw;
       }
     }
+    APP_TS(4);
     // ---- 4. S += phi_k(K - K_q)^T V_q, P += sum phi_k(K - K_q) over the group's valid tokens (Eq. 5, Eq. 6) ----
-    if (have_states) {
-      const int half_sel = tid >> 7, ff = tid & 127;
-      const half_t* W = Wk + (long long)half_sel * kHeadDim * (kRank / 2) + ff;
+    // With V_q[t][c] = z_t + s_t code[t][c]:  S[f][c] += sum_t (phi[t][f] s_t) code[t][c] + sum_t phi[t][f] z_t.
+    // Both contractions take binary16 operands whose products are exact: the codes are small integers, W_k is
+    // binary16, and the key error and phi s are split into two binary16 terms (hi + lo).
+    if (states_live) {
+      float Z_f = 0.0f;  // sum_t phi[t][f] z_t of this group, f = tid
       for (int t0 = 0; t0 < valid; t0 += kChunk) {
         __syncthreads();
         for (int i = tid; i < kChunk * kHeadDim; i += kThreads) {
           const int tt = i >> 7, ch = i & 127, t = t0 + tt;
-          float ke = 0.0f, vh = 0.0f;
-          if (t < valid) {
-            ke = (float)L.sK[t][ch] - (L.kScale[ch] * (float)L.cK[t][ch] + L.kZero[ch]);
-            vh = L.vScale[t] * (float)L.cV[t][ch] + L.vZero[t];
-          }
-          L.kErr[tt][ch] = ke;
-          L.vHat[tt][ch] = vh;
+          float ke = 0.0f;
+          if (t < valid) ke = (float)L.sK[t][ch] - (L.kScale[ch] * (float)L.cK[t][ch] + L.kZero[ch]);
+          const half_t hi = (half_t)ke;
+          L.kErrH[tt][ch] = hi;
+          L.kErrL[tt][ch] = (half_t)(ke - (float)hi);
+          L.cVh[tt][ch] = (half_t)(float)L.cV[t][ch];
         }
         __syncthreads();
-        float acc[kChunk];
-#pragma unroll
-        for (int tt = 0; tt < kChunk; ++tt) acc[tt] = 0.0f;
-        for (int ch = 0; ch < kHeadDim; ch += 4) {
-          const float w0 = (float)W[(ch + 0) * (kRank / 2)], w1 = (float)W[(ch + 1) * (kRank / 2)];
-          const float w2 = (float)W[(ch + 2) * (kRank / 2)], w3 = (float)W[(ch + 3) * (kRank / 2)];
-#pragma unroll
-          for (int tt = 0; tt < kChunk; ++tt) {
-            const float4 e = *reinterpret_cast<const float4*>(&L.kErr[tt][ch]);
-            acc[tt] = fmaf(e.x, w0, acc[tt]);
-            acc[tt] = fmaf(e.y, w1, acc[tt]);
-            acc[tt] = fmaf(e.z, w2, acc[tt]);
-            acc[tt] = fmaf(e.w, w3, acc[tt]);
+        // logits[t][f] = sum_c kErr[t][c] W[c][f]: rows = 4 tokens, block = 4 features, k = 4 channels
+        {
+          float4_t dH[4], dL[4];
+          half4_t aH[4][2], aL[4][2];
+#pragma clang loop unroll(full)
+          for (int tb = 0; tb < 4; ++tb) {
+            dH[tb] = float4_t{0.f, 0.f, 0.f, 0.f};
+            dL[tb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma clang loop unroll(full)
+            for (int pr = 0; pr < 2; ++pr) {
+              aH[tb][pr] = *reinterpret_cast<const half4_t*>(&L.kErrH[4 * tb + jq][64 * pr + 4 * blk]);
+              aL[tb][pr] = *reinterpret_cast<const half4_t*>(&L.kErrL[4 * tb + jq][64 * pr + 4 * blk]);
+            }
           }
+#pragma clang loop unroll(full)
+          for (int cs = 0; cs < 32; ++cs)
+#pragma clang loop unroll(full)
+            for (int tb = 0; tb < 4; ++tb) {
+              dH[tb] = mfma_bcast(aH[tb][cs >> 4], wop[cs], dH[tb], cs & 15);
+              dL[tb] = mfma_bcast(aL[tb][cs >> 4], wop[cs], dL[tb], cs & 15);
+            }
+#pragma clang loop unroll(full)
+          for (int tb = 0; tb < 4; ++tb)
+#pragma clang loop unroll(full)
+            for (int i = 0; i < 4; ++i) L.phi[4 * tb + i][fwave + lane] = dH[tb][i] + dL[tb][i];
         }
-#pragma unroll
-        for (int tt = 0; tt < kChunk; ++tt) L.phi[tt][tid] = acc[tt];
         __syncthreads();
         // softmax over each half (128 features) of each token row: 2*kChunk rows, one wave per row at a time
         for (int row = wave; row < 2 * kChunk; row += kThreads / 64) {
@@ -292,47 +331,101 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
           float* p = &L.phi[tt][hs * 128];
           const float a0 = p[lane], a1 = p[lane + 64];
           float m = fmaxf(a0, a1);
-#pragma unroll
+#pragma clang loop unroll(full)
           for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
           const float e0 = __expf(a0 - m), e1 = __expf(a1 - m);
-          float s = e0 + e1;
-#pragma unroll
-          for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-          const float inv = (t0 + tt < valid) ? 1.0f / s : 0.0f;
+          float sum = e0 + e1;
+#pragma clang loop unroll(full)
+          for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+          const float inv = (t0 + tt < valid) ? 1.0f / sum : 0.0f;
           p[lane] = e0 * inv;
           p[lane + 64] = e1 * inv;
         }
         __syncthreads();
-#pragma unroll 1
+#pragma clang loop unroll(full)
         for (int tt = 0; tt < kChunk; ++tt) {
           const float ph = L.phi[tt][tid];
           P_f += ph;
-#pragma unroll
-          for (int ch = 0; ch < kHeadDim; ch += 4) {
-            const float4 v = *reinterpret_cast<const float4*>(&L.vHat[tt][ch]);
-            S_row[ch] = fmaf(ph, v.x, S_row[ch]);
-            S_row[ch + 1] = fmaf(ph, v.y, S_row[ch + 1]);
-            S_row[ch + 2] = fmaf(ph, v.z, S_row[ch + 2]);
-            S_row[ch + 3] = fmaf(ph, v.w, S_row[ch + 3]);
+          Z_f += ph * L.vZero[min(t0 + tt, kGroup - 1)];
+        }
+        // S[f][c] += sum_t (phi s)[t][f] code[t][c]: rows = 4 features, block = 4 channels, k = 4 tokens
+        {
+          half4_t bop[4][2];
+#pragma clang loop unroll(full)
+          for (int ts = 0; ts < 4; ++ts)
+#pragma clang loop unroll(full)
+            for (int hh = 0; hh < 2; ++hh) {
+              half4_t v;
+#pragma clang loop unroll(full)
+              for (int k = 0; k < 4; ++k) v[k] = L.cVh[4 * ts + k][64 * hh + lane];
+              bop[ts][hh] = v;
+            }
+          const int ts_mine = blk & 3;  // the A operand of token step ts is taken from block ts
+          float sc4[4];
+#pragma clang loop unroll(full)
+          for (int k = 0; k < 4; ++k) sc4[k] = L.vScale[min(t0 + 4 * ts_mine + k, kGroup - 1)];
+#pragma clang loop unroll(full)
+          for (int fb0 = 0; fb0 < 16; fb0 += 4) {
+            half4_t aH[4], aL[4];
+#pragma clang loop unroll(full)
+            for (int u = 0; u < 4; ++u) {
+              const int f = fwave + 4 * (fb0 + u) + jq;
+#pragma clang loop unroll(full)
+              for (int k = 0; k < 4; ++k) {
+                const float a = L.phi[4 * ts_mine + k][f] * sc4[k];
+                const half_t hi = (half_t)a;
+                aH[u][k] = hi;
+                aL[u][k] = (half_t)(a - (float)hi);
+              }
+            }
+#pragma clang loop unroll(full)
+            for (int ts = 0; ts < 4; ++ts)
+#pragma clang loop unroll(full)
+              for (int hh = 0; hh < 2; ++hh)
+#pragma clang loop unroll(full)
+                for (int u = 0; u < 4; ++u) {
+                  sacc[fb0 + u][hh] = mfma_bcast(aH[u], bop[ts][hh], sacc[fb0 + u][hh], ts);
+                  sacc[fb0 + u][hh] = mfma_bcast(aL[u], bop[ts][hh], sacc[fb0 + u][hh], ts);
+                }
           }
+        }
+      }
+      APP_TS(5);
+      // the zero-point term is the same for every channel of a row
+      __syncthreads();
+      L.zs[tid] = Z_f;
+      __syncthreads();
+#pragma clang loop unroll(full)
+      for (int fb = 0; fb < 16; ++fb) {
+        const float4 z4 = *reinterpret_cast<const float4*>(&L.zs[fwave + 4 * fb]);
+#pragma clang loop unroll(full)
+        for (int hh = 0; hh < 2; ++hh) {
+          sacc[fb][hh][0] += z4.x;
+          sacc[fb][hh][1] += z4.y;
+          sacc[fb][hh][2] += z4.z;
+          sacc[fb][hh][3] += z4.w;
         }
       }
     }
     __syncthreads();
   }
 
-  if (have_states && plan.n_groups > 0) {
-#pragma unroll
-    for (int i = 0; i < kHeadDim; i += 4)
-      *reinterpret_cast<float4*>(S_glob + i) = make_float4(S_row[i], S_row[i + 1], S_row[i + 2], S_row[i + 3]);
-    c.P[bh * kRank + tid] = P_f;
-    // binary16 tile copy of S for the decode kernel: tile (part r, channel half hh, feature step fs) holds
-    // S[64 r + 4 fs + k][64 hh + l] at [l][k]; this thread owns feature f = tid, i.e. (r, fs, k).
+  if (states_live) {
+    // fp32 master copy, row-major, and the binary16 tile copy for the decode kernel: tile (64-feature block = wave,
+    // channel half hh, feature step fb) holds S[64 wave + 4 fb + k][64 hh + l] at [l][k] -- exactly one accumulator.
     half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
-    const int r = tid >> 6, fs = (tid & 63) >> 2, k = tid & 3;
 #pragma unroll
-    for (int ch = 0; ch < kHeadDim; ++ch)
-      tiles[(((r * 2 + (ch >> 6)) * 16 + fs) * 64 + (ch & 63)) * 4 + k] = (half_t)S_row[ch];
+    for (int fb = 0; fb < 16; ++fb)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = sacc[fb][hh][i];
+        const half4_t t16 = {(half_t)sacc[fb][hh][0], (half_t)sacc[fb][hh][1], (half_t)sacc[fb][hh][2],
+                             (half_t)sacc[fb][hh][3]};
+        *reinterpret_cast<half4_t*>(tiles + (((wave * 2 + hh) * 16 + fb) * 64 + lane) * 4) = t16;
+      }
+    c.P[bh * kRank + tid] = P_f;
   }
   if (bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
 
@@ -357,6 +450,12 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
 }
 
 }  // namespace
+
+#ifdef KVLINC_TUNING
+extern "C" int kvlinc_app_ts_read(long long* dst, size_t n) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_app_ts), n * sizeof(long long));
+}
+#endif
 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream) {

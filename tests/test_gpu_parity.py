@@ -167,3 +167,76 @@ def test_run_to_run_determinism(kv):
     cache2, *_ = _build(kv, 15, B, H_q, H_kv, lengths)
     for name in ("groups", "k_res", "v_res", "S", "P"):
         assert torch.equal(getattr(cache, name), getattr(cache2, name)), name
+
+
+@pytest.mark.parametrize("n_quant,n_res", [(0, 1), (0, 64), (0, 65), (0, 128), (128, 1), (128, 63), (256, 64),
+                                           (256, 65), (384, 127), (1024, 128)])
+def test_window_boundaries(kv, n_quant, n_res):
+    """Every way the fp16 window can meet its two 64-token halves, with and without quantized groups before it."""
+    B, H_q, H_kv = 2, 8, 2
+    n = n_quant + n_res
+    lengths = [n, n]
+    cache, K, V, Wq, Wk = _build(kv, 16, B, H_q, H_kv, lengths)
+    assert cache.n_quant.cpu().tolist() == [n_quant] * B and cache.n_res.cpu().tolist() == [n_res] * B
+    q = tl.gen_q(16, B, H_q)
+    out = cache.decode(tl.to_dev(q), max_context=n).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, [n_quant] * B, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+
+
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7])
+def test_batch_sizes_around_the_correction_width(kv, B):
+    """The correction workgroups serve 4 sequences each: batches that do not fill the last one."""
+    H_q, H_kv = 4, 1
+    lengths = [300 + 131 * b for b in range(B)]
+    cache, K, V, Wq, Wk = _build(kv, 17, B, H_q, H_kv, lengths)
+    q = tl.gen_q(17, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+
+
+def test_result_does_not_depend_on_the_launch_bound(kv):
+    """max_context only sizes the launch: any upper bound gives the same result up to the summation order."""
+    import torch
+    B, H_q, H_kv = 1, 4, 1
+    lengths = [2000]
+    cache, K, V, Wq, Wk = _build(kv, 18, B, H_q, H_kv, lengths, capacity=16384)
+    q = tl.gen_q(18, B, H_q)
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    outs = []
+    for bound in (2000, 2048, 5000, 0):  # 0 = the cache's capacity
+        out = cache.decode(tl.to_dev(q), max_context=bound).cpu().numpy()
+        tl.check_outputs(out, want)
+        outs.append(out.astype(np.float64))
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() <= 2e-3
+    assert int(cache.split_done.abs().sum().item()) == 0
+
+
+def test_timed_entry_point_gives_the_same_bits(kv):
+    """kvlinc_decode_attention_timed is kvlinc_decode_attention plus two events on the dispatch."""
+    import ctypes
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    lengths = [900, 1300]
+    cache, K, V, Wq, Wk = _build(kv, 19, B, H_q, H_kv, lengths)
+    q = tl.to_dev(tl.gen_q(19, B, H_q))
+    plain = cache.decode(q).clone()
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+    out = torch.empty_like(q)
+    ws = cache.workspace(0)
+    rc = kv.kvlinc_decode_attention_timed(cache, q, out, ws, e0.value, e1.value)
+    assert rc == kv.KVLINC_OK
+    torch.cuda.synchronize()
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+    assert 0.0 < ms.value < 50.0
+    assert torch.equal(out, plain)
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)

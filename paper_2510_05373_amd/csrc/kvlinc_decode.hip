@@ -271,7 +271,10 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc
   for (int hf = 0; hf < 2; ++hf) {
     const float vs = h2f((uint16_t)(g.sz[hf] & 0xFFFFu));
     const float vmid = h2f((uint16_t)(g.sz[hf] >> 16)) + 1.5f * vs;
-    const float vsg = vs * lc.vgain;       // value scale with the k-slot gain of this lane's token
+    // value scale with the k-slot gain of this lane's token.  The weights p vsg are packed to binary16 by
+    // truncation (one instruction for two values), which on its own pulls them down by half an ulp on average
+    // (~2^-11.5 relative) against the exactly summed denominator; the factor centres that error.
+    const float vsg = vs * lc.vgain * 1.000345f;
     const float comp = -1.5f / lc.vgain;   // exact (power of two times 1.5)
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {

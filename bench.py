@@ -48,7 +48,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--layers", type=int, default=8, help="distinct layer caches cycled through")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="distinct layer caches cycled through (default: 8; 4 for the two largest workloads)")
+    ap.add_argument("--workload", type=int, default=WORKLOAD, choices=[2, 3, 4, 5],
+                    help="index into kvlinc_synth.CONFIGS; the default is the workload the metric is quoted on, the "
+                         "others run on device-generated N(0, 1) data without the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run 4 plain device copies of 256 MiB, the known-size reference for scaling the "
@@ -67,37 +71,59 @@ def main():
     import kvlinc_synth as synth
     import paper_2510_05373_amd as kv
 
-    cfg = synth.CONFIGS[WORKLOAD]
-    B, H_q, H_kv, n0 = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["n"]
-    L, K_steps, W = args.layers, args.steps, args.warmup
+    wl = args.workload
+    cfg = synth.CONFIGS[wl]
+    B, H_q, H_kv = cfg["B"], cfg["H_q"], cfg["H_kv"]
+    L = args.layers if args.layers else (8 if wl in (2, 3) else 4)
+    K_steps, W = args.steps, args.warmup
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if wl == 5:
+        base_len = synth.ragged_lengths(wl, B, cfg["n_min"], cfg["n_max"]).astype(np.int64)
+    else:
+        base_len = np.full(B, cfg["n"], dtype=np.int64)
+    n0 = int(base_len.max())
 
-    # ---- inputs: one seeded K/V history (host, for the oracle sample) copied into L distinct caches ----------
+    # ---- inputs: one seeded K/V history copied into L distinct caches.  For the default workload it is generated
+    # on the host (the oracle leg needs it); the other workloads take device-generated N(0, 1) data.
     t0 = time.time()
-    Kh = np.empty((B, H_kv, n0, 128), dtype=np.float16)
-    Vh = np.empty_like(Kh)
-    for b in range(B):
-        for g in range(H_kv):
-            Kh[b, g] = synth.keys(WORKLOAD, b, g, n0)
-            Vh[b, g] = synth.values(WORKLOAD, b, g, n0)
-    Wq_h, Wk_h = synth.adapters_q(WORKLOAD, H_q), synth.adapters_k(WORKLOAD, H_kv)
-    Kd, Vd = torch.from_numpy(Kh).to(dev), torch.from_numpy(Vh).to(dev)
+    Wq_h, Wk_h = synth.adapters_q(wl, H_q), synth.adapters_k(wl, H_kv)
     Wq, Wk = torch.from_numpy(Wq_h).to(dev), torch.from_numpy(Wk_h).to(dev)
+    if wl == WORKLOAD:
+        Kh = np.empty((B, H_kv, n0, 128), dtype=np.float16)
+        Vh = np.empty_like(Kh)
+        for b in range(B):
+            for g in range(H_kv):
+                Kh[b, g] = synth.keys(wl, b, g, n0)
+                Vh[b, g] = synth.values(wl, b, g, n0)
+        Kd, Vd = torch.from_numpy(Kh).to(dev), torch.from_numpy(Vh).to(dev)
+    else:
+        g0 = torch.Generator(device=dev)
+        g0.manual_seed(synth.BASE_SEED + wl)
+        Kd = torch.empty(B, H_kv, n0, 128, dtype=torch.float16, device=dev)
+        Vd = torch.empty_like(Kd)
+        for b in range(B):  # per sequence, to bound the fp32 temporaries
+            Kd[b] = torch.randn(H_kv, n0, 128, device=dev, generator=g0).half()
+            Vd[b] = torch.randn(H_kv, n0, 128, device=dev, generator=g0).half()
     total_steps = W + K_steps
     per_layer = -(-total_steps // L)
-    # Windows flush once per 128 appends.  Layers start a few tokens short of the nominal context, staggered so
-    # that flush steps fall inside the timed region at about their natural rate (here 2 layers out of 8).
+    # Windows flush once per 128 appends.  With equal lengths the layers start a few tokens short of the nominal
+    # context, staggered so that flush steps fall inside the timed region at about their natural rate (here 2 layers
+    # out of 8); ragged lengths are staggered by themselves.
     caches, start_len = [], []
     for j in range(L):
         short = 0
-        if j % 4 == 0:
+        if wl != 5 and j % 4 == 0:
             short = min(n0 - 1, W // L + 3 + (j // 4) * 7)  # its window (full at n0) flushes at append `short`+1
-        n_start = n0 - short
+        n_start = base_len - short
         c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk)
-        c.append(Kd[:, :, :n_start].contiguous(), Vd[:, :, :n_start].contiguous())
+        t_max = int(n_start.max())
+        c.append(Kd[:, :, :t_max].contiguous(), Vd[:, :, :t_max].contiguous(),
+                 n_new=torch.from_numpy(n_start.astype(np.int32)).to(dev))
         caches.append(c)
-        start_len.append(n_start)
+        start_len.append(n_start.copy())
+    if wl != WORKLOAD:
+        del Kd, Vd
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.BASE_SEED)
     k_new = torch.randn(total_steps, B, H_kv, 1, 128, device=dev, generator=gen).half()
@@ -126,7 +152,7 @@ def main():
     for i in range(W):
         assert f_app(*app_args[i]) == 0 and f_dec(*dec_args[i]) == 0
     torch.cuda.synchronize()
-    lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]
+    lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]  # per layer: [B] lengths
 
     # ---- timed region: exactly K steps.  Every EVENT_STRIDE-th decode launch carries a start and a stop event
     # attached to its own dispatch on the launch stream (kvlinc_decode_attention_timed), so the kernel's duration is
@@ -168,11 +194,11 @@ def main():
     alg_bytes = []
     for s in range(K_steps):
         j = (W + s) % L
-        lens[j] += 1
+        lens[j] = lens[j] + 1
         n = lens[j]
-        tokens += B * n
+        tokens += int(n.sum())
         n_res = (n - 1) % 128 + 1
-        alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, [n - n_res] * B, [n_res] * B))
+        alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, n - n_res, n_res))
     if use_events:
         decode_ms = np.empty(len(timed))
         for k, s in enumerate(timed):
@@ -187,7 +213,7 @@ def main():
     decode_avg_s = float(decode_ms.mean()) * 1e-3
     achieved = float(np.mean(alg_bytes)) / decode_avg_s / 1e9
     traffic = None
-    if MEASURED_TRAFFIC_BYTES is not None and n0 == 8192:
+    if MEASURED_TRAFFIC_BYTES is not None and wl == WORKLOAD:
         traffic = MEASURED_TRAFFIC_BYTES
 
     result = {
@@ -200,7 +226,7 @@ def main():
         "dtype": "u2 codes, f16 operands, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": cfg["name"], "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
-                   "context": n0, "window": 128, "group": 128, "bits": 2, "correction_rank": 256,
+                   "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0), "window": 128, "group": 128, "bits": 2, "correction_rank": 256,
                    "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
                    "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),
                    "launch_loop_cpu_ms_per_step": (t_cpu_done - t_start) / K_steps * 1e3, "setup_s": setup_s},
@@ -220,7 +246,9 @@ def main():
         del src, dst
 
     # ---- the oracle beside it: same decode step, bounded sample, host cores ----------------------------------
-    if not args.no_cpu_baseline:
+    if wl != WORKLOAD:
+        result["cpu_baseline"] = None  # the oracle leg runs on the default workload only
+    elif not args.no_cpu_baseline:
         from oracle import attention as o_attn
         from oracle import kvcache as o_cache
         try:
@@ -231,9 +259,10 @@ def main():
         # parity of the bench configuration on the sample + timing of the oracle's decode of the same rows
         i_chk = W + K_steps - 1
         j = i_chk % L
-        n = lens[j]
+        n = int(lens[j][0])  # equal lengths in this workload
+        s0 = int(start_len[j][0])
         nq, nr = o_cache.window_split(n)
-        n_app = n - start_len[j]
+        n_app = n - s0
         idx = [i for i in range(W + K_steps) if i % L == j]
         k_app = k_new[idx][:, :, :, 0].cpu().numpy()  # [n_app, B, H_kv, 128]
         v_app = v_new[idx][:, :, :, 0].cpu().numpy()
@@ -243,8 +272,8 @@ def main():
         gq = H_q // H_kv
         refs = []
         for (b, g) in pairs:
-            Kf = np.concatenate([Kh[b, g, :start_len[j]], k_app[:n_app, b, g]])
-            Vf = np.concatenate([Vh[b, g, :start_len[j]], v_app[:n_app, b, g]])
+            Kf = np.concatenate([Kh[b, g, :s0], k_app[:n_app, b, g]])
+            Vf = np.concatenate([Vh[b, g, :s0], v_app[:n_app, b, g]])
             refs.append(o_cache.build_cache(Kf, Vf, nq, Wk=Wk_h[g]))
         t_cpu, rows, reps = 0.0, 0, 0
         err_num = err_den = 0.0

@@ -1,16 +1,17 @@
 // Decode: single-query attention read directly from the packed 2-bit cache on the CDNA4 matrix cores, with the
 // linear correction and the fp16 window (Sec. 3.3, Alg. 1; Sec. 3.2, Eq. 5-6; Sec. 3.1 for the rotated value basis).
 //
-// decode_main_kernel: one kind of workgroup, (sequence, kv head, split).  Its four waves take the groups of
-// the split round-robin; a wave owns a group of 128 tokens at a time and keeps its own (m, l, acc).  A group record
-// is fetched in two parts, each requested again for the next group as soon as its contraction has consumed it.
-// On the side a workgroup computes its share of the correction terms (C_n = phi_q S, C_d = phi_q P, split into
-// four parts over the rows of S) and one wave
-// may own half of the fp16 window, processed as one more block of tokens.  The waves are combined through LDS and
-// the workgroup writes one (m, l, Y_s) per query head (Alg. 1 line 11).
-// The split of a (sequence, kv head) that finishes last merges, one wave per query head: it weighs the splits by
-// 2^(m_j - M), adds the correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies H^T and stores fp16 (Alg. 1
-// lines 13-15 with Eq. 5).  One launch per decode step.
+// decode_main_kernel, one launch per decode step, two kinds of workgroups:
+//   streaming workgroups (sequence, kv head, split): the four waves take groups of 128 tokens from a static schedule
+//   that is the same for every sequence length; a wave keeps its own (m, l, acc).  A group record is fetched in two
+//   parts, each requested again for the wave's next group as soon as its contraction has consumed it.  Two waves per
+//   (sequence, kv head) also own a 64-token half of the fp16 window, processed as one more block of tokens.  The
+//   waves are combined through LDS and the workgroup writes one (m, l, Y_s) per query head (Alg. 1 line 11);
+//   correction workgroups (kv head, part of phi, 4 sequences): C_n = phi_q S and C_d = phi_q P, cut into parts over
+//   the rows of S, on the matrix cores.
+// Every workgroup counts itself in at its (sequence, kv head); the one that arrives last merges, one wave per query
+// head: it weighs the splits by 2^(m_j - M), adds the correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies
+// H^T and stores fp16 (Alg. 1 lines 13-15 with Eq. 5).  No workgroup waits for another.
 //
 // Both contractions of a group run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad
 // (cbsz=4, abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
@@ -693,14 +694,8 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   }
 #endif
 
-#ifdef KVLINC_CORR_LAST
-  const int n_stream_wg = c.B * c.H_kv * n_splits;
-  const bool is_corr = (int)blockIdx.x >= n_stream_wg;
-  const int corr_id = blockIdx.x - n_stream_wg, stream_id = blockIdx.x;
-#else
   const bool is_corr = (int)blockIdx.x < n_corr;
   const int corr_id = blockIdx.x, stream_id = blockIdx.x - n_corr;
-#endif
   if (is_corr) {
     // ---- one part of the correction (Sec. 3.3: C_n, C_d) for up to kCorrSeqs sequences of one kv head ----
     const int id = corr_id;
@@ -743,10 +738,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   // + split; the groups 0, 1, 2, ... go to the slots in order, except that the two waves that own a half of the
   // window sit out their first kSkip slots (the window is their work for that time).  Consecutive groups thus go to
   // different workgroups, and every split gets the same share whatever the length.
-#ifndef KVLINC_SKIP
-#define KVLINC_SKIP 2
-#endif
-  constexpr int kSkip = KVLINC_SKIP;
+  constexpr int kSkip = 2;
   const int slots = kWaves * n_splits;
   int my_half = -1;
   if (n_splits >= 2) {

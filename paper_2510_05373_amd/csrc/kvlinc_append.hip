@@ -30,6 +30,9 @@ struct Lds {
   half_t kErrH[kChunk][kHeadDim + 8];
   half_t kErrL[kChunk][kHeadDim + 8];
   half_t cVh[kChunk][kHeadDim + 8];
+  // phi s of the chunk, transposed (feature-major) and in two binary16 terms: the A operands of the S update
+  half_t phTH[kRank][kChunk + 4];
+  half_t phTL[kRank][kChunk + 4];
   float zs[kRank];
 };
 
@@ -58,6 +61,41 @@ __device__ inline void fwht128_wave(float& x0, float& x1, int lane) {
   // The contract rounds the product to binary32 first and to fp16 afterwards.  Keep the two roundings apart: a
   // fused multiply-and-convert instruction would round the exact product once and differ in rare near-tie cases.
   asm volatile("" : "+v"(x0), "+v"(x1));
+}
+
+// The same rotation for NV independent vectors at once (their cross-lane exchanges overlap); per vector the
+// operations and their order are those of fwht128_wave.
+template <int NV>
+__device__ inline void fwht128_wave_multi(float (&x0)[NV], float (&x1)[NV], int lane) {
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const float a = x0[u] + x1[u];
+    const float b = x0[u] - x1[u];
+    x0[u] = a;
+    x1[u] = b;
+  }
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const bool upper = (lane & m) != 0;
+    float o0[NV], o1[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      o0[u] = __shfl_xor(x0[u], m, 64);
+      o1[u] = __shfl_xor(x1[u], m, 64);
+    }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      x0[u] = upper ? (o0[u] - x0[u]) : (x0[u] + o0[u]);
+      x1[u] = upper ? (o1[u] - x1[u]) : (x1[u] + o1[u]);
+    }
+  }
+  const float c = 0x1.6a09e6p-4f;  // fl32(1/sqrt(128))
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    x0[u] = x0[u] * c;
+    x1[u] = x1[u] * c;
+    asm volatile("" : "+v"(x0[u]), "+v"(x1[u]));  // keep the binary32 rounding apart from the conversion to fp16
+  }
 }
 
 // Eq. 1 at 2 bits against the stored fp16 scale / zero-point, decided in binary32 without a division.
@@ -204,12 +242,26 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     __syncthreads();
     APP_TS(1);
     // rotate the rows that came from new tokens (window rows are rotated already)
-    for (int t = wave; t < valid; t += kThreads / 64) {
-      if (j * kGroup + t < nr) continue;
-      float x0 = (float)L.sV[t][2 * lane], x1 = (float)L.sV[t][2 * lane + 1];
-      fwht128_wave(x0, x1, lane);
-      L.sV[t][2 * lane] = (half_t)x0;
-      L.sV[t][2 * lane + 1] = (half_t)x1;
+    for (int tb = wave; tb < valid; tb += 4 * (kThreads / 64)) {  // rows tb, tb + 4, tb + 8, tb + 12 together
+      float x0[4], x1[4];
+      bool act[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = tb + 4 * u;
+        act[u] = t < valid && j * kGroup + t >= nr;
+        x0[u] = act[u] ? (float)L.sV[t][2 * lane] : 0.0f;
+        x1[u] = act[u] ? (float)L.sV[t][2 * lane + 1] : 0.0f;
+      }
+      if (!(act[0] || act[1] || act[2] || act[3])) continue;
+      fwht128_wave_multi<4>(x0, x1, lane);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (act[u]) {
+          const int t = tb + 4 * u;
+          L.sV[t][2 * lane] = (half_t)x0[u];
+          L.sV[t][2 * lane + 1] = (half_t)x1[u];
+        }
+      }
     }
     __syncthreads();
     APP_TS(2);
@@ -217,6 +269,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     if (tid < kGroup) {
       const int ch = tid;
       float mn = INFINITY, mx = -INFINITY;
+#pragma unroll 8
       for (int t = 0; t < valid; ++t) {
         const half_t h = L.sK[t][ch];
         bad |= nonfinite_bits(h);
@@ -225,6 +278,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
         mx = fmaxf(mx, x);
       }
       const Q2 p = q2_params(mn, mx);
+#pragma unroll 8
       for (int t = 0; t < kGroup; ++t) L.cK[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sK[t][ch], p) : 0;
       L.kScale[ch] = p.s;
       L.kZero[ch] = p.z;
@@ -238,6 +292,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       p.z16 = p.s16 = (half_t)0.0f;
       if (t < valid) {
         float mn = INFINITY, mx = -INFINITY;
+#pragma unroll 8
         for (int ch = 0; ch < kHeadDim; ++ch) {
           const half_t h = L.sV[t][ch];
           bad |= nonfinite_bits(h);
@@ -247,6 +302,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
         }
         p = q2_params(mn, mx);
       }
+#pragma unroll 8
       for (int ch = 0; ch < kHeadDim; ++ch) L.cV[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sV[t][ch], p) : 0;
       L.vScale[t] = p.s;
       L.vZero[t] = p.z;
@@ -325,21 +381,44 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
             for (int i = 0; i < 4; ++i) L.phi[4 * tb + i][fwave + lane] = dH[tb][i] + dL[tb][i];
         }
         __syncthreads();
-        // softmax over each half (128 features) of each token row: 2*kChunk rows, one wave per row at a time
-        for (int row = wave; row < 2 * kChunk; row += kThreads / 64) {
-          const int tt = row >> 1, hs = row & 1;
-          float* p = &L.phi[tt][hs * 128];
-          const float a0 = p[lane], a1 = p[lane + 64];
-          float m = fmaxf(a0, a1);
+        // softmax over each half (128 features) of each token row: 2*kChunk rows, a wave takes two rows at a time so
+        // that their cross-lane reductions overlap.  Besides phi (fp32, for P and the zero-point term) it leaves
+        // phi s_t as two binary16 terms, feature-major.
+        for (int row = 2 * wave; row < 2 * kChunk; row += 2 * (kThreads / 64)) {
+          float a0[2], a1[2], m[2], e0[2], e1[2], sum[2];
 #pragma clang loop unroll(full)
-          for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-          const float e0 = __expf(a0 - m), e1 = __expf(a1 - m);
-          float sum = e0 + e1;
+          for (int u = 0; u < 2; ++u) {
+            const float* p = &L.phi[(row + u) >> 1][((row + u) & 1) * 128];
+            a0[u] = p[lane];
+            a1[u] = p[lane + 64];
+            m[u] = fmaxf(a0[u], a1[u]);
+          }
 #pragma clang loop unroll(full)
-          for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-          const float inv = (t0 + tt < valid) ? 1.0f / sum : 0.0f;
-          p[lane] = e0 * inv;
-          p[lane + 64] = e1 * inv;
+          for (int u = 0; u < 2; ++u) m[u] = wave_allmax(m[u]);
+#pragma clang loop unroll(full)
+          for (int u = 0; u < 2; ++u) {
+            e0[u] = __expf(a0[u] - m[u]);
+            e1[u] = __expf(a1[u] - m[u]);
+            sum[u] = e0[u] + e1[u];
+          }
+#pragma clang loop unroll(full)
+          for (int u = 0; u < 2; ++u) sum[u] = wave_allsum(sum[u]);
+#pragma clang loop unroll(full)
+          for (int u = 0; u < 2; ++u) {
+            const int tt = (row + u) >> 1, hs = (row + u) & 1;
+            const bool live = t0 + tt < valid;
+            const float inv = live ? 1.0f / sum[u] : 0.0f;
+            const float sc_t = live ? L.vScale[t0 + tt] : 0.0f;
+            const float p0 = e0[u] * inv, p1 = e1[u] * inv;
+            L.phi[tt][hs * 128 + lane] = p0;
+            L.phi[tt][hs * 128 + lane + 64] = p1;
+            const float w0 = p0 * sc_t, w1 = p1 * sc_t;
+            const half_t h0 = (half_t)w0, h1 = (half_t)w1;
+            L.phTH[hs * 128 + lane][tt] = h0;
+            L.phTH[hs * 128 + lane + 64][tt] = h1;
+            L.phTL[hs * 128 + lane][tt] = (half_t)(w0 - (float)h0);
+            L.phTL[hs * 128 + lane + 64][tt] = (half_t)(w1 - (float)h1);
+          }
         }
         __syncthreads();
 #pragma clang loop unroll(full)
@@ -361,22 +440,14 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
               bop[ts][hh] = v;
             }
           const int ts_mine = blk & 3;  // the A operand of token step ts is taken from block ts
-          float sc4[4];
-#pragma clang loop unroll(full)
-          for (int k = 0; k < 4; ++k) sc4[k] = L.vScale[min(t0 + 4 * ts_mine + k, kGroup - 1)];
 #pragma clang loop unroll(full)
           for (int fb0 = 0; fb0 < 16; fb0 += 4) {
             half4_t aH[4], aL[4];
 #pragma clang loop unroll(full)
             for (int u = 0; u < 4; ++u) {
               const int f = fwave + 4 * (fb0 + u) + jq;
-#pragma clang loop unroll(full)
-              for (int k = 0; k < 4; ++k) {
-                const float a = L.phi[4 * ts_mine + k][f] * sc4[k];
-                const half_t hi = (half_t)a;
-                aH[u][k] = hi;
-                aL[u][k] = (half_t)(a - (float)hi);
-              }
+              aH[u] = *reinterpret_cast<const half4_t*>(&L.phTH[f][4 * ts_mine]);
+              aL[u] = *reinterpret_cast<const half4_t*>(&L.phTL[f][4 * ts_mine]);
             }
 #pragma clang loop unroll(full)
             for (int ts = 0; ts < 4; ++ts)

@@ -53,26 +53,6 @@ __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
-constexpr int kRowRor4 = 0x124, kRowRor8 = 0x128, kRowRor1 = 0x121, kRowRor2 = 0x122;
-
-__device__ __forceinline__ float wave_allmax(float v) {
-  v = fmaxf(v, dpp_f<kRowRor1>(v));
-  v = fmaxf(v, dpp_f<kRowRor2>(v));
-  v = fmaxf(v, dpp_f<kRowRor4>(v));
-  v = fmaxf(v, dpp_f<kRowRor8>(v));
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  v = fmaxf(v, __shfl_xor(v, 32, 64));
-  return v;
-}
-__device__ __forceinline__ float wave_allsum(float v) {
-  v += dpp_f<kRowRor1>(v);
-  v += dpp_f<kRowRor2>(v);
-  v += dpp_f<kRowRor4>(v);
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
 // sum over the 16 lanes that share lane % 4 (one per quad)
 __device__ __forceinline__ float quadlane_allsum(float v) {
   v += dpp_f<kRowRor4>(v);

@@ -34,6 +34,29 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
 constexpr int kQuadSwap1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int kQuadSwap2 = 0x4E;   // quad_perm [2,3,0,1]
 
+// reductions over the 64 lanes of a wave, result in every lane: rotations inside the rows of 16 lanes, then two
+// cross-row exchanges
+constexpr int kRowRor4 = 0x124, kRowRor8 = 0x128, kRowRor1 = 0x121, kRowRor2 = 0x122;
+
+__device__ __forceinline__ float wave_allmax(float v) {
+  v = fmaxf(v, dpp_f<kRowRor1>(v));
+  v = fmaxf(v, dpp_f<kRowRor2>(v));
+  v = fmaxf(v, dpp_f<kRowRor4>(v));
+  v = fmaxf(v, dpp_f<kRowRor8>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_allsum(float v) {
+  v += dpp_f<kRowRor1>(v);
+  v += dpp_f<kRowRor2>(v);
+  v += dpp_f<kRowRor4>(v);
+  v += dpp_f<kRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 // D = A B + C on the sixteen 4x4 blocks of a wave, k = 4, binary16 operands, binary32 accumulate.  Lane 4 b + i holds
 // row i of A_b (4 halves), column i of B_b (4 halves) and column i of D_b (4 floats).  Here every block uses the A
 // of block `abid` (broadcast), so one register pair can carry the A operands of 16 successive steps.

@@ -59,8 +59,7 @@ int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, 
 
 size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_context) {
   if (kvlinc_cache_validate(cache) != KVLINC_OK) return 0;
-  const int n_splits = kvlinc::decode_splits(*cache, max_context);
-  return kvlinc::decode_workspace_floats(*cache, n_splits) * sizeof(float);
+  return kvlinc::decode_workspace_floats(*cache, kvlinc::decode_splits(*cache, max_context).most) * sizeof(float);
 }
 
 static int decode_checked(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
@@ -71,8 +70,7 @@ static int decode_checked(const kvlinc_cache* cache, const kvlinc_half* q, kvlin
   if ((start == nullptr) != (stop == nullptr)) return KVLINC_EINVAL;
   if (bad_ptr(workspace, 16) || workspace_bytes < kvlinc_decode_workspace_bytes(cache, max_context))
     return KVLINC_EWORKSPACE;
-  const int n_splits = kvlinc::decode_splits(*cache, max_context);
-  return kvlinc::launch_decode(*cache, q, out, static_cast<float*>(workspace), n_splits,
+  return kvlinc::launch_decode(*cache, q, out, static_cast<float*>(workspace), kvlinc::decode_splits(*cache, max_context),
                                static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(start),
                                static_cast<hipEvent_t>(stop));
 }

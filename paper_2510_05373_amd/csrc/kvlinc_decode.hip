@@ -3,7 +3,8 @@
 //
 // decode_main_kernel, one launch per decode step, two kinds of workgroups:
 //   streaming workgroups (sequence, kv head, split): the four waves take groups of 128 tokens from a static schedule
-//   that is the same for every sequence length; a wave keeps its own (m, l, acc).  A group record is fetched in two
+//   that is the same for every sequence length; a wave keeps its own (m, l, acc).  The number of splits of a
+//   sequence follows its share of the batch's groups, so that sequences of unequal lengths end together.  A group record is fetched in two
 //   parts, each requested again for the wave's next group as soon as its contraction has consumed it.  Two waves per
 //   (sequence, kv head) also own a 64-token half of the fp16 window, processed as one more block of tokens.  The
 //   waves are combined through LDS and the workgroup writes one (m, l, Y_s) per query head (Alg. 1 line 11);
@@ -523,9 +524,10 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
 
 // MB = splits whose partial results are requested together
 template <int MB>
-__device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr, int n_splits,
-                                          int row, int lane, half_t* __restrict__ out) {
-  const float* p0 = part + (long long)row * n_splits * kPartStride;
+__device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr,
+                                          int max_splits, int n_splits, int row, int lane,
+                                          half_t* __restrict__ out) {
+  const float* p0 = part + (long long)row * max_splits * kPartStride;
   // correction parts first (their values are needed last): {Cd_r, m_r, Z_r, -, Cn_r[128]}
   float c_cd[kCorrParts], c_m[kCorrParts], c_z[kCorrParts], c_x[kCorrParts], c_y[kCorrParts];
   if (corr != nullptr) {
@@ -634,10 +636,33 @@ __device__ long long g_dbg_ts[1 << 18];
 #define DBG_TS(slot)
 #endif
 
-__device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr, int n_splits,
-                                           int row, int lane, half_t* __restrict__ out) {
-  if (n_splits <= 4) merge_row<4>(part, corr, n_splits, row, lane, out);
-  else merge_row<8>(part, corr, n_splits, row, lane, out);
+__device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr,
+                                           int max_splits, int n_splits, int row, int lane,
+                                           half_t* __restrict__ out) {
+  if (n_splits <= 4) merge_row<4>(part, corr, max_splits, n_splits, row, lane, out);
+  else merge_row<8>(part, corr, max_splits, n_splits, row, lane, out);
+}
+
+// Splits the groups of a sequence are cut into.  The host fixes the average over the batch (avg_splits) and the most
+// one sequence may take (max_splits; grid and workspace are sized for it).  A sequence takes its share of
+// B * avg_splits in proportion to its number of groups, rounded up from a quarter on, so that the long and the short
+// sequences of a batch end together; a batch of equal lengths gives avg_splits to every sequence.  Integer
+// arithmetic only: every wave of the launch that needs the number gets the same one from the same counters.
+__device__ __forceinline__ int sequence_splits(const kvlinc_cache& c, int nq_b, int avg_splits, int max_splits,
+                                               int lane) {
+  if (c.B == 1) return avg_splits;
+  int total = 0;
+  for (int i = lane; i < c.B; i += 64) total += (c.n_quant[i] + kGroup - 1) / kGroup;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) total += __shfl_xor(total, m, 64);
+  const int count = (nq_b + kGroup - 1) / kGroup;
+  int s = avg_splits;
+  if (total > 0) {  // ceil(avg count B / total - 1/4)
+    const long long num = 4ll * avg_splits * count * c.B - total;
+    s = num <= 0 ? 0 : (int)((unsigned long long)(num + 4ll * total - 1) / (unsigned long long)(4ll * total));
+  }
+  s = min(s, min(max_splits, (count + kWaves - 1) / kWaves));  // at least one group per wave
+  return max(s, 1);
 }
 
 // Arrival of a workgroup at its (sequence, kv head): every wave first waits until its write-through stores have been
@@ -650,13 +675,15 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
   return *sFlag == expected - 1;
 }
 
-// Workgroups 0 .. B H_kv n_splits - 1 stream the groups and the window of split sp of a (sequence, kv head); when
-// the correction is on, 4 more workgroups per (sequence, kv head) follow, one per part of the correction.  All of
-// them count themselves in at split_done; the last arrival merges.
+// Grid: B H_kv max_splits streaming workgroups, split-major (workgroup = split * B H_kv + sequence * H_kv + kv head),
+// each streaming the groups and the window share of one split of a (sequence, kv head), or leaving at once when its
+// sequence uses fewer splits; and, when the correction is on, the correction workgroups, before or after them
+// (corr_first).  All of them count themselves in at split_done; the last arrival merges.
 template <int NB>
 __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
-                                                                   half_t* __restrict__ out, int n_splits, int gq) {
+                                                                   half_t* __restrict__ out, int max_splits,
+                                                                   int avg_splits, int gq, int corr_first) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
   __shared__ int sFlag;
 
@@ -665,7 +692,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the schedule in scalar registers
   // correction workgroups come first in the grid: they are long chains of dependent steps and must start at once
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
-  const int expected = n_splits + (corr != nullptr ? kCorrParts : 0);
+  const int n_parts = corr != nullptr ? kCorrParts : 0;
   DBG_TS(0);
 #ifdef KVLINC_TUNING
   if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096) {
@@ -674,13 +701,21 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   }
 #endif
 
-  const bool is_corr = (int)blockIdx.x < n_corr;
-  const int corr_id = blockIdx.x, stream_id = blockIdx.x - n_corr;
+  const int n_stream = gridDim.x - n_corr;
+  const bool is_corr = corr_first ? (int)blockIdx.x < n_corr : (int)blockIdx.x >= n_stream;
+  const int corr_id = corr_first ? blockIdx.x : blockIdx.x - n_stream;
+  const int stream_id = corr_first ? blockIdx.x - n_corr : blockIdx.x;
   if (is_corr) {
     // ---- one part of the correction (Sec. 3.3: C_n, C_d) for up to kCorrSeqs sequences of one kv head ----
     const int id = corr_id;
     const int n_sb = (c.B + kCorrSeqs - 1) / kCorrSeqs;
+#ifdef KVLINC_CORR_OLDMAP
     const int sb = id % n_sb, r = (id / n_sb) % kCorrParts, g = id / (n_sb * kCorrParts);
+#else
+    // The workgroups that read the same slice of W (same kv head and part, different sequences) are H_kv * kCorrParts
+    // apart in the grid: workgroups are dealt to the 8 XCDs in turn, so with an even H_kv they share one L2.
+    const int r = id % kCorrParts, g = (id / kCorrParts) % c.H_kv, sb = id / (kCorrParts * c.H_kv);
+#endif
     const int b_first = sb * kCorrSeqs;
     const int n_seq = min(kCorrSeqs, c.B - b_first);
     // A sequence without quantized tokens has S = P = 0 (the states only change at a flush), so its parts come out
@@ -696,9 +731,11 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
                                            __HIP_MEMORY_SCOPE_SYSTEM);
     __syncthreads();
     for (int s = 0; s < n_seq; ++s) {
-      if (sFlags[s] == expected - 1) {
-        const int b = b_first + s, bh = b * c.H_kv + g;
-        for (int h = wave; h < gq; h += kWaves) merge_rows(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+      const int b = b_first + s, bh = b * c.H_kv + g;
+      const int n_splits = sequence_splits(c, c.n_quant[b], avg_splits, max_splits, lane);
+      if (sFlags[s] == n_splits + n_parts - 1) {
+        for (int h = wave; h < gq; h += kWaves)
+          merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, out);
         if (tid == 0) c.split_done[bh] = 0;
       }
     }
@@ -708,8 +745,10 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
 
   // ---- one split of the groups and of the window (Alg. 1, the loop over blocks) ----
   const int wg = stream_id;
-  const int bh = wg / n_splits;
-  const int sp = wg % n_splits;
+  // split-major: the splits that only long sequences use come last in the grid, and the workgroups of any one split
+  // index are dealt evenly to the XCDs
+  const int bh = wg % (c.B * c.H_kv);
+  const int sp = wg / (c.B * c.H_kv);
   const int b = bh / c.H_kv;
   const int g = bh % c.H_kv;
 
@@ -719,31 +758,36 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   // window sit out their first kSkip slots (the window is their work for that time).  Consecutive groups thus go to
   // different workgroups, and every split gets the same share whatever the length.
   constexpr int kSkip = 2;
-  const int slots = kWaves * n_splits;
-  int my_half = -1;
-  if (n_splits >= 2) {
-    if (wave == kWaves - 1 && sp >= n_splits - 2) my_half = n_splits - 1 - sp;
-  } else if (wave >= kWaves - 2) {
-    my_half = kWaves - 1 - wave;
-  }
-  const int base0 = n_splits >= 2 ? slots - 1 : kWaves - 1;  // round-0 slots of the owners of half 0 and half 1
-  const int base1 = n_splits >= 2 ? slots - 2 : kWaves - 2;
-  // group(round) = slot - (slots skipped before it).  A wave's slot offset is at most base0, so the owner of half 0
-  // has skipped min(round, kSkip) slots before it and the owner of half 1 one more if it comes earlier in the round.
-  const int off = wave * n_splits + sp;
-  const int lead1 = off > base1 ? 1 : 0;
+  int n_splits = avg_splits;  // first guess: right for a batch of equal lengths
+  int slots, my_half, off, lead1, rd, idx;
   auto group_of_round = [&](int round) {
     return round * slots + off - min(round, kSkip) - min(round + lead1, kSkip);
   };
-  int rd = my_half >= 0 ? kSkip : 0;
-  int idx = group_of_round(rd);
+  auto plan = [&]() {
+    slots = kWaves * n_splits;
+    my_half = -1;
+    if (n_splits >= 2) {
+      if (wave == kWaves - 1 && sp >= n_splits - 2) my_half = n_splits - 1 - sp;
+    } else if (wave >= kWaves - 2) {
+      my_half = kWaves - 1 - wave;
+    }
+    // group(round) = slot - (slots skipped before it).  The owners of half 0 and half 1 have the round's last and
+    // last but one slot, so the owner of half 0 has skipped min(round, kSkip) slots before a wave's slot and the
+    // owner of half 1 one more if it comes earlier in the round.
+    const int base1 = n_splits >= 2 ? slots - 2 : kWaves - 2;
+    off = wave * n_splits + sp;
+    lead1 = off > base1 ? 1 : 0;
+    rd = my_half >= 0 ? kSkip : 0;
+    idx = group_of_round(rd);
+  };
+  plan();
 
   // The first record is requested before the sequence length is known (any group index below the capacity is
   // readable memory); what it holds is used only if the group exists.
   const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
   KeyRegs kr;
   ValueRegs vr;
-  {
+  if (sp < avg_splits) {
     const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
     load_keys(kr, rec0 + first * kRecordWords, lane);
     load_values(vr, rec0 + first * kRecordWords, lane);
@@ -752,6 +796,18 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int nq = c.n_quant[b];
   const int nr = c.n_res[b];
   const int count = (nq + kGroup - 1) / kGroup;
+  {
+    const int mine = sequence_splits(c, nq, avg_splits, max_splits, lane);
+    if (sp >= mine) return;  // this sequence uses fewer splits than the grid provides
+    if (mine != n_splits) {  // lengths differ within the batch: plan again, request the right first record
+      n_splits = mine;
+      plan();
+      const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
+      load_keys(kr, rec0 + first * kRecordWords, lane);
+      load_values(vr, rec0 + first * kRecordWords, lane);
+    }
+  }
+  const int expected = n_splits + n_parts;
 
   // per-lane constants
   const int quad = lane >> 2, hrow = lane & 3;
@@ -800,16 +856,29 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     // While a group is consumed the wave's next record is already requested: its key part right after the scores,
     // its value part right after E V.  Past the last group the current (cached) record is requested once more, so
     // that no branch joins between a request and its first use and the waits stay partial.
+#ifdef KVLINC_ITER_TS
+    int it = 0;
+#define ITER_TS(k) do { if (it >= 1 && it <= 2) DBG_TS(8 + 4 * (it - 1) + (k)); } while (0)
+#else
+#define ITER_TS(k)
+#endif
     while (idx < count) {
       const int nxt = group_of_round(++rd);
       const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
       float4_t sc[NB][2];
+      ITER_TS(0);
       qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), Qs, lc, sc);
+      ITER_TS(1);
       load_keys(kr, src, lane);
       update_reference<NB>(sc, st);
+      ITER_TS(2);
       pv_phase<NB>(vr, sc, lc, st);
+      ITER_TS(3);
       load_values(vr, src, lane);
       idx = nxt;
+#ifdef KVLINC_ITER_TS
+      ++it;
+#endif
     }
   }
   DBG_TS(3);
@@ -844,7 +913,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
         l = fmaf(f, sL[w][h], l);
       }
     }
-    float* dst = part + (((long long)b * c.H_q + g * gq + h) * n_splits + sp) * kPartStride;
+    float* dst = part + (((long long)b * c.H_q + g * gq + h) * max_splits + sp) * kPartStride;
     if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
     st_coherent(dst + 4 + ch, a);
   }
@@ -853,7 +922,8 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   // The workgroup that arrives last merges (Alg. 1 lines 13-15): it reads what the others wrote with coherent
   // loads.  No workgroup waits for another.
   if (arrive(c.split_done + bh, expected, &sFlag)) {
-    for (int h = wave; h < gq; h += kWaves) merge_rows(part, corr, n_splits, b * c.H_q + g * gq + h, lane, out);
+    for (int h = wave; h < gq; h += kWaves)
+      merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, out);
     if (tid == 0) c.split_done[bh] = 0;
   }
   DBG_TS(7);
@@ -867,7 +937,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
 // workgroup next to two streaming ones finishes late.  The kernel for more than 4 query heads per kv head holds only
 // two workgroups per compute unit, and there four splits measured better than three.  At most 32 splits (the merge
 // walks the splits serially), at least one group per wave.
-int decode_splits(const kvlinc_cache& c, int max_context) {
+DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
   constexpr int kTargetWorkgroups = 512, kMaxSplits = 32;
   const long long cap = (long long)c.max_groups * kGroup + c.R;
   const long long ctx = (max_context > 0 && max_context < cap) ? max_context : cap;
@@ -881,20 +951,30 @@ int decode_splits(const kvlinc_cache& c, int max_context) {
   if (s > kMaxSplits) s = kMaxSplits;
   const long long most = (groups + kWaves - 1) / kWaves;
   if (s > most) s = most;
+  if (s < 1) s = 1;
+  // Head room for the longest sequences of a batch of unequal lengths (a single sequence has nobody to differ from).
+  long long m = c.B > 1 ? 2 * s : s;
 #ifdef KVLINC_TUNING  // sweep builds only: override the split policy from the environment
-  if (const char* e = getenv("KVLINC_SPLITS")) s = atoi(e);
-#endif
+  if (const char* e = getenv("KVLINC_SPLITS")) { s = atoi(e); m = c.B > 1 ? 2 * s : s; }
+  if (const char* e = getenv("KVLINC_MAX_SPLITS")) m = atoi(e);
   if (s < 1) s = 1;
   if (s > 1024) s = 1024;
-  return (int)s;
+  if (m > 1024) m = 1024;
+#else
+  if (m > kMaxSplits) m = kMaxSplits;
+#endif
+  if (m > most) m = most;
+  if (m < s) m = s;
+  return DecodeSplits{(int)s, (int)m};
 }
 
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
   return (size_t)c.B * c.H_q * (n_splits + kCorrParts) * kPartStride;  // split partials, then the correction parts
 }
 
-int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
+int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, DecodeSplits sp,
                   hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
+  const int n_splits = sp.most;
   const int gq = c.H_q / c.H_kv;
   const int BH = c.B * c.H_kv;
   const half_t* qq = reinterpret_cast<const half_t*>(q);
@@ -903,16 +983,24 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const dim3 grid(BH * n_splits + n_corr), block(kThreads);
+  // The correction workgroups are chains of dependent steps and go first in the grid when the launch is resident at
+  // once or nearly so.  When they alone would fill most of the chip (many sequences, short contexts), the streaming
+  // workgroups go first: the longest of them decide when the launch ends.
+  const int resident = 256 * (gq <= 4 ? 3 : 2);
+  int corr_first = 2 * n_corr <= resident ? 1 : 0;
+#ifdef KVLINC_TUNING
+  if (const char* e = getenv("KVLINC_CORR_FIRST")) corr_first = atoi(e);
+#endif
   if (start != nullptr) {  // timestamps of the dispatch itself, no extra packets on the stream
     if (gq <= 4)
-      hipExtLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, n_splits, gq);
+      hipExtLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
     else
-      hipExtLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, n_splits, gq);
+      hipExtLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
   } else {
     if (gq <= 4)
-      hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, oo, n_splits, gq);
+      hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
     else
-      hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, oo, n_splits, gq);
+      hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
   }
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }

@@ -48,14 +48,17 @@ __host__ __device__ inline AppendPlan plan_append(int n_quant, int n_res, int n_
   return p;
 }
 
-// Split count of the decode launch: blocks of groups per (sequence, KV head).
-int decode_splits(const kvlinc_cache& c, int max_context);
+// Splits of the decode launch (blocks of groups per (sequence, KV head)): the average over the batch, which a batch
+// of equal lengths uses for every sequence, and the most one sequence may take; grid and workspace are sized for
+// `most`.
+struct DecodeSplits { int avg, most; };
+DecodeSplits decode_splits(const kvlinc_cache& c, int max_context);
 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream);
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits);
 // start / stop: optional events attached to the kernel's own dispatch (both or neither)
-int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, int n_splits,
+int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out, float* workspace, DecodeSplits splits,
                   hipStream_t stream, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 }  // namespace kvlinc

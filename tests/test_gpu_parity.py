@@ -196,6 +196,24 @@ def test_batch_sizes_around_the_correction_width(kv, B):
     tl.check_outputs(out, want)
 
 
+@pytest.mark.parametrize("gq", [4, 7])
+def test_unequal_lengths_take_unequal_splits(kv, gq):
+    """A batch whose sequences differ 80-fold in length: the launch gives each a number of splits in proportion to its
+    groups (here 1 to 10), down to a sequence without any quantized token; every row must still match."""
+    import torch
+    B, H_kv = 5, 2
+    H_q = gq * H_kv
+    lengths = [300, 2500, 5000, 57, 1290]
+    cache, K, V, Wq, Wk = _build(kv, 18, B, H_q, H_kv, lengths)
+    q = tl.gen_q(18, B, H_q)
+    out = cache.decode(tl.to_dev(q))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0 and int(cache.split_done.abs().sum().item()) == 0
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out.cpu().numpy(), want)
+    assert torch.equal(cache.decode(tl.to_dev(q)), out)  # same bits on a second call
+
+
 def test_result_does_not_depend_on_the_launch_bound(kv):
     """max_context only sizes the launch: any upper bound gives the same result up to the summation order."""
     import torch

@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--layers", type=int, default=None,
                     help="distinct layer caches cycled through (default: 8; 4 for the two largest workloads)")
-    ap.add_argument("--workload", type=int, default=WORKLOAD, choices=[2, 3, 4, 5],
+    ap.add_argument("--workload", type=int, default=WORKLOAD, choices=[2, 3, 4, 5, 6, 7],
                     help="index into kvlinc_synth.CONFIGS; the default is the workload the metric is quoted on, the "
                          "others run on device-generated N(0, 1) data without the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -74,7 +74,7 @@ def main():
     wl = args.workload
     cfg = synth.CONFIGS[wl]
     B, H_q, H_kv = cfg["B"], cfg["H_q"], cfg["H_kv"]
-    L = args.layers if args.layers else (8 if wl in (2, 3) else 4)
+    L = args.layers if args.layers else (4 if wl in (4, 5) else 8)
     K_steps, W = args.steps, args.warmup
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

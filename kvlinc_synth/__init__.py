@@ -20,7 +20,7 @@ RANK_D = 256
 N_OUTLIER = 4
 OUTLIER_GAIN = 8.0
 
-# The five workloads: B sequences, H_q query heads, H_kv KV heads, context n (tokens already in the
+# The workloads: B sequences, H_q query heads, H_kv KV heads, context n (tokens already in the
 # cache when the query arrives), R window capacity, keep = fp16 tokens a bulk build leaves
 # (None = the lazy block flush).
 CONFIGS = {
@@ -30,6 +30,10 @@ CONFIGS = {
     4: dict(name="c4_qwen25_7b_b32_ctx32k", B=32, H_q=28, H_kv=4, n=32768, R=128, keep=None),
     5: dict(name="c5_ragged_b64_append", B=64, H_q=32, H_kv=8, n=None, n_min=1024, n_max=16384, steps=256,
             R=128, keep=None),
+    # Two shapes of the paper's end-to-end throughput experiment (Sec. 4.4: prompt 256 + 1024 generated tokens):
+    # a multi-head model (one query head per KV head) and the grouped-query model at a large batch.
+    6: dict(name="c6_llama2_7b_mha_b32_ctx1280", B=32, H_q=32, H_kv=32, n=1280, R=128, keep=None),
+    7: dict(name="c7_llama3_8b_b144_ctx1280", B=144, H_q=32, H_kv=8, n=1280, R=128, keep=None),
 }
 
 

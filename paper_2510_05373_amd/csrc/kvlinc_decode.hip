@@ -965,7 +965,17 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
 #endif
   if (m > most) m = most;
   if (m < s) m = s;
-  return DecodeSplits{(int)s, (int)m};
+  // The correction workgroups are chains of dependent steps and go first in the grid, except when they alone would
+  // fill most of the chip while the streaming workgroups have long contexts ahead of them (many sequences, 16 or
+  // more groups per wave): then the streaming workgroups go first, the longest of them decide when the launch ends,
+  // and the correction fills the places the short sequences leave.
+  const long long all_corr = c.S != nullptr ? (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
+  const long long resident = 256 * (gq <= 4 ? 3 : 2);
+  int corr_first = (2 * all_corr > resident && groups >= 16 * kWaves * s) ? 0 : 1;
+#ifdef KVLINC_TUNING
+  if (const char* e = getenv("KVLINC_CORR_FIRST")) corr_first = atoi(e);
+#endif
+  return DecodeSplits{(int)s, (int)m, corr_first};
 }
 
 size_t decode_workspace_floats(const kvlinc_cache& c, int n_splits) {
@@ -983,14 +993,7 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const dim3 grid(BH * n_splits + n_corr), block(kThreads);
-  // The correction workgroups are chains of dependent steps and go first in the grid when the launch is resident at
-  // once or nearly so.  When they alone would fill most of the chip (many sequences, short contexts), the streaming
-  // workgroups go first: the longest of them decide when the launch ends.
-  const int resident = 256 * (gq <= 4 ? 3 : 2);
-  int corr_first = 2 * n_corr <= resident ? 1 : 0;
-#ifdef KVLINC_TUNING
-  if (const char* e = getenv("KVLINC_CORR_FIRST")) corr_first = atoi(e);
-#endif
+  const int corr_first = sp.corr_first;
   if (start != nullptr) {  // timestamps of the dispatch itself, no extra packets on the stream
     if (gq <= 4)
       hipExtLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);

@@ -50,8 +50,8 @@ __host__ __device__ inline AppendPlan plan_append(int n_quant, int n_res, int n_
 
 // Splits of the decode launch (blocks of groups per (sequence, KV head)): the average over the batch, which a batch
 // of equal lengths uses for every sequence, and the most one sequence may take; grid and workspace are sized for
-// `most`.
-struct DecodeSplits { int avg, most; };
+// `most`.  corr_first: the correction workgroups come before the streaming ones in the grid.
+struct DecodeSplits { int avg, most, corr_first; };
 DecodeSplits decode_splits(const kvlinc_cache& c, int max_context);
 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,

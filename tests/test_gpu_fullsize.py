@@ -93,6 +93,14 @@ def test_config4_qwen25_7b_batch32_ctx32k_gqa7(kv):
     _run_bulk_config(kv, 4, [(0, 0), (31, 3)])
 
 
+def test_config6_mha_batch32_ctx1280(kv):
+    _run_bulk_config(kv, 6, [(0, 0), (13, 17), (31, 31)])
+
+
+def test_config7_batch144_ctx1280(kv):
+    _run_bulk_config(kv, 7, [(0, 0), (77, 4), (143, 7)])
+
+
 def test_config5_ragged_batch64_with_appends(kv):
     """Ragged contexts, one token appended to every sequence per step for 256 steps (every sequence crosses two flush
     boundaries); seeded pairs are compared with the oracle at the first step, around step 127 / 128 and at the end."""

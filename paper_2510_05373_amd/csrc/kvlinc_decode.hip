@@ -662,7 +662,7 @@ __device__ __forceinline__ int sequence_splits(const kvlinc_cache& c, int nq_b, 
     s = num <= 0 ? 0 : (int)((unsigned long long)(num + 4ll * total - 1) / (unsigned long long)(4ll * total));
   }
   s = min(s, min(max_splits, (count + kWaves - 1) / kWaves));  // at least one group per wave
-  return max(s, 1);
+  return __builtin_amdgcn_readfirstlane(max(s, 1));            // the same in every lane: keep it in a scalar register
 }
 
 // Arrival of a workgroup at its (sequence, kv head): every wave first waits until its write-through stores have been

@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 WORKLOAD = 2  # index into kvlinc_synth.CONFIGS
 # HBM bytes one decode launch of this workload moved (read + written) according to the FETCH_SIZE and WRITE_SIZE
 # counters, each scaled by what the same counter reports for a plain copy of known size; None = not measured.
-MEASURED_TRAFFIC_BYTES = 102.6e6
+MEASURED_TRAFFIC_BYTES = 96.4e6
 EVENT_STRIDE = 4  # every 4th decode launch of the timed region is timed with dispatch events
 
 

@@ -702,9 +702,31 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
 #endif
 
   const int n_stream = gridDim.x - n_corr;
-  const bool is_corr = corr_first ? (int)blockIdx.x < n_corr : (int)blockIdx.x >= n_stream;
-  const int corr_id = corr_first ? blockIdx.x : blockIdx.x - n_stream;
-  const int stream_id = corr_first ? blockIdx.x - n_corr : blockIdx.x;
+  // corr_first = 0: the correction workgroups come last; L >= 1: they lead each of the first L runs of 256
+  // workgroups in equal shares.  The dispatcher deals workgroup i to compute unit i mod 256 while places are free, so
+  // with L = 2 the correction workgroups pair up on compute units of their own and no streaming workgroup has one
+  // as a neighbour.
+  bool is_corr;
+  int corr_id, stream_id;
+  int L = corr_first;  // every run that leads with correction workgroups must lie inside the grid and hold its share
+  while (L > 1 && ((int)gridDim.x < 256 * (L - 1) + (n_corr + L - 1) / L || (n_corr + L - 1) / L > 256)) --L;
+  if (L == 0 || n_corr == 0) {
+    is_corr = (int)blockIdx.x >= n_stream;
+    corr_id = blockIdx.x - n_stream;
+    stream_id = blockIdx.x;
+  } else if (L == 1) {
+    is_corr = (int)blockIdx.x < n_corr;
+    corr_id = blockIdx.x;
+    stream_id = blockIdx.x - n_corr;
+  } else {
+    const int per = (n_corr + L - 1) / L;
+    const int layer = min((int)blockIdx.x / 256, L), pos = layer < L ? (int)blockIdx.x % 256 : 0;
+    const int before = min(n_corr, layer * per + min(pos, per));  // correction workgroups ahead of this one
+    is_corr = layer < L && pos < per && before < n_corr;
+    corr_id = before;
+    stream_id = blockIdx.x - before;
+  }
+
   if (is_corr) {
     // ---- one part of the correction (Sec. 3.3: C_n, C_d) for up to kCorrSeqs sequences of one kv head ----
     const int id = corr_id;
@@ -972,6 +994,20 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
   const long long all_corr = c.S != nullptr ? (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const long long resident = 256 * (gq <= 4 ? 3 : 2);
   int corr_first = (2 * all_corr > resident && groups >= 16 * kWaves * s) ? 0 : 1;
+  // One or a few long sequences: about one streaming workgroup per compute unit.  The streaming workgroups that
+  // would share a compute unit with a correction workgroup finish late (measured 3.6 us at a context of 128k), so
+  // the correction workgroups pair up on compute units of their own (two runs of the grid lead with them) and the
+  // splits are cut back to leave those compute units free.
+  if (all_corr > 0 && bh * s <= 256 && bh * s + all_corr > 256) {
+    const long long s2 = (256 - (all_corr + 1) / 2) / bh;
+    if (s2 >= 1 && 4 * s2 >= 3 * s) {
+      s = s2 < s ? s2 : s;
+      if (m > s) m = c.B > 1 ? 2 * s : s;
+      if (m > most) m = most;
+      if (m < s) m = s;
+      corr_first = 2;
+    }
+  }
 #ifdef KVLINC_TUNING
   if (const char* e = getenv("KVLINC_CORR_FIRST")) corr_first = atoi(e);
 #endif

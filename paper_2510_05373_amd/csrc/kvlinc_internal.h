@@ -50,7 +50,8 @@ __host__ __device__ inline AppendPlan plan_append(int n_quant, int n_res, int n_
 
 // Splits of the decode launch (blocks of groups per (sequence, KV head)): the average over the batch, which a batch
 // of equal lengths uses for every sequence, and the most one sequence may take; grid and workspace are sized for
-// `most`.  corr_first: the correction workgroups come before the streaming ones in the grid.
+// `most`.  corr_first: 0 = the correction workgroups come after the streaming ones in the grid, L >= 1 = they lead
+// each of the first L runs of 256 workgroups.
 struct DecodeSplits { int avg, most, corr_first; };
 DecodeSplits decode_splits(const kvlinc_cache& c, int max_context);
 

@@ -162,8 +162,10 @@ size_t kvlinc_decode_workspace_bytes(const kvlinc_cache* cache, int32_t max_cont
  *
  * One kernel launch: blocks of groups are processed by separate workgroups that leave (max, sum, numerator) partials
  * in the workspace (Alg. 1, the per-block outputs); the workgroup of a (sequence, KV head) that finishes last, counted
- * in cache->split_done, merges them, adds the correction and writes `out`.  Results are deterministic for a given
- * max_context (it fixes the block boundaries and hence the summation order).
+ * in cache->split_done, merges them, adds the correction and writes `out`.  The number of blocks of a sequence follows
+ * max_context and the sequence's share of the batch's tokens, so results are deterministic (bit for bit) for a given
+ * max_context and given lengths of the sequences of the batch; across different bounds or batch compositions they
+ * agree up to the summation order.
  */
 int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
                             size_t workspace_bytes, int32_t max_context, void* stream);

@@ -730,14 +730,9 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   if (is_corr) {
     // ---- one part of the correction (Sec. 3.3: C_n, C_d) for up to kCorrSeqs sequences of one kv head ----
     const int id = corr_id;
-    const int n_sb = (c.B + kCorrSeqs - 1) / kCorrSeqs;
-#ifdef KVLINC_CORR_OLDMAP
-    const int sb = id % n_sb, r = (id / n_sb) % kCorrParts, g = id / (n_sb * kCorrParts);
-#else
     // The workgroups that read the same slice of W (same kv head and part, different sequences) are H_kv * kCorrParts
     // apart in the grid: workgroups are dealt to the 8 XCDs in turn, so with an even H_kv they share one L2.
     const int r = id % kCorrParts, g = (id / kCorrParts) % c.H_kv, sb = id / (kCorrParts * c.H_kv);
-#endif
     const int b_first = sb * kCorrSeqs;
     const int n_seq = min(kCorrSeqs, c.B - b_first);
     // A sequence without quantized tokens has S = P = 0 (the states only change at a flush), so its parts come out

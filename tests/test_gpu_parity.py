@@ -184,11 +184,11 @@ def test_window_boundaries(kv, n_quant, n_res):
     tl.check_outputs(out, want)
 
 
-@pytest.mark.parametrize("B", [1, 2, 3, 5, 7])
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7, 32, 33, 47])
 def test_batch_sizes_around_the_correction_width(kv, B):
-    """The correction workgroups serve 4 sequences each: batches that do not fill the last one."""
+    """The correction workgroups serve 4 sequences each: batches that do not fill the last one, small and large."""
     H_q, H_kv = 4, 1
-    lengths = [300 + 131 * b for b in range(B)]
+    lengths = [300 + (131 * b) % 917 for b in range(B)]
     cache, K, V, Wq, Wk = _build(kv, 17, B, H_q, H_kv, lengths)
     q = tl.gen_q(17, B, H_q)
     out = cache.decode(tl.to_dev(q)).cpu().numpy()

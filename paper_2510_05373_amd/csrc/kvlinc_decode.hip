@@ -677,8 +677,9 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
 
 // Grid: B H_kv max_splits streaming workgroups, split-major (workgroup = split * B H_kv + sequence * H_kv + kv head),
 // each streaming the groups and the window share of one split of a (sequence, kv head), or leaving at once when its
-// sequence uses fewer splits; and, when the correction is on, the correction workgroups, before or after them
-// (corr_first).  All of them count themselves in at split_done; the last arrival merges.
+// sequence uses fewer splits; and, when the correction is on, the correction workgroups: after them (corr_first = 0)
+// or leading the first corr_first runs of 256 workgroups (1: all of them first -- they are long chains of dependent
+// steps and should start at once).  All of them count themselves in at split_done; the last arrival merges.
 template <int NB>
 __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
@@ -690,7 +691,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the schedule in scalar registers
-  // correction workgroups come first in the grid: they are long chains of dependent steps and must start at once
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const int n_parts = corr != nullptr ? kCorrParts : 0;
   DBG_TS(0);

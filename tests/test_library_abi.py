@@ -110,3 +110,21 @@ def test_workspace_size_is_monotone_and_bounded():
     assert sizes[-1] == kb.kvlinc_decode_workspace_bytes(c, 80 * 128 + 128)
     # per (sequence, query head): at most 1024 splits + 4 correction parts of 132 floats
     assert sizes[-1] <= 16 * 32 * (1024 + 4) * 132 * 4
+
+
+def test_split_policy_of_the_workloads():
+    """The most splits a sequence may take, read off the workspace size (B * H_q * (splits + 4 correction parts) * 132
+    floats): twice the batch's average of 3 / 4 / 1 / 1 / 1 splits for workloads 2, 4, 5, 6, 7 (head room for
+    unequal lengths), 30 for the single long sequence of workload 3, one group per wave (2 splits) for the 1k context
+    of workload 1.  A change of the launch policy has to show up here."""
+    import kvlinc_synth as synth
+    want = {1: 2, 2: 6, 3: 30, 4: 8, 5: 2, 6: 2, 7: 2}
+    for cfg_id, cfg in synth.CONFIGS.items():
+        n = cfg.get("n") or cfg["n_max"]
+        c = fake_struct(B=cfg["B"], H_q=cfg["H_q"], H_kv=cfg["H_kv"], max_groups=(n + 512) // 128)
+        per_row = kb.kvlinc_decode_workspace_bytes(c, n) // (cfg["B"] * cfg["H_q"] * 132 * 4)
+        assert per_row - 4 == want[cfg_id], (cfg_id, per_row)
+        # without the correction there are no correction parts
+        c0 = fake_struct(B=cfg["B"], H_q=cfg["H_q"], H_kv=cfg["H_kv"], max_groups=(n + 512) // 128, S=0, S16=0, P=0,
+                         Wq=0, Wk=0)
+        assert kb.kvlinc_decode_workspace_bytes(c0, n) % (cfg["B"] * cfg["H_q"] * 132 * 4) == 0

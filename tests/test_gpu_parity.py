@@ -133,6 +133,27 @@ def test_degenerate_inputs(kv):
     assert int(cache.status.item()) == 0
 
 
+def test_signed_zeros_give_a_positive_zero_point(kv):
+    """A group minimum that is a negative zero is stored as +0 (the quantizer contract), on the GPU as in the oracle:
+    a key channel of negative zeros only, one whose only zero is a -0 below positive values, and zeros of both signs."""
+    B, H_q, H_kv = 1, 4, 1
+    lengths = [256]
+    K, V = tl.gen_kv(19, B, H_kv, lengths)
+    K[0, 0, :, 3] = np.float16(-0.0)
+    K[0, 0, :, 5] = np.abs(K[0, 0, :, 5]) + np.float16(0.25)
+    K[0, 0, 17, 5] = np.float16(-0.0)
+    K[0, 0, ::2, 9] = np.float16(-0.0)
+    K[0, 0, 1::2, 9] = np.float16(0.0)
+    Wq, Wk = synth.adapters_q(19, H_q), synth.adapters_k(19, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K), tl.to_dev(V))
+    tl.check_cache_against_oracle(cache, K, V, lengths, [(0, 0)], Wk=Wk)
+    rec = cache.groups[0, 0, 0].cpu().numpy().view(np.uint32)
+    kz = rec[2112:2176]  # key zero-points, channel 2i in the low half of word i
+    assert (kz[1] >> 16) == 0 and (kz[4] >> 16) == 0, "channels 3 and 9: zero-point +0"
+    assert (kz[2] >> 16) == 0, "channel 5: minimum -0 stored as +0"
+
+
 def test_status_bits_and_rejections(kv):
     import torch
     B, H_q, H_kv = 1, 4, 1

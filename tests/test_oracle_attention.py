@@ -58,6 +58,22 @@ def test_rotation_invariance_without_quantization():
     np.testing.assert_allclose(a, b, atol=1e-12)
 
 
+def test_the_three_arithmetic_modes_describe_the_same_cache():
+    """`spec32` (the GPU contract), `exact16` and `real` differ only in where they round: rotated window values agree
+    to an fp16 ulp, almost all codes coincide, and the attention outputs agree far inside the output tolerance."""
+    q, K, V, Wq, Wk = _case(n=300, seed=12)
+    c32 = kvcache.build_cache(K, V, 256, mode="spec32", Wk=Wk)
+    c16 = kvcache.build_cache(K, V, 256, mode="exact16", Wk=Wk)
+    cre = kvcache.build_cache(K, V, 256, mode="real", Wk=Wk)
+    want = V[256:].astype(np.float64) @ hadamard.orthonormal(128)
+    for c in (c32, c16, cre):
+        assert np.abs(c["v_res"].astype(np.float64) - want).max() <= 2.0 ** -9 * np.abs(want).max()
+    assert (c32["k_codes"] != c16["k_codes"]).mean() < 1e-3 and (c32["v_codes"] != c16["v_codes"]).mean() < 1e-3
+    assert (c32["v_codes"] != cre["v_codes"]).mean() < 2e-2
+    a, b, r = (attention.decode(q, c, Wq) for c in (c32, c16, cre))
+    assert np.abs(a - b).max() < 2e-3 and np.abs(a - r).max() < 2e-2
+
+
 def test_rotated_value_quantization_beats_raw_on_outlier_values():
     # Obs. 3: token-wise quantization of rotated values has a smaller error than of raw values once a token has
     # an outlier channel

@@ -73,3 +73,46 @@ def test_state_tiles_are_a_bijection():
     for f, c in [(0, 0), (3, 5), (64, 63), (130, 64), (255, 127), (77, 100)]:
         t = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4
         assert tiles[t, c % 64, f % 4] == S[f, c]
+
+
+def test_record_fields_sit_where_the_header_says():
+    """include/kvlinc.h: a record is 2304 words -- key tile [0, 1024), value tile [1024, 2048), key scale [2048, 2112)
+    and key zero-point [2112, 2176) as fp16 pairs (channel 2i in the low half of word i), then one word per token with
+    the value scale in the low and the value zero-point in the high half."""
+    z = lambda *shape: np.zeros(shape, dtype=np.float16)
+    codes0 = np.zeros((1, 128, 128), dtype=np.int64)
+
+    def record(**fields):
+        f = dict(k_codes=codes0, v_codes=codes0, k_scale=z(1, 128), k_zero=z(1, 128), v_scale=z(1, 128),
+                 v_zero=z(1, 128))
+        f.update(fields)
+        return layout.pack_records(f["k_codes"], f["v_codes"], f["k_scale"], f["k_zero"], f["v_scale"], f["v_zero"])[0]
+
+    one = codes0.copy()
+    one[0, 0, 0] = 3
+    r = record(k_codes=one)
+    assert r.shape == (2304,) and r[0] == 3 and np.count_nonzero(r) == 1
+    r = record(v_codes=one)
+    assert r[1024] == 3 and np.count_nonzero(r) == 1
+    h = z(1, 128)
+    h[0, 5] = 1.5  # fp16 0x3E00; channel 5 = high half of word 2
+    r = record(k_scale=h)
+    assert r[2048 + 2] == 0x3E00 << 16 and np.count_nonzero(r) == 1
+    r = record(k_zero=h)
+    assert r[2112 + 2] == 0x3E00 << 16 and np.count_nonzero(r) == 1
+    r = record(v_scale=h)
+    assert r[2176 + 5] == 0x3E00 and np.count_nonzero(r) == 1
+    r = record(v_zero=h)
+    assert r[2176 + 5] == 0x3E00 << 16 and np.count_nonzero(r) == 1
+    # and the whole record round-trips
+    rng = np.random.default_rng(3)
+    f = dict(k_codes=rng.integers(0, 4, size=(2, 128, 128)), v_codes=rng.integers(0, 4, size=(2, 128, 128)),
+             k_scale=rng.standard_normal((2, 128)).astype(np.float16), k_zero=rng.standard_normal((2, 128)).astype(np.float16),
+             v_scale=rng.standard_normal((2, 128)).astype(np.float16), v_zero=rng.standard_normal((2, 128)).astype(np.float16))
+    back = layout.unpack_records(layout.pack_records(**f))
+    for name, want in f.items():
+        got = back[name]
+        if want.dtype == np.float16:
+            assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), name
+        else:
+            assert np.array_equal(got, want), name

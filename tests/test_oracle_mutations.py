@@ -1,0 +1,138 @@
+"""Do the pins bite?  Each case plants one plausible mistake in the oracle -- a wrong sign, a dropped factor, a swapped
+axis, an off-by-one -- by editing the source text of one oracle function in memory, and checks that at least one of the
+named pins then fails.  Everything here runs on the CPU; the files on disk are never touched."""
+import inspect
+import textwrap
+
+import pytest
+
+from oracle import accounting, attention, hadamard, kvcache, layout, quantizer
+from tests import test_oracle_attention as pa
+from tests import test_oracle_layout as pl
+from tests import test_oracle_quantizer as pq
+
+
+def _planted(monkeypatch, module, name, old, new, count=1):
+    """Replace `old` by `new` in the source of module.name and install the result for the duration of the test."""
+    src = textwrap.dedent(inspect.getsource(getattr(module, name)))
+    assert src.count(old) >= count, (name, old)
+    namespace = dict(vars(module))
+    exec(compile(src.replace(old, new), "<planted mistake in %s.%s>" % (module.__name__, name), "exec"), namespace)
+    monkeypatch.setattr(module, name, namespace[name])
+
+
+def _some_pin_fails(pins):
+    failed = []
+    for pin in pins:
+        fn, args = (pin, ()) if callable(pin) else (pin[0], pin[1:])
+        try:
+            fn(*args)
+        except Exception as e:  # an assertion, or a shape error the mistake provokes
+            failed.append((fn.__name__, type(e).__name__))
+    assert failed, "no pin noticed the planted mistake"
+    return failed
+
+
+CASES = [
+    # (module, function, old text, new text, pins that should notice)
+    ("dequantize sign of the zero-point", quantizer, "dequantize", "+ z[..., None]", "- z[..., None]",
+     [pa.test_bits_to_16_converges_to_textbook_attention, (pq.test_eq1_round_trip_bound_and_levels, 2)]),
+    ("Eq. 1 scale over 2^b instead of 2^b - 1", quantizer, "quantize_real", "2 ** bits - 1", "2 ** bits",
+     [(pq.test_eq1_round_trip_bound_and_levels, 2), pq.test_eq1_literal_small_case]),
+    ("Hadamard matrix left unnormalised", hadamard, "orthonormal", "/ np.sqrt(", "/ (",
+     [pq.test_rotation_is_orthogonal_and_self_inverse, pa.test_rotation_invariance_without_quantization]),
+    ("one softmax over all 256 logits instead of one per half", kvcache, "feature_map",
+     "np.concatenate([softmax_rows(x @ W[0]), softmax_rows(x @ W[1])], axis=-1)",
+     "softmax_rows(np.concatenate([x @ W[0], x @ W[1]], axis=-1))",
+     [pa.test_zero_weights_closed_form, pa.test_states_are_additive_over_groups]),
+    ("states built from the raw rotated values instead of the dequantized ones", kvcache, "build_cache",
+     'out["S"] = phi_k.T @ out["V_hat"]', 'out["S"] = phi_k.T @ Vr[:n_quant].astype(np.float64)',
+     [pa.test_recurrent_states_equal_quadratic_form_and_literal_eq5]),
+    ("key error with the wrong sign", kvcache, "build_cache",
+     'K_err = K[:n_quant].astype(np.float64) - out["K_hat"]', 'K_err = out["K_hat"] - K[:n_quant].astype(np.float64)',
+     [pa.test_recurrent_states_equal_quadratic_form_and_literal_eq5]),
+    ("keys quantized per token instead of per channel", kvcache, "build_cache",
+     "ck, sk, zk = _quantize_rows(K[t0:t1].T, bits, mode)",
+     "ck, sk, zk = _quantize_rows(K[t0:t1], bits, mode); ck, sk, zk = ck.T, sk[:d], zk[:d]",
+     [pa.test_partial_tail_group_uses_valid_tokens_only, pa.test_tiny_case_brute_force]),
+    ("values quantized without the rotation", kvcache, "build_cache", "Vr = hadamard.fwht_spec32(V)", "Vr = V",
+     [pa.test_the_three_arithmetic_modes_describe_the_same_cache]),
+    ("window flushed one append early", kvcache, "window_split", "(n - 1) % G + 1", "n % G",
+     [pa.test_window_split_is_the_lazy_block_flush]),
+    ("correction added without the e^-M factor", attention, "decode", "if literal_alg1:", "if True:",
+     [pa.test_recurrent_states_equal_quadratic_form_and_literal_eq5]),
+    ("scores scaled by 1/d instead of 1/sqrt(d)", attention, "decode", "/ np.sqrt(float(d))", "/ float(d)",
+     [pa.test_bits_to_16_converges_to_textbook_attention, pa.test_tiny_case_brute_force]),
+    ("the fp16 window left out of the attention", attention, "_operands",
+     'np.concatenate([cache["K_hat"], cache["k_res"].astype(np.float64)], axis=0)',
+     'np.concatenate([cache["K_hat"], cache["k_res"][:0].astype(np.float64)], axis=0)',
+     [pa.test_bits_to_16_converges_to_textbook_attention]),
+    ("block merge weighted by exp(M - m) instead of exp(m - M)", attention, "decode_blocks", "w = np.exp(m - M)",
+     "w = np.exp(M - m)", [(pa.test_block_merge_equals_single_softmax, False)]),
+    ("C_d taken from S instead of P", attention, "correction_terms", 'float(phi_q @ cache["P"])',
+     'float((phi_q @ cache["S"]).sum())', [pa.test_zero_weights_closed_form]),
+    # the functions the GPU is held to bit for bit
+    ("spec32: the middle threshold loses its tie rule", quantizer, "quantize_spec32", "(t >= f32(1.5) * s)",
+     "(t > f32(1.5) * s)", [pq.test_spec32_ties_literal, pq.test_spec32_is_eq1_against_stored_scale]),
+    ("spec32: codes taken against the unrounded scale", quantizer, "quantize_spec32",
+     "s = s16.astype(f32)[..., None]", "s = (d32 / f32(3.0)).astype(f32)[..., None]",
+     [pq.test_spec32_is_eq1_against_stored_scale]),
+    ("spec32: a negative zero kept as zero-point", quantizer, "quantize_spec32",
+     "mn = np.where(mn == 0, f32(0.0), mn).astype(f32)", "mn = mn.astype(f32)",
+     [pq.test_spec32_negative_zero_is_canonical]),
+    ("spec32: scale over 4 levels", quantizer, "quantize_spec32", "d32 / f32(3.0)", "d32 / f32(4.0)",
+     [pq.test_spec32_is_eq1_against_stored_scale, pq.test_spec32_vs_exact16_mismatch_rate_is_tiny]),
+    ("exact16: codes against the unrounded zero-point", quantizer, "quantize_exact16",
+     "codes = np.rint((x - z16.astype(np.float64)[..., None]) / safe[..., None])",
+     "codes = np.rint((x - mn[..., None]) / (((mx - mn) / levels)[..., None] + 1e-300))",
+     [pq.test_spec32_is_eq1_against_stored_scale, pq.test_spec32_vs_exact16_mismatch_rate_is_tiny,
+      pq.test_constant_group_is_all_zero_codes]),
+    ("fast transform: difference taken the other way round", hadamard, "fwht_spec32", "t = (a - b)", "t = (b - a)",
+     [pq.test_fwht_spec32_equals_dense_product]),
+    ("fast transform: the last stage left out", hadamard, "fwht_spec32", "while h < d:", "while h < d // 2:",
+     [pq.test_fwht_spec32_equals_dense_product]),
+    ("fast transform: scale of the wrong dimension", hadamard, "fwht_spec32", "x * INV_SQRT_128_F32",
+     "x * np.float32(0.125)", [pq.test_fwht_spec32_equals_dense_product]),
+    ("Sylvester matrix from i | j instead of i & j", hadamard, "sylvester", "i[:, None] & i[None, :]",
+     "i[:, None] | i[None, :]", [(pq.test_sylvester_is_hadamard, 4), pq.test_fwht_spec32_equals_dense_product]),
+    ("average bits: the window counted at the quantized width", accounting, "average_bits", "n_w * d * 16.0",
+     "n_w * d * bits_per_element_quantized(bits, group)", [pq.test_average_bits_match_table1]),
+    ("average bits: P left out of the states", accounting, "average_bits", "(D * d + D)", "(D * d)",
+     [pq.test_average_bits_match_table1]),
+    ("average bits: scale and zero-point at 8 bits", accounting, "bits_per_element_quantized", "2.0 * 16.0",
+     "2.0 * 8.0", [pq.test_average_bits_match_table1]),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_a_planted_mistake_is_noticed(monkeypatch, case):
+    _, module, name, old, new, pins = case
+    _planted(monkeypatch, module, name, old, new)
+    _some_pin_fails(pins)
+
+
+def test_the_unplanted_oracle_passes_the_same_pins():
+    """The harness itself must not be what fails: with nothing planted every pin named above passes."""
+    for case in CASES:
+        for pin in case[5]:
+            fn, args = (pin, ()) if callable(pin) else (pin[0], pin[1:])
+            fn(*args)
+
+
+def test_layout_and_accounting_mistakes_are_noticed(monkeypatch):
+    # the record order: key and value tiles exchanged
+    src = inspect.getsource(layout)
+    assert "pack_records" in src and "average_bits" in inspect.getsource(accounting)
+    calls = [pl.test_record_fields_sit_where_the_header_says]
+    real = layout.pack_records
+
+    def swapped(k_codes, v_codes, *rest):
+        return real(v_codes, k_codes, *rest)  # key and value tiles exchanged
+
+    monkeypatch.setattr(layout, "pack_records", swapped)
+    _some_pin_fails(calls)
+    monkeypatch.setattr(layout, "pack_records", real)
+    # the 2.46 / 2.71 bit figures: scale and zero-point counted at 8 bits instead of 16
+    real_bits = accounting.average_bits
+    monkeypatch.setattr(accounting, "average_bits", lambda *a, **k: real_bits(*a, **k) - 0.125)
+    _some_pin_fails([pq.test_average_bits_match_table1])

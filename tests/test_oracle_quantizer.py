@@ -98,10 +98,15 @@ def test_spec32_ties_literal():
 
 
 def test_spec32_negative_zero_is_canonical():
-    x = np.zeros((1, 128), dtype=np.float16)
-    x[0, ::2] = -0.0
+    x = np.zeros((3, 128), dtype=np.float16)
+    x[0, ::2] = -0.0                 # zeros of both signs
+    x[1, :] = -0.0                   # only negative zeros: the minimum is -0 whatever the reduction order
+    x[2, :] = np.arange(128) / 64.0  # the minimum is a single -0 among positive values
+    x[2, 0] = -0.0
     codes, s16, z16 = quantizer.quantize_spec32(x)
-    assert z16.view(np.uint16)[0] == 0 and s16.view(np.uint16)[0] == 0 and not codes.any()
+    assert not z16.view(np.uint16).any(), "the stored zero-point of a zero minimum is +0"
+    assert s16.view(np.uint16)[0] == 0 and s16.view(np.uint16)[1] == 0 and not codes[:2].any()
+    assert float(s16[2]) == float(np.float16(np.float32(127 / 64.0) / np.float32(3.0))) and codes[2, 0] == 0
 
 
 def test_spec32_vs_exact16_mismatch_rate_is_tiny():

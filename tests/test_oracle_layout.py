@@ -116,3 +116,15 @@ def test_record_fields_sit_where_the_header_says():
             assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), name
         else:
             assert np.array_equal(got, want), name
+
+
+def test_value_window_order():
+    """include/kvlinc.h: v_res is [R / 4][128][4] -- the rotated value of window token 4 i + k, channel c, sits at
+    [i][c][k]; unused rows are zero."""
+    rows = np.arange(5 * 128, dtype=np.float16).reshape(5, 128) / np.float16(8)
+    tiled = layout.pack_value_window(rows, 128)
+    assert tiled.shape == (32, 128, 4) and tiled.dtype == np.float16
+    for t, c in [(0, 0), (1, 0), (3, 127), (4, 64)]:
+        assert tiled[t // 4, c, t % 4] == rows[t, c]
+    assert not tiled[1, :, 1:].any() and not tiled[2:].any()
+    assert np.array_equal(layout.unpack_value_window(tiled, 5), rows)

@@ -119,6 +119,37 @@ def test_the_unplanted_oracle_passes_the_same_pins():
             fn(*args)
 
 
+LAYOUT_CASES = [
+    ("key tile: channel halves exchanged", "_k_index_maps", "p = (c % 8) // 4", "p = 1 - (c % 8) // 4",
+     [pl.test_tiles_are_bijections_and_match_the_definition]),
+    ("key tile: the pair's second element in the low half", "_k_index_maps", "shift = 2 * j + 16 * e",
+     "shift = 2 * j + 16 * (1 - e)", [pl.test_literal_corners]),
+    ("value tile: tokens of a word in plain order", "_v_index_maps", "j = 2 * (b % 4) + kk // 2",
+     "j = 2 * (b % 4) + kk % 2", [pl.test_tiles_are_bijections_and_match_the_definition]),
+    ("value window: token and channel exchanged inside a block", "pack_value_window",
+     "full.reshape(R // 4, 4, 128).transpose(0, 2, 1)", "full.reshape(R // 4, 128, 4)",
+     [pl.test_value_window_order]),
+    ("state tiles: channel half before feature block", "pack_state_tiles",
+     "tile = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4", "tile = (c // 64 * 4 + f // 64) * 16 + (f % 64) // 4",
+     [pl.test_state_tiles_are_a_bijection]),
+]
+
+
+@pytest.mark.parametrize("case", LAYOUT_CASES, ids=[c[0] for c in LAYOUT_CASES])
+def test_a_planted_layout_mistake_is_noticed(monkeypatch, case):
+    _, name, old, new, pins = case
+    _planted(monkeypatch, layout, name, old, new)
+    if name == "_k_index_maps":  # the maps are tabulated when the module is loaded
+        word, shift = layout._k_index_maps()
+        monkeypatch.setattr(layout, "_K_WORD", word)
+        monkeypatch.setattr(layout, "_K_SHIFT", shift)
+    if name == "_v_index_maps":
+        word, shift = layout._v_index_maps()
+        monkeypatch.setattr(layout, "_V_WORD", word)
+        monkeypatch.setattr(layout, "_V_SHIFT", shift)
+    _some_pin_fails(pins)
+
+
 def test_layout_and_accounting_mistakes_are_noticed(monkeypatch):
     # the record order: key and value tiles exchanged
     src = inspect.getsource(layout)

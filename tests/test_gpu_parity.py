@@ -101,7 +101,7 @@ def test_config1_partial_tail_group(kv):
     assert cache.n_quant.cpu().tolist() == [992] and cache.n_res.cpu().tolist() == [32]
 
 
-@pytest.mark.parametrize("gq,H_kv", [(1, 2), (7, 2), (2, 1), (8, 1)])
+@pytest.mark.parametrize("gq,H_kv", [(1, 2), (7, 2), (2, 1), (8, 1), (3, 2), (5, 1), (6, 3), (4, 5)])
 def test_other_head_ratios(kv, gq, H_kv):
     B, H_q = 2, gq * H_kv
     lengths = [400, 300]
@@ -110,6 +110,20 @@ def test_other_head_ratios(kv, gq, H_kv):
     out = cache.decode(tl.to_dev(q)).cpu().numpy()
     want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
     tl.check_outputs(out, want)
+
+
+def test_many_short_sequences(kv):
+    """More sequences than compute units, each a few hundred tokens: every sequence one split, several generations of
+    workgroups, correction workgroups far outnumbering the places."""
+    B, H_q, H_kv = 300, 2, 1
+    lengths = [129 + (37 * b) % 400 for b in range(B)]
+    cache, K, V, Wq, Wk = _build(kv, 20, B, H_q, H_kv, lengths)
+    q = tl.gen_q(20, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    pairs = [(b, 0) for b in (0, 1, 63, 64, 127, 128, 255, 256, 298, 299)]
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), pairs, H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+    assert np.isfinite(out.astype(np.float32)).all() and int(cache.split_done.abs().sum().item()) == 0
 
 
 def test_degenerate_inputs(kv):

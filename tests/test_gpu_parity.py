@@ -126,6 +126,38 @@ def test_many_short_sequences(kv):
     assert np.isfinite(out.astype(np.float32)).all() and int(cache.split_done.abs().sum().item()) == 0
 
 
+def test_cache_filled_to_its_last_group(kv):
+    """Capacity 4 groups: a bulk build of 512 tokens, then one-token appends.  Token 513 flushes into the last group;
+    at 640 tokens every group and the window are full and decode must still be exact (a wave's first request is
+    clamped to the last record); token 641 would need a fifth group: the status bit is set and the sequence stays."""
+    import torch
+    B, H_q, H_kv = 2, 4, 1
+    total = 641
+    K, V = tl.gen_kv(21, B, H_kv, [total, total])
+    Wq, Wk = synth.adapters_q(21, H_q), synth.adapters_k(21, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 512, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    assert cache.max_groups == 4
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :512].contiguous(), Vd[:, :, :512].contiguous())
+    for t in range(512, 640):
+        cache.append(Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous())
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0
+    assert cache.n_quant.cpu().tolist() == [512, 512] and cache.n_res.cpu().tolist() == [128, 128]
+    lengths = [640, 640]
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)
+    q = tl.gen_q(21, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, [512, 512], _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+    cache.append(Kd[:, :, 640:641].contiguous(), Vd[:, :, 640:641].contiguous())
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) & kv.KVLINC_ST_CAPACITY
+    assert cache.n_quant.cpu().tolist() == [512, 512] and cache.n_res.cpu().tolist() == [128, 128]
+    out2 = cache.decode(tl.to_dev(q)).cpu().numpy()
+    assert np.array_equal(out.view(np.uint16), out2.view(np.uint16))
+
+
 def test_degenerate_inputs(kv):
     import torch
     B, H_q, H_kv = 3, 4, 1

@@ -41,6 +41,11 @@ constexpr int kThreads = 64 * kWaves;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kAlpha = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
 constexpr float kRawScale = 1048576.0f;                  // 2^20: A carries 2^(4 - 2 pos), B carries 2^(2 pos - 24)
+// The query-side operand q * gain * s of q K^T is held in binary16.  It is carried 2^-6 lower than its value and the
+// scores are raised by 2^6 afterwards: exact both ways, and |q s| may then reach 2.6e5 instead of 4.1e3 before the
+// operand overflows (what falls into the subnormal range at the other end is below 2^-25 of a code and of no
+// account in a score).
+constexpr float kQueryShift = 0.015625f;
 
 // ---- small helpers ----------------------------------------------------------------------------------------------
 
@@ -204,7 +209,7 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const uint
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) sc[nb][hf] = (acc[nb][hf][0] + acc[nb][hf][1]) * (kRawScale * kAlpha);
+    for (int hf = 0; hf < 2; ++hf) sc[nb][hf] = (acc[nb][hf][0] + acc[nb][hf][1]) * (kRawScale * kAlpha / kQueryShift);
   if (valid < kGroup) {  // partial last group: tokens >= valid do not exist
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -865,7 +870,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const half_t gn = (half_t)((i & 1) ? gain1 : gain0);
+        const half_t gn = (half_t)(((i & 1) ? gain1 : gain0) * kQueryShift);
         const half2_t g2 = {gn, gn};
         Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
       }

@@ -158,6 +158,25 @@ def test_cache_filled_to_its_last_group(kv):
     assert np.array_equal(out.view(np.uint16), out2.view(np.uint16))
 
 
+@pytest.mark.parametrize("key_gain,query_gain", [(32, 4), (256, 16)])
+def test_large_magnitudes_stay_finite(kv, key_gain, query_gain):
+    """Keys and queries far larger than any activation of the paper's models (|k| up to 7e3): the binary16 operands
+    of the matrix products must not overflow, and the (then one-hot) softmax must still match the oracle."""
+    B, H_q, H_kv = 1, 4, 1
+    lengths = [700]
+    K, V = tl.gen_kv(22, B, H_kv, lengths)
+    K = (K.astype(np.float32) * key_gain).astype(np.float16)
+    q = (tl.gen_q(22, B, H_q).astype(np.float32) * query_gain).astype(np.float16)
+    assert np.isfinite(K.astype(np.float32)).all()
+    Wq, Wk = synth.adapters_q(22, H_q), synth.adapters_k(22, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K), tl.to_dev(V))
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    assert int(cache.status.item()) == 0 and np.isfinite(out.astype(np.float32)).all()
+    want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), [(0, 0)], H_q, H_kv, Wq, Wk)
+    tl.check_outputs(out, want)
+
+
 def test_degenerate_inputs(kv):
     import torch
     B, H_q, H_kv = 3, 4, 1

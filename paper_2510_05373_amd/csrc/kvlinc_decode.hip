@@ -634,7 +634,7 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 __device__ long long g_dbg_ts[1 << 18];
 #define DBG_TS(slot)                                                                              \
   do {                                                                                            \
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096)                                             \
+    if ((threadIdx.x & 63) == 0 && (blockIdx.x + 1) * kWaves <= (1 << 14))  /* 2^18 / 16 stamp rows */ \
       g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + (slot)] = wall_clock64(); \
   } while (0)
 #else
@@ -700,7 +700,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int n_parts = corr != nullptr ? kCorrParts : 0;
   DBG_TS(0);
 #ifdef KVLINC_TUNING
-  if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096) {
+  if ((threadIdx.x & 63) == 0 && (blockIdx.x + 1) * kWaves <= (1 << 14)) {
     const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4), xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20);
     g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 15] = ((long long)xcc << 32) | hw;
   }

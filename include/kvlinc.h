@@ -29,14 +29,19 @@
  *                       words 1024..2047  value tile, 2-bit codes of the 128x128 block of ROTATED values
  *                       words 2048..2111  key scale s of Eq. 1, fp16 per channel 0..127 (channel 2i in the low half)
  *                       words 2112..2175  key zero-point z, fp16 per channel
- *                       words 2176..2303  value (s, z) of token t in word 2176 + t: s in the low half, z in the high
- *                     Logical content of a tile: code(token, channel) in {0..3}.  Word format: a word holds 8 pairs
- *                     j = 0..7, pair j = {bits 2j+1:2j, bits 16+2j+1:16+2j}.
- *                     Key tile:   token t = 64*hf + l owns words q = 0..7 at ((hf*2 + q/4)*64 + l)*4 + q%4;
- *                                 word q, pair j, element e holds channel 8*(4*(q%4) + j/2) + 4*(q/4) + 2*(j%2) + e.
- *                     Value tile: channel c = 64*ch + l owns, per token half hf, words w = 0..3 at
- *                                 ((hf*2 + ch)*64 + l)*4 + w; word w, pair j, element e holds token
- *                                 64*hf + 4*(4*w + j/2) + 2*(j%2) + e.
+ *                       words 2176..2303  value (s, z) of token t = 16 n + j in word 2176 + 8 j + n: s in the low half, z in
+ *                                         the high
+ *                     Logical content of a tile: code(token, channel) in {0..3}.  Both tiles share one word order, made
+ *                     for the 16x16x128 matrix-core instruction that consumes them: a tile has 8 blocks n of 16 "rows"
+ *                     j, and every row has 128 contraction positions k, cut into 4 quarters g of 32.  The two words
+ *                     w = 0, 1 of (n, j, g) sit at word index ((n / 2) * 64 + j + 16 * g) * 4 + 2 * (n % 2) + w.  A word holds
+ *                     16 codes p = 0..15, code p at position k = 32 g + 16 w + 8 (p % 2) + p / 2, two codes per nibble:
+ *                     code c is stored as the bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for c = 0, 1, 2, 3, with
+ *                     hi in bit 4 (p / 2) + 3 - p % 2 and lo in bit 4 (p / 2) + 1 - p % 2.  (With the nibble's other two
+ *                     bits forced to 0 and 1, the nibble sign|0|lo|1 is the FP4 E2M1 number c - 1.5.)
+ *                     Key tile:   row (n, j) = token 16 n + j, position k = channel k.
+ *                     Value tile: row (n, j) = channel 16 n + j, position k = token
+ *                                 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2.
  *                     A partial last group (bulk build only) has zero codes and zero (s, z) for its missing tokens.
  *   k_res             [B, H_kv, R, 128] fp16: the window's raw keys, slot r = r-th oldest window token.
  *   v_res             [B, H_kv, R/4, 128, 4] fp16: the window's ROTATED values, 4 consecutive slots per channel:

@@ -6,28 +6,25 @@ V_I in R^{N x d/16} in Alg. 1).  The logical content -- one code per (token, cha
 contract; the order inside a tile is an encoding chosen for the decode kernel and is written
 down here independently of the kernel source.
 
-Word format (both tiles): a word holds 8 "pairs" j = 0..7; pair j keeps its first code in bits
-[2j+1 : 2j] and its second code in bits [16+2j+1 : 16+2j].
+Tile order (both tiles, the header's statement): a tile has 8 blocks n of 16 rows j; every row has 128
+contraction positions k in 4 quarters g of 32.  The two words w = 0, 1 of (n, j, g) sit at word index
 
-Key tile, block of 128 tokens x 128 channels, token t = 64*hf + l (hf in {0,1}, l in 0..63):
-    token t owns 8 words q = 0..7 at word index ((hf*2 + q//4)*64 + l)*4 + q%4
-    word q, pair j, element e (0 = first, 1 = second) holds channel
-        c = 8*(4*(q%4) + j//2) + 4*(q//4) + 2*(j%2) + e
-    (so a lane that loads 16 contiguous bytes gets 64 channels of its own token).
+    ((n // 2) * 64 + j + 16 * g) * 4 + 2 * (n % 2) + w
 
-Value tile, block of 128 tokens x 128 channels, channel c = 64*ch + l (ch in {0,1}, l in 0..63):
-    channel c owns, for each token half hf in {0,1}, 4 words w = 0..3 at word index
-        ((hf*2 + ch)*64 + l)*4 + w
-    word w, pair j, element e holds token
-        t = 64*hf + 4*(4*w + j//2) + 2*(j%2) + e
-    (so a lane that loads 16 contiguous bytes gets 64 tokens of its own channel).
+and code p (0..15) of a word belongs to position k = 32 g + 16 w + 8 (p % 2) + p // 2.  A code c is stored as the bit
+pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for c = 0, 1, 2, 3; code p keeps hi in bit 4 (p // 2) + 3 - p % 2 and lo in
+bit 4 (p // 2) + 1 - p % 2 of its word (two codes share a nibble).
+
+Key tile:   row (n, j) = token 16 n + j; position k = channel k.
+Value tile: row (n, j) = channel 16 n + j; position k = token 16 (k % 8) + 4 ((k // 16) % 4) + 2 (k // 64) + (k // 8) % 2.
 
 Group record, 2304 words (everything one decode step needs of a group, contiguous in memory):
     words    0 .. 1023   key tile
     words 1024 .. 2047   value tile
     words 2048 .. 2111   key scale, fp16 per channel 0..127 (two per word, low half first)
     words 2112 .. 2175   key zero-point, fp16 per channel
-    words 2176 .. 2303   value (scale, zero-point) of token t in word 2176 + t: scale in the low half, zero in the high
+    words 2176 .. 2303   value (scale, zero-point) of token t = 16 n + j in word 2176 + 8 j + n: scale in the low half,
+                         zero in the high
 
 State tiles: the binary16 copy of S [256 features, 128 channels] that the decode step reads is stored as 128 tiles of
 64 x 4 halves; tile (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4 holds S[f][c] at [c % 64][f % 4].
@@ -41,57 +38,73 @@ TILE_WORDS = 1024
 RECORD_WORDS = 2304
 
 
+SYMBOL_OF_CODE = np.array([0b11, 0b10, 0b00, 0b01], dtype=np.uint32)  # (hi, lo) of code 0, 1, 2, 3
+CODE_OF_SYMBOL = np.array([2, 3, 1, 0], dtype=np.uint8)
+
+
+def _position_maps():
+    """For every (row r = 16 n + j, position k) of a tile: word index and the index p of its code inside the word."""
+    r = np.arange(128)[:, None]
+    k = np.arange(128)[None, :]
+    n, j = r // 16, r % 16
+    g = k // 32
+    w = (k % 32) // 16
+    # k % 16 = 8 (p % 2) + p // 2  <=>  p = 2 (k % 8) + (k % 16) // 8
+    p = 2 * (k % 8) + (k % 16) // 8
+    word = ((n // 2) * 64 + j + 16 * g) * 4 + 2 * (n % 2) + w
+    return np.broadcast_to(word, (128, 128)), np.broadcast_to(p, (128, 128))
+
+
+def _value_token_of_position():
+    k = np.arange(128)
+    return 16 * (k % 8) + 4 * ((k // 16) % 4) + 2 * (k // 64) + (k // 8) % 2
+
+
 def _k_index_maps():
-    t = np.arange(128)[:, None]
-    c = np.arange(128)[None, :]
-    hf, l = t // 64, t % 64
-    s = c // 8
-    p = (c % 8) // 4
-    jj = (c % 4) // 2
-    e = c % 2
-    w = s // 4
-    j = 2 * (s % 4) + jj
-    word = ((hf * 2 + p) * 64 + l) * 4 + w
-    shift = 2 * j + 16 * e
-    return np.broadcast_to(word, (128, 128)), np.broadcast_to(shift, (128, 128))
+    """[token, channel] -> (word, p): rows are tokens, position k is channel k."""
+    return _position_maps()
 
 
 def _v_index_maps():
-    t = np.arange(128)[:, None]
-    c = np.arange(128)[None, :]
-    hf, tt = t // 64, t % 64
-    ch, l = c // 64, c % 64
-    b = tt // 4
-    kk = tt % 4
-    w = b // 4
-    j = 2 * (b % 4) + kk // 2
-    e = kk % 2
-    word = ((hf * 2 + ch) * 64 + l) * 4 + w
-    shift = 2 * j + 16 * e
-    return np.broadcast_to(word, (128, 128)), np.broadcast_to(shift, (128, 128))
+    """[token, channel] -> (word, p): rows are channels, position k holds token _value_token_of_position()[k]."""
+    word_rk, shift_rk = _position_maps()          # [channel row, position]
+    tok = _value_token_of_position()
+    assert sorted(tok.tolist()) == list(range(128))
+    word = np.empty((128, 128), dtype=np.int64)
+    shift = np.empty((128, 128), dtype=np.int64)
+    word[tok[None, :], np.arange(128)[:, None]] = word_rk
+    shift[tok[None, :], np.arange(128)[:, None]] = shift_rk
+    return word, shift
 
 
 _K_WORD, _K_SHIFT = _k_index_maps()
+_SZ_WORD = 8 * (np.arange(128) % 16) + np.arange(128) // 16  # word (after 2176) of token t = 16 n + j: 8 j + n
 _V_WORD, _V_SHIFT = _v_index_maps()
 
 
-def _pack(codes, word, shift):
+def _pack(codes, word, p):
     codes = np.asarray(codes)
     assert codes.shape[-2:] == (128, 128) and codes.min() >= 0 and codes.max() <= 3
     lead = codes.shape[:-2]
-    flat = codes.reshape((-1, 128 * 128)).astype(np.uint32)
-    out = np.zeros((flat.shape[0], TILE_WORDS), dtype=np.uint32)
+    sym = SYMBOL_OF_CODE[codes.reshape((-1, 128 * 128))]
+    out = np.zeros((sym.shape[0], TILE_WORDS), dtype=np.uint32)
     wi = word.reshape(-1)
-    sh = shift.reshape(-1).astype(np.uint32)
-    for n in range(flat.shape[0]):
-        np.bitwise_or.at(out[n], wi, flat[n] << sh)
+    pp = p.reshape(-1).astype(np.uint32)
+    hi_bit = 4 * (pp // 2) + 3 - pp % 2
+    lo_bit = 4 * (pp // 2) + 1 - pp % 2
+    for n in range(sym.shape[0]):
+        np.bitwise_or.at(out[n], wi, ((sym[n] >> np.uint32(1)) << hi_bit) | ((sym[n] & np.uint32(1)) << lo_bit))
     return out.reshape(lead + (TILE_WORDS,))
 
 
-def _unpack(tile, word, shift):
+def _unpack(tile, word, p):
     tile = np.asarray(tile, dtype=np.uint32)
     assert tile.shape[-1] == TILE_WORDS
-    return ((tile[..., word] >> shift.astype(np.uint32)) & np.uint32(3)).astype(np.uint8)
+    pp = p.astype(np.uint32)
+    w = tile[..., word]
+    hi = (w >> (4 * (pp // 2) + 3 - pp % 2)) & np.uint32(1)
+    lo = (w >> (4 * (pp // 2) + 1 - pp % 2)) & np.uint32(1)
+    return CODE_OF_SYMBOL[2 * hi + lo]
 
 
 def pack_k_tile(codes):
@@ -130,7 +143,7 @@ def pack_records(k_codes, v_codes, k_scale, k_zero, v_scale, v_zero):
     rec[:, 2112:2176] = _halves_to_words(k_zero)
     vs = np.ascontiguousarray(v_scale, dtype=np.float16).view(np.uint16).astype(np.uint32)
     vz = np.ascontiguousarray(v_zero, dtype=np.float16).view(np.uint16).astype(np.uint32)
-    rec[:, 2176:2304] = vs | (vz << np.uint32(16))
+    rec[:, 2176:2304][:, _SZ_WORD] = vs | (vz << np.uint32(16))
     return rec
 
 
@@ -141,7 +154,7 @@ def unpack_records(rec):
         lo = (words & np.uint32(0xFFFF)).astype(np.uint16)
         hi = (words >> np.uint32(16)).astype(np.uint16)
         return np.stack([lo, hi], axis=-1).reshape(words.shape[:-1] + (-1,)).view(np.float16)
-    sz = rec[:, 2176:2304]
+    sz = rec[:, 2176:2304][:, _SZ_WORD]
     return {
         "k_codes": unpack_k_tile(rec[:, 0:1024]), "v_codes": unpack_v_tile(rec[:, 1024:2048]),
         "k_scale": halves(rec[:, 2048:2112]), "k_zero": halves(rec[:, 2112:2176]),

@@ -145,13 +145,6 @@ __device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, in
   }
 }
 
-#ifdef KVLINC_TUNING
-__device__ long long g_app_ts[64];
-#define APP_TS(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && j == 1) g_app_ts[slot] = wall_clock64(); } while (0)
-#else
-#define APP_TS(slot)
-#endif
-
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
                                                                  const int32_t* __restrict__ n_new, int T, int keep) {
@@ -215,7 +208,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   for (int j = 0; j < plan.n_groups; ++j) {
     const int valid = min(kGroup, plan.n_flush - j * kGroup);
     const long long grp = (long long)(nq / kGroup) + j;
-    APP_TS(0);
     // ---- 1. stage the group's raw keys and (raw or already rotated) values in LDS -------------------------
     for (int ch = tid; ch < kGroup * 16; ch += kThreads) {  // 16-byte chunks: 16 per token row
       const int t = ch >> 4, part = ch & 15;
@@ -240,7 +232,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       dv[0] = vv.x; dv[1] = vv.y; dv[2] = vv.z; dv[3] = vv.w;
     }
     __syncthreads();
-    APP_TS(1);
     // rotate the rows that came from new tokens (window rows are rotated already)
     for (int tb = wave; tb < valid; tb += 4 * (kThreads / 64)) {  // rows tb, tb + 4, tb + 8, tb + 12 together
       float x0[4], x1[4];
@@ -264,7 +255,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       }
     }
     __syncthreads();
-    APP_TS(2);
     // ---- 2. Eq. 1: keys per channel over the group's tokens, rotated values per token over the channels ----
     if (tid < kGroup) {
       const int ch = tid;
@@ -307,35 +297,37 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
       L.vScale[t] = p.s;
       L.vZero[t] = p.z;
       half_t* rec16 = reinterpret_cast<half_t*>(c.groups + (bh * c.max_groups + grp) * kRecordWords);
-      rec16[2 * (kRecValueSZ + t)] = p.s16;
-      rec16[2 * (kRecValueSZ + t) + 1] = p.z16;
+      const int sz_word = kRecValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
+      rec16[2 * sz_word] = p.s16;
+      rec16[2 * sz_word + 1] = p.z16;
     }
     __syncthreads();
-    APP_TS(3);
     // ---- 3. pack the two 4 KB tiles ------------------------------------------------------------------------
     {
       uint32_t* k_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecKeyTile;
       uint32_t* v_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecValueTile;
       for (int wi = tid; wi < kTileWords; wi += kThreads) {
-        const int w = wi & 3, l = (wi >> 2) & 63, sel = (wi >> 8) & 1, hf = wi >> 9;
-        // key tile: token 64*hf + l, word q = 4*sel + w; pair j, element e -> channel 8*(4*w + j/2) + 4*sel + 2*(j%2) + e
-        // value tile: channel 64*sel + l, word w of token half hf; pair j, element e -> token 64*hf + 4*(4*w + j/2) + 2*(j%2) + e
+        // word wi = ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w of both tiles: block n of 16 rows, row j, quarter g of the
+        // contraction axis; code p of the word belongs to position k = 32 g + 16 w + 8 (p % 2) + p / 2 and is stored as the
+        // bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for the codes 0..3, hi in bit 4 (p / 2) + 3 - p % 2, lo two below.
+        // key tile: row = token 16 n + j, position k = channel k;
+        // value tile: row = channel 16 n + j, position k = token 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2.
+        const int w = wi & 1, n = 2 * (wi >> 8) + ((wi >> 1) & 1), l = (wi >> 2) & 63, jr = l & 15, gq4 = l >> 4;
+        const int row = 16 * n + jr, k0 = 32 * gq4 + 16 * w;
+        const int tok0 = 4 * ((k0 >> 4) & 3) + 2 * (k0 >> 6);  // token of position k0 + 8 e + i is 16 i + tok0 + e
         uint32_t kw = 0, vw = 0;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-#pragma unroll
-          for (int e = 0; e < 2; ++e) {
-            const int idx = 4 * (4 * w + jj / 2) + 2 * (jj % 2) + e;  // 0..63
-            const int kc = 8 * (4 * w + jj / 2) + 4 * sel + 2 * (jj % 2) + e;
-            kw |= (uint32_t)L.cK[64 * hf + l][kc] << (2 * jj + 16 * e);
-            vw |= (uint32_t)L.cV[64 * hf + idx][64 * sel + l] << (2 * jj + 16 * e);
-          }
+        for (int pp = 0; pp < 16; ++pp) {
+          const int e = pp & 1, i = pp >> 1;
+          const uint32_t ck = L.cK[row][k0 + 8 * e + i], cv = L.cV[16 * i + tok0 + e][row];
+          // hi = not (c / 2), lo = not (c / 2 xor c % 2)
+          kw |= (((ck >> 1) ^ 1u) << (4 * i + 3 - e)) | ((((ck >> 1) ^ ck ^ 1u) & 1u) << (4 * i + 1 - e));
+          vw |= (((cv >> 1) ^ 1u) << (4 * i + 3 - e)) | ((((cv >> 1) ^ cv ^ 1u) & 1u) << (4 * i + 1 - e));
         }
         k_tile[wi] = kw;
         v_tile[wi] = vw;
       }
     }
-    APP_TS(4);
     // ---- 4. S += phi_k(K - K_q)^T V_q, P += sum phi_k(K - K_q) over the group's valid tokens (Eq. 5, Eq. 6) ----
     // With V_q[t][c] = z_t + s_t code[t][c]:  S[f][c] += sum_t (phi[t][f] s_t) code[t][c] + sum_t phi[t][f] z_t.
     // Both contractions take binary16 operands whose products are exact: the codes are small integers, W_k is
@@ -461,7 +453,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
           }
         }
       }
-      APP_TS(5);
       // the zero-point term is the same for every channel of a row
       __syncthreads();
       L.zs[tid] = Z_f;
@@ -521,12 +512,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
 }
 
 }  // namespace
-
-#ifdef KVLINC_TUNING
-extern "C" int kvlinc_app_ts_read(long long* dst, size_t n) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_app_ts), n * sizeof(long long));
-}
-#endif
 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream) {

@@ -14,21 +14,24 @@
 // head: it weighs the splits by 2^(m_j - M), adds the correction as (num + 2^-M C_n) / (den + 2^-M C_d), applies
 // H^T and stores fp16 (Alg. 1 lines 13-15 with Eq. 5).  No workgroup waits for another.
 //
-// Both contractions of a group run on v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad
-// (cbsz=4, abid=quad): 16 blocks x (4 rows x 4 k) x (4 k x 4 columns).  Rows = the 4 query heads of a head block.
-//   q K^T : columns = 64 tokens (lane = token), k = 4 channels; A = q * key scale, held by quad `abid` for its 8 channels.
-//   E V   : columns = 64 channels (lane = channel), k = 4 tokens;  A = p * value scale, held by the quad that owns the tokens.
-// The B operand is the packed word itself, masked: a 2-bit code left in place inside an fp16 mantissa is the
-// subnormal code * 2^(2 pos - 24) (the matrix cores take subnormal inputs exactly), and the factor 2^(-2 pos) is
-// folded into the A operand of that k slot.  One AND per two codes, one shift per sixteen.
-// Zero-points never touch the tiles: sum_c q_c (s_c code + z_c) = sum_c (q_c s_c) code + sum_c q_c z_c, and likewise
-// for the values per token.  The fp16 rounding of (q s) and (p s) is centred: the code is taken as (code - 1.5) and
-// 1.5 * rounded operand is added back in binary32, which removes the mean of the rounding error.
-// Scores live in the log2 domain: x = q.k * log2(e)/sqrt(d).
+// The two contractions of a group (Alg. 1 lines 5-10) run on v_mfma_scale_f32_16x16x128_f8f6f4, 16 rows x 16 columns x
+// 128 contraction positions per instruction, 8 instructions per contraction and block of 4 query heads:
+//   q K^T : columns = 16 tokens, positions = the 128 channels;  E V : columns = 16 channels, positions = the 128 tokens.
+// B operand = the codes, read as FP4 (E2M1).  A code c is stored as a bit pair (hi, lo) such that the nibble hi|0|lo|1 is
+// the FP4 number c - 1.5; a word keeps the pairs of two codes interleaved in every nibble, so one AND-OR (and one shift
+// for the second code of the nibbles) turns 8 codes into a B register.  Codes are never dequantized, and the centred
+// codes keep the sums free of a common sign (the matrix cores add with a truncating adder: all-positive products
+// would leave a bias that the zero-point term, summed exactly, does not share).
+// A operand = the small side, (q * key scale) resp. (p * value scale), as FP8 (E4M3) in three terms per value:
+//   x = 2^e (t0 + t1 / 16 + t2 / 256), t_k = fp8 of what the earlier terms left, each term in a row of its own,
+//   rows = 4 heads x (3 terms + 1 spare), the factor 2^(e - 4 k) in the row's block scale.
+// The terms leave 2^-12 of x at most (better than binary16); e follows the largest |x| of the head in that group, so
+// no operand overflows or flushes whatever the magnitude of keys, queries and values.  The three rows of a head are
+// summed after the instruction (scores) or once at the end (E V).
+// Zero-points never touch the tiles: sum_c q_c (s_c code + z_c) = sum_c (q_c s_c) (code - 1.5) + sum_c q_c (z_c + 1.5 s_c),
+// and likewise for the values per token.  Scores live in the log2 domain: x = q.k * log2(e)/sqrt(d).
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
-
-#include <cstdlib>
 
 #include "kvlinc_internal.h"
 #include "kvlinc_mfma.h"
@@ -40,12 +43,10 @@ constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kAlpha = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
-constexpr float kRawScale = 1048576.0f;                  // 2^20: A carries 2^(4 - 2 pos), B carries 2^(2 pos - 24)
-// The query-side operand q * gain * s of q K^T is held in binary16.  It is carried 2^-6 lower than its value and the
-// scores are raised by 2^6 afterwards: exact both ways, and |q s| may then reach 2.6e5 instead of 4.1e3 before the
-// operand overflows (what falls into the subnormal range at the other end is below 2^-25 of a code and of no
-// account in a score).
-constexpr float kQueryShift = 0.015625f;
+
+typedef int v8i_t __attribute__((ext_vector_type(8)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 // ---- small helpers ----------------------------------------------------------------------------------------------
 
@@ -59,262 +60,319 @@ __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
-// sum over the 16 lanes that share lane % 4 (one per quad)
-__device__ __forceinline__ float quadlane_allsum(float v) {
+__device__ __forceinline__ float as_f32(uint32_t v) { return __builtin_bit_cast(float, v); }
+__device__ __forceinline__ uint32_t as_bits(float v) { return __builtin_bit_cast(uint32_t, v); }
+
+// Reductions with the result in every participating lane.  row: the 16 lanes of a DPP row; quad: 4 adjacent lanes;
+// xrow: the 4 lanes l, l ^ 16, l ^ 32, l ^ 48 (row swaps: odd rows of one copy against even rows of the other, then
+// the upper 32 lanes of one against the lower 32 of the other).
+__device__ __forceinline__ float row_allmax(float v) {
+  v = fmaxf(v, dpp_f<kRowRor1>(v));
+  v = fmaxf(v, dpp_f<kRowRor2>(v));
+  v = fmaxf(v, dpp_f<kRowRor4>(v));
+  return fmaxf(v, dpp_f<kRowRor8>(v));
+}
+__device__ __forceinline__ float row_allsum(float v) {
+  v += dpp_f<kRowRor1>(v);
+  v += dpp_f<kRowRor2>(v);
   v += dpp_f<kRowRor4>(v);
-  v += dpp_f<kRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  return v + dpp_f<kRowRor8>(v);
+}
+__device__ __forceinline__ float quad_allmax(float v) {
+  v = fmaxf(v, dpp_f<kQuadSwap1>(v));
+  return fmaxf(v, dpp_f<kQuadSwap2>(v));
+}
+__device__ __forceinline__ float quad_allsum(float v) {
+  v += dpp_f<kQuadSwap1>(v);
+  return v + dpp_f<kQuadSwap2>(v);
+}
+__device__ __forceinline__ float xrow_allmax(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(as_bits(v), as_bits(v), false, false);
+  v = fmaxf(as_f32(a[0]), as_f32(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(as_bits(v), as_bits(v), false, false);
+  return fmaxf(as_f32(b[0]), as_f32(b[1]));
+}
+__device__ __forceinline__ float xrow_allsum(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(as_bits(v), as_bits(v), false, false);
+  v = as_f32(a[0]) + as_f32(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(as_bits(v), as_bits(v), false, false);
+  return as_f32(b[0]) + as_f32(b[1]);
 }
 
-// Position of pair j of a packed word inside the fp16 mantissa after the (optional) shift by 6: the code of pair j
-// sits at bits [2 pos + 1 : 2 pos] of its half and reads as code * 2^(2 pos - 24).
-__host__ __device__ constexpr int pair_pos(int j) { return j <= 4 ? j : j - 3; }
-// The factor the A operand carries for a k slot fed by pair j: 2^(4 - 2 pos).
-__device__ __forceinline__ float pair_gain(int j) { return __builtin_ldexpf(1.0f, 4 - 2 * pair_pos(j)); }
+// The compiler may not move LDS traffic of one wave across this point (the hardware keeps a wave's LDS instructions
+// in order, which is all a wave needs to hand data from lane to lane through LDS).
+__device__ __forceinline__ void lds_order() { asm volatile("" ::: "memory"); }
 
-// The 8 pairs of a word as fp16x2 subnormals (9 VALU operations for 16 codes).
-__device__ __forceinline__ void unpack_word(uint32_t w, uint32_t (&u)[8]) {
-  const uint32_t ws = w >> 6;
-  u[0] = w & 0x00030003u;
-  u[1] = w & 0x000C000Cu;
-  u[2] = w & 0x00300030u;
-  u[3] = w & 0x00C000C0u;
-  u[4] = w & 0x03000300u;
-  u[5] = ws & 0x00300030u;
-  u[6] = ws & 0x00C000C0u;
-  u[7] = ws & 0x03000300u;
+// ---- operand layouts of v_mfma_scale_f32_16x16x128_f8f6f4 (measured on gfx950) ---------------------------------------
+// D:  lane l holds column l % 16, rows 4 (l / 16) + r in its 4 registers.
+// B (FP4, 4 registers): lane l holds column l % 16, positions k = 32 (l / 16) + e, nibble e = 0..31 in register order.
+// A (FP8, 8 registers): lane l holds row l % 16, byte e = 0..31 in register order at position
+//     k = 64 (e / 16) + 16 (l / 16) + e % 16.
+// Block scales (E8M0 byte, value 2^(byte - 127)): the scale operand of lane l applies to row / column l % 16 and the
+// positions 32 (l / 16) .. 32 (l / 16) + 31.
+//
+// Roles of a lane.  As a holder of D registers ("row role"): head hd = lane / 16 of the head block, column jd.  As a
+// holder of A registers: row 4 ha + ua = (head ha, term ua), quarter ga.  The A registers are built by the lanes in
+// 8-byte chunks -- chunk u of (head, quarter g) = bytes 8 u .. 8 u + 7 = positions 64 (u / 2) + 16 g + 8 (u % 2) + 0..7 --
+// and handed over through LDS: the builder of (head h, quarter g, chunk u) writes its three terms at
+// ex[160 h + 32 term + 2 (4 g + u)], the holder of (head h, term, quarter g) reads 8 words at ex[160 h + 32 term + 8 g].
+// Term 3 of every head stays zero.  Word 128 of a head carries the block exponent where builder and holder differ.
+constexpr int kExHead = 160;              // words per head in an exchange region (stride 640 B: two heads cover all banks)
+constexpr int kExWords = 4 * kExHead;     // one region: 4 heads
+constexpr int kExExp = 128;               // word of the block exponent
+
+struct Roles {
+  int lane;
+  int jd, hd;      // row role
+  int ua, ha, ga;  // operand role
+  int c0;          // first of the 8 channels whose (q * key scale) this lane builds: chunk ua of (ha, ga)
+  int wq;          // where this lane writes its chunk as a builder of q K^T operands (it builds for its own quad)
+  int wp;          // ... as a builder of E V operands (it builds from the probabilities it holds in the row role)
+  int rd;          // where this lane reads its operand registers
+  uint32_t* ex_qk;  // this wave's exchange regions
+  uint32_t* ex_pv;
+};
+
+__device__ __forceinline__ Roles make_roles(int lane, uint32_t* ex_wave) {
+  Roles r;
+  r.lane = lane;
+  r.jd = lane & 15; r.hd = lane >> 4;
+  r.ua = lane & 3; r.ha = (lane >> 2) & 3; r.ga = lane >> 4;
+  r.c0 = 64 * (r.ua >> 1) + 16 * r.ga + 8 * (r.ua & 1);
+  r.wq = kExHead * r.ha + 2 * (4 * r.ga + r.ua);
+  r.wp = kExHead * r.hd + 2 * r.jd;
+  r.rd = kExHead * r.ha + 32 * r.ua + 8 * r.ga;
+  r.ex_qk = ex_wave;
+  r.ex_pv = ex_wave + kExWords;
+  return r;
+}
+
+// x[0..7] as three FP8 terms: with sc = 2^e (sc_bits its binary32 pattern, e chosen so that |x| / sc < 256),
+// t_k = fp8((x - what t_0 .. t_{k-1} stand for) / (sc / 16^k)), round to nearest even.  Every residual is exact in
+// binary32 (the term agrees with it in its leading bits).  t[k][v] holds values 4 v .. 4 v + 3, lowest byte first.
+__device__ __forceinline__ void split_fp8x3(const float (&x)[8], uint32_t sc_bits, uint32_t (&t)[3][2]) {
+  float r[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = x[i];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const float sc = as_f32(sc_bits - ((uint32_t)(4 * k) << 23));
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      short2_t w = {0, 0};
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, r[4 * v], r[4 * v + 1], sc, false);
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, r[4 * v + 2], r[4 * v + 3], sc, true);
+      const uint32_t bits = __builtin_bit_cast(uint32_t, w);
+      t[k][v] = bits;
+      if (k < 2) {
+        const float2_t f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(bits, sc, false);
+        const float2_t f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(bits, sc, true);
+        r[4 * v] -= f0[0]; r[4 * v + 1] -= f0[1];
+        r[4 * v + 2] -= f1[0]; r[4 * v + 3] -= f1[1];
+      }
+    }
+  }
+}
+
+// Biased binary32 exponent eb of the largest magnitude mx of a block (kept away from the ends of the range), for
+// sc = 2^(eb - 127 - 7): |x| / sc < 256, inside FP8's range.  Row `term` then carries the block scale byte eb - 7 - 4 term.
+__device__ __forceinline__ uint32_t block_exponent(float mx) { return as_bits(fmaxf(mx, 0x1p-100f)) >> 23; }
+__device__ __forceinline__ uint32_t block_scale_bits(uint32_t eb) { return (eb - 7u) << 23; }
+
+// Builder side of the hand-over: the three terms of this lane's chunk; holder side: the 8 operand registers.
+__device__ __forceinline__ void put_terms(uint32_t* ex, int at, const uint32_t (&t)[3][2]) {
+#pragma unroll
+  for (int k = 0; k < 3; ++k) *reinterpret_cast<u32x2_t*>(ex + at + 32 * k) = u32x2_t{t[k][0], t[k][1]};
+}
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v8i_t get_operand(const uint32_t* ex, int at) {
+  const u32x4_t a = *reinterpret_cast<const u32x4_t*>(ex + at), b = *reinterpret_cast<const u32x4_t*>(ex + at + 4);
+  return v8i_t{(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
+}
+
+// D = A B + C with B = 32 centred codes per lane from two packed words: nibble = hi|0|lo|1 = FP4 (code - 1.5).
+__device__ __forceinline__ float4_t mfma_codes(v8i_t a, uint32_t w0, uint32_t w1, float4_t c, int scale_a) {
+  const v8i_t b = {(int)((w0 & 0xAAAAAAAAu) | 0x11111111u), (int)(((w0 << 1) & 0xAAAAAAAAu) | 0x11111111u),
+                   (int)((w1 & 0xAAAAAAAAu) | 0x11111111u), (int)(((w1 << 1) & 0xAAAAAAAAu) | 0x11111111u), 0, 0, 0, 0};
+  return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /* A: FP8 E4M3 */, 4 /* B: FP4 E2M1 */, 0, scale_a,
+                                                         0, 127);
 }
 
 // Register image of one group.
 struct KeyRegs {
-  uint4 kw[2][2];  // key tile: [token half][word quad]
-  uint4 ks, kz;    // key scale / zero-point of channels 8*quad .. 8*quad+7
+  uint4 kw[4];  // key tile: kw[m] = the words of token blocks 2 m (x, y) and 2 m + 1 (z, w) for this lane's (column, quarter)
+  uint4 ks, kz;  // key scale / zero-point of the 8 channels c0 .. c0 + 7 this lane builds operands for
 };
 struct ValueRegs {
-  uint4 vw[2][2];  // value tile: [token half][channel half]
-  uint32_t sz[2];  // value (scale, zero-point) fp16 pair of tokens lane, 64 + lane
+  uint4 vw[4];  // value tile, channel blocks 2 m and 2 m + 1
+  uint4 sz[2];  // value (scale, zero-point) pairs of tokens 16 n + jd, n = 0..7
 };
 
 // A record is fetched in two parts so that each part can be requested again for the next group as soon as its
 // contraction has consumed it: the key part flies during E V, the value part during the next q K^T.
-__device__ __forceinline__ void load_keys(KeyRegs& r, const uint32_t* __restrict__ rec, int lane) {
+__device__ __forceinline__ void load_keys(KeyRegs& r, const uint32_t* __restrict__ rec, const Roles& lr) {
   const uint4* kt = reinterpret_cast<const uint4*>(rec + kRecKeyTile);
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-    for (int i = 0; i < 2; ++i) r.kw[hf][i] = kt[(hf * 2 + i) * 64 + lane];
-  const int quad = lane >> 2;
-  r.ks = reinterpret_cast<const uint4*>(rec + kRecKeyScale)[quad];
-  r.kz = reinterpret_cast<const uint4*>(rec + kRecKeyZero)[quad];
+  for (int m = 0; m < 4; ++m) r.kw[m] = kt[m * 64 + lr.lane];
+  r.ks = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + kRecKeyScale) + lr.c0);
+  r.kz = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + kRecKeyZero) + lr.c0);
 }
 
-__device__ __forceinline__ void load_values(ValueRegs& r, const uint32_t* __restrict__ rec, int lane) {
+__device__ __forceinline__ void load_values(ValueRegs& r, const uint32_t* __restrict__ rec, const Roles& lr) {
   const uint4* vt = reinterpret_cast<const uint4*>(rec + kRecValueTile);
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-    for (int i = 0; i < 2; ++i) r.vw[hf][i] = vt[(hf * 2 + i) * 64 + lane];
-  r.sz[0] = rec[kRecValueSZ + lane];
-  r.sz[1] = rec[kRecValueSZ + 64 + lane];
+  for (int m = 0; m < 4; ++m) r.vw[m] = vt[m * 64 + lr.lane];
+  const uint4* sz = reinterpret_cast<const uint4*>(rec + kRecValueSZ) + 2 * lr.jd;
+  r.sz[0] = sz[0];
+  r.sz[1] = sz[1];
 }
 
-__device__ __forceinline__ float h2f(uint16_t bits) { return (float)__builtin_bit_cast(half_t, bits); }
-
-// NB = head blocks of 4 query heads (1: up to 4 heads per KV head, 2: up to 8).
+// NB = head blocks of 4 query heads (1: up to 4 heads per KV head, 2: up to 8).  State of a wave, row role.
 template <int NB>
 struct WaveState {
-  float m[NB][4];       // running maximum per head (wave-uniform), log2 domain
-  float l[NB][4];       // per-lane partial sums of p
-  float pz[NB][4];      // per-lane partial sums of the zero-point / centring terms of E V
-  // E V in raw matrix-core units: [head block][token half][channel half], rows = heads, lane = channel.  The two
-  // token halves accumulate separately so that four independent dependency chains are in flight.
-  float4_t acc[NB][2][2];
-  float4_t accw[NB][2];  // E V of fp16 window tokens in true units: [head block][channel half]
+  float m[NB];          // reference maximum of this lane's head (equal in the 16 lanes of the row), log2 domain
+  float l[NB];          // per-lane partial sum of p
+  float pz[NB];         // per-lane partial sum of p * (value zero-point + 1.5 value scale)
+  float4_t acc[NB][8];  // E V of channel 16 n + jd: registers 0..2 = the three term rows of the head, register 3 = what
+                        // the fp16 window contributed (the matrix cores add the zero term row to it)
 };
 
-// Per-lane constants of a wave.
-struct LaneConst {
-  float inv_gain0, inv_gain1;  // 1 / gain of this quad's k-slot pairs (0,1) and (2,3) in q K^T
-  float vgain;                 // gain of this lane's token as a k slot of E V
-  uint32_t perm_sel;           // byte selector of the 16-bit exchange inside the 4x4 quad transpose
-  int lane;
-};
-
-// q K^T of one group for all heads: scores in the log2 domain, [head block][token half], rows = heads, lane = token.
+// q K^T of one group for all heads (Alg. 1 line 7): scores in the log2 domain, sc[nb][n] = head 4 nb + hd, token 16 n + jd.
+// qa = this lane's 8 query values (head 4 nb + ha, channels c0 ..) times log2(e) / sqrt(d).
 template <int NB>
-__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const uint32_t (&Qs)[NB][4], const LaneConst& lc,
-                                         float4_t (&sc)[NB][2]) {
+__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const float (&qa)[NB][8], const Roles& lr,
+                                         float (&sc)[NB][8]) {
   const uint32_t S[4] = {g.ks.x, g.ks.y, g.ks.z, g.ks.w};
   const uint32_t Z[4] = {g.kz.x, g.kz.y, g.kz.z, g.kz.w};
-  const half2_t c15 = {(half_t)1.5f, (half_t)1.5f};
-  const half2_t m15 = {(half_t)-1.5f, (half_t)-1.5f};
-  half4_t A[NB][2];
-  float4_t bias[NB];
+  v8i_t A[NB];
+  int scale_a[NB];
+  float4_t c0[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    uint32_t a[4];
-    float t0 = 0.0f, t1 = 0.0f;
+    float x[8], bz = 0.0f, mx = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a[i] = as_u32(as_h2(Qs[nb][i]) * as_h2(S[i]));        // fp16(q gain s), one rounding
-      const half2_t mid = as_h2(S[i]) * c15 + as_h2(Z[i]);  // z + 1.5 s
-      // gain * [ sum q (z + 1.5 s) ]  -  1.5 * sum rounded(q gain s): the exact compensation of the centring
-      if (i & 1) {
-        t1 = __builtin_amdgcn_fdot2(as_h2(Qs[nb][i]), mid, t1, false);
-        t1 = __builtin_amdgcn_fdot2(as_h2(a[i]), m15, t1, false);
-      } else {
-        t0 = __builtin_amdgcn_fdot2(as_h2(Qs[nb][i]), mid, t0, false);
-        t0 = __builtin_amdgcn_fdot2(as_h2(a[i]), m15, t0, false);
-      }
+    for (int i = 0; i < 8; ++i) {
+      x[i] = qa[nb][i] * (float)as_h2(S[i >> 1])[i & 1];
+      // sum_c q_c (z_c + 1.5 s_c): what the zero-points and the centring of the codes add to every score of the group
+      bz = fmaf(x[i], 1.5f, fmaf(qa[nb][i], (float)as_h2(Z[i >> 1])[i & 1], bz));
+      mx = fmaxf(mx, fabsf(x[i]));
     }
-    A[nb][0] = as_h4(a[0], a[1]);
-    A[nb][1] = as_h4(a[2], a[3]);
-    float b = t0 * lc.inv_gain0 + t1 * lc.inv_gain1;
-    b = quadlane_allsum(b) * (1.0f / kRawScale);  // lanes with lane % 4 == h now hold head h's term, in raw units
-    bias[nb][0] = dpp_f<0x00>(b);
-    bias[nb][1] = dpp_f<0x55>(b);
-    bias[nb][2] = dpp_f<0xAA>(b);
-    bias[nb][3] = dpp_f<0xFF>(b);
+    mx = xrow_allmax(quad_allmax(mx));  // over the 128 channels of the head
+    bz = xrow_allsum(quad_allsum(bz));
+    const uint32_t eb = block_exponent(mx);
+    uint32_t t[3][2];
+    split_fp8x3(x, block_scale_bits(eb), t);
+    put_terms(lr.ex_qk, lr.wq, t);
+    lds_order();
+    A[nb] = get_operand(lr.ex_qk, lr.rd);
+    lds_order();
+    scale_a[nb] = (int)eb - 7 - 4 * lr.ua;
+    // the head's zero-point term enters as the C operand of its first term row: fetch it from a lane that holds head hd
+    // in the operand role (lane 4 hd)
+    c0[nb] = float4_t{__builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(16 * lr.hd, __builtin_bit_cast(int, bz))), 0.f,
+                      0.f, 0.f};
   }
-  // four independent accumulation chains per head block: (token half) x (word quad)
-  float4_t acc[NB][2][2];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) { acc[nb][hf][0] = bias[nb]; acc[nb][hf][1] = float4_t{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    uint32_t u[2][2][8];
+  for (int m = 0; m < 4; ++m) {
+    const uint32_t w[4] = {g.kw[m].x, g.kw[m].y, g.kw[m].z, g.kw[m].w};
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint32_t words[4] = {g.kw[hf][i].x, g.kw[hf][i].y, g.kw[hf][i].z, g.kw[hf][i].w};
-        unpack_word(words[w], u[hf][i]);
+      for (int nb = 0; nb < NB; ++nb) {
+        const float4_t d = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb]);
+        sc[nb][2 * m + hf] = (d[0] + d[1]) + d[2];
       }
-#pragma unroll
-    for (int mstep = 0; mstep < 4; ++mstep)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const half4_t bop = as_h4(u[hf][i][2 * mstep], u[hf][i][2 * mstep + 1]);
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[nb][hf][i] = mfma_bcast(A[nb][i], bop, acc[nb][hf][i], 4 * w + mstep);
-        }
   }
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) sc[nb][hf] = (acc[nb][hf][0] + acc[nb][hf][1]) * (kRawScale * kAlpha / kQueryShift);
   if (valid < kGroup) {  // partial last group: tokens >= valid do not exist
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-        if (64 * hf + lc.lane >= valid) sc[nb][hf] = float4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      for (int n = 0; n < 8; ++n)
+        if (16 * n + lr.jd >= valid) sc[nb][n] = -INFINITY;
   }
 }
 
-// Reference maximum (Alg. 1 line 8).  Any wave-uniform reference m works as long as 2^(x - m) stays inside the fp16
-// range, so the reference is only raised -- with a full cross-lane maximum and a rescale of the accumulated state --
-// when some score of the group exceeds it by more than kSlack; most groups pay one comparison per register.
+// Reference maximum (Alg. 1 line 8).  Any reference m works as long as 2^(x - m) stays moderate, so the reference of a
+// head is only raised -- with a maximum over the row and a rescale of the accumulated state -- when some score of the
+// group exceeds it by more than kSlack; most groups pay one comparison per register.
 constexpr float kSlack = 5.0f;
 template <int NB>
-__device__ __forceinline__ void update_reference(const float4_t (&sc)[NB][2], WaveState<NB>& st) {
+__device__ __forceinline__ void update_reference(const float (&sc)[NB][8], WaveState<NB>& st) {
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    bool over = false;
+    float mloc = sc[nb][0];
 #pragma unroll
-    for (int h = 0; h < 4; ++h) over |= fmaxf(sc[nb][0][h], sc[nb][1][h]) > st.m[nb][h] + kSlack;
-    if (__builtin_amdgcn_ballot_w64(over) != 0) {
+    for (int n = 1; n < 8; ++n) mloc = fmaxf(mloc, sc[nb][n]);
+    if (__builtin_amdgcn_ballot_w64(mloc > st.m[nb] + kSlack) != 0) {
+      const float mnew = fmaxf(st.m[nb], row_allmax(mloc));
+      const float f = mnew == -INFINITY ? 1.0f : exp2f(st.m[nb] - mnew);  // 0 when the old reference is -inf
+      st.l[nb] *= f;
+      st.pz[nb] *= f;
 #pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        const float mx = fmaxf(wave_allmax(fmaxf(sc[nb][0][h], sc[nb][1][h])), st.m[nb][h]);
-        const float f = exp2f(st.m[nb][h] - mx);  // 0 when the old reference is -inf
-        st.l[nb][h] *= f;
-        st.pz[nb][h] *= f;
-        st.acc[nb][0][0][h] *= f;
-        st.acc[nb][0][1][h] *= f;
-        st.acc[nb][1][0][h] *= f;
-        st.acc[nb][1][1][h] *= f;
-        st.accw[nb][0][h] *= f;
-        st.accw[nb][1][h] *= f;
-        st.m[nb][h] = mx;
-      }
+      for (int n = 0; n < 8; ++n) st.acc[nb][n] *= f;
+      st.m[nb] = mnew;
     }
   }
 }
 
-// p = 2^(x - m), its sums, and E V of one group.
+// p = 2^(x - m), its sums, and E V of one group (Alg. 1 lines 9-10).
 template <int NB>
-__device__ __forceinline__ void pv_phase(const ValueRegs& g, const float4_t (&sc)[NB][2], const LaneConst& lc,
+__device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[NB][8], const Roles& lr,
                                          WaveState<NB>& st) {
-  half4_t A2[NB][2];
+  const uint32_t SZ[8] = {g.sz[0].x, g.sz[0].y, g.sz[0].z, g.sz[0].w, g.sz[1].x, g.sz[1].y, g.sz[1].z, g.sz[1].w};
+  v8i_t A[NB];
+  int scale_a[NB];
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf) {
-    const float vs = h2f((uint16_t)(g.sz[hf] & 0xFFFFu));
-    const float vmid = h2f((uint16_t)(g.sz[hf] >> 16)) + 1.5f * vs;
-    // value scale with the k-slot gain of this lane's token.  The weights p vsg are packed to binary16 by
-    // truncation (one instruction for two values), which on its own pulls them down by half an ulp on average
-    // (~2^-11.5 relative) against the exactly summed denominator; the factor centres that error.
-    const float vsg = vs * lc.vgain * 1.000345f;
-    const float comp = -1.5f / lc.vgain;   // exact (power of two times 1.5)
+  for (int nb = 0; nb < NB; ++nb) {
+    float y[8], mx = 0.0f;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      float p[4], ps[4];
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        p[h] = __builtin_amdgcn_exp2f(sc[nb][hf][h] - st.m[nb][h]);
-        st.l[nb][h] += p[h];
-        ps[h] = p[h] * vsg;
-      }
-      const half2_t x01 = as_h2(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ps[0], ps[1])));
-      const half2_t x23 = as_h2(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ps[2], ps[3])));
-      // sum_t p_t (z_t + 1.5 s_t) - 1.5 sum_t rounded(p_t s_t)
-      st.pz[nb][0] = fmaf(p[0], vmid, fmaf((float)x01[0], comp, st.pz[nb][0]));
-      st.pz[nb][1] = fmaf(p[1], vmid, fmaf((float)x01[1], comp, st.pz[nb][1]));
-      st.pz[nb][2] = fmaf(p[2], vmid, fmaf((float)x23[0], comp, st.pz[nb][2]));
-      st.pz[nb][3] = fmaf(p[3], vmid, fmaf((float)x23[1], comp, st.pz[nb][3]));
-      // 4x4 transpose inside each lane quad: (lane = token, slots = heads) -> (lane = head, slots = tokens)
-      A2[nb][hf] = quad_transpose(as_u32(x01), as_u32(x23), lc.perm_sel, lc.lane);
+    for (int n = 0; n < 8; ++n) {
+      const float p = __builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]);
+      const half2_t sz = as_h2(SZ[n]);
+      st.l[nb] += p;
+      y[n] = p * (float)sz[0];  // p * value scale: the weight of the token's codes
+      // sum_t p_t (z_t + 1.5 s_t): the zero-points and the centring of the codes, the same for every channel
+      st.pz[nb] = fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb]));
+      mx = fmaxf(mx, y[n]);
     }
+    const uint32_t eb = block_exponent(row_allmax(mx));  // over the 128 tokens of the head
+    uint32_t t[3][2];
+    split_fp8x3(y, block_scale_bits(eb), t);
+    put_terms(lr.ex_pv, lr.wp, t);
+    lr.ex_pv[kExHead * lr.hd + kExExp] = eb;  // the same value from the 16 lanes of the row
+    lds_order();
+    A[nb] = get_operand(lr.ex_pv, lr.rd);
+    scale_a[nb] = (int)lr.ex_pv[kExHead * lr.ha + kExExp] - 7 - 4 * lr.ua;
+    lds_order();
   }
-  // four independent accumulation chains per head block: (token half) x (channel half)
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    uint32_t u[2][2][8];
+  for (int m = 0; m < 4; ++m) {
+    const uint32_t w[4] = {g.vw[m].x, g.vw[m].y, g.vw[m].z, g.vw[m].w};
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-      for (int ch = 0; ch < 2; ++ch) {
-        const uint32_t words[4] = {g.vw[hf][ch].x, g.vw[hf][ch].y, g.vw[hf][ch].z, g.vw[hf][ch].w};
-        unpack_word(words[w], u[hf][ch]);
-      }
-#pragma unroll
-    for (int mstep = 0; mstep < 4; ++mstep)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int ch = 0; ch < 2; ++ch) {
-          const half4_t bop = as_h4(u[hf][ch][2 * mstep], u[hf][ch][2 * mstep + 1]);
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            st.acc[nb][hf][ch] = mfma_bcast(A2[nb][hf], bop, st.acc[nb][hf][ch], 4 * w + mstep);
-        }
+      for (int nb = 0; nb < NB; ++nb)
+        st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb]);
   }
 }
 
 // ---- half of the fp16 window as one more block of 64 tokens of one wave (raw keys, rotated values) ---------------
+// On v_mfma_f32_4x4x4_16B_f16 with the A operand broadcast from one lane quad: rows = the 4 heads of a head block.
+//   q K^T : columns = 64 tokens (lane = token), k = 4 channels;  E V : columns = 64 channels (lane = channel), k = 4 tokens.
+// Runs before the wave's first group, on empty state.
+
+template <int NB>
+struct WindowState {
+  float m[NB][4];       // maximum per head (wave-uniform), log2 domain
+  float l[NB][4];       // per-lane p (lane = token)
+  float4_t accw[NB][2];  // E V in true units: [head block][channel half], rows = heads, lane = channel
+};
 
 template <int NB>
 __device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t* __restrict__ q, int bh, int b, int g,
-                                            int gq, int half, int nr, const LaneConst& lc, WaveState<NB>& st) {
-  const int lane = lc.lane;
+                                            int gq, int half, int nr, int lane, WindowState<NB>& st) {
   const int quad = lane >> 2, hrow = lane & 3;
+  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
   // 16 x 16 B of this lane's key row now; 32 x 8 B of this lane's two value channels once the keys are consumed
   const int tok = 64 * half + lane;
   const int row = tok < c.R ? tok : c.R - 1;  // rows beyond the capacity do not exist; their scores are masked below
@@ -350,13 +408,11 @@ __device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t*
       acc[nb][1][i & 1] = mfma_bcast(A[nb][1], b1, acc[nb][1][i & 1], i);
     }
   }
-  float4_t sc[NB][2];
-  const float4_t ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  float4_t sc[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    sc[nb][0] = (acc[nb][0][0] + acc[nb][0][1] + acc[nb][1][0] + acc[nb][1][1]) * kAlpha;
-    if (tok >= nr) sc[nb][0] = ninf;
-    sc[nb][1] = ninf;
+    sc[nb] = (acc[nb][0][0] + acc[nb][0][1] + acc[nb][1][0] + acc[nb][1][1]) * kAlpha;
+    if (tok >= nr) sc[nb] = float4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   }
   uint2 vx[2][16];
 #pragma unroll
@@ -366,24 +422,20 @@ __device__ __forceinline__ void window_half(const kvlinc_cache& c, const half_t*
       const int blk = 16 * half + bq;
       vx[ch][bq] = blk < n_blocks ? vbase[(long long)blk * kHeadDim + 64 * ch + lane] : make_uint2(0, 0);
     }
-  update_reference<NB>(sc, st);
   half4_t A2[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     float p[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-      p[h] = __builtin_amdgcn_exp2f(sc[nb][0][h] - st.m[nb][h]);
-      st.l[nb][h] += p[h];
+      st.m[nb][h] = wave_allmax(sc[nb][h]);  // finite: the caller passes a half that holds a token
+      p[h] = __builtin_amdgcn_exp2f(sc[nb][h] - st.m[nb][h]);
+      st.l[nb][h] = p[h];
     }
     const half2_t x01 = {(half_t)p[0], (half_t)p[1]}, x23 = {(half_t)p[2], (half_t)p[3]};
-    const uint32_t X = as_u32(x01), Y = as_u32(x23);
-    const uint32_t TX = dpp_u<kQuadSwap1>(X), TY = dpp_u<kQuadSwap1>(Y);
-    const uint32_t X1 = __builtin_amdgcn_perm(TX, X, lc.perm_sel);
-    const uint32_t Y1 = __builtin_amdgcn_perm(TY, Y, lc.perm_sel);
-    const uint32_t X2 = dpp_u<kQuadSwap2>(X1), Y2 = dpp_u<kQuadSwap2>(Y1);
-    const bool upper = (lane & 2) != 0;
-    A2[nb] = as_h4(upper ? Y2 : X1, upper ? Y1 : X2);
+    // 4x4 transpose inside each lane quad: (lane = token, slots = heads) -> (lane = head, slots = tokens)
+    A2[nb] = quad_transpose(as_u32(x01), as_u32(x23), perm_sel, lane);
+    st.accw[nb][0] = st.accw[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
   for (int bq = 0; bq < 16; ++bq)
@@ -629,18 +681,6 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 // ---- launch 1 -------------------------------------------------------------------------------------------------------
 
 
-
-#ifdef KVLINC_TUNING  // sweep builds only: wall-clock stamps per wave
-__device__ long long g_dbg_ts[1 << 18];
-#define DBG_TS(slot)                                                                              \
-  do {                                                                                            \
-    if ((threadIdx.x & 63) == 0 && (blockIdx.x + 1) * kWaves <= (1 << 14))  /* 2^18 / 16 stamp rows */ \
-      g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + (slot)] = wall_clock64(); \
-  } while (0)
-#else
-#define DBG_TS(slot)
-#endif
-
 __device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr,
                                            int max_splits, int n_splits, int row, int lane,
                                            half_t* __restrict__ out) {
@@ -691,6 +731,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
                                                                    half_t* __restrict__ out, int max_splits,
                                                                    int avg_splits, int gq, int corr_first) {
   __shared__ __align__(16) float lds[2 * kWaves * NB * 4 + kWaves * NB * 4 * kHeadDim];
+  __shared__ __align__(16) uint32_t ex[kWaves][2 * kExWords];  // per wave: operand hand-over of q K^T and of E V
   __shared__ int sFlag;
 
   const int tid = threadIdx.x;
@@ -698,13 +739,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the schedule in scalar registers
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const int n_parts = corr != nullptr ? kCorrParts : 0;
-  DBG_TS(0);
-#ifdef KVLINC_TUNING
-  if ((threadIdx.x & 63) == 0 && (blockIdx.x + 1) * kWaves <= (1 << 14)) {
-    const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4), xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20);
-    g_dbg_ts[((long long)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 15] = ((long long)xcc << 32) | hw;
-  }
-#endif
 
   const int n_stream = gridDim.x - n_corr;
   // corr_first = 0: the correction workgroups come last; L >= 1: they lead each of the first L runs of 256
@@ -743,7 +777,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     // A sequence without quantized tokens has S = P = 0 (the states only change at a flush), so its parts come out
     // as zero without looking at n_quant.
     correction_workgroup(c, q, corr, gq, g, r, b_first, n_seq, NB, lane, wave, lds);
-    DBG_TS(5);
     // count this workgroup in at each of its sequences; merge those it completes
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -761,7 +794,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
         if (tid == 0) c.split_done[bh] = 0;
       }
     }
-    DBG_TS(7);
     return;
   }
 
@@ -807,14 +839,14 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   // The first record is requested before the sequence length is known (any group index below the capacity is
   // readable memory); what it holds is used only if the group exists.
   const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
+  const Roles lr = make_roles(lane, ex[wave]);
   KeyRegs kr;
   ValueRegs vr;
   if (sp < avg_splits) {
     const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
-    load_keys(kr, rec0 + first * kRecordWords, lane);
-    load_values(vr, rec0 + first * kRecordWords, lane);
+    load_keys(kr, rec0 + first * kRecordWords, lr);
+    load_values(vr, rec0 + first * kRecordWords, lr);
   }
-  DBG_TS(1);
   const int nq = c.n_quant[b];
   const int nr = c.n_res[b];
   const int count = (nq + kGroup - 1) / kGroup;
@@ -825,101 +857,93 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       n_splits = mine;
       plan();
       const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
-      load_keys(kr, rec0 + first * kRecordWords, lane);
-      load_values(vr, rec0 + first * kRecordWords, lane);
+      load_keys(kr, rec0 + first * kRecordWords, lr);
+      load_values(vr, rec0 + first * kRecordWords, lr);
     }
   }
   const int expected = n_splits + n_parts;
 
-  // per-lane constants
-  const int quad = lane >> 2, hrow = lane & 3;
-  const int j0 = 2 * (quad & 3), j1 = j0 + 1;  // pairs feeding this quad's k slots (0,1) and (2,3)
-  const float gain0 = pair_gain(j0), gain1 = pair_gain(j1);
-  LaneConst lc;
-  lc.inv_gain0 = 1.0f / gain0;
-  lc.inv_gain1 = 1.0f / gain1;
-  lc.vgain = pair_gain(2 * ((lane >> 2) & 3) + ((lane >> 1) & 1));
-  lc.perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
-  lc.lane = lane;
+  // the spare term row of every head reads as zero from here on (this wave's own regions: no barrier needed)
+  for (int i = lane; i < 2 * 4 * 32; i += 64) ex[wave][(i >> 7) * kExWords + ((i >> 5) & 3) * kExHead + 96 + (i & 31)] = 0u;
+  lds_order();
+
+  float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                    // [kWaves][NB*4]
+  float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);  // [kWaves][NB*4]
+  float (*sAcc)[NB * 4][kHeadDim] = reinterpret_cast<float (*)[NB * 4][kHeadDim]>(lds + 2 * kWaves * NB * 4);
 
   WaveState<NB> st;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
+    st.m[nb] = -INFINITY; st.l[nb] = 0.f; st.pz[nb] = 0.f;
 #pragma unroll
-    for (int h = 0; h < 4; ++h) { st.m[nb][h] = -INFINITY; st.l[nb][h] = 0.f; st.pz[nb][h] = 0.f; }
+    for (int n = 0; n < 8; ++n) st.acc[nb][n] = float4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  if (my_half >= 0 && nr > 64 * my_half) {
+    // this wave's half of the window first, then its results move to the row role: (lane = channel, registers = heads)
+    // -> (row = head, lane = channel % 16, register 3 of channel block n), through this wave's part of the combine buffer
+    WindowState<NB> ws;
+    window_half<NB>(c, q, bh, b, g, gq, my_half, nr, lane, ws);
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      st.accw[nb][hf] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) {
+      float lsum[4];
 #pragma unroll
-      for (int ch = 0; ch < 2; ++ch) st.acc[nb][hf][ch] = float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int h = 0; h < 4; ++h) {
+        lsum[h] = wave_allsum(ws.l[nb][h]);
+        sAcc[wave][nb * 4 + h][lane] = ws.accw[nb][0][h];
+        sAcc[wave][nb * 4 + h][64 + lane] = ws.accw[nb][1][h];
+      }
+      lds_order();
+#pragma unroll
+      for (int n = 0; n < 8; ++n) st.acc[nb][n][3] = sAcc[wave][nb * 4 + lr.hd][16 * n + lr.jd];
+      lds_order();
+      const float m_mine = lr.hd == 0 ? ws.m[nb][0] : lr.hd == 1 ? ws.m[nb][1] : lr.hd == 2 ? ws.m[nb][2] : ws.m[nb][3];
+      const float l_mine = lr.hd == 0 ? lsum[0] : lr.hd == 1 ? lsum[1] : lr.hd == 2 ? lsum[2] : lsum[3];
+      st.m[nb] = m_mine;
+      st.l[nb] = lr.jd == 0 ? l_mine : 0.f;
     }
   }
 
-  if (my_half >= 0 && nr > 64 * my_half) window_half<NB>(c, q, bh, b, g, gq, my_half, nr, lc, st);
-  DBG_TS(2);
-
   if (idx < count) {
-    // q of this lane's head (row hrow of each head block), channels 8*quad .. 8*quad+7, times the k-slot gains;
-    // heads beyond gq read as 0
-    uint32_t Qs[NB][4];
+    // q of the head this lane builds operands for (head 4 nb + ha), channels c0 .. c0 + 7, in the log2 domain; heads
+    // beyond gq read as 0
+    float qa[NB][8];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int h = nb * 4 + hrow;
+      const int h = nb * 4 + lr.ha;
       uint4 raw = make_uint4(0, 0, 0, 0);
-      if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + 8 * quad);
+      if (h < gq) raw = *reinterpret_cast<const uint4*>(q + ((long long)b * c.H_q + g * gq + h) * kHeadDim + lr.c0);
       const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const half_t gn = (half_t)(((i & 1) ? gain1 : gain0) * kQueryShift);
-        const half2_t g2 = {gn, gn};
-        Qs[nb][i] = as_u32(as_h2(r[i]) * g2);  // exact unless it leaves the fp16 range
-      }
+      for (int i = 0; i < 8; ++i) qa[nb][i] = (float)as_h2(r[i >> 1])[i & 1] * kAlpha;
     }
     // While a group is consumed the wave's next record is already requested: its key part right after the scores,
     // its value part right after E V.  Past the last group the current (cached) record is requested once more, so
     // that no branch joins between a request and its first use and the waits stay partial.
-#ifdef KVLINC_ITER_TS
-    int it = 0;
-#define ITER_TS(k) do { if (it >= 1 && it <= 2) DBG_TS(8 + 4 * (it - 1) + (k)); } while (0)
-#else
-#define ITER_TS(k)
-#endif
     while (idx < count) {
       const int nxt = group_of_round(++rd);
       const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
-      float4_t sc[NB][2];
-      ITER_TS(0);
-      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), Qs, lc, sc);
-      ITER_TS(1);
-      load_keys(kr, src, lane);
+      float sc[NB][8];
+      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), qa, lr, sc);
+      load_keys(kr, src, lr);
       update_reference<NB>(sc, st);
-      ITER_TS(2);
-      pv_phase<NB>(vr, sc, lc, st);
-      ITER_TS(3);
-      load_values(vr, src, lane);
+      pv_phase<NB>(vr, sc, lr, st);
+      load_values(vr, src, lr);
       idx = nxt;
-#ifdef KVLINC_ITER_TS
-      ++it;
-#endif
     }
   }
-  DBG_TS(3);
 
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
-  float (*sM)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds);                    // [kWaves][NB*4]
-  float (*sL)[NB * 4] = reinterpret_cast<float (*)[NB * 4]>(lds + kWaves * NB * 4);  // [kWaves][NB*4]
-  float (*sAcc)[NB * 4][kHeadDim] = reinterpret_cast<float (*)[NB * 4][kHeadDim]>(lds + 2 * kWaves * NB * 4);
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int nb = 0; nb < NB; ++nb) {
+    const float l = row_allsum(st.l[nb]);
+    const float pz = row_allsum(st.pz[nb]);
+    const int h = nb * 4 + lr.hd;
+    if (lr.jd == 0) { sM[wave][h] = st.m[nb]; sL[wave][h] = l; }
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const float l = wave_allsum(st.l[nb][h]);
-      const float pz = wave_allsum(st.pz[nb][h]);
-      if (lane == 0) { sM[wave][nb * 4 + h] = st.m[nb][h]; sL[wave][nb * 4 + h] = l; }
-      sAcc[wave][nb * 4 + h][lane] = (st.acc[nb][0][0][h] + st.acc[nb][1][0][h]) * kRawScale + pz + st.accw[nb][0][h];
-      sAcc[wave][nb * 4 + h][64 + lane] =
-          (st.acc[nb][0][1][h] + st.acc[nb][1][1][h]) * kRawScale + pz + st.accw[nb][1][h];
-    }
+    for (int n = 0; n < 8; ++n)
+      sAcc[wave][h][16 * n + lr.jd] = ((st.acc[nb][n][0] + st.acc[nb][n][1]) + (st.acc[nb][n][2] + st.acc[nb][n][3])) + pz;
+  }
   __syncthreads();
   for (int i = tid; i < gq * kHeadDim; i += kThreads) {
     const int h = i >> 7, ch = i & 127;
@@ -939,7 +963,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
     st_coherent(dst + 4 + ch, a);
   }
-  DBG_TS(6);
 
   // The workgroup that arrives last merges (Alg. 1 lines 13-15): it reads what the others wrote with coherent
   // loads.  No workgroup waits for another.
@@ -948,7 +971,6 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, out);
     if (tid == 0) c.split_done[bh] = 0;
   }
-  DBG_TS(7);
 }
 
 }  // namespace
@@ -976,15 +998,7 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
   if (s < 1) s = 1;
   // Head room for the longest sequences of a batch of unequal lengths (a single sequence has nobody to differ from).
   long long m = c.B > 1 ? 2 * s : s;
-#ifdef KVLINC_TUNING  // sweep builds only: override the split policy from the environment
-  if (const char* e = getenv("KVLINC_SPLITS")) { s = atoi(e); m = c.B > 1 ? 2 * s : s; }
-  if (const char* e = getenv("KVLINC_MAX_SPLITS")) m = atoi(e);
-  if (s < 1) s = 1;
-  if (s > 1024) s = 1024;
-  if (m > 1024) m = 1024;
-#else
   if (m > kMaxSplits) m = kMaxSplits;
-#endif
   if (m > most) m = most;
   if (m < s) m = s;
   // The correction workgroups are chains of dependent steps and go first in the grid, except when they alone would
@@ -1008,9 +1022,6 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
       corr_first = 2;
     }
   }
-#ifdef KVLINC_TUNING
-  if (const char* e = getenv("KVLINC_CORR_FIRST")) corr_first = atoi(e);
-#endif
   return DecodeSplits{(int)s, (int)m, corr_first};
 }
 
@@ -1046,8 +1057,3 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
 
 }  // namespace kvlinc
 
-#ifdef KVLINC_TUNING
-extern "C" int kvlinc_dbg_read(long long* dst, size_t n) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(kvlinc::g_dbg_ts), n * sizeof(long long));
-}
-#endif

@@ -189,7 +189,8 @@ def test_degenerate_inputs(kv):
     cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
     cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
     tl.check_cache_against_oracle(cache, K, V, lengths, [(1, 0), (2, 0)], Wk=Wk)
-    assert not cache.groups[2, 0, :2, :1024].any() and not cache.groups[2, 0, :2, 2048:2112].any()  # key codes, scales
+    # constant keys: every key code is 0 (stored as the bit pair 1,1: all-ones words) and every key scale is 0
+    assert (cache.groups[2, 0, :2, :1024] == -1).all() and not cache.groups[2, 0, :2, 2048:2112].any()
     q = tl.gen_q(14, B, H_q)
     out = cache.decode(tl.to_dev(q)).cpu().numpy()
     assert not out[0].any()  # no tokens -> zeros

@@ -5,24 +5,38 @@ import numpy as np
 from oracle import layout
 
 
-def _k_slot(t, c):
-    hf, l = divmod(t, 64)
-    for q in range(8):
-        for j in range(8):
-            for e in range(2):
-                if 8 * (4 * (q % 4) + j // 2) + 4 * (q // 4) + 2 * (j % 2) + e == c:
-                    return ((hf * 2 + q // 4) * 64 + l) * 4 + q % 4, 2 * j + 16 * e
+def _slot_of_position(n, j, k):
+    """Word index and code index p of contraction position k of row (n, j), by search over the header's statement:
+    word ((n // 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w, code p at k = 32 g + 16 w + 8 (p % 2) + p // 2."""
+    for g in range(4):
+        for w in range(2):
+            for p in range(16):
+                if 32 * g + 16 * w + 8 * (p % 2) + p // 2 == k:
+                    return ((n // 2) * 64 + j + 16 * g) * 4 + 2 * (n % 2) + w, p
     raise AssertionError
 
 
+def _code_at(word, p):
+    """The header's bit format: hi in bit 4 (p // 2) + 3 - p % 2, lo in bit 4 (p // 2) + 1 - p % 2; (hi, lo) = (1,1),
+    (1,0), (0,0), (0,1) for the codes 0, 1, 2, 3."""
+    hi = (int(word) >> (4 * (p // 2) + 3 - p % 2)) & 1
+    lo = (int(word) >> (4 * (p // 2) + 1 - p % 2)) & 1
+    return {(1, 1): 0, (1, 0): 1, (0, 0): 2, (0, 1): 3}[(hi, lo)]
+
+
+def _word_with(p, code):
+    hi, lo = {0: (1, 1), 1: (1, 0), 2: (0, 0), 3: (0, 1)}[code]
+    return (hi << (4 * (p // 2) + 3 - p % 2)) | (lo << (4 * (p // 2) + 1 - p % 2))
+
+
+def _k_slot(t, c):
+    return _slot_of_position(t // 16, t % 16, c)  # row = token, position = channel
+
+
 def _v_slot(t, c):
-    ch, l = divmod(c, 64)
-    hf = t // 64
-    for w in range(4):
-        for j in range(8):
-            for e in range(2):
-                if 64 * hf + 4 * (4 * w + j // 2) + 2 * (j % 2) + e == t:
-                    return ((hf * 2 + ch) * 64 + l) * 4 + w, 2 * j + 16 * e
+    for k in range(128):  # row = channel, position k holds token 16 (k % 8) + 4 ((k // 16) % 4) + 2 (k // 64) + (k // 8) % 2
+        if 16 * (k % 8) + 4 * ((k // 16) % 4) + 2 * (k // 64) + (k // 8) % 2 == t:
+            return _slot_of_position(c // 16, c % 16, k)
     raise AssertionError
 
 
@@ -37,30 +51,43 @@ def test_tiles_are_bijections_and_match_the_definition():
         seen = set()
         for t in range(0, 128, 7):
             for c in range(128):
-                w, s = slot(t, c)
-                assert (int(tile[w]) >> s) & 3 == codes[t, c]
-                seen.add((w, s))
+                w, p = slot(t, c)
+                assert _code_at(tile[w], p) == codes[t, c]
+                seen.add((w, p))
         assert len(seen) == len(range(0, 128, 7)) * 128
-        one = np.zeros((128, 128), dtype=np.int64)
-        one[70, 9] = 3
-        w, s = slot(70, 9)
-        t1 = pack(one)
-        assert t1[w] == 3 << s and np.count_nonzero(t1) == 1
+        # a tile of code 2 is all zero bits; one other code in it sets exactly its own bit pair
+        base = np.full((128, 128), 2, dtype=np.int64)
+        assert not pack(base).any()
+        base[70, 9] = 0
+        w, p = slot(70, 9)
+        t1 = pack(base)
+        assert t1[w] == _word_with(p, 0) and np.count_nonzero(t1) == 1
 
 
 def test_literal_corners():
-    one = np.zeros((128, 128), dtype=np.int64)
-    one[0, 1] = 1  # key: token 0, channel 1 -> word 0, second element of pair 0 -> bit 16
-    assert layout.pack_k_tile(one)[0] == 1 << 16
-    one[:] = 0
-    one[1, 0] = 2  # key: token 1 -> lane 1 -> word 4
-    assert layout.pack_k_tile(one)[4] == 2
-    one[:] = 0
-    one[1, 0] = 1  # value: channel 0, token 1 -> word 0, second element of pair 0
-    assert layout.pack_v_tile(one)[0] == 1 << 16
-    one[:] = 0
-    one[0, 64] = 3  # value: channel 64 = second channel half, lane 0 -> word (0*2+1)*64*4
-    assert layout.pack_v_tile(one)[256] == 3
+    """Hand-placed codes in a tile of code 2 (which is stored as zero bits)."""
+    def one(t, c, code):
+        a = np.full((128, 128), 2, dtype=np.int64)
+        a[t, c] = code
+        return a
+    # key: token 0 -> block 0, row 0; channel 1 = position 1 -> g 0, w 0, p 2 -> word 0, nibble 1, bits 7 (hi) and 5 (lo)
+    assert layout.pack_k_tile(one(0, 1, 0))[0] == (1 << 7) | (1 << 5)
+    assert layout.pack_k_tile(one(0, 1, 1))[0] == 1 << 7
+    assert layout.pack_k_tile(one(0, 1, 3))[0] == 1 << 5
+    # channel 8 -> p 1 of the same word: nibble 0, bits 2 (hi) and 0 (lo)
+    assert layout.pack_k_tile(one(0, 8, 0))[0] == (1 << 2) | 1
+    # key: token 1 -> row j = 1 -> word 4; p 0 -> bits 3 and 1
+    assert layout.pack_k_tile(one(1, 0, 1))[4] == 1 << 3
+    # key: token 16 -> block 1 (odd block: + 2); channel 16 -> w 1, p 0 -> word 3
+    assert layout.pack_k_tile(one(16, 16, 3))[3] == 1 << 1
+    # key: token 33 -> block 2, row 1; channel 40 -> g 1, w 0, p 1 -> word (64 + 1 + 16) * 4, bits 2 and 0
+    assert layout.pack_k_tile(one(33, 40, 1))[(64 + 17) * 4] == 1 << 2
+    # value: channel 0 -> block 0 row 0; token 16 = position 1 (k % 8 = 1) -> p 2 of word 0
+    assert layout.pack_v_tile(one(16, 0, 3))[0] == 1 << 5
+    # value: channel 64 -> block 4, row 0 -> words from 2 * 64 * 4; token 1 = position 8 -> p 1
+    assert layout.pack_v_tile(one(1, 64, 0))[512] == (1 << 2) | 1
+    # value: channel 17 -> block 1, row 1; token 2 = position 64 -> g 2 -> word (1 + 32) * 4 + 2, p 0
+    assert layout.pack_v_tile(one(2, 17, 1))[(1 + 32) * 4 + 2] == 1 << 3
 
 
 def test_state_tiles_are_a_bijection():
@@ -77,10 +104,10 @@ def test_state_tiles_are_a_bijection():
 
 def test_record_fields_sit_where_the_header_says():
     """include/kvlinc.h: a record is 2304 words -- key tile [0, 1024), value tile [1024, 2048), key scale [2048, 2112)
-    and key zero-point [2112, 2176) as fp16 pairs (channel 2i in the low half of word i), then one word per token with
-    the value scale in the low and the value zero-point in the high half."""
+    and key zero-point [2112, 2176) as fp16 pairs (channel 2i in the low half of word i), then one word per token
+    (token 16 n + j in word 2176 + 8 j + n) with the value scale in the low and the value zero-point in the high half."""
     z = lambda *shape: np.zeros(shape, dtype=np.float16)
-    codes0 = np.zeros((1, 128, 128), dtype=np.int64)
+    codes0 = np.full((1, 128, 128), 2, dtype=np.int64)  # code 2 is stored as zero bits
 
     def record(**fields):
         f = dict(k_codes=codes0, v_codes=codes0, k_scale=z(1, 128), k_zero=z(1, 128), v_scale=z(1, 128),
@@ -89,21 +116,25 @@ def test_record_fields_sit_where_the_header_says():
         return layout.pack_records(f["k_codes"], f["v_codes"], f["k_scale"], f["k_zero"], f["v_scale"], f["v_zero"])[0]
 
     one = codes0.copy()
-    one[0, 0, 0] = 3
+    one[0, 0, 0] = 3  # code 3 = bit pair (0, 1), p 0: lo in bit 1
     r = record(k_codes=one)
-    assert r.shape == (2304,) and r[0] == 3 and np.count_nonzero(r) == 1
+    assert r.shape == (2304,) and r[0] == 2 and np.count_nonzero(r) == 1
     r = record(v_codes=one)
-    assert r[1024] == 3 and np.count_nonzero(r) == 1
+    assert r[1024] == 2 and np.count_nonzero(r) == 1
     h = z(1, 128)
     h[0, 5] = 1.5  # fp16 0x3E00; channel 5 = high half of word 2
     r = record(k_scale=h)
     assert r[2048 + 2] == 0x3E00 << 16 and np.count_nonzero(r) == 1
     r = record(k_zero=h)
     assert r[2112 + 2] == 0x3E00 << 16 and np.count_nonzero(r) == 1
-    r = record(v_scale=h)
-    assert r[2176 + 5] == 0x3E00 and np.count_nonzero(r) == 1
+    r = record(v_scale=h)  # token 5 = 16 * 0 + 5 -> word 2176 + 8 * 5 + 0
+    assert r[2176 + 40] == 0x3E00 and np.count_nonzero(r) == 1
     r = record(v_zero=h)
-    assert r[2176 + 5] == 0x3E00 << 16 and np.count_nonzero(r) == 1
+    assert r[2176 + 40] == 0x3E00 << 16 and np.count_nonzero(r) == 1
+    h2 = z(1, 128)
+    h2[0, 35] = 1.5  # token 35 = 16 * 2 + 3 -> word 2176 + 8 * 3 + 2
+    r = record(v_scale=h2)
+    assert r[2176 + 26] == 0x3E00 and np.count_nonzero(r) == 1
     # and the whole record round-trips
     rng = np.random.default_rng(3)
     f = dict(k_codes=rng.integers(0, 4, size=(2, 128, 128)), v_codes=rng.integers(0, 4, size=(2, 128, 128)),

@@ -120,12 +120,20 @@ def test_the_unplanted_oracle_passes_the_same_pins():
 
 
 LAYOUT_CASES = [
-    ("key tile: channel halves exchanged", "_k_index_maps", "p = (c % 8) // 4", "p = 1 - (c % 8) // 4",
+    ("tile: odd and even codes of a word exchanged", "_position_maps", "p = 2 * (k % 8) + (k % 16) // 8",
+     "p = 2 * (k % 8) + 1 - (k % 16) // 8", [pl.test_tiles_are_bijections_and_match_the_definition, pl.test_literal_corners]),
+    ("tile: the words of odd blocks before those of even blocks", "_position_maps", "2 * (n % 2) + w",
+     "2 * (1 - n % 2) + w", [pl.test_literal_corners]),
+    ("tile: quarters of the contraction axis 8 rows apart instead of 16", "_position_maps", "j + 16 * g", "j + 8 * g",
      [pl.test_tiles_are_bijections_and_match_the_definition]),
-    ("key tile: the pair's second element in the low half", "_k_index_maps", "shift = 2 * j + 16 * e",
-     "shift = 2 * j + 16 * (1 - e)", [pl.test_literal_corners]),
-    ("value tile: tokens of a word in plain order", "_v_index_maps", "j = 2 * (b % 4) + kk // 2",
-     "j = 2 * (b % 4) + kk % 2", [pl.test_tiles_are_bijections_and_match_the_definition]),
+    ("value tile: positions hold the tokens in plain order", "_value_token_of_position",
+     "return 16 * (k % 8) + 4 * ((k // 16) % 4) + 2 * (k // 64) + (k // 8) % 2", "return k",
+     [pl.test_tiles_are_bijections_and_match_the_definition]),
+    ("value tile: rows are tokens instead of channels", "_v_index_maps",
+     "word[tok[None, :], np.arange(128)[:, None]] = word_rk", "word[np.arange(128)[:, None], tok[None, :]] = word_rk",
+     [pl.test_tiles_are_bijections_and_match_the_definition]),
+    ("record: value scales and zero-points in plain token order", "pack_records",
+     "rec[:, 2176:2304][:, _SZ_WORD] = ", "rec[:, 2176:2304] = ", [pl.test_record_fields_sit_where_the_header_says]),
     ("value window: token and channel exchanged inside a block", "pack_value_window",
      "full.reshape(R // 4, 4, 128).transpose(0, 2, 1)", "full.reshape(R // 4, 128, 4)",
      [pl.test_value_window_order]),
@@ -139,15 +147,24 @@ LAYOUT_CASES = [
 def test_a_planted_layout_mistake_is_noticed(monkeypatch, case):
     _, name, old, new, pins = case
     _planted(monkeypatch, layout, name, old, new)
-    if name == "_k_index_maps":  # the maps are tabulated when the module is loaded
+    if name in ("_position_maps", "_value_token_of_position", "_v_index_maps"):  # tabulated when the module is loaded
         word, shift = layout._k_index_maps()
         monkeypatch.setattr(layout, "_K_WORD", word)
         monkeypatch.setattr(layout, "_K_SHIFT", shift)
-    if name == "_v_index_maps":
         word, shift = layout._v_index_maps()
         monkeypatch.setattr(layout, "_V_WORD", word)
         monkeypatch.setattr(layout, "_V_SHIFT", shift)
     _some_pin_fails(pins)
+
+
+def test_a_wrong_symbol_table_is_noticed(monkeypatch):
+    """The bit pairs of codes 0 and 1 exchanged (pack side), and of codes 2 and 3 (unpack side)."""
+    import numpy as np
+    monkeypatch.setattr(layout, "SYMBOL_OF_CODE", np.array([0b10, 0b11, 0b00, 0b01], dtype=np.uint32))
+    _some_pin_fails([pl.test_literal_corners])
+    monkeypatch.undo()
+    monkeypatch.setattr(layout, "CODE_OF_SYMBOL", np.array([3, 2, 1, 0], dtype=np.uint8))
+    _some_pin_fails([pl.test_tiles_are_bijections_and_match_the_definition])
 
 
 def test_layout_and_accounting_mistakes_are_noticed(monkeypatch):

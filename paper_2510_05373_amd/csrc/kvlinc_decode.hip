@@ -121,6 +121,16 @@ constexpr int kExHead = 160;              // words per head in an exchange regio
 constexpr int kExWords = 4 * kExHead;     // one region: 4 heads
 constexpr int kExExp = 128;               // word of the block exponent
 
+// B registers from packed words: nibble = hi|0|lo|1 = FP4 (code - 1.5).  One bit-field insert per register: the code bits of the word where `pick` has ones, the constant mantissa bit elsewhere.
+// `pick` is 0xAAAAAAAA held in a scalar register (see code_bits_mask) so that the insert is a single instruction.
+__device__ __forceinline__ uint32_t centred_nibbles(uint32_t w, uint32_t pick) {
+  return 0x11111111u ^ (pick & (w ^ 0x11111111u));  // = (w & pick) | (0x11111111 & ~pick), in the form that selects v_bfi_b32
+}
+__device__ __forceinline__ uint32_t code_bits_mask() {
+  uint32_t m = 0xAAAAAAAAu;
+  asm volatile("" : "+s"(m));  // opaque to constant folding, so that the insert stays one instruction
+  return m;
+}
 struct Roles {
   int lane;
   int jd, hd;      // row role
@@ -131,6 +141,7 @@ struct Roles {
   int rd;          // where this lane reads its operand registers
   uint32_t* ex_qk;  // this wave's exchange regions
   uint32_t* ex_pv;
+  uint32_t pick;    // code_bits_mask()
 };
 
 __device__ __forceinline__ Roles make_roles(int lane, uint32_t* ex_wave) {
@@ -144,6 +155,7 @@ __device__ __forceinline__ Roles make_roles(int lane, uint32_t* ex_wave) {
   r.rd = kExHead * r.ha + 32 * r.ua + 8 * r.ga;
   r.ex_qk = ex_wave;
   r.ex_pv = ex_wave + kExWords;
+  r.pick = code_bits_mask();
   return r;
 }
 
@@ -190,10 +202,10 @@ __device__ __forceinline__ v8i_t get_operand(const uint32_t* ex, int at) {
   return v8i_t{(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
 }
 
-// D = A B + C with B = 32 centred codes per lane from two packed words: nibble = hi|0|lo|1 = FP4 (code - 1.5).
-__device__ __forceinline__ float4_t mfma_codes(v8i_t a, uint32_t w0, uint32_t w1, float4_t c, int scale_a) {
-  const v8i_t b = {(int)((w0 & 0xAAAAAAAAu) | 0x11111111u), (int)(((w0 << 1) & 0xAAAAAAAAu) | 0x11111111u),
-                   (int)((w1 & 0xAAAAAAAAu) | 0x11111111u), (int)(((w1 << 1) & 0xAAAAAAAAu) | 0x11111111u), 0, 0, 0, 0};
+// D = A B + C with B = 32 centred codes per lane from two packed words (see centred_nibbles).
+__device__ __forceinline__ float4_t mfma_codes(v8i_t a, uint32_t w0, uint32_t w1, float4_t c, int scale_a, uint32_t pick) {
+  const v8i_t b = {(int)centred_nibbles(w0, pick), (int)centred_nibbles(w0 << 1, pick), (int)centred_nibbles(w1, pick),
+                   (int)centred_nibbles(w1 << 1, pick), 0, 0, 0, 0};
   return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /* A: FP8 E4M3 */, 4 /* B: FP4 E2M1 */, 0, scale_a,
                                                          0, 127);
 }
@@ -238,10 +250,10 @@ struct WaveState {
 };
 
 // q K^T of one group for all heads (Alg. 1 line 7): scores in the log2 domain, sc[nb][n] = head 4 nb + hd, token 16 n + jd.
-// qa = this lane's 8 query values (head 4 nb + ha, channels c0 ..) times log2(e) / sqrt(d).
+// qa = this lane's 8 query values (head 4 nb + ha, channels c0 ..) times log2(e) / sqrt(d); qh = the same as binary16 pairs.
 template <int NB>
-__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const float (&qa)[NB][8], const Roles& lr,
-                                         float (&sc)[NB][8]) {
+__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const float (&qa)[NB][8], const uint32_t (&qh)[NB][4],
+                                         const Roles& lr, float (&sc)[NB][8]) {
   const uint32_t S[4] = {g.ks.x, g.ks.y, g.ks.z, g.ks.w};
   const uint32_t Z[4] = {g.kz.x, g.kz.y, g.kz.z, g.kz.w};
   v8i_t A[NB];
@@ -252,10 +264,16 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const floa
     float x[8], bz = 0.0f, mx = 0.0f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      x[i] = qa[nb][i] * (float)as_h2(S[i >> 1])[i & 1];
-      // sum_c q_c (z_c + 1.5 s_c): what the zero-points and the centring of the codes add to every score of the group
-      bz = fmaf(x[i], 1.5f, fmaf(qa[nb][i], (float)as_h2(Z[i >> 1])[i & 1], bz));
+      x[i] = fmaf(qa[nb][i], (float)as_h2(S[i >> 1])[i & 1], 0.0f);  // (the fused form reads the binary16 operand as it is)
       mx = fmaxf(mx, fabsf(x[i]));
+    }
+    // sum_c q_c (z_c + 1.5 s_c): what the zero-points and the centring of the codes add to every score of the group.
+    // Mid-points and query in binary16 pairs, products summed in binary32: the term is a common offset of the
+    // group's scores and small (keys are centred), its rounding (2^-12 of it) is of no account.
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const half2_t mid = as_h2(S[i]) * half2_t{(half_t)1.5f, (half_t)1.5f} + as_h2(Z[i]);
+      bz = __builtin_amdgcn_fdot2(as_h2(qh[nb][i]), mid, bz, false);
     }
     mx = xrow_allmax(quad_allmax(mx));  // over the 128 channels of the head
     bz = xrow_allsum(quad_allsum(bz));
@@ -279,7 +297,7 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const floa
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const float4_t d = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb]);
+        const float4_t d = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb], lr.pick);
         sc[nb][2 * m + hf] = (d[0] + d[1]) + d[2];
       }
   }
@@ -330,7 +348,7 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
       const float p = __builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]);
       const half2_t sz = as_h2(SZ[n]);
       st.l[nb] += p;
-      y[n] = p * (float)sz[0];  // p * value scale: the weight of the token's codes
+      y[n] = fmaf(p, (float)sz[0], 0.0f);  // p * value scale: the weight of the token's codes
       // sum_t p_t (z_t + 1.5 s_t): the zero-points and the centring of the codes, the same for every channel
       st.pz[nb] = fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb]));
       mx = fmaxf(mx, y[n]);
@@ -352,7 +370,7 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb]);
+        st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick);
   }
 }
 
@@ -908,6 +926,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     // q of the head this lane builds operands for (head 4 nb + ha), channels c0 .. c0 + 7, in the log2 domain; heads
     // beyond gq read as 0
     float qa[NB][8];
+    uint32_t qh[NB][4];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int h = nb * 4 + lr.ha;
@@ -916,6 +935,8 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int i = 0; i < 8; ++i) qa[nb][i] = (float)as_h2(r[i >> 1])[i & 1] * kAlpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) qh[nb][i] = as_u32(half2_t{(half_t)qa[nb][2 * i], (half_t)qa[nb][2 * i + 1]});
     }
     // While a group is consumed the wave's next record is already requested: its key part right after the scores,
     // its value part right after E V.  Past the last group the current (cached) record is requested once more, so
@@ -924,7 +945,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       const int nxt = group_of_round(++rd);
       const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
       float sc[NB][8];
-      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), qa, lr, sc);
+      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), qa, qh, lr, sc);
       load_keys(kr, src, lr);
       update_reference<NB>(sc, st);
       pv_phase<NB>(vr, sc, lr, st);

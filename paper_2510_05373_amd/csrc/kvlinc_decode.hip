@@ -65,7 +65,8 @@ __device__ __forceinline__ uint32_t as_bits(float v) { return __builtin_bit_cast
 
 // Reductions with the result in every participating lane.  row: the 16 lanes of a DPP row; quad: 4 adjacent lanes;
 // xrow: the 4 lanes l, l ^ 16, l ^ 32, l ^ 48 (row swaps: odd rows of one copy against even rows of the other, then
-// the upper 32 lanes of one against the lower 32 of the other).
+// the upper 32 lanes of one against the lower 32 of the other).  The *_umax forms take bit patterns of non-negative
+// numbers, which order like the numbers themselves (one instruction per step, no NaN handling).
 __device__ __forceinline__ float row_allmax(float v) {
   v = fmaxf(v, dpp_f<kRowRor1>(v));
   v = fmaxf(v, dpp_f<kRowRor2>(v));
@@ -78,19 +79,25 @@ __device__ __forceinline__ float row_allsum(float v) {
   v += dpp_f<kRowRor4>(v);
   return v + dpp_f<kRowRor8>(v);
 }
-__device__ __forceinline__ float quad_allmax(float v) {
-  v = fmaxf(v, dpp_f<kQuadSwap1>(v));
-  return fmaxf(v, dpp_f<kQuadSwap2>(v));
+__device__ __forceinline__ uint32_t row_umax(uint32_t v) {
+  v = max(v, dpp_u<kRowRor1>(v));
+  v = max(v, dpp_u<kRowRor2>(v));
+  v = max(v, dpp_u<kRowRor4>(v));
+  return max(v, dpp_u<kRowRor8>(v));
+}
+__device__ __forceinline__ uint32_t quad_umax(uint32_t v) {
+  v = max(v, dpp_u<kQuadSwap1>(v));
+  return max(v, dpp_u<kQuadSwap2>(v));
 }
 __device__ __forceinline__ float quad_allsum(float v) {
   v += dpp_f<kQuadSwap1>(v);
   return v + dpp_f<kQuadSwap2>(v);
 }
-__device__ __forceinline__ float xrow_allmax(float v) {
-  auto a = __builtin_amdgcn_permlane16_swap(as_bits(v), as_bits(v), false, false);
-  v = fmaxf(as_f32(a[0]), as_f32(a[1]));
-  auto b = __builtin_amdgcn_permlane32_swap(as_bits(v), as_bits(v), false, false);
-  return fmaxf(as_f32(b[0]), as_f32(b[1]));
+__device__ __forceinline__ uint32_t xrow_umax(uint32_t v) {
+  auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  v = max(a[0], a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return max(b[0], b[1]);
 }
 __device__ __forceinline__ float xrow_allsum(float v) {
   auto a = __builtin_amdgcn_permlane16_swap(as_bits(v), as_bits(v), false, false);
@@ -171,7 +178,7 @@ __device__ __forceinline__ void split_fp8x3(const float (&x)[8], uint32_t sc_bit
     const float sc = as_f32(sc_bits - ((uint32_t)(4 * k) << 23));
 #pragma unroll
     for (int v = 0; v < 2; ++v) {
-      short2_t w = {0, 0};
+      short2_t w = __builtin_bit_cast(short2_t, r[4 * v]);  // any register: both halves are written below
       w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, r[4 * v], r[4 * v + 1], sc, false);
       w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, r[4 * v + 2], r[4 * v + 3], sc, true);
       const uint32_t bits = __builtin_bit_cast(uint32_t, w);
@@ -186,9 +193,10 @@ __device__ __forceinline__ void split_fp8x3(const float (&x)[8], uint32_t sc_bit
   }
 }
 
-// Biased binary32 exponent eb of the largest magnitude mx of a block (kept away from the ends of the range), for
-// sc = 2^(eb - 127 - 7): |x| / sc < 256, inside FP8's range.  Row `term` then carries the block scale byte eb - 7 - 4 term.
-__device__ __forceinline__ uint32_t block_exponent(float mx) { return as_bits(fmaxf(mx, 0x1p-100f)) >> 23; }
+// Biased binary32 exponent eb of the largest magnitude of a block, from its bit pattern (kept away from the low end of
+// the range), for sc = 2^(eb - 127 - 7): |x| / sc < 256, inside FP8's range.  Row `term` then carries the block scale
+// byte eb - 7 - 4 term.
+__device__ __forceinline__ uint32_t block_exponent(uint32_t mx_bits) { return max(mx_bits, as_bits(0x1p-100f)) >> 23; }
 __device__ __forceinline__ uint32_t block_scale_bits(uint32_t eb) { return (eb - 7u) << 23; }
 
 // Builder side of the hand-over: the three terms of this lane's chunk; holder side: the 8 operand registers.
@@ -275,9 +283,8 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const floa
       const half2_t mid = as_h2(S[i]) * half2_t{(half_t)1.5f, (half_t)1.5f} + as_h2(Z[i]);
       bz = __builtin_amdgcn_fdot2(as_h2(qh[nb][i]), mid, bz, false);
     }
-    mx = xrow_allmax(quad_allmax(mx));  // over the 128 channels of the head
+    const uint32_t eb = block_exponent(xrow_umax(quad_umax(as_bits(mx))));  // over the 128 channels of the head
     bz = xrow_allsum(quad_allsum(bz));
-    const uint32_t eb = block_exponent(mx);
     uint32_t t[3][2];
     split_fp8x3(x, block_scale_bits(eb), t);
     put_terms(lr.ex_qk, lr.wq, t);
@@ -353,7 +360,7 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
       st.pz[nb] = fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb]));
       mx = fmaxf(mx, y[n]);
     }
-    const uint32_t eb = block_exponent(row_allmax(mx));  // over the 128 tokens of the head
+    const uint32_t eb = block_exponent(row_umax(as_bits(mx)));  // over the 128 tokens of the head
     uint32_t t[3][2];
     split_fp8x3(y, block_scale_bits(eb), t);
     put_terms(lr.ex_pv, lr.wp, t);

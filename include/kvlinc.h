@@ -19,7 +19,14 @@
  *   - kvlinc_half is the bit pattern of an IEEE binary16 number.
  *   - Return value: 0 = enqueued; negative = rejected before any launch, nothing was touched.
  *   - Faults only the device can see (capacity exhausted, non-finite input, append to a cache whose
- *     last group is partial) set bits in *status and leave that sequence unchanged.
+ *     last group is partial) set bits in *status and leave that sequence unchanged: its counters, its live group
+ *     records and window rows, and its states S, P, S16 (in all KV heads) are bit for bit what they were.  Storage
+ *     beyond the counters (group records from n_quant / 128 on, window slots from n_res on) is dead and may have
+ *     been overwritten; a non-finite value is never stored into the window.
+ *   - Magnitudes: the operands of the matrix products carry a block exponent per group and query head, so keys,
+ *     queries and values of any finite binary16 magnitude keep the tolerance.  What can leave its range is the
+ *     16-bit copy of the state: an entry of S beyond +-65504 is stored saturated and reported as
+ *     KVLINC_ST_STATE_RANGE (S grows with the context when the rotated values have a common sign).
  *   - Query head h reads KV head h / (H_q / H_kv).  The softmax scale is 1/sqrt(d) (Eq. 3).
  *
  * Cache layout (per sequence b, KV head g; "group" = 128 consecutive tokens from token 0):
@@ -91,7 +98,8 @@ enum {
 enum {
   KVLINC_ST_CAPACITY = 1,  /* a sequence would need more than max_groups groups */
   KVLINC_ST_NONFINITE = 2, /* a key or rotated value that was quantized is Inf or NaN */
-  KVLINC_ST_STATIC = 4     /* append to a sequence whose last group is partial, or an unsupported keep_residual */
+  KVLINC_ST_STATIC = 4,    /* append to a sequence whose last group is partial, or an unsupported keep_residual */
+  KVLINC_ST_STATE_RANGE = 8 /* an entry of S left the binary16 range: S16 holds +-65504 there, the correction is off */
 };
 
 typedef struct kvlinc_cache {
@@ -141,8 +149,10 @@ int kvlinc_cache_validate(const kvlinc_cache* cache);
  *
  * Per flushed group: key scale / zero-point / codes per channel, value scale / zero-point / codes per token
  * of the rotated value, S += phi_k(K - K_q)^T V_q and P += sum phi_k(K - K_q) when the adapters are given.
- * New tokens that stay in the window are stored as raw key and rotated fp16 value.  One kernel launch: the
- * workgroup of a sequence that finishes last updates n_quant / n_res, after all of them have read the old values.
+ * New tokens that stay in the window are stored as raw key and rotated fp16 value.  One kernel launch (a bulk
+ * append, T > 1, to a cache with more than one KV head is preceded by a short launch that looks for non-finite
+ * input): the workgroup of a sequence that finishes last updates n_quant / n_res, after all of them have read the
+ * old values, and only if none of them found a fault.
  */
 int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, const kvlinc_half* v_new,
                            const int32_t* n_new, int32_t T, int32_t keep_residual, void* stream);

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(HERE, "libkvlinc.so")
 
 KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP = 0, -1, -2, -3
-KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC = 1, 2, 4
+KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC, KVLINC_ST_STATE_RANGE = 1, 2, 4, 8
 
 
 class KVLincError(RuntimeError):

@@ -125,24 +125,59 @@ __device__ inline uint32_t q2_code(float x, const Q2& p) {
 }
 
 // The counters of a sequence change only after every workgroup of that sequence (one per kv head) has read them:
-// each workgroup counts itself in when it is done, and the one that completes the count writes n_quant / n_res (or
-// the error bit) and leaves the counter at zero.  The counter is the sequence's first split_done entry, which the
-// decode kernel uses in the same way and also leaves at zero.
-__device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan) {
+// each workgroup counts itself in when it is done -- with a vote in the upper half of the counter if it found a
+// fault -- and the one that completes the count writes n_quant / n_res unless somebody voted against, and leaves the
+// counter (and the sequence's fault flag of the scan launch, see below) at zero.  The counter is the sequence's first
+// split_done entry, which the decode kernel uses in the same way and also leaves at zero.
+constexpr int kFaultVote = 1 << 16;
+__device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan, int err) {
   __syncthreads();
   if (threadIdx.x == 0) {
     int* counter = c.split_done + (long long)b * c.H_kv;
-    const int before = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    if (before == c.H_kv - 1) {
-      if (plan.err) {
-        atomicOr(c.status, plan.err);
-      } else if (n > 0) {
+    if (err) atomicOr(c.status, err);
+    const int before = __hip_atomic_fetch_add(counter, err ? 1 + kFaultVote : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if ((before & (kFaultVote - 1)) == c.H_kv - 1) {
+      if (err == 0 && before < kFaultVote && n > 0) {
         c.n_quant[b] = nq + plan.n_flush;
         c.n_res[b] = plan.new_res;
       }
       *counter = 0;
+      if (c.H_kv > 1) counter[1] = 0;
     }
   }
+}
+
+// Non-finite input is refused before anything of the sequence is stored (the window never holds a non-finite value,
+// so only the new tokens need a look): a raw key, or a rotated value after its rounding to fp16, that is Inf or NaN.
+// One wave, one row: lane l looks at elements 2 l and 2 l + 1.
+__device__ inline bool row_is_bad(const half_t* __restrict__ k_row, const half_t* __restrict__ v_row, int lane) {
+  const uint32_t kk = *reinterpret_cast<const uint32_t*>(k_row + 2 * lane);
+  bool bad = ((kk & 0x7C00u) == 0x7C00u) || ((kk & 0x7C000000u) == 0x7C000000u);
+  float x0 = (float)v_row[2 * lane], x1 = (float)v_row[2 * lane + 1];
+  fwht128_wave(x0, x1, lane);
+  return bad || nonfinite_bits((half_t)x0) || nonfinite_bits((half_t)x1);
+}
+
+// Scan launch of a bulk append (T > 1) to a cache with more than one kv head: every new row of every (sequence, kv
+// head) is looked at once, and a fault raises the sequence's flag -- its second split_done entry -- so that ALL the
+// workgroups of that sequence in the append launch that follows refuse the append, whichever head the fault is in.
+// (With one kv head per sequence the append workgroup is alone and needs no flag; a one-token append looks at the
+// new rows of all heads itself.)  Grid: (B H_kv, chunks of kScanRows rows).
+constexpr int kScanRows = 256;
+__global__ __launch_bounds__(kThreads) void append_scan_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
+                                                                const half_t* __restrict__ v_new,
+                                                                const int32_t* __restrict__ n_new, int T) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.x / c.H_kv;
+  int n = n_new ? n_new[b] : T;
+  n = n < 0 ? 0 : (n > T ? T : n);
+  const int first = blockIdx.y * kScanRows, last = min(n, first + kScanRows);
+  const half_t* k_src = k_new + (long long)blockIdx.x * T * kHeadDim;
+  const half_t* v_src = v_new + (long long)blockIdx.x * T * kHeadDim;
+  bool bad = false;
+  for (int t = first + wave; t < last; t += kThreads / 64)
+    bad |= row_is_bad(k_src + (long long)t * kHeadDim, v_src + (long long)t * kHeadDim, lane);
+  if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(c.split_done + (long long)b * c.H_kv + 1, 1);
 }
 
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
@@ -164,8 +199,32 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   n = n < 0 ? 0 : (n > T ? T : n);
   const AppendPlan plan = plan_append(nq, nr, n, c.R, keep, c.max_groups);
   if (plan.err || n == 0) {
-    commit_sequence(c, b, nq, n, plan);
+    commit_sequence(c, b, nq, n, plan, plan.err);
     return;
+  }
+  {
+    // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
+    bool refuse = false;
+    if (T == 1) {  // the one new row of every kv head of this sequence
+      for (int g2 = wave; g2 < c.H_kv; g2 += kThreads / 64) {
+        const long long row = ((long long)b * c.H_kv + g2) * kHeadDim;
+        refuse |= row_is_bad(k_new + row, v_new + row, lane);
+      }
+    } else if (c.H_kv > 1) {
+      refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
+    } else {
+      // bulk append, one kv head: this workgroup is the sequence's only one.  The new rows that will stay in the
+      // window (at most R) are looked at here; those that get quantized are looked at when their group is staged,
+      // before anything but dead storage has been written.
+      const half_t* ks = k_new + (long long)b * T * kHeadDim;
+      const half_t* vs = v_new + (long long)b * T * kHeadDim;
+      for (int u = max(plan.n_flush, nr) + wave; u < nr + n; u += kThreads / 64)
+        refuse |= row_is_bad(ks + (long long)(u - nr) * kHeadDim, vs + (long long)(u - nr) * kHeadDim, lane);
+    }
+    if (__syncthreads_or(refuse)) {
+      commit_sequence(c, b, nq, n, plan, KVLINC_ST_NONFINITE);
+      return;
+    }
   }
 
   const half_t* k_res = reinterpret_cast<const half_t*>(c.k_res) + bh * c.R * kHeadDim;
@@ -472,24 +531,35 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     __syncthreads();
   }
 
+  // A fault seen only now (one kv head per sequence in a bulk append: this workgroup is the sequence's only one) leaves
+  // states, window and counters as they were; the records written above lie beyond n_quant and are dead storage.
+  if (__syncthreads_or(bad)) {
+    commit_sequence(c, b, nq, n, plan, KVLINC_ST_NONFINITE);
+    return;
+  }
   if (states_live) {
     // fp32 master copy, row-major, and the binary16 tile copy for the decode kernel: tile (64-feature block = wave,
     // channel half hh, feature step fb) holds S[64 wave + 4 fb + k][64 hh + l] at [l][k] -- exactly one accumulator.
+    // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
     half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
+    bool out_of_range = false;
 #pragma unroll
     for (int fb = 0; fb < 16; ++fb)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
+        half4_t t16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = sacc[fb][hh][i];
-        const half4_t t16 = {(half_t)sacc[fb][hh][0], (half_t)sacc[fb][hh][1], (half_t)sacc[fb][hh][2],
-                             (half_t)sacc[fb][hh][3]};
+        for (int i = 0; i < 4; ++i) {
+          const float v = sacc[fb][hh][i];
+          c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = v;
+          out_of_range |= !(fabsf(v) <= 65504.0f);
+          t16[i] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+        }
         *reinterpret_cast<half4_t*>(tiles + (((wave * 2 + hh) * 16 + fb) * 64 + lane) * 4) = t16;
       }
     c.P[bh * kRank + tid] = P_f;
+    if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 && lane == 0) atomicOr(c.status, KVLINC_ST_STATE_RANGE);
   }
-  if (bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
 
   // ---- 5. new tokens that stay in the window: raw key, rotated value ----------------------------------------
   // Stream index u >= n_flush goes to slot u - n_flush.  Old window tokens either all left (n_flush >= nr) or
@@ -508,7 +578,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = (half_t)x0;
     v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = (half_t)x1;
   }
-  commit_sequence(c, b, nq, n, plan);
+  commit_sequence(c, b, nq, n, plan, 0);
 }
 
 }  // namespace
@@ -516,13 +586,13 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
 int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_half* v_new, const int32_t* n_new,
                   int T, int keep, hipStream_t stream) {
   static_assert(sizeof(Lds) <= 160 * 1024, "LDS budget of one CU");
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(append_flush_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds)) != hipSuccess)
-      return KVLINC_EHIP;
-    attr_set = true;
-  }
+  // per device and cheap: set on every call rather than remembered in process state
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(append_flush_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)sizeof(Lds)) != hipSuccess)
+    return KVLINC_EHIP;
+  if (T > 1 && c.H_kv > 1)
+    hipLaunchKernelGGL(append_scan_kernel, dim3(c.B * c.H_kv, (T + kScanRows - 1) / kScanRows), dim3(kThreads), 0, stream, c,
+                       reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T);
   hipLaunchKernelGGL(append_flush_kernel, dim3(c.B * c.H_kv), dim3(kThreads), sizeof(Lds), stream, c,
                      reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;

@@ -8,8 +8,17 @@ from oracle import kvcache as o_cache
 from oracle import layout as o_layout
 
 OUT_MAX_ABS = 1e-2   # attention output tolerance (fp16 I/O, fp32 accumulate)
-OUT_REL_L2 = 2e-3
+OUT_REL_L2 = 2e-3    # over all compared rows, and for every single row
 STATE_REL_L2 = 1e-4  # S, P: fp32 accumulation of up to ~1e5 products against fp64
+# Element-wise bounds on the states, relative to the largest magnitude of the tensor.  phi_k is a binary32 softmax of
+# binary32 logits whose products are exact (relative error of an entry ~ 1e-6, from the fast exponential), the values
+# are exact, and the sums run in binary32 in flush order: an element of S = sum_t phi[t][f] v[t][c] (terms of both
+# signs, |S| ~ sqrt(n) |phi v|) is off by at most ~ 1e-6 sum_t |phi v| ~ 1e-6 sqrt(n) |S| if the errors of phi all
+# pointed one way, i.e. 4e-4 |S| at n = 131072; they do not: measured 4e-6 .. 1.2e-5 of max |S| for n = 1280 .. 131072.
+# P = sum_t phi[t][f] has terms of one sign: the relative error of its terms plus binary32 summation, measured
+# 1.4e-6 .. 1.1e-5 of max |P|.  The bounds leave a factor of 4 to 8 over the worst measured value.
+STATE_S_ELEMENT = 1e-4
+STATE_P_ELEMENT = 5e-5
 
 
 def gen_kv(config, B, H_kv, lengths):
@@ -46,6 +55,38 @@ def check_counters(cache, lengths, keep=None):
     return n_quant, n_res
 
 
+def _ordered16(h16):
+    """fp16 bit patterns as integers that order like the numbers (for distances in units in the last place)."""
+    u = np.ascontiguousarray(h16, dtype=np.float16).view(np.uint16).astype(np.int32)
+    return np.where(u & 0x8000, -(u & 0x7FFF), u)
+
+
+def check_states_against(cache, b, g, S_ref, P_ref, quiet=False):
+    """S, P of one (sequence, kv head) against the oracle's (fp64): by norm, element by element, and the binary16 tile
+    copy against binary16 of the ORACLE's S -- equal up to one unit in the last place (the rounding of a value that
+    differs in its last binary32 bits), or inside the element-wise bound where |S| is small against the tensor's
+    largest entries."""
+    S = cache.S[b, g].cpu().numpy().astype(np.float64)
+    P = cache.P[b, g].cpu().numpy().astype(np.float64)
+    for got, want, nm in ((S, S_ref, "S"), (P, P_ref, "P")):
+        den = np.linalg.norm(want)
+        err = np.linalg.norm(got - want)
+        assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
+    s_max, p_max = np.abs(S_ref).max(), np.abs(P_ref).max()
+    s_err, p_err = np.abs(S - S_ref).max(), np.abs(P - P_ref).max()
+    assert s_err <= STATE_S_ELEMENT * s_max + 1e-12, ("S element", b, g, s_err, s_max)
+    assert p_err <= STATE_P_ELEMENT * p_max + 1e-12, ("P element", b, g, p_err, p_max)
+    S16 = o_layout.unpack_state_tiles(cache.S16[b, g].cpu().numpy())
+    ulps = np.abs(_ordered16(S16) - _ordered16(S_ref.astype(np.float16)))
+    near = np.abs(S16.astype(np.float64) - S_ref) <= STATE_S_ELEMENT * s_max
+    assert np.isfinite(S16.astype(np.float32)).all()
+    assert ((ulps <= 1) | near).all(), ("S16", b, g, int(ulps.max()))
+    if not quiet:
+        print("  [states] (%d, %d) S elem err %.2e of max, P elem err %.2e of max, S16 != fp16(oracle S) at %d of %d entries"
+              % (b, g, s_err / max(s_max, 1e-300), p_err / max(p_max, 1e-300), int((ulps != 0).sum()), ulps.size))
+    return s_err / max(s_max, 1e-300), p_err / max(p_max, 1e-300)
+
+
 def check_pair_against_oracle(cache, b, g, k_rows, v_rows, nq, nr, Wk_g=None, check_states=True):
     """Bit-exact comparison of everything the append path stores for one (sequence, kv head) whose token history is
     k_rows, v_rows [n, 128]; returns the oracle's cache."""
@@ -66,16 +107,7 @@ def check_pair_against_oracle(cache, b, g, k_rows, v_rows, nq, nr, Wk_g=None, ch
     v_win = o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
     assert np.array_equal(u16(v_win), u16(ref["v_res"])), ("v_res", b, g)
     if Wk_g is not None and check_states:
-        S = cache.S[b, g].cpu().numpy().astype(np.float64)
-        P = cache.P[b, g].cpu().numpy().astype(np.float64)
-        for got, want, nm in ((S, ref["S"], "S"), (P, ref["P"], "P")):
-            den = np.linalg.norm(want)
-            err = np.linalg.norm(got - want)
-            assert err <= STATE_REL_L2 * den + 1e-12, (nm, b, g, err, den)
-        # the binary16 tile copy the decode step reads: the fp32 state (checked above) rounded to nearest, in the
-        # documented tile order
-        S16 = o_layout.unpack_state_tiles(cache.S16[b, g].cpu().numpy())
-        assert np.array_equal(u16(S16), u16(cache.S[b, g].cpu().numpy().astype(np.float16))), ("S16", b, g)
+        check_states_against(cache, b, g, ref["S"], ref["P"])
     return ref
 
 
@@ -111,4 +143,5 @@ def check_outputs(got, want):
     print("  [parity] rows %d max_abs %.3e rel_l2 %.3e worst_row_rel_l2 %.3e" % (len(w), max_abs, rel_l2, worst_row))
     assert max_abs <= OUT_MAX_ABS, ("max abs", max_abs)
     assert rel_l2 <= OUT_REL_L2, ("rel l2", rel_l2, "worst row", worst_row)
+    assert worst_row <= OUT_REL_L2, ("worst row rel l2", worst_row)
     return max_abs, rel_l2, worst_row

@@ -1,13 +1,22 @@
 """GPU parity at the full workload sizes, in the launch configuration the benchmark uses (bulk-built cache, decode with
-max_context = the batch's longest context).  The oracle cannot replay a whole batch at these sizes, so a few seeded
-(sequence, KV head) pairs carry the workload's seeded inputs and are compared element by element (records bit for bit,
-outputs within tolerance); every other pair is filled with device-generated N(0, 1) data so that the launch has its
-real shape."""
+max_context = the batch's longest context).
+
+Scope: workloads 2 and 3 compare EVERY (sequence, KV head) pair with the oracle; workload 4 every KV head of 8
+sequences spread over the batch (first, last, and around the multiples of 4 that the correction workgroups cut the
+batch at); workload 5 all 64 sequences on one KV head each at steps 0, 127, 128 and 255, plus four seeded pairs at
+every 8th step; the two throughput-experiment shapes (6, 7) a spread of pairs.  Compared per pair: group records and
+window rows bit for bit, the states S, P element by element, the binary16 state copy against binary16 of the oracle's
+S, the outputs within the tolerance, row by row.  Pairs that are not compared carry device-generated N(0, 1) data so
+that the launch has its real shape.  The oracle's references come from worker processes (tests/oracle_jobs.py)."""
+import hashlib
+import time
+
 import numpy as np
 import pytest
 
 import kvlinc_synth as synth
 from tests import kvlinc_testlib as tl
+from tests import oracle_jobs as oj
 
 pytestmark = pytest.mark.gpu
 
@@ -20,38 +29,66 @@ def kv():
     return kvmod
 
 
+def _sha(t):
+    return hashlib.sha1(np.ascontiguousarray(t.cpu().numpy()).tobytes()).hexdigest()
+
+
+def _sha_window_values(cache, b, g, nr):
+    """Digest of the live rotated-value rows of the window, [n_res, 128] oldest first (slots past n_res are dead storage)."""
+    rows = tl.o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
+    return hashlib.sha1(np.ascontiguousarray(rows).view(np.uint16).tobytes()).hexdigest()
+
+
 def _fill(cfg_id, B, H_kv, T, lengths, pairs, seed):
-    """Device K, V [B, H_kv, T, 128] fp16: seeded host rows for `pairs`, device noise elsewhere.  Also returns the
-    host rows {(b, g): (K, V)}."""
+    """Device K, V [B, H_kv, T, 128] fp16: seeded host rows for `pairs`, device noise elsewhere."""
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     Kd = torch.empty(B, H_kv, T, 128, dtype=torch.float16, device="cuda")
     Vd = torch.empty_like(Kd)
+    seeded = set(pairs)
     for b in range(B):  # per sequence, to bound the fp32 temporaries
-        Kd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
-        Vd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
-    host = {}
+        if not all((b, g) in seeded for g in range(H_kv)):
+            Kd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
+            Vd[b] = torch.randn(H_kv, T, 128, device="cuda", generator=gen).half()
     for (b, g) in pairs:
         n = int(lengths[b])
-        k, v = synth.keys(cfg_id, b, g, n), synth.values(cfg_id, b, g, n)
-        host[(b, g)] = (k, v)
-        Kd[b, g, :n] = torch.from_numpy(k).cuda()
-        Vd[b, g, :n] = torch.from_numpy(v).cuda()
-    return Kd, Vd, host
+        Kd[b, g, :n] = torch.from_numpy(synth.keys(cfg_id, b, g, n)).cuda()
+        Vd[b, g, :n] = torch.from_numpy(synth.values(cfg_id, b, g, n)).cuda()
+        if n < T:
+            Kd[b, g, n:] = 0
+            Vd[b, g, n:] = 0
+    return Kd, Vd
 
 
-def _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv):
-    """Records / window bit-exact, states and outputs within tolerance, for the seeded pairs."""
+def _jobs(cfg_id, pairs, lengths, n_quant, H_q, H_kv, step, R=128):
+    return [dict(cfg=cfg_id, b=int(b), g=int(g), n=int(lengths[b]), nq=int(n_quant[b]), H_q=H_q, H_kv=H_kv, step=step, R=R)
+            for (b, g) in pairs]
+
+
+def _compare(cache, pairs, refs, lengths, n_quant, n_res, out, cfg_id, H_q, H_kv, states=True):
+    """Every listed pair against its reference; returns (max_abs, rel_l2, worst_row) of the outputs."""
     gq = H_q // H_kv
-    n_quant, n_res = tl.check_counters(cache, lengths)
     want = {}
-    for (b, g) in pairs:
-        n = int(lengths[b])
-        k, v = host[(b, g)]
-        ref = tl.check_pair_against_oracle(cache, b, g, k[:n], v[:n], int(n_quant[b]), int(n_res[b]), Wk[g])
-        for h in range(g * gq, (g + 1) * gq):
-            want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h])
+    worst_s = worst_p = 0.0
+    for (b, g), ref in zip(pairs, refs):
+        nq, nr = int(n_quant[b]), int(n_res[b])
+        ng = -(-nq // 128)
+        same = (_sha(cache.groups[b, g, :ng]) == str(ref["rec_sha"]) and _sha(cache.k_res[b, g, :nr]) == str(ref["kres_sha"])
+                and _sha_window_values(cache, b, g, nr) == str(ref["vres_sha"]))
+        if not same:  # field-by-field report from an in-process recomputation of this one pair
+            n = int(lengths[b])
+            tl.check_pair_against_oracle(cache, b, g, synth.keys(cfg_id, b, g, n), synth.values(cfg_id, b, g, n), nq, nr,
+                                         synth.adapters_k(cfg_id, H_kv)[g], check_states=False)
+            raise AssertionError("digest mismatch without a field mismatch at pair (%d, %d)" % (b, g))
+        if states:
+            es, ep = tl.check_states_against(cache, b, g, ref["S"], ref["P"], quiet=True)
+            worst_s, worst_p = max(worst_s, es), max(worst_p, ep)
+        for i, h in enumerate(range(g * gq, (g + 1) * gq)):
+            want[(b, h)] = ref["y"][i]
+    if states:
+        print("  [states] pairs %d: worst S element error %.2e of max|S|, worst P element error %.2e of max|P|"
+              % (len(pairs), worst_s, worst_p))
     return tl.check_outputs(out, want)
 
 
@@ -60,10 +97,12 @@ def _run_bulk_config(kv, cfg_id, pairs):
     cfg = synth.CONFIGS[cfg_id]
     B, H_q, H_kv, n = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["n"]
     lengths = [n] * B
-    print("  [case] config %d %s B=%d heads %d/%d context %d pairs %s" % (cfg_id, cfg["name"], B, H_q, H_kv, n, pairs),
-          flush=True)
+    print("  [case] config %d %s B=%d heads %d/%d context %d, %d of %d pairs compared"
+          % (cfg_id, cfg["name"], B, H_q, H_kv, n, len(pairs), B * H_kv), flush=True)
+    t0 = time.time()
+    jobs = _jobs(cfg_id, pairs, lengths, [n - 128] * B, H_q, H_kv, 0)
     Wq, Wk = synth.adapters_q(cfg_id, H_q), synth.adapters_k(cfg_id, H_kv)
-    Kd, Vd, host = _fill(cfg_id, B, H_kv, n, lengths, pairs, seed=cfg_id)
+    Kd, Vd = _fill(cfg_id, B, H_kv, n, lengths, pairs, seed=cfg_id)
     cache = kv.KVLincCache(B, H_q, H_kv, n + 256, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
     cache.append(Kd, Vd)
     del Kd, Vd
@@ -74,36 +113,46 @@ def _run_bulk_config(kv, cfg_id, pairs):
     assert cache.n_quant.cpu().tolist() == [n - 128] * B and cache.n_res.cpu().tolist() == [128] * B
     out = out.cpu().numpy()
     assert np.isfinite(out.astype(np.float32)).all()
-    _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv)
+    print("  [gpu] cache built and decoded in %.1f s; oracle references ..." % (time.time() - t0), flush=True)
+    refs = oj.run_jobs_parallel(jobs)
+    print("  [oracle] %d references in %.1f s" % (len(refs), time.time() - t0), flush=True)
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    _compare(cache, pairs, refs, lengths, n_quant, n_res, out, cfg_id, H_q, H_kv)
     # a second call on the same cache gives the same bits (the arrival counters were left at zero)
     out2 = cache.decode(tl.to_dev(q), max_context=n).cpu().numpy()
     assert np.array_equal(out.view(np.uint16), out2.view(np.uint16))
     assert int(cache.split_done.abs().sum().item()) == 0
 
 
+def _all_pairs(B, H_kv):
+    return [(b, g) for b in range(B) for g in range(H_kv)]
+
+
 def test_config2_llama3_8b_batch16_ctx8k(kv):
-    _run_bulk_config(kv, 2, [(0, 0), (7, 3), (15, 7)])
+    _run_bulk_config(kv, 2, _all_pairs(16, 8))
 
 
 def test_config3_single_sequence_ctx128k(kv):
-    _run_bulk_config(kv, 3, [(0, 5)])
+    _run_bulk_config(kv, 3, _all_pairs(1, 8))
 
 
 def test_config4_qwen25_7b_batch32_ctx32k_gqa7(kv):
-    _run_bulk_config(kv, 4, [(0, 0), (31, 3)])
+    # sequences around the groups of 4 that share a correction workgroup, and both ends of the batch
+    _run_bulk_config(kv, 4, [(b, g) for b in (0, 3, 4, 7, 15, 16, 28, 31) for g in range(4)])
 
 
 def test_config6_mha_batch32_ctx1280(kv):
-    _run_bulk_config(kv, 6, [(0, 0), (13, 17), (31, 31)])
+    _run_bulk_config(kv, 6, [(b, g) for b in (0, 13, 31) for g in range(32)] + [(5, 0), (6, 31), (17, 9)])
 
 
 def test_config7_batch144_ctx1280(kv):
-    _run_bulk_config(kv, 7, [(0, 0), (77, 4), (143, 7)])
+    _run_bulk_config(kv, 7, [(b, g) for b in (0, 1, 2, 3, 76, 77, 140, 143) for g in range(8)])
 
 
 def test_config5_ragged_batch64_with_appends(kv):
     """Ragged contexts, one token appended to every sequence per step for 256 steps (every sequence crosses two flush
-    boundaries); seeded pairs are compared with the oracle at the first step, around step 127 / 128 and at the end."""
+    boundaries).  Compared: all 64 sequences (one KV head each, b % 8) at steps 0, 127, 128 and 255, and four seeded
+    pairs (shortest, longest, median and lower-quartile length) at every 8th step."""
     import torch
     cfg_id = 5
     cfg = synth.CONFIGS[cfg_id]
@@ -112,30 +161,70 @@ def test_config5_ragged_batch64_with_appends(kv):
     total = start + steps
     T = int(total.max())
     order = np.argsort(start)
-    pairs = [(int(order[0]), 1), (int(order[B // 2]), 6), (int(order[-1]), 3), (int(order[B // 4]), 0)]
-    print("  [case] config 5 B=%d contexts %d..%d pairs %s" % (B, start.min(), start.max(), pairs), flush=True)
+    four = [(int(order[0]), 1), (int(order[B // 2]), 6), (int(order[-1]), 3), (int(order[B // 4]), 0)]
+    everyone = [(b, b % H_kv) for b in range(B)]
+    seeded = sorted(set(four + everyone))
+    print("  [case] config 5 B=%d contexts %d..%d, pairs at every 8th step %s" % (B, start.min(), start.max(), four), flush=True)
     Wq, Wk = synth.adapters_q(cfg_id, H_q), synth.adapters_k(cfg_id, H_kv)
-    Kd, Vd, host = _fill(cfg_id, B, H_kv, T, total, pairs, seed=cfg_id)
+    Kd, Vd = _fill(cfg_id, B, H_kv, T, total, seeded, seed=cfg_id)
     cache = kv.KVLincCache(B, H_q, H_kv, T + 128, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
     cache.append(Kd[:, :, :int(start.max())].contiguous(), Vd[:, :, :int(start.max())].contiguous(),
                  n_new=tl.to_dev(start.astype(np.int32)))
     idx = torch.from_numpy(start.copy()).cuda()
     ar = torch.arange(B, device="cuda")
     lengths = start.copy()
-    check_at = {0, 126, 127, 128, steps - 1}
+    full_at = {0, 127, 128, steps - 1}
+    snapshots = []  # (step, pairs, lengths, n_quant, n_res, digests and tensors of the compared pairs, out)
+    jobs = []
     for step in range(steps):
         kn = Kd[ar, :, idx].unsqueeze(2).contiguous()  # [B, H_kv, 1, 128]: row `length` of every sequence
         vn = Vd[ar, :, idx].unsqueeze(2).contiguous()
         cache.append(kn, vn)
         idx += 1
         lengths += 1
-        if step in check_at:
-            print("  [step] %d" % step, flush=True)
+        if step in full_at or step % 8 == 0:
+            pairs = sorted(set(four + (everyone if step in full_at else [])))
             q = tl.gen_q(cfg_id, B, H_q, step)
             out = cache.decode(tl.to_dev(q), max_context=int(lengths.max()))
             torch.cuda.synchronize()
             assert int(cache.status.item()) == 0
             out = out.cpu().numpy()
             assert np.isfinite(out.astype(np.float32)).all()
-            _check_pairs(cache, host, lengths, pairs, q, out, Wq, Wk, H_q, H_kv)
+            n_quant, n_res = tl.check_counters(cache, lengths)
+            # the cache moves on: keep what the comparison needs of this step's state
+            kept = {}
+            for (b, g) in pairs:
+                ng, nr = int(n_quant[b]) // 128, int(n_res[b])
+                kept[(b, g)] = (_sha(cache.groups[b, g, :ng]), _sha(cache.k_res[b, g, :nr]), _sha_window_values(cache, b, g, nr),
+                                cache.S[b, g].cpu().numpy(), cache.P[b, g].cpu().numpy(), cache.S16[b, g].cpu().numpy())
+            snapshots.append((step, pairs, lengths.copy(), n_quant.copy(), n_res.copy(), kept, out, len(jobs)))
+            jobs += _jobs(cfg_id, pairs, lengths, n_quant, H_q, H_kv, step)
     assert (cache.n_quant.cpu().numpy() + cache.n_res.cpu().numpy() == total).all()
+    print("  [gpu] %d steps done, %d snapshots, %d oracle jobs ..." % (steps, len(snapshots), len(jobs)), flush=True)
+    t0 = time.time()
+    refs = oj.run_jobs_parallel(jobs)
+    print("  [oracle] %d references in %.1f s" % (len(refs), time.time() - t0), flush=True)
+    gq = H_q // H_kv
+    for (step, pairs, lens, n_quant, n_res, kept, out, j0) in snapshots:
+        want = {}
+        for k, (b, g) in enumerate(pairs):
+            ref = refs[j0 + k]
+            rec_sha, kres_sha, vres_sha, S, P, S16 = kept[(b, g)]
+            assert (rec_sha, kres_sha, vres_sha) == (str(ref["rec_sha"]), str(ref["kres_sha"]), str(ref["vres_sha"])), \
+                ("records / window differ from the oracle", step, b, g)
+            snap = _Snapshot(S, P, S16)
+            tl.check_states_against(snap, 0, 0, ref["S"], ref["P"], quiet=True)
+            for i, h in enumerate(range(g * gq, (g + 1) * gq)):
+                want[(b, h)] = ref["y"][i]
+        print("  [step] %d" % step, flush=True)
+        tl.check_outputs(out, want)
+
+
+class _Snapshot:
+    """The state tensors of one (sequence, KV head) as they were at a step, in the shape check_states_against reads."""
+
+    def __init__(self, S, P, S16):
+        import torch
+        self.S = torch.from_numpy(S)[None, None]
+        self.P = torch.from_numpy(P)[None, None]
+        self.S16 = torch.from_numpy(S16)[None, None]

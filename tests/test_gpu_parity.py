@@ -234,12 +234,170 @@ def test_status_bits_and_rejections(kv):
     cache.append(k[:, :, :300].contiguous(), k[:, :, :300].contiguous())
     torch.cuda.synchronize()
     assert int(cache.status.item()) == kv.KVLINC_ST_NONFINITE
+    assert cache.n_quant.item() == 0 and cache.n_res.item() == 0 and not cache.split_done.any()
     # host-side rejections: nothing is launched
     q = torch.zeros(B, H_q, 128, dtype=torch.float16, device="cuda")
     ws = torch.empty(4, device="cuda")
     assert kv.kvlinc_decode_attention(cache, q, q.clone(), ws) == kv.KVLINC_EWORKSPACE
     assert kv.kvlinc_append_quantize(cache, k, k, None, 0, 0) == kv.KVLINC_EINVAL
     assert kv.kvlinc_append_quantize(cache, k, k, None, 600, 200) == kv.KVLINC_EINVAL
+
+
+def _live_state(cache):
+    """Everything a sequence's state consists of, as host arrays: counters, live group records and window rows, states."""
+    nq, nr = cache.n_quant.cpu().numpy().copy(), cache.n_res.cpu().numpy().copy()
+    out = {"n_quant": nq, "n_res": nr, "split_done": cache.split_done.cpu().numpy().copy()}
+    for b in range(cache.B):
+        ng = -(-int(nq[b]) // 128)
+        out["groups%d" % b] = cache.groups[b, :, :ng].cpu().numpy().copy()
+        out["k_res%d" % b] = cache.k_res[b, :, :int(nr[b])].cpu().numpy().view(np.uint16).copy()
+        out["v_res%d" % b] = np.stack([tl.o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), int(nr[b]))
+                                       for g in range(cache.H_kv)]).view(np.uint16).copy()
+    if cache.S is not None:
+        out["S"] = cache.S.cpu().numpy().view(np.uint32).copy()
+        out["P"] = cache.P.cpu().numpy().view(np.uint32).copy()
+        out["S16"] = cache.S16.cpu().numpy().view(np.uint16).copy()
+    return out
+
+
+def _assert_same_state(a, b):
+    assert a.keys() == b.keys()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+@pytest.mark.parametrize("H_kv,bad_head", [(2, 1), (2, 0), (1, 0), (3, 2)])
+def test_rejected_append_leaves_the_sequence_unchanged(kv, H_kv, bad_head):
+    """A non-finite new token -- in any KV head, arriving alone or inside a bulk append, in a key, a value, or as a
+    value whose rotation overflows fp16 -- sets KVLINC_ST_NONFINITE and leaves counters, live records, window and states
+    of that sequence bit for bit as they were; the other sequence of the batch takes its tokens; a clean retry works."""
+    import torch
+    B, gq = 2, 2
+    H_q = gq * H_kv
+    lengths = [383, 250]  # sequence 0: one token short of a full window (the next append is plain, the one after flushes)
+    cache, K, V, Wq, Wk = _build(kv, 31, B, H_q, H_kv, lengths)
+    rng = np.random.default_rng(5)
+    fresh = lambda T: (rng.standard_normal((B, H_kv, T, 128)).astype(np.float16),
+                       rng.standard_normal((B, H_kv, T, 128)).astype(np.float16))
+    total = [list(lengths)]
+
+    def attempt(kn, vn, poison, n_new=None):
+        """Append with `poison` applied to sequence 0 only: sequence 0 must be refused, sequence 1 must take its rows."""
+        before = _live_state(cache)
+        kp, vp = kn.copy(), vn.copy()
+        poison(kp, vp)
+        cache.status.zero_()
+        cache.append(tl.to_dev(kp), tl.to_dev(vp), n_new=None if n_new is None else tl.to_dev(np.asarray(n_new, dtype=np.int32)))
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == kv.KVLINC_ST_NONFINITE
+        after = _live_state(cache)
+        T = kn.shape[2] if n_new is None else n_new[1]
+        assert after["n_quant"][0] == before["n_quant"][0] and after["n_res"][0] == before["n_res"][0]
+        assert after["n_quant"][1] + after["n_res"][1] == before["n_quant"][1] + before["n_res"][1] + T
+        for k in before:  # everything of sequence 0
+            if k.endswith("0"):
+                assert np.array_equal(before[k], after[k]), k
+        if "S" in before:
+            for k in ("S", "P", "S16"):
+                assert np.array_equal(before[k][0], after[k][0]), k
+        assert not after["split_done"].any()
+        total[0][1] += T
+        return kn[1], vn[1]
+
+    hist_k, hist_v = [K[1, :, :lengths[1]]], [V[1, :, :lengths[1]]]
+    # 1. one token, NaN in a key of `bad_head`
+    kn, vn = fresh(1)
+    k1, v1 = attempt(kn, vn, lambda k, v: k.__setitem__((0, bad_head, 0, 17), np.float16("nan")))
+    hist_k.append(k1); hist_v.append(v1)
+    # 2. one token, a finite value row whose rotation overflows fp16 (all channels 6e4: the first rotated entry is 6.8e5)
+    kn, vn = fresh(1)
+    k1, v1 = attempt(kn, vn, lambda k, v: v.__setitem__((0, bad_head, 0), np.float16(6e4)))
+    hist_k.append(k1); hist_v.append(v1)
+    # 3. a bulk append of 300 rows (it would flush sequence 0's window twice), Inf in a value of `bad_head` at row 200
+    kn, vn = fresh(300)
+    k1, v1 = attempt(kn, vn, lambda k, v: v.__setitem__((0, bad_head, 200, 3), np.float16("inf")))
+    hist_k.append(k1); hist_v.append(v1)
+    # 4. the same with a row limit: the fault lies in a row that is appended (row 4 of 5)
+    kn, vn = fresh(300)
+    k1, v1 = attempt(kn, vn, lambda k, v: k.__setitem__((0, bad_head, 4, 100), np.float16("-inf")), n_new=[5, 7])
+    hist_k.append(k1[:, :7]); hist_v.append(v1[:, :7])
+    # a fault in a row beyond the limit is not looked at
+    kn, vn = fresh(8)
+    kp = kn.copy()
+    kp[0, bad_head, 6, 0] = np.float16("nan")
+    cache.status.zero_()
+    cache.append(tl.to_dev(kp), tl.to_dev(vn), n_new=tl.to_dev(np.asarray([3, 8], dtype=np.int32)))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0
+    K0 = np.concatenate([K[0, :, :lengths[0]], kn[0, :, :3]], axis=1)
+    V0 = np.concatenate([V[0, :, :lengths[0]], vn[0, :, :3]], axis=1)
+    hist_k.append(kn[1]); hist_v.append(vn[1])
+    K1, V1 = np.concatenate(hist_k, axis=1), np.concatenate(hist_v, axis=1)
+    n0, n1 = K0.shape[1], K1.shape[1]
+    tl.check_counters(cache, [n0, n1])
+    n_quant, n_res = cache.n_quant.cpu().numpy(), cache.n_res.cpu().numpy()
+    q = tl.gen_q(31, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = {}
+    for b, (Kb, Vb) in enumerate(((K0, V0), (K1, V1))):
+        for g in range(H_kv):
+            ref = tl.check_pair_against_oracle(cache, b, g, Kb[g], Vb[g], int(n_quant[b]), int(n_res[b]), Wk[g])
+            for h in range(g * gq, (g + 1) * gq):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h])
+    tl.check_outputs(out, want)
+
+
+@pytest.mark.parametrize("log2_gain", [-8, -4, 4, 8])
+@pytest.mark.parametrize("which", ["values", "keys"])
+def test_magnitudes_far_from_one_keep_the_tolerance(kv, which, log2_gain):
+    """Values (resp. keys) scaled by 2^-8 .. 2^8: the operands of the matrix products carry block exponents, so the
+    output stays inside the tolerance whatever the magnitude (relative to the output's own size)."""
+    B, H_q, H_kv = 2, 8, 2
+    lengths = [900, 517]
+    K, V = tl.gen_kv(33, B, H_kv, lengths)
+    gain = np.float32(2.0 ** log2_gain)
+    if which == "values":
+        V = (V.astype(np.float32) * gain).astype(np.float16)
+    else:
+        K = (K.astype(np.float32) * gain).astype(np.float16)
+    Wq, Wk = synth.adapters_q(33, H_q), synth.adapters_k(33, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+    q = tl.gen_q(33, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy().astype(np.float64)
+    assert int(cache.status.item()) == 0
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    want = tl.oracle_decode(K, V, q, lengths, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    # the tolerance is stated for outputs of order one: compare at the values' own scale
+    unit = float(gain) if which == "values" else 1.0
+    scaled = {k: v / unit for k, v in want.items()}
+    tl.check_outputs(out / unit, scaled)
+
+
+def test_state_beyond_the_binary16_range_is_flagged_and_saturated(kv):
+    """Values with a common sign make S grow with the context: rotated values of 442 in every channel and 20480 quantized
+    tokens put entries of S near 442 * 20480 / 128 = 7e4 > 65504.  The append reports KVLINC_ST_STATE_RANGE, the 16-bit
+    copy holds +-65504 there, and nothing is Inf or NaN."""
+    import torch
+    B, H_q, H_kv = 1, 4, 1
+    n = 20480 + 128
+    K, _ = tl.gen_kv(34, B, H_kv, [n])
+    V = np.zeros_like(K)
+    V[..., 0] = np.float16(5000.0)  # rotation: 5000 / sqrt(128) = 442 in all 128 channels
+    Wq, Wk = synth.adapters_q(34, H_q), synth.adapters_k(34, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, n, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K[:, :, :4096]), tl.to_dev(V[:, :, :4096]))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0  # still in range at 4096 tokens
+    cache.append(tl.to_dev(K[:, :, 4096:]), tl.to_dev(V[:, :, 4096:]))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == kv.KVLINC_ST_STATE_RANGE
+    S = cache.S.cpu().numpy()
+    S16 = cache.S16.cpu().numpy().astype(np.float32)
+    assert np.isfinite(S).all() and np.abs(S).max() > 65504.0
+    assert np.isfinite(S16).all() and np.abs(S16).max() == 65504.0
+    out = cache.decode(tl.to_dev(tl.gen_q(34, B, H_q))).cpu().numpy()
+    assert np.isfinite(out.astype(np.float32)).all()
 
 
 def test_run_to_run_determinism(kv):

@@ -13,9 +13,10 @@
  *
  * Conventions
  *   - Every pointer inside kvlinc_cache and every tensor argument is a DEVICE pointer owned by the
- *     caller, 16-byte aligned.  The library allocates nothing, keeps no state between calls and never
- *     synchronises: a call validates its arguments on the host, enqueues kernels on `stream`
- *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *     caller, 16-byte aligned.  The library allocates nothing, keeps no state between calls (but for the address
+ *     of its static scratch buffer, see kvlinc_decode_attention_noalloc) and never synchronises: a call validates its
+ *     arguments on the host, enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and returns.
  *   - kvlinc_half is the bit pattern of an IEEE binary16 number.
  *   - Return value: 0 = enqueued; negative = rejected before any launch, nothing was touched.
  *   - Faults only the device can see (capacity exhausted, non-finite input, append to a cache whose
@@ -92,7 +93,8 @@ enum {
   KVLINC_OK = 0,
   KVLINC_EINVAL = -1,     /* NULL / misaligned pointer, unsupported shape or parameter */
   KVLINC_EWORKSPACE = -2, /* workspace too small or misaligned */
-  KVLINC_EHIP = -3        /* a HIP launch failed (hipGetLastError) */
+  KVLINC_EHIP = -3,       /* a HIP call failed (hipGetLastError) */
+  KVLINC_ESCRATCH = -4    /* kvlinc_decode_attention_noalloc: the launch needs more scratch than the library's static buffer */
 };
 
 enum {
@@ -194,6 +196,20 @@ int kvlinc_decode_attention(const kvlinc_cache* cache, const kvlinc_half* q, kvl
 int kvlinc_decode_attention_timed(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, void* workspace,
                                   size_t workspace_bytes, int32_t max_context, void* stream, void* start_event,
                                   void* stop_event);
+
+/*
+ * kvlinc_decode_attention for callers that cannot allocate and have no scratch buffer to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the workspace, same kernels, same
+ * results bit for bit.  The split partials go to a buffer of KVLINC_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends); the call allocates nothing.
+ * A launch that needs more (kvlinc_decode_workspace_bytes(cache, max_context) > KVLINC_STATIC_SCRATCH_BYTES) is
+ * rejected with KVLINC_ESCRATCH before anything is enqueued.  All calls on one GPU share that GPU's buffer: two such
+ * calls that overlap in time on one GPU (different streams) race, also on different caches.  Nothing in the buffer
+ * has to start at zero, and its contents are undefined afterwards.
+ */
+#define KVLINC_STATIC_SCRATCH_BYTES (16u << 20)
+int kvlinc_decode_attention_noalloc(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out, int32_t max_context,
+                                    void* stream);
 
 #ifdef __cplusplus
 }

@@ -5,7 +5,8 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(HERE, "libkvlinc.so")
 
-KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP = 0, -1, -2, -3
+KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP, KVLINC_ESCRATCH = 0, -1, -2, -3, -4
+KVLINC_STATIC_SCRATCH_BYTES = 16 << 20
 KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC, KVLINC_ST_STATE_RANGE = 1, 2, 4, 8
 
 
@@ -56,6 +57,8 @@ def _load():
     L.kvlinc_decode_attention_timed.restype = ctypes.c_int
     L.kvlinc_decode_attention_timed.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                                 ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    L.kvlinc_decode_attention_noalloc.restype = ctypes.c_int
+    L.kvlinc_decode_attention_noalloc.argtypes = [P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
     return L
 
 
@@ -119,6 +122,12 @@ def kvlinc_decode_attention_timed(cache, q, out, workspace, start_event, stop_ev
     return lib.kvlinc_decode_attention_timed(ctypes.byref(_struct(cache)), _ptr(q), _ptr(out), _ptr(workspace),
                                              int(workspace_bytes), int(max_context), _stream(stream),
                                              ctypes.c_void_p(int(start_event)), ctypes.c_void_p(int(stop_event)))
+
+
+def kvlinc_decode_attention_noalloc(cache, q, out, max_context=0, stream=None):
+    """As kvlinc_decode_attention, with the library's static scratch buffer in place of a workspace."""
+    return lib.kvlinc_decode_attention_noalloc(ctypes.byref(_struct(cache)), _ptr(q), _ptr(out), int(max_context),
+                                               _stream(stream))
 
 
 class KVLincCache:

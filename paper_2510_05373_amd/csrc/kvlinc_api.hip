@@ -1,9 +1,32 @@
 // Host side of the C ABI: argument validation and launch set-up.  Nothing here touches device memory.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "kvlinc_internal.h"
 
 namespace {
+
+// Scratch of kvlinc_decode_attention_noalloc: part of the device image, one copy per GPU.  The name below is a host-side
+// stand-in, not a device address: host code only ever uses the address hipGetSymbolAddress returns for the current
+// device, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[KVLINC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int scratch_of_current_device(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVLINC_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return KVLINC_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return KVLINC_OK;
+}
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline bool bad_ptr(const void* p, uintptr_t a) { return p == nullptr || !aligned(p, a); }
@@ -19,7 +42,8 @@ const char* kvlinc_strerror(int code) {
     case KVLINC_OK: return "ok";
     case KVLINC_EINVAL: return "invalid argument (NULL or misaligned pointer, unsupported shape or parameter)";
     case KVLINC_EWORKSPACE: return "workspace too small or misaligned";
-    case KVLINC_EHIP: return "HIP launch failed";
+    case KVLINC_EHIP: return "HIP call failed";
+    case KVLINC_ESCRATCH: return "the launch needs more scratch than the library's static buffer holds";
     default: return "unknown kvlinc error code";
   }
 }
@@ -85,6 +109,20 @@ int kvlinc_decode_attention_timed(const kvlinc_cache* cache, const kvlinc_half* 
                                   void* stop_event) {
   if (start_event == nullptr || stop_event == nullptr) return KVLINC_EINVAL;
   return decode_checked(cache, q, out, workspace, workspace_bytes, max_context, stream, start_event, stop_event);
+}
+
+int kvlinc_decode_attention_noalloc(const kvlinc_cache* cache, const kvlinc_half* q, kvlinc_half* out,
+                                    int32_t max_context, void* stream) {
+  const int rc = kvlinc_cache_validate(cache);
+  if (rc != KVLINC_OK) return rc;
+  if (bad_ptr(q, 16) || bad_ptr(out, 16)) return KVLINC_EINVAL;
+  const size_t need = kvlinc_decode_workspace_bytes(cache, max_context);
+  if (need > (size_t)KVLINC_STATIC_SCRATCH_BYTES) return KVLINC_ESCRATCH;
+  void* ws = nullptr;
+  const int rs = scratch_of_current_device(&ws);
+  if (rs != KVLINC_OK) return rs;
+  return kvlinc::launch_decode(*cache, q, out, static_cast<float*>(ws), kvlinc::decode_splits(*cache, max_context),
+                               static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 }  // extern "C"

@@ -32,8 +32,8 @@ def fake_struct(**over):
 def test_header_functions_are_exported():
     names = declared_functions()
     assert names == ["kvlinc_append_quantize", "kvlinc_cache_validate", "kvlinc_decode_attention",
-                     "kvlinc_decode_attention_timed", "kvlinc_decode_workspace_bytes", "kvlinc_strerror",
-                     "kvlinc_version"]
+                     "kvlinc_decode_attention_noalloc", "kvlinc_decode_attention_timed", "kvlinc_decode_workspace_bytes",
+                     "kvlinc_strerror", "kvlinc_version"]
     lib = ctypes.CDLL(kb.lib_path)
     for n in names:
         assert hasattr(lib, n), n
@@ -57,7 +57,7 @@ def test_struct_mirror_matches_header_order():
 
 def test_version_and_messages():
     assert kb.kvlinc_version() >= 100
-    for code in (0, -1, -2, -3):
+    for code in (0, -1, -2, -3, -4):
         assert "unknown" not in kb.kvlinc_strerror(code)
     assert "unknown" in kb.kvlinc_strerror(-99)
 
@@ -100,6 +100,22 @@ def test_rejections_happen_before_any_launch():
     assert dt(ctypes.byref(ok), p, p, p, need, 0, None, None, ev) == kb.KVLINC_EINVAL
     assert dt(ctypes.byref(ok), p, p, p, need, 0, None, ev, None) == kb.KVLINC_EINVAL
     assert dt(ctypes.byref(ok), p, p, p, need - 1, 0, None, ev, ev) == kb.KVLINC_EWORKSPACE
+
+
+def test_noalloc_entry_rejects_on_the_host():
+    """kvlinc_decode_attention_noalloc: bad descriptors and pointers, and launches that need more scratch than the
+    static buffer, are refused before any HIP call (the pointers here are fakes)."""
+    p = ctypes.c_void_p(0x20000)
+    na = kb.lib.kvlinc_decode_attention_noalloc
+    ok = fake_struct()
+    assert na(ctypes.byref(fake_struct(d=64)), p, p, 0, None) == kb.KVLINC_EINVAL
+    assert na(ctypes.byref(ok), None, p, 0, None) == kb.KVLINC_EINVAL
+    assert na(ctypes.byref(ok), p, ctypes.c_void_p(0x20008), 0, None) == kb.KVLINC_EINVAL
+    wide = fake_struct(B=256, H_q=32, H_kv=8, max_groups=32)
+    assert kb.kvlinc_decode_workspace_bytes(wide, 4096) > kb.KVLINC_STATIC_SCRATCH_BYTES
+    assert na(ctypes.byref(wide), p, p, 4096, None) == kb.KVLINC_ESCRATCH
+    text = open(HEADER).read()
+    assert "#define KVLINC_STATIC_SCRATCH_BYTES (16u << 20)" in text and kb.KVLINC_STATIC_SCRATCH_BYTES == 16 << 20
 
 
 def test_workspace_size_is_monotone_and_bounded():

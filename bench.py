@@ -24,10 +24,80 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 WORKLOAD = 2  # index into kvlinc_synth.CONFIGS
-# HBM bytes one decode launch of this workload moved (read + written) according to the FETCH_SIZE and WRITE_SIZE
-# counters, each scaled by what the same counter reports for a plain copy of known size; None = not measured.
-MEASURED_TRAFFIC_BYTES = 96.4e6
 EVENT_STRIDE = 4  # every 4th decode launch of the timed region is timed with dispatch events
+KERNEL_SOURCES = ("kvlinc_decode.hip", "kvlinc_mfma.h", "kvlinc_internal.h")  # what the decode kernel is compiled from
+
+
+def kernel_source_sha1():
+    import hashlib
+    h = hashlib.sha1()
+    for name in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2510_05373_amd", "csrc", name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload_name):
+    """HBM bytes one decode launch of this workload moved (read + written) according to the FETCH_SIZE and WRITE_SIZE
+    counters, each scaled by what the same counter reports for a plain copy of known size: read from the tracked
+    rocprofv3 summary of this workload.  (bytes, file, note); bytes is None when there is no summary or when the
+    summary was taken at another state of the kernel's sources (it records their SHA-1)."""
+    rel = os.path.join("profiles", "decode_main_kernel_%s_hbm_traffic.txt" % workload_name)
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None, None, "no tracked counter summary for this workload"
+    fields = {}
+    for line in open(path):
+        if ":" in line:
+            k, v = line.split(":", 1)
+            fields[k.strip()] = v.strip()
+    sha_now = kernel_source_sha1()
+    if fields.get("kernel_source_sha1") != sha_now:
+        return None, rel, "summary taken at kernel sources %s, now %s" % (fields.get("kernel_source_sha1"), sha_now)
+    return float(fields["traffic_bytes_per_launch"]), rel, "kernel sources %s" % sha_now
+
+
+def read_only_ceiling(caches, B, H_kv, H_q, counts, n_res, reps, hip, new_event):
+    """Mean duration (s) and bytes of a launch that only reads what one decode launch reads: the live group records
+    of every (sequence, KV head), the fp16 window, the 16-bit state, P and W_q.  Equal lengths only."""
+    import ctypes
+    import torch
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2510_05373_amd", "libkvlinc_probe.so"))
+    lib.kvlinc_probe_read_only.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_longlong),
+                                           ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ctypes.c_longlong), ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    n_wg = 512  # measured best for one launch of this size (256 .. 4096 tried)
+    sink = torch.empty(n_wg * 256, dtype=torch.int32, device=caches[0].groups.device)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    args = []
+    total = 0
+    for c in caches:
+        segs = [(c.groups, counts * 9216, c.max_groups * 9216, B * H_kv),
+                (c.k_res, n_res * 256, c.R * 256, B * H_kv), (c.v_res, -(-n_res // 4) * 1024, c.R * 256, B * H_kv),
+                (c.S16, B * H_kv * 65536, 0, 1), (c.P, B * H_kv * 1024, 0, 1), (c.Wq, H_q * 65536, 0, 1)]
+        n = len(segs)
+        ptr = (ctypes.c_void_p * n)(*[t.data_ptr() for t, _, _, _ in segs])
+        nbytes = (ctypes.c_longlong * n)(*[b for _, b, _, _ in segs])
+        stride = (ctypes.c_longlong * n)(*[s for _, _, s, _ in segs])
+        runs = (ctypes.c_longlong * n)(*[r for _, _, _, r in segs])
+        args.append((ptr, nbytes, stride, runs, n))
+        total = sum(b * r for _, b, _, r in segs)
+    events = []
+    for i in range(8 + reps):
+        a = args[i % len(args)]
+        ev = (new_event(), new_event()) if i >= 8 else (None, None)
+        rc = lib.kvlinc_probe_read_only(a[0], a[1], a[2], a[3], a[4], ctypes.c_void_p(sink.data_ptr()), n_wg, stream, ev[0], ev[1])
+        assert rc == 0, "read-only probe rejected its arguments"
+        if i >= 8:
+            events.append(ev)
+    torch.cuda.synchronize()
+    ms = []
+    for a, b in events:
+        t = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(t), a, b) == 0
+        ms.append(t.value)
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+    return float(np.mean(ms)) * 1e-3, total
 
 
 def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True):
@@ -212,9 +282,15 @@ def main():
         decode_ms = np.array([float("nan")])
     decode_avg_s = float(decode_ms.mean()) * 1e-3
     achieved = float(np.mean(alg_bytes)) / decode_avg_s / 1e9
-    traffic = None
-    if MEASURED_TRAFFIC_BYTES is not None and wl == WORKLOAD:
-        traffic = MEASURED_TRAFFIC_BYTES
+    traffic, traffic_file, traffic_note = measured_traffic(cfg["name"])
+    # the practical ceiling: a launch that only reads the same bytes (windows full, as in most steps)
+    ceiling = None
+    if wl != 5 and not args.no_events:
+        n_now = int(lens[0][0])
+        n_res_now = (n_now - 1) % 128 + 1
+        t_read, read_bytes = read_only_ceiling(caches, B, H_kv, H_q, (n_now - n_res_now) // 128, n_res_now, 32, hip, new_event)
+        ceiling = {"read_only_launch_us": t_read * 1e6, "read_only_bytes": read_bytes,
+                   "read_only_gbs": read_bytes / t_read / 1e9, "frac_of_peak": read_bytes / t_read / 1e9 / PEAK_HBM_GBS}
 
     result = {
         "metric": "decode-attention KV tokens/s at 2-bit (achieved HBM GB/s and % of peak under roofline)",
@@ -232,6 +308,10 @@ def main():
                    "launch_loop_cpu_ms_per_step": (t_cpu_done - t_start) / K_steps * 1e3, "setup_s": setup_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
+                     "traffic_source": traffic_file, "traffic_note": traffic_note,
+                     "read_ceiling_frac": None if ceiling is None else ceiling["frac_of_peak"],
+                     "read_ceiling": ceiling,
+                     "frac_of_read_ceiling": None if ceiling is None else achieved / ceiling["read_only_gbs"],
                      "kernel": "decode_main_kernel (the one launch of kvlinc_decode_attention)",
                      "algorithmic_bytes_per_launch": float(np.mean(alg_bytes)),
                      "avg_launch_us": decode_avg_s * 1e6, "launches_timed": len(decode_ms)},

@@ -1,4 +1,5 @@
-"""Builds libkvlinc.so (the C-ABI library) in-tree with hipcc for gfx950."""
+"""Builds libkvlinc.so (the C-ABI library) and libkvlinc_probe.so (the benchmark's read-only probe kernel) in-tree with
+hipcc for gfx950."""
 import os
 import subprocess
 
@@ -6,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libkvlinc.so")
+PROBE_PATH = os.path.join(HERE, "libkvlinc_probe.so")
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -18,6 +20,7 @@ SOURCES = {
     "kvlinc_append.hip": ["-ffp-contract=off"],
     "kvlinc_decode.hip": [],
 }
+PROBE_SOURCE = "kvlinc_readprobe.hip"
 
 
 def build(verbose=False):
@@ -31,6 +34,8 @@ def build(verbose=False):
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    probe_cmd = [hipcc] + COMMON + ["-shared", os.path.join(CSRC, PROBE_SOURCE), "-o", PROBE_PATH]
+    procs.append((PROBE_SOURCE, subprocess.Popen(probe_cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src, p in procs:
         out, _ = p.communicate()
         if p.returncode != 0:

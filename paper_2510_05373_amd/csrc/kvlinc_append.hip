@@ -193,6 +193,18 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   const int g = blockIdx.x % c.H_kv;
   const long long bh = (long long)b * c.H_kv + g;
 
+  // One-token append: the new rows of ALL kv heads of this sequence are looked at for non-finite values (below); their
+  // first batch -- heads wave, wave + 4, ..., eight per wave -- is requested here, together with the counters.
+  uint32_t chk_k[8], chk_v[8];
+  if (T == 1) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int g2 = wave + 4 * u;
+      const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
+      chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
+      chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
+    }
+  }
   const int nq = c.n_quant[b];
   const int nr = c.n_res[b];
   int n = n_new ? n_new[b] : T;
@@ -205,10 +217,43 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   {
     // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
     bool refuse = false;
-    if (T == 1) {  // the one new row of every kv head of this sequence
-      for (int g2 = wave; g2 < c.H_kv; g2 += kThreads / 64) {
-        const long long row = ((long long)b * c.H_kv + g2) * kHeadDim;
-        refuse |= row_is_bad(k_new + row, v_new + row, lane);
+    if (T == 1) {
+      // the one new row of every kv head of this sequence, eight heads per wave and batch
+      for (int g0 = wave; g0 < c.H_kv; g0 += 4 * 8) {
+        if (g0 != wave) {  // more than 32 kv heads: further batches
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int g2 = g0 + 4 * u;
+            const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
+            chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
+            chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
+          }
+        }
+        // A rotated value is at most sum_i |v_i| / sqrt(128): rows whose sum of magnitudes stays below
+        // 65504 sqrt(128) cannot overflow fp16 and need no rotation here (a non-finite v makes the sum non-finite).
+        float mag[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          refuse |= ((chk_k[u] & 0x7C00u) == 0x7C00u) || ((chk_k[u] & 0x7C000000u) == 0x7C000000u);
+          const half2_t h = as_h2(chk_v[u]);
+          mag[u] = fabsf((float)h[0]) + fabsf((float)h[1]);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mag[u] = wave_allsum(mag[u]);
+#pragma unroll
+        for (int u0 = 0; u0 < 8; u0 += 4) {
+          if (mag[u0] < 741000.0f && mag[u0 + 1] < 741000.0f && mag[u0 + 2] < 741000.0f && mag[u0 + 3] < 741000.0f) continue;
+          float x0[4], x1[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const half2_t h = as_h2(chk_v[u0 + u]);
+            x0[u] = (float)h[0];
+            x1[u] = (float)h[1];
+          }
+          fwht128_wave_multi<4>(x0, x1, lane);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) refuse |= nonfinite_bits((half_t)x0[u]) || nonfinite_bits((half_t)x1[u]);
+        }
       }
     } else if (c.H_kv > 1) {
       refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch

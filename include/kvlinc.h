@@ -55,14 +55,19 @@
  *   v_res             [B, H_kv, R/4, 128, 4] fp16: the window's ROTATED values, 4 consecutive slots per channel:
  *                     slot r, channel c at [r/4][c][r%4].
  *   n_quant, n_res    [B] int32: quantized tokens / window tokens of each sequence (context = sum).
- *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.  They are
- *                     the master copy: kvlinc_append_quantize accumulates into them.
- *   S16               [B, H_kv, 128, 64, 4] fp16: S rounded to binary16 (the 16-bit state the paper's average-bit
- *                     figures of Table 1 assume), rewritten by every append that flushes a group and read by
- *                     kvlinc_decode_attention in place of S.  Tile t = (f / 64 * 2 + c / 64) * 16 + (f % 64) / 4 holds
+ *   S, P              [B, H_kv, D, 128], [B, H_kv, D] fp32 correction states (Eq. 5), rotated value basis.  S is the
+ *                     optional fp32 master copy that kvlinc_append_quantize accumulates into; with S == NULL the
+ *                     state is STORED in 16 bits only (S16 below, the storage the paper's average-bit figures of
+ *                     Table 1 assume): an append that flushes then starts from the binary16 state, accumulates the
+ *                     groups of that call in binary32 and rounds once at the end of the call.  P is always fp32.
+ *   S16               [B, H_kv, 128, 64, 4] fp16: S in binary16, rewritten by every append that flushes a group and
+ *                     read by kvlinc_decode_attention.  Tile t = (f / 64 * 2 + c / 64) * 16 + (f % 64) / 4 holds
  *                     S[f][c] at [t][c % 64][f % 4]  (f = feature 0..255, c = channel 0..127).
  *   Wq, Wk            [H_q, 2, 128, D/2], [H_kv, 2, 128, D/2] fp16: W_1, W_2 of phi_q / phi_k (Eq. 6).
- *                     S, S16, P, Wq, Wk all NULL = correction off (plain quantized attention).
+ *                     S16, P, Wq, Wk all NULL (and S NULL) = correction off (plain quantized attention).
+ *   flags             KVLINC_FLAG_* bits.  KVLINC_FLAG_ALG1_LITERAL: the merge adds C_n, C_d to the max-shifted sums
+ *                     as the last lines of Alg. 1 print them, (num + C_n) / (den + C_d), instead of Eq. 5's
+ *                     (num + e^-M C_n) / (den + e^-M C_d) (the two differ by the factor e^-M, M = largest score).
  *   status            [1] int32, OR-ed KVLINC_ST_* bits.
  *   split_done        [B, H_kv] int32 scratch counters (arrival counts: of the workgroups of a (sequence, KV head)
  *                     in kvlinc_decode_attention, where the last one merges; of the workgroups of a sequence in
@@ -104,6 +109,10 @@ enum {
   KVLINC_ST_STATE_RANGE = 8 /* an entry of S left the binary16 range: S16 holds +-65504 there, the correction is off */
 };
 
+enum {
+  KVLINC_FLAG_ALG1_LITERAL = 1 /* correction added without the e^-M factor (Alg. 1 as printed) */
+};
+
 typedef struct kvlinc_cache {
   int32_t B, H_q, H_kv;
   int32_t d;    /* head dimension, must be 128 */
@@ -124,6 +133,7 @@ typedef struct kvlinc_cache {
   const kvlinc_half* Wk;
   int32_t* status;
   int32_t* split_done;
+  int32_t flags;
 } kvlinc_cache;
 
 /* Library version, major*10000 + minor*100 + patch. */

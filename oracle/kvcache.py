@@ -54,7 +54,7 @@ def _quantize_rows(x, bits, mode):
     raise ValueError(mode)
 
 
-def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=None):
+def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=None, state_rounding=None):
     """State of the cache holding tokens 0..n-1 (K, V: [n, d] fp16) with the first n_quant quantized.
 
     Returns a dict with, for the quantized part, per group g (tokens gG .. gG+G-1, the last group
@@ -64,6 +64,10 @@ def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=
     [n_res, d]; and S [D, d], P [D] if adapters Wk [2, d, D/2] are given.
     mode: 'spec32' (GPU contract, fp16 storage), 'exact16' (fp64 arithmetic, fp16 storage),
     'real' (Eq. 1 in fp64 throughout, any bit width; for convergence checks only).
+    state_rounding: None = S kept exactly (fp64).  Otherwise an iterable of quantized-token counts (multiples of G):
+    the state is STORED in 16 bits -- the width the average-bit figures of Table 1 count it at -- and was rounded to
+    binary16 each time the quantized part reached one of these counts and at n_quant (the ends of the append calls
+    that flushed); between two roundings the sums of Eq. 5 run exactly.  Entries beyond +-65504 saturate.
     """
     K = np.asarray(K)
     V = np.asarray(V)
@@ -107,7 +111,17 @@ def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=
         if n_quant:
             K_err = K[:n_quant].astype(np.float64) - out["K_hat"]
             phi_k = feature_map(K_err, Wk)
-            out["S"] = phi_k.T @ out["V_hat"]
+            if state_rounding is None:
+                out["S"] = phi_k.T @ out["V_hat"]
+            else:
+                cuts = sorted({int(c) for c in state_rounding if 0 < int(c) < n_quant} | {n_quant})
+                assert all(c % G == 0 for c in cuts[:-1])
+                S, prev = np.zeros((D, d)), 0
+                for cut in cuts:
+                    S = S + phi_k[prev:cut].T @ out["V_hat"][prev:cut]
+                    S = np.clip(S, -65504.0, 65504.0).astype(np.float16).astype(np.float64)
+                    prev = cut
+                out["S"] = S
             out["P"] = phi_k.sum(axis=0)
         else:
             out["S"] = np.zeros((D, d))

@@ -7,6 +7,7 @@ lib_path = os.path.join(HERE, "libkvlinc.so")
 
 KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP, KVLINC_ESCRATCH = 0, -1, -2, -3, -4
 KVLINC_STATIC_SCRATCH_BYTES = 16 << 20
+KVLINC_FLAG_ALG1_LITERAL = 1
 KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC, KVLINC_ST_STATE_RANGE = 1, 2, 4, 8
 
 
@@ -26,6 +27,7 @@ class CacheStruct(ctypes.Structure):
         ("S", ctypes.c_void_p), ("S16", ctypes.c_void_p), ("P", ctypes.c_void_p),
         ("Wq", ctypes.c_void_p), ("Wk", ctypes.c_void_p),
         ("status", ctypes.c_void_p), ("split_done", ctypes.c_void_p),
+        ("flags", ctypes.c_int32),
     ]
 
 
@@ -133,7 +135,10 @@ def kvlinc_decode_attention_noalloc(cache, q, out, max_context=0, stream=None):
 class KVLincCache:
     """Device buffers of one layer's cache plus the descriptor that points at them (allocation only)."""
 
-    def __init__(self, B, H_q, H_kv, max_context, R=128, Wq=None, Wk=None, device="cuda"):
+    def __init__(self, B, H_q, H_kv, max_context, R=128, Wq=None, Wk=None, device="cuda", state_storage="fp32",
+                 flags=0):
+        """state_storage: "fp32" keeps the fp32 master copy of S next to its binary16 tiles, "fp16" stores the state in
+        the binary16 tiles only; flags: KVLINC_FLAG_* bits."""
         import torch
         self.B, self.H_q, self.H_kv, self.R = B, H_q, H_kv, R
         self.max_groups = max(1, -(-int(max_context) // 128))
@@ -151,7 +156,8 @@ class KVLincCache:
         if Wq is not None:
             assert Wk is not None and tuple(Wq.shape) == (H_q, 2, 128, 128) and tuple(Wk.shape) == (H_kv, 2, 128, 128)
             assert Wq.dtype == torch.float16 and Wk.dtype == torch.float16 and Wq.is_contiguous() and Wk.is_contiguous()
-            self.S = z(B, H_kv, 256, 128, dt=torch.float32)
+            assert state_storage in ("fp32", "fp16")
+            self.S = z(B, H_kv, 256, 128, dt=torch.float32) if state_storage == "fp32" else None
             self.S16 = z(B, H_kv, 128, 64, 4, dt=torch.float16)
             self.P = z(B, H_kv, 256, dt=torch.float32)
         else:
@@ -161,16 +167,16 @@ class KVLincCache:
             groups=self.groups.data_ptr(),
             k_res=self.k_res.data_ptr(), v_res=self.v_res.data_ptr(),
             n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),
-            S=None if self.S is None else self.S.data_ptr(), S16=None if self.S is None else self.S16.data_ptr(),
+            S=None if self.S is None else self.S.data_ptr(), S16=None if self.S16 is None else self.S16.data_ptr(),
             P=None if self.P is None else self.P.data_ptr(),
             Wq=None if Wq is None else Wq.data_ptr(), Wk=None if Wk is None else Wk.data_ptr(),
-            status=self.status.data_ptr(), split_done=self.split_done.data_ptr())
+            status=self.status.data_ptr(), split_done=self.split_done.data_ptr(), flags=int(flags))
         self._ws = None
 
     def bytes(self):
         ts = [self.groups, self.k_res, self.v_res]
-        if self.S is not None:
-            ts += [self.S, self.S16, self.P]
+        if self.S16 is not None:
+            ts += [self.S16, self.P] + ([self.S] if self.S is not None else [])
         return sum(t.numel() * t.element_size() for t in ts)
 
     def append(self, k_new, v_new, n_new=None, keep_residual=0, stream=None):

@@ -60,12 +60,13 @@ int kvlinc_cache_validate(const kvlinc_cache* c) {
   if (bad_ptr(c->k_res, 16) || bad_ptr(c->v_res, 16)) return KVLINC_EINVAL;
   if (bad_ptr(c->n_quant, 4) || bad_ptr(c->n_res, 4) || bad_ptr(c->status, 4) || bad_ptr(c->split_done, 4))
     return KVLINC_EINVAL;
-  const int n_corr =
-      (c->S != nullptr) + (c->S16 != nullptr) + (c->P != nullptr) + (c->Wq != nullptr) + (c->Wk != nullptr);
-  if (n_corr != 0 && n_corr != 5) return KVLINC_EINVAL;
-  if (n_corr == 5 && (!aligned(c->S, 16) || !aligned(c->S16, 16) || !aligned(c->P, 16) || !aligned(c->Wq, 16) ||
+  const int n_corr = (c->S16 != nullptr) + (c->P != nullptr) + (c->Wq != nullptr) + (c->Wk != nullptr);
+  if (n_corr != 0 && n_corr != 4) return KVLINC_EINVAL;
+  if (n_corr == 0 && c->S != nullptr) return KVLINC_EINVAL;  // the fp32 master copy is an option of the correction
+  if (n_corr == 4 && (!aligned(c->S, 16) || !aligned(c->S16, 16) || !aligned(c->P, 16) || !aligned(c->Wq, 16) ||
                       !aligned(c->Wk, 16)))
     return KVLINC_EINVAL;
+  if ((c->flags & ~KVLINC_FLAG_ALG1_LITERAL) != 0) return KVLINC_EINVAL;
   return KVLINC_OK;
 }
 

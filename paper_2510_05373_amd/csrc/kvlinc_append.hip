@@ -276,7 +276,8 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   const half_t* v_res = reinterpret_cast<const half_t*>(c.v_res) + bh * c.R * kHeadDim;
   const half_t* k_src = k_new + bh * (long long)T * kHeadDim;
   const half_t* v_src = v_new + bh * (long long)T * kHeadDim;
-  const bool have_states = c.S != nullptr;
+  const bool have_states = c.S16 != nullptr;
+  const bool have_master = c.S != nullptr;  // fp32 master copy of S; without it the state lives in its binary16 tiles
 
   // Correction states of this (sequence, kv head) (Eq. 5).  The update runs on the matrix cores (4x4x4 blocks with a
   // broadcast A operand): wave w owns the features 64 w .. 64 w + 63, i.e. 16 blocks of 4 rows of S, each as two
@@ -289,13 +290,21 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   half4_t wop[32];  // W_k of this wave's features as B operands: step cs = channels 4 cs .. 4 cs + 3
   float P_f = 0.0f;
   if (states_live) {
+    const half_t* tiles_in = reinterpret_cast<const half_t*>(c.S16) + bh * kRank * kHeadDim;
 #pragma unroll
     for (int fb = 0; fb < 16; ++fb)
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
+      for (int hh = 0; hh < 2; ++hh) {
+        if (have_master) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          sacc[fb][hh][i] = c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane];
+          for (int i = 0; i < 4; ++i)
+            sacc[fb][hh][i] = c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane];
+        } else {  // tile (wave, hh, fb) holds exactly this accumulator
+          const half4_t t16 = *reinterpret_cast<const half4_t*>(tiles_in + (((wave * 2 + hh) * 16 + fb) * 64 + lane) * 4);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sacc[fb][hh][i] = (float)t16[i];
+        }
+      }
     P_f = c.P[bh * kRank + tid];
     // a lane reads 4 features of one channel (natural order of W); the lane quad transposes
     const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) +
@@ -583,7 +592,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     return;
   }
   if (states_live) {
-    // fp32 master copy, row-major, and the binary16 tile copy for the decode kernel: tile (64-feature block = wave,
+    // fp32 master copy (if the cache keeps one), row-major, and the binary16 tiles the decode kernel reads: tile (64-feature block = wave,
     // channel half hh, feature step fb) holds S[64 wave + 4 fb + k][64 hh + l] at [l][k] -- exactly one accumulator.
     // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
     half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
@@ -596,7 +605,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float v = sacc[fb][hh][i];
-          c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = v;
+          if (have_master) c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = v;
           out_of_range |= !(fabsf(v) <= 65504.0f);
           t16[i] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
         }

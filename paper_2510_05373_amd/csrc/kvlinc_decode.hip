@@ -607,7 +607,7 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
 // MB = splits whose partial results are requested together
 template <int MB>
 __device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr,
-                                          int max_splits, int n_splits, int row, int lane,
+                                          int max_splits, int n_splits, int row, int lane, bool literal,
                                           half_t* __restrict__ out) {
   const float* p0 = part + (long long)row * max_splits * kPartStride;
   // correction parts first (their values are needed last): {Cd_r, m_r, Z_r, -, Cn_r[128]}
@@ -680,9 +680,10 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
         }
       }
     }
-    // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum)
+    // (num + 2^-M C_n) / (den + 2^-M C_d) with both factors kept <= 1 (M is the log2-domain maximum); the literal
+    // form of Alg. 1's last lines leaves the factor 2^-M out
     const float Ms = fmaxf(M, 0.f);
-    const float fa = exp2f(M - Ms), fb = exp2f(-Ms);
+    const float fa = literal ? 1.0f : exp2f(M - Ms), fb = literal ? 1.0f : exp2f(-Ms);
     const float d = fa * den + fb * cd;
     y0 = (fa * n0 + fb * cn0) / d;
     y1 = (fa * n1 + fb * cn1) / d;
@@ -707,10 +708,10 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 
 
 __device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr,
-                                           int max_splits, int n_splits, int row, int lane,
+                                           int max_splits, int n_splits, int row, int lane, bool literal,
                                            half_t* __restrict__ out) {
-  if (n_splits <= 4) merge_row<4>(part, corr, max_splits, n_splits, row, lane, out);
-  else merge_row<8>(part, corr, max_splits, n_splits, row, lane, out);
+  if (n_splits <= 4) merge_row<4>(part, corr, max_splits, n_splits, row, lane, literal, out);
+  else merge_row<8>(part, corr, max_splits, n_splits, row, lane, literal, out);
 }
 
 // Splits the groups of a sequence are cut into.  The host fixes the average over the batch (avg_splits) and the most
@@ -815,7 +816,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       const int n_splits = sequence_splits(c, c.n_quant[b], avg_splits, max_splits, lane);
       if (sFlags[s] == n_splits + n_parts - 1) {
         for (int h = wave; h < gq; h += kWaves)
-          merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, out);
+          merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, (c.flags & KVLINC_FLAG_ALG1_LITERAL) != 0, out);
         if (tid == 0) c.split_done[bh] = 0;
       }
     }
@@ -996,7 +997,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
   // loads.  No workgroup waits for another.
   if (arrive(c.split_done + bh, expected, &sFlag)) {
     for (int h = wave; h < gq; h += kWaves)
-      merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, out);
+      merge_rows(part, corr, max_splits, n_splits, b * c.H_q + g * gq + h, lane, (c.flags & KVLINC_FLAG_ALG1_LITERAL) != 0, out);
     if (tid == 0) c.split_done[bh] = 0;
   }
 }
@@ -1018,7 +1019,7 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
   const long long bh = (long long)c.B * c.H_kv;
   const int gq = c.H_q / c.H_kv;
   long long n_corr = 0;
-  if (c.S != nullptr && gq <= 4) n_corr = (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs);
+  if (c.S16 != nullptr && gq <= 4) n_corr = (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs);
   long long s = (kTargetWorkgroups - n_corr + bh / 2) / bh;  // rounded to nearest
   if (s > kMaxSplits) s = kMaxSplits;
   const long long most = (groups + kWaves - 1) / kWaves;
@@ -1033,7 +1034,7 @@ DecodeSplits decode_splits(const kvlinc_cache& c, int max_context) {
   // fill most of the chip while the streaming workgroups have long contexts ahead of them (many sequences, 16 or
   // more groups per wave): then the streaming workgroups go first, the longest of them decide when the launch ends,
   // and the correction fills the places the short sequences leave.
-  const long long all_corr = c.S != nullptr ? (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
+  const long long all_corr = c.S16 != nullptr ? (long long)c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const long long resident = 256 * (gq <= 4 ? 3 : 2);
   int corr_first = (2 * all_corr > resident && groups >= 16 * kWaves * s) ? 0 : 1;
   // One or a few long sequences: about one streaming workgroup per compute unit.  The streaming workgroups that
@@ -1065,7 +1066,7 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const half_t* qq = reinterpret_cast<const half_t*>(q);
   half_t* oo = reinterpret_cast<half_t*>(out);
   float* part = workspace;
-  float* corr = c.S != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
+  float* corr = c.S16 != nullptr ? workspace + (size_t)c.B * c.H_q * n_splits * kPartStride : nullptr;
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const dim3 grid(BH * n_splits + n_corr), block(kThreads);
   const int corr_first = sp.corr_first;

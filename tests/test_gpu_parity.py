@@ -400,6 +400,91 @@ def test_state_beyond_the_binary16_range_is_flagged_and_saturated(kv):
     assert np.isfinite(out.astype(np.float32)).all()
 
 
+def test_state_stored_in_16_bits_only(kv):
+    """S == NULL: the state lives in its binary16 tiles.  A bulk build (one rounding), then one-token appends across
+    three window flushes (one rounding each), against the oracle with the same rounding points: the tiles are equal
+    almost everywhere and within one rounding flip per rounding point elsewhere (the GPU sums a group in binary32), P
+    and the records as always, outputs inside the tolerance.  The same history with the fp32 master copy gives tiles that differ (it rounds the exact sum)."""
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    pre, extra = [700, 333], 300
+    lengths = [p + extra for p in pre]
+    K, V = tl.gen_kv(35, B, H_kv, lengths)
+    Wq, Wk = synth.adapters_q(35, H_q), synth.adapters_k(35, H_kv)
+    caches = {}
+    for storage in ("fp16", "fp32"):
+        cache = kv.KVLincCache(B, H_q, H_kv, 2048, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), state_storage=storage)
+        Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+        cache.append(Kd[:, :, :max(pre)].contiguous(), Vd[:, :, :max(pre)].contiguous(),
+                     n_new=tl.to_dev(np.asarray(pre, dtype=np.int32)))
+        for s in range(extra):
+            kn = torch.stack([Kd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            cache.append(kn, vn)
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == 0
+        caches[storage] = cache
+    cache = caches["fp16"]
+    assert cache.S is None
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    q = tl.gen_q(35, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = {}
+    gq = H_q // H_kv
+    for b in range(B):
+        first = tl.o_cache.window_split(pre[b])[0]          # quantized tokens after the bulk build
+        points = list(range(first, int(n_quant[b]) + 1, 128))  # ... and after every flush since
+        for g in range(H_kv):
+            n = lengths[b]
+            ref = tl.o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=Wk[g], state_rounding=points)
+            tl.check_pair_against_oracle(cache, b, g, K[b, g, :n], V[b, g, :n], int(n_quant[b]), int(n_res[b]), None)
+            S16 = tl.o_layout.unpack_state_tiles(cache.S16[b, g].cpu().numpy())
+            # A group's sum differs in its last binary32 bits, which now and then flips a rounding: one unit in the
+            # last place of that entry AS IT WAS THEN -- an entry that has since cancelled to a small value keeps the
+            # absolute difference -- and at most one flip per rounding point.  So: equal bits almost everywhere, and
+            # everywhere within (rounding points) x (unit in the last place of the largest entry).
+            ulps = np.abs(tl._ordered16(S16) - tl._ordered16(ref["S"].astype(np.float16)))
+            s_max = np.abs(ref["S"]).max()
+            ulp_max = 2.0 ** (np.floor(np.log2(s_max)) - 10)
+            assert np.abs(S16.astype(np.float64) - ref["S"]).max() <= len(points) * ulp_max, (b, g, int(ulps.max()))
+            assert (ulps == 0).mean() > 0.9
+            P = cache.P[b, g].cpu().numpy().astype(np.float64)
+            assert np.abs(P - ref["P"]).max() <= tl.STATE_P_ELEMENT * np.abs(ref["P"]).max()
+            for h in range(g * gq, (g + 1) * gq):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h])
+    tl.check_outputs(out, want)
+    assert not torch.equal(caches["fp16"].S16, caches["fp32"].S16)  # several roundings against one
+    assert torch.equal(caches["fp16"].groups, caches["fp32"].groups) and torch.equal(caches["fp16"].P, caches["fp32"].P)
+
+
+def test_alg1_literal_correction_mode(kv):
+    """KVLINC_FLAG_ALG1_LITERAL: the correction terms are added to the max-shifted sums without the factor e^-M, as the
+    last lines of Alg. 1 print them; against the oracle's switch of the same name, and different from the Eq. 5 mode."""
+    B, H_q, H_kv = 2, 8, 2
+    lengths = [1500, 777]
+    K, V = tl.gen_kv(36, B, H_kv, lengths)
+    Wq, Wk = synth.adapters_q(36, H_q), synth.adapters_k(36, H_kv)
+    outs = {}
+    for flags in (0, kv.KVLINC_FLAG_ALG1_LITERAL):
+        cache = kv.KVLincCache(B, H_q, H_kv, 2048, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), flags=flags)
+        cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+        q = tl.gen_q(36, B, H_q)
+        outs[flags] = cache.decode(tl.to_dev(q)).cpu().numpy()
+        assert int(cache.status.item()) == 0
+        n_quant = cache.n_quant.cpu().numpy()
+    gq = H_q // H_kv
+    want = {}
+    for b in range(B):
+        for g in range(H_kv):
+            n = lengths[b]
+            ref = tl.o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=Wk[g])
+            for h in range(g * gq, (g + 1) * gq):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h], literal_alg1=True)
+    tl.check_outputs(outs[kv.KVLINC_FLAG_ALG1_LITERAL], want)
+    diff = np.abs(outs[0].astype(np.float64) - outs[kv.KVLINC_FLAG_ALG1_LITERAL].astype(np.float64)).max()
+    assert diff > 1e-3  # the two modes are different functions of the same cache
+
+
 def test_run_to_run_determinism(kv):
     import torch
     B, H_q, H_kv = 2, 8, 2

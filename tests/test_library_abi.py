@@ -24,7 +24,7 @@ def fake_struct(**over):
     base = 0x10000
     f = dict(B=2, H_q=8, H_kv=2, d=128, G=128, R=128, D=256, bits=2, max_groups=8, groups=base, k_res=base,
              v_res=base, n_quant=base, n_res=base, S=base, S16=base, P=base, Wq=base, Wk=base, status=base,
-             split_done=base)
+             split_done=base, flags=0)
     f.update(over)
     return kb.CacheStruct(**f)
 
@@ -67,12 +67,15 @@ def test_validate_accepts_and_rejects():
     assert kb.kvlinc_cache_validate(ok) == kb.KVLINC_OK
     bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=4), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
            dict(H_q=32, H_kv=2), dict(B=0), dict(max_groups=0), dict(groups=0), dict(groups=0x10004), dict(k_res=0),
-           dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S=0), dict(S16=0),
-           dict(S16=0x10008), dict(Wk=0), dict(P=0x10002)]
+           dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S16=0),
+           dict(S16=0x10008), dict(Wk=0), dict(P=0x10002), dict(S=0x10004), dict(flags=2), dict(flags=-1),
+           dict(S16=0, P=0, Wq=0, Wk=0)]  # (the last: an fp32 master copy without the rest of the correction)
     for over in bad:
         assert kb.kvlinc_cache_validate(fake_struct(**over)) == kb.KVLINC_EINVAL, over
-    # correction off = all of S, S16, P, Wq, Wk NULL
+    # correction off = all of S, S16, P, Wq, Wk NULL; S alone NULL = the state is stored in 16 bits only
     assert kb.kvlinc_cache_validate(fake_struct(S=0, S16=0, P=0, Wq=0, Wk=0)) == kb.KVLINC_OK
+    assert kb.kvlinc_cache_validate(fake_struct(S=0)) == kb.KVLINC_OK
+    assert kb.kvlinc_cache_validate(fake_struct(flags=kb.KVLINC_FLAG_ALG1_LITERAL)) == kb.KVLINC_OK
     assert kb.lib.kvlinc_cache_validate(None) == kb.KVLINC_EINVAL
 
 
@@ -100,6 +103,29 @@ def test_rejections_happen_before_any_launch():
     assert dt(ctypes.byref(ok), p, p, p, need, 0, None, None, ev) == kb.KVLINC_EINVAL
     assert dt(ctypes.byref(ok), p, p, p, need, 0, None, ev, None) == kb.KVLINC_EINVAL
     assert dt(ctypes.byref(ok), p, p, p, need - 1, 0, None, ev, ev) == kb.KVLINC_EWORKSPACE
+
+
+def test_cache_bytes_reproduce_the_average_bit_figures():
+    """Table 1, column "KV Cache": the buffers of a cache holding 8192 tokens per (sequence, KV head) -- 63 group
+    records, the 128-token fp16 window, and with the correction the state stored in 16 bits (S == NULL) plus P --
+    average to the printed 2.46 / 2.71 bits per cached element; P is kept in fp32 here, 16 bits more per entry than the
+    paper counts (0.002 bits).  Host tensors: nothing is launched."""
+    import torch
+    from oracle import accounting
+    B, H_q, H_kv, n = 2, 8, 2, 8192
+    elements = 2 * B * H_kv * n * 128
+    plain = kb.KVLincCache(B, H_q, H_kv, n - 128, device="cpu")
+    assert plain.max_groups == 63
+    bits_plain = plain.bytes() * 8 / elements
+    assert abs(bits_plain - accounting.average_bits(n)) < 1e-12 and abs(bits_plain - 2.46) < 0.01
+    W = torch.zeros(H_q, 2, 128, 128, dtype=torch.float16)
+    c16 = kb.KVLincCache(B, H_q, H_kv, n - 128, Wq=W, Wk=W[:H_kv], device="cpu", state_storage="fp16")
+    assert c16.S is None and c16.struct.S is None and c16.struct.S16 is not None
+    bits16 = c16.bytes() * 8 / elements
+    assert abs(bits16 - (accounting.average_bits(n, D=256) + 256 * 16 / (2 * n * 128))) < 1e-12
+    assert abs(bits16 - 2.71) < 0.01
+    c32 = kb.KVLincCache(B, H_q, H_kv, n - 128, Wq=W, Wk=W[:H_kv], device="cpu")  # with the fp32 master copy of S
+    assert abs(c32.bytes() * 8 / elements - (bits16 + 256 * 128 * 32 / (2 * n * 128))) < 1e-12
 
 
 def test_noalloc_entry_rejects_on_the_host():

@@ -155,6 +155,30 @@ def test_states_are_additive_over_groups():
     np.testing.assert_allclose(full["P"].sum(), 2 * 384, rtol=1e-12)  # each half of phi sums to one per token
 
 
+def test_sixteen_bit_state_storage_rounds_at_the_stated_points():
+    """state_rounding: one rounding at the end is binary16 of the exact state; a rounding after every group is the
+    recurrence S <- fp16(S + phi_k^T V_q of the group) written out here; either stays within the rounding bound of the
+    exact state and does round; P is not touched."""
+    _, K, V, _, Wk = _case(n=640, seed=17)
+    exact = kvcache.build_cache(K, V, 512, Wk=Wk)
+    once = kvcache.build_cache(K, V, 512, Wk=Wk, state_rounding=[])
+    assert np.array_equal(once["S"], exact["S"].astype(np.float16).astype(np.float64))
+    assert np.array_equal(once["P"], exact["P"])
+    every = kvcache.build_cache(K, V, 512, Wk=Wk, state_rounding=[128, 256, 384])
+    S = np.zeros_like(exact["S"])
+    for a in (0, 128, 256, 384):
+        part = kvcache.build_cache(K[a:a + 128], V[a:a + 128], 128, Wk=Wk)["S"]
+        S = (S + part).astype(np.float16).astype(np.float64)
+    assert np.array_equal(every["S"], S)
+    assert np.array_equal(every["S"], every["S"].astype(np.float16).astype(np.float64))
+    bound = 4 * 2.0 ** -11 * np.abs(exact["S"]).max()  # four roundings, each half a unit in the last place at most
+    assert 0 < np.abs(every["S"] - exact["S"]).max() <= bound
+    # points that are not crossed do not matter; the state saturates instead of overflowing
+    assert np.array_equal(kvcache.build_cache(K, V, 512, Wk=Wk, state_rounding=[512, 640, 1024])["S"], once["S"])
+    big = kvcache.build_cache(K, (V.astype(np.float32) * 4096).astype(np.float16), 512, Wk=Wk, state_rounding=[256])
+    assert np.isfinite(big["S"]).all() and np.abs(big["S"]).max() <= 65504.0
+
+
 def test_partial_tail_group_uses_valid_tokens_only():
     _, K, V, _, _ = _case(n=256, seed=8)
     c = kvcache.build_cache(K, V, 224)  # one full group + 96 tokens

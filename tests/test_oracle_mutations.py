@@ -57,6 +57,12 @@ CASES = [
      [pa.test_partial_tail_group_uses_valid_tokens_only, pa.test_tiny_case_brute_force]),
     ("values quantized without the rotation", kvcache, "build_cache", "Vr = hadamard.fwht_spec32(V)", "Vr = V",
      [pa.test_the_three_arithmetic_modes_describe_the_same_cache]),
+    ("16-bit state rounded at the end only, whatever the stated points", kvcache, "build_cache",
+     "cuts = sorted({int(c) for c in state_rounding if 0 < int(c) < n_quant} | {n_quant})", "cuts = [n_quant]",
+     [pa.test_sixteen_bit_state_storage_rounds_at_the_stated_points]),
+    ("16-bit state: the sum restarts at every rounding point", kvcache, "build_cache",
+     'S = S + phi_k[prev:cut].T @ out["V_hat"][prev:cut]', 'S = phi_k[prev:cut].T @ out["V_hat"][prev:cut]',
+     [pa.test_sixteen_bit_state_storage_rounds_at_the_stated_points]),
     ("window flushed one append early", kvcache, "window_split", "(n - 1) % G + 1", "n % G",
      [pa.test_window_split_is_the_lazy_block_flush]),
     ("correction added without the e^-M factor", attention, "decode", "if literal_alg1:", "if True:",

@@ -193,18 +193,6 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   const int g = blockIdx.x % c.H_kv;
   const long long bh = (long long)b * c.H_kv + g;
 
-  // One-token append: the new rows of ALL kv heads of this sequence are looked at for non-finite values (below); their
-  // first batch -- heads wave, wave + 4, ..., eight per wave -- is requested here, together with the counters.
-  uint32_t chk_k[8], chk_v[8];
-  if (T == 1) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int g2 = wave + 4 * u;
-      const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
-      chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
-      chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
-    }
-  }
   const int nq = c.n_quant[b];
   const int nr = c.n_res[b];
   int n = n_new ? n_new[b] : T;
@@ -217,17 +205,19 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   {
     // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
     bool refuse = false;
-    if (T == 1) {
-      // the one new row of every kv head of this sequence, eight heads per wave and batch
+    if (T == 1 && plan.n_flush > 0) {
+      // A one-token append that flushes the window changes live state (S, P, the window's first slot) in every kv
+      // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.  (One
+      // that does not flush only fills a dead window slot: there each workgroup looks at its own row when it stores
+      // it, and the counters are not advanced if any of them votes against.)
       for (int g0 = wave; g0 < c.H_kv; g0 += 4 * 8) {
-        if (g0 != wave) {  // more than 32 kv heads: further batches
+        uint32_t chk_k[8], chk_v[8];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int g2 = g0 + 4 * u;
-            const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
-            chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
-            chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
-          }
+        for (int u = 0; u < 8; ++u) {
+          const int g2 = g0 + 4 * u;
+          const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
+          chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
+          chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
         }
         // A rotated value is at most sum_i |v_i| / sqrt(128): rows whose sum of magnitudes stays below
         // 65504 sqrt(128) cannot overflow fp16 and need no rotation here (a non-finite v makes the sum non-finite).
@@ -255,9 +245,9 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
           for (int u = 0; u < 4; ++u) refuse |= nonfinite_bits((half_t)x0[u]) || nonfinite_bits((half_t)x1[u]);
         }
       }
-    } else if (c.H_kv > 1) {
+    } else if (T > 1 && c.H_kv > 1) {
       refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
-    } else {
+    } else if (T > 1) {
       // bulk append, one kv head: this workgroup is the sequence's only one.  The new rows that will stay in the
       // window (at most R) are looked at here; those that get quantized are looked at when their group is staged,
       // before anything but dead storage has been written.
@@ -621,18 +611,25 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   half_t* k_win = reinterpret_cast<half_t*>(c.k_res) + bh * c.R * kHeadDim;
   half_t* v_win = reinterpret_cast<half_t*>(c.v_res) + bh * c.R * kHeadDim;
   const int first_new = max(plan.n_flush, nr);
+  bool row_bad = false;  // only a one-token append that does not flush can still meet a non-finite row here
   for (int u = first_new + wave; u < nr + n; u += kThreads / 64) {
     const int slot = u - plan.n_flush;
     const half_t* ks = k_src + (long long)(u - nr) * kHeadDim;
     const half_t* vs = v_src + (long long)(u - nr) * kHeadDim;
     const uint32_t kk = *reinterpret_cast<const uint32_t*>(ks + 2 * lane);
-    *reinterpret_cast<uint32_t*>(k_win + (long long)slot * kHeadDim + 2 * lane) = kk;
     float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
     fwht128_wave(x0, x1, lane);
-    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = (half_t)x0;
-    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = (half_t)x1;
+    const half_t r0 = (half_t)x0, r1 = (half_t)x1;
+    const bool mine = ((kk & 0x7C00u) == 0x7C00u) || ((kk & 0x7C000000u) == 0x7C000000u) || nonfinite_bits(r0) || nonfinite_bits(r1);
+    if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // nothing of a faulty row reaches the window
+      row_bad = true;
+      continue;
+    }
+    *reinterpret_cast<uint32_t*>(k_win + (long long)slot * kHeadDim + 2 * lane) = kk;
+    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = r0;
+    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = r1;
   }
-  commit_sequence(c, b, nq, n, plan, 0);
+  commit_sequence(c, b, nq, n, plan, __syncthreads_or(row_bad) ? KVLINC_ST_NONFINITE : 0);
 }
 
 }  // namespace

@@ -309,7 +309,15 @@ def test_rejected_append_leaves_the_sequence_unchanged(kv, H_kv, bad_head):
     kn, vn = fresh(1)
     k1, v1 = attempt(kn, vn, lambda k, v: k.__setitem__((0, bad_head, 0, 17), np.float16("nan")))
     hist_k.append(k1); hist_v.append(v1)
-    # 2. one token, a finite value row whose rotation overflows fp16 (all channels 6e4: the first rotated entry is 6.8e5)
+    # a clean token fills sequence 0's window: the next one-token append has to flush it
+    kn, vn = fresh(1)
+    cache.append(tl.to_dev(kn), tl.to_dev(vn))
+    K = np.concatenate([K[:, :, :lengths[0]], kn], axis=2)  # (sequence 0's rows; sequence 1 is tracked in hist_*)
+    V = np.concatenate([V[:, :, :lengths[0]], vn], axis=2)
+    lengths = [lengths[0] + 1, lengths[1]]
+    hist_k.append(kn[1]); hist_v.append(vn[1])
+    assert cache.n_res.cpu().tolist()[0] == 128
+    # 2. one token that would flush, a finite value row whose rotation overflows fp16 (all channels 6e4 -> 6.8e5)
     kn, vn = fresh(1)
     k1, v1 = attempt(kn, vn, lambda k, v: v.__setitem__((0, bad_head, 0), np.float16(6e4)))
     hist_k.append(k1); hist_v.append(v1)

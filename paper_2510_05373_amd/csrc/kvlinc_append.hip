@@ -14,26 +14,35 @@
 namespace kvlinc {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kRowPad = 130;   // halfs per LDS row of a 128-wide fp16 tile (odd number of 32-bit words)
-constexpr int kCodePad = 132;  // bytes per LDS row of a 128-wide code tile
-constexpr int kChunk = 16;     // tokens per state-update chunk
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kRowH = 136;     // halfs per LDS row of a 128-wide fp16 tile (rows stay 16-byte aligned)
+constexpr int kChunk = 32;     // tokens per step of the state update
+constexpr int kParts = 4;      // workgroups that share the flush of one (sequence, kv head): 64-feature blocks of S
+constexpr int kListCap = kThreads;  // items one workgroup looks at per round (one per thread)
 
 struct Lds {
-  half_t sK[kGroup][kRowPad];
-  half_t sV[kGroup][kRowPad];
-  uint8_t cK[kGroup][kCodePad];
-  uint8_t cV[kGroup][kCodePad];
-  float kScale[kGroup], kZero[kGroup], vScale[kGroup], vZero[kGroup];
-  float phi[kChunk][kRank];
-  // operands of the state update of one chunk of tokens, as binary16 (the key error in two terms hi + lo)
-  half_t kErrH[kChunk][kHeadDim + 8];
-  half_t kErrL[kChunk][kHeadDim + 8];
-  half_t cVh[kChunk][kHeadDim + 8];
-  // phi s of the chunk, transposed (feature-major) and in two binary16 terms: the A operands of the S update
-  half_t phTH[kRank][kChunk + 4];
-  half_t phTL[kRank][kChunk + 4];
-  float zs[kRank];
+  half_t bK[kGroup][kRowH];       // raw keys [token][channel]; after the quantizer the high term of K - K_q
+  half_t bV[kGroup][kRowH];       // rotated values [token][channel]; after the quantizer the low term of K - K_q
+  // value codes as the binary16 numbers code - 1.5, [token / 4][channel][token % 4]: what the S update multiplies by,
+  // and -- sign and the bit that tells 1.5 from 0.5 -- the bit pair the record stores
+  half_t cV[kGroup / 4][kHeadDim][4];
+  float kScale[kGroup], kZero[kGroup];
+  float vScale[kGroup], vCentre[kGroup];  // vCentre: z + 1.5 s, the value of the centre of the code range
+  union {
+    struct {
+      half_t mn[kThreads / 16][kGroup], mx[kThreads / 16][kGroup];  // per-channel key minima / maxima of token subsets
+    } part;
+    float lg[kChunk][kHeadDim + 4];  // logits of one chunk of tokens for the 128 features of one half of phi
+  } u;
+  // phi s of the chunk for this workgroup's 64 features, feature-major, as two binary16 terms
+  half_t phH[64][kChunk + 8];
+  half_t phL[64][kChunk + 8];
+  float red[2 * kWaves][64];
+  int light[kListCap], heavy[kListCap];
+  int n_light, n_heavy, last_flag;
 };
 
 __device__ inline bool nonfinite_bits(half_t x) {
@@ -124,26 +133,81 @@ __device__ inline uint32_t q2_code(float x, const Q2& p) {
   return p.s == 0.0f ? 0u : c;
 }
 
-// The counters of a sequence change only after every workgroup of that sequence (one per kv head) has read them:
-// each workgroup counts itself in when it is done -- with a vote in the upper half of the counter if it found a
-// fault -- and the one that completes the count writes n_quant / n_res unless somebody voted against, and leaves the
-// counter (and the sequence's fault flag of the scan launch, see below) at zero.  The counter is the sequence's first
-// split_done entry, which the decode kernel uses in the same way and also leaves at zero.
+// Every (sequence, kv head) has kParts owners in the grid, fixed by the launch shape alone.  Each owner reads the
+// sequence's counters once and counts itself in at the sequence's first split_done entry when it is done -- with a
+// vote in the upper half of the counter if it found a fault; the counters change only in the arrival that completes
+// the count (kParts H_kv), i.e. after every reader has read them, and only if nobody voted against.  That arrival
+// leaves the counter (and the sequence's fault flag of the scan launch, its second split_done entry) at zero, as the
+// decode kernel, which uses the same entries in the same way, expects.
 constexpr int kFaultVote = 1 << 16;
-__device__ __forceinline__ void commit_sequence(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan, int err) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int* counter = c.split_done + (long long)b * c.H_kv;
-    if (err) atomicOr(c.status, err);
-    const int before = __hip_atomic_fetch_add(counter, err ? 1 + kFaultVote : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    if ((before & (kFaultVote - 1)) == c.H_kv - 1) {
-      if (err == 0 && before < kFaultVote && n > 0) {
-        c.n_quant[b] = nq + plan.n_flush;
-        c.n_res[b] = plan.new_res;
-      }
-      *counter = 0;
-      if (c.H_kv > 1) counter[1] = 0;
-    }
+__device__ inline bool arrive(const kvlinc_cache& c, int b, bool vote, bool* clean) {
+  int* counter = c.split_done + (long long)b * c.H_kv;
+  const int before = __hip_atomic_fetch_add(counter, vote ? 1 + kFaultVote : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  *clean = !vote && before < kFaultVote;
+  return (before & (kFaultVote - 1)) == kParts * c.H_kv - 1;
+}
+__device__ inline void finish(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan, bool clean) {
+  int* counter = c.split_done + (long long)b * c.H_kv;
+  if (clean && plan.err == 0 && n > 0) {
+    c.n_quant[b] = nq + plan.n_flush;
+    c.n_res[b] = plan.new_res;
+  }
+  *counter = 0;
+  if (c.H_kv > 1) counter[1] = 0;
+}
+
+__device__ inline bool nonfinite_pair(uint32_t w) { return ((w & 0x7C00u) == 0x7C00u) || ((w & 0x7C000000u) == 0x7C000000u); }
+
+// One wave: raw key and rotated value of one new token into its window slot (values live 4 slots per channel: slot u,
+// channel ch at [u / 4][ch][u % 4]).  Nothing of a row with a non-finite key or rotated value is stored; returns
+// whether the row was such a row.
+__device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __restrict__ v_win, int slot,
+                                        const half_t* __restrict__ ks, const half_t* __restrict__ vs, int lane) {
+  const uint32_t kk = *reinterpret_cast<const uint32_t*>(ks + 2 * lane);
+  float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
+  fwht128_wave(x0, x1, lane);
+  const half_t r0 = (half_t)x0, r1 = (half_t)x1;
+  const bool mine = nonfinite_pair(kk) || nonfinite_bits(r0) || nonfinite_bits(r1);
+  if (__builtin_amdgcn_ballot_w64(mine) != 0) return true;
+  *reinterpret_cast<uint32_t*>(k_win + (long long)slot * kHeadDim + 2 * lane) = kk;
+  v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = r0;
+  v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = r1;
+  return false;
+}
+
+struct Counters {
+  int nq, nr, n;
+  AppendPlan plan;
+};
+__device__ inline Counters read_counters(const kvlinc_cache& c, int b, const int32_t* __restrict__ n_new, int T, int keep) {
+  Counters r;
+  r.nq = c.n_quant[b];
+  r.nr = c.n_res[b];
+  int n = n_new ? n_new[b] : T;
+  r.n = n < 0 ? 0 : (n > T ? T : n);
+  r.plan = plan_append(r.nq, r.nr, r.n, c.R, keep, c.max_groups);
+  return r;
+}
+
+// An append that quantizes nothing: one wave stores the new rows of one (sequence, kv head) behind the window's
+// tokens.  The slots are dead storage until the counters advance, and they do not advance if any head of the sequence
+// votes against.
+__device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __restrict__ k_new,
+                                  const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
+                                  int lane) {
+  const int b = p / c.H_kv;
+  const Counters s = read_counters(c, b, n_new, T, keep);
+  half_t* k_win = reinterpret_cast<half_t*>(c.k_res) + (long long)p * c.R * kHeadDim;
+  half_t* v_win = reinterpret_cast<half_t*>(c.v_res) + (long long)p * c.R * kHeadDim;
+  const half_t* k_src = k_new + (long long)p * T * kHeadDim;
+  const half_t* v_src = v_new + (long long)p * T * kHeadDim;
+  bool row_bad = false;
+  for (int i = 0; i < s.n; ++i)
+    row_bad |= store_window_row(k_win, v_win, s.nr + i, k_src + (long long)i * kHeadDim, v_src + (long long)i * kHeadDim, lane);
+  if (lane == 0) {
+    if (row_bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
+    bool clean;
+    if (arrive(c, b, row_bad, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
   }
 }
 
@@ -180,41 +244,96 @@ __global__ __launch_bounds__(kThreads) void append_scan_kernel(kvlinc_cache c, c
   if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(c.split_done + (long long)b * c.H_kv + 1, 1);
 }
 
-__global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
-                                                                 const half_t* __restrict__ v_new,
-                                                                 const int32_t* __restrict__ n_new, int T, int keep) {
-  extern __shared__ __align__(16) unsigned char lds_raw[];
-  Lds& L = *reinterpret_cast<Lds*>(lds_raw);
+__device__ inline void unpack8(const uint4& raw, float (&x)[8]) {
+  const half2_t a = as_h2(raw.x), b = as_h2(raw.y), c = as_h2(raw.z), d = as_h2(raw.w);
+  x[0] = (float)a[0]; x[1] = (float)a[1]; x[2] = (float)b[0]; x[3] = (float)b[1];
+  x[4] = (float)c[0]; x[5] = (float)c[1]; x[6] = (float)d[0]; x[7] = (float)d[1];
+}
+__device__ inline bool nonfinite_any(const uint4& raw) {
+  return nonfinite_pair(raw.x) || nonfinite_pair(raw.y) || nonfinite_pair(raw.z) || nonfinite_pair(raw.w);
+}
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int b = blockIdx.x / c.H_kv;
-  const int g = blockIdx.x % c.H_kv;
-  const long long bh = (long long)b * c.H_kv + g;
+// reductions over the 16 lanes of a row, and over a pair of rows (lanes 0..31 / 32..63), result in every lane
+__device__ __forceinline__ float row16_min(float v) {
+  v = fminf(v, dpp_f<kRowRor1>(v));
+  v = fminf(v, dpp_f<kRowRor2>(v));
+  v = fminf(v, dpp_f<kRowRor4>(v));
+  return fminf(v, dpp_f<kRowRor8>(v));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f<kRowRor1>(v));
+  v = fmaxf(v, dpp_f<kRowRor2>(v));
+  v = fmaxf(v, dpp_f<kRowRor4>(v));
+  return fmaxf(v, dpp_f<kRowRor8>(v));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<kRowRor1>(v);
+  v += dpp_f<kRowRor2>(v);
+  v += dpp_f<kRowRor4>(v);
+  return v + dpp_f<kRowRor8>(v);
+}
+// The exchange swaps the odd rows of its first operand with the even rows of its second: given the same value twice,
+// lane l ends up with its own value and that of lane l ^ 16.  (The second copy is made opaque: this compiler otherwise
+// takes the two results of the exchange for equal.)
+__device__ __forceinline__ void rowpair_exchange(float v, float& mine_or_other, float& other_or_mine) {
+  uint32_t x = __builtin_bit_cast(uint32_t, v), y = x;
+  asm volatile("" : "+v"(y));
+  const auto a = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+  uint32_t a0 = a[0], a1 = a[1];
+  asm volatile("" : "+v"(a0), "+v"(a1));
+  mine_or_other = __builtin_bit_cast(float, a0);
+  other_or_mine = __builtin_bit_cast(float, a1);
+}
+__device__ __forceinline__ float rowpair_max(float v) {
+  float p, q;
+  rowpair_exchange(row16_max(v), p, q);
+  return fmaxf(p, q);
+}
+__device__ __forceinline__ float rowpair_sum(float v) {
+  float p, q;
+  rowpair_exchange(row16_sum(v), p, q);
+  return p + q;
+}
 
-  const int nq = c.n_quant[b];
-  const int nr = c.n_res[b];
-  int n = n_new ? n_new[b] : T;
-  n = n < 0 ? 0 : (n > T ? T : n);
-  const AppendPlan plan = plan_append(nq, nr, n, c.R, keep, c.max_groups);
-  if (plan.err || n == 0) {
-    commit_sequence(c, b, nq, n, plan, plan.err);
-    return;
-  }
+// bits of the binary16 number code - 1.5 that make the stored bit pair: hi = sign (codes 0, 1), lo = magnitude 1.5
+// rather than 0.5 (codes 0, 3)
+__device__ __forceinline__ uint32_t hi_of(uint32_t h16) { return (h16 >> 15) & 1u; }
+__device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u; }
+
+// One of the kParts workgroups that flush the groups of one (sequence, kv head).  All of them stage and quantize the
+// whole group (the quantizer's outputs feed every part of the state update); part fp writes a quarter of the record's
+// tile words (part 0 also the scales and zero-points) and owns the features 64 fp .. 64 fp + 63 of S and P.  The state
+// update runs on the matrix cores (16x16x32, binary16 operands whose products are exact: the centred codes are
+// multiples of 0.5, W_k is binary16, the key error and phi s are carried as two binary16 terms):
+//   logits[t][f] = sum_c (K - K_q)[t][c] W_k[c][f]   for the 128 features of the half of phi the part belongs to,
+//   phi = softmax over that half (Eq. 6),
+//   S[f][c] += sum_t (phi s_t)[t][f] (code[t][c] - 1.5) + sum_t phi[t][f] (z_t + 1.5 s_t),   P[f] += sum_t phi[t][f]   (Eq. 5)
+// with V_q[t][c] = z_t + s_t code[t][c].  S stays in registers for all groups of the call.  The matrix instruction lines
+// its 32 products and its addend up with the largest of them before it adds, so what it is given is kept small and of
+// both signs: every chunk's products start from a zero addend and are added to S by ordinary binary32 additions, the
+// codes are centred (the other part is the same for all channels of a row), and the two terms of the key error
+// are contracted separately.
+__device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
+                           const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int p = item / kParts, fp = item % kParts;
+  const int b = p / c.H_kv, g = p % c.H_kv;
+  const long long bh = p;
+  const Counters s = read_counters(c, b, n_new, T, keep);
+  const int nq = s.nq, nr = s.nr, n = s.n;
+  const AppendPlan plan = s.plan;
+
   {
     // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
     bool refuse = false;
-    if (T == 1 && plan.n_flush > 0) {
+    if (T == 1) {
       // A one-token append that flushes the window changes live state (S, P, the window's first slot) in every kv
-      // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.  (One
-      // that does not flush only fills a dead window slot: there each workgroup looks at its own row when it stores
-      // it, and the counters are not advanced if any of them votes against.)
-      for (int g0 = wave; g0 < c.H_kv; g0 += 4 * 8) {
+      // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.
+      for (int g0 = wave; g0 < c.H_kv; g0 += kWaves * 8) {
         uint32_t chk_k[8], chk_v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          const int g2 = g0 + 4 * u;
+          const int g2 = g0 + kWaves * u;
           const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
           chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
           chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
@@ -224,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
         float mag[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          refuse |= ((chk_k[u] & 0x7C00u) == 0x7C00u) || ((chk_k[u] & 0x7C000000u) == 0x7C000000u);
+          refuse |= nonfinite_pair(chk_k[u]);
           const half2_t h = as_h2(chk_v[u]);
           mag[u] = fabsf((float)h[0]) + fabsf((float)h[1]);
         }
@@ -245,19 +364,23 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
           for (int u = 0; u < 4; ++u) refuse |= nonfinite_bits((half_t)x0[u]) || nonfinite_bits((half_t)x1[u]);
         }
       }
-    } else if (T > 1 && c.H_kv > 1) {
+    } else if (c.H_kv > 1) {
       refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
-    } else if (T > 1) {
-      // bulk append, one kv head: this workgroup is the sequence's only one.  The new rows that will stay in the
-      // window (at most R) are looked at here; those that get quantized are looked at when their group is staged,
-      // before anything but dead storage has been written.
+    } else {
+      // bulk append, one kv head: the parts of this (sequence, kv head) are the sequence's only workgroups and see the
+      // same rows.  The new rows that will stay in the window (at most R) are looked at here; those that get quantized
+      // are looked at when their group is staged, before anything but dead storage has been written.
       const half_t* ks = k_new + (long long)b * T * kHeadDim;
       const half_t* vs = v_new + (long long)b * T * kHeadDim;
-      for (int u = max(plan.n_flush, nr) + wave; u < nr + n; u += kThreads / 64)
+      for (int u = max(plan.n_flush, nr) + wave; u < nr + n; u += kWaves)
         refuse |= row_is_bad(ks + (long long)(u - nr) * kHeadDim, vs + (long long)(u - nr) * kHeadDim, lane);
     }
     if (__syncthreads_or(refuse)) {
-      commit_sequence(c, b, nq, n, plan, KVLINC_ST_NONFINITE);
+      if (tid == 0) {
+        if (fp == 0) atomicOr(c.status, KVLINC_ST_NONFINITE);
+        bool clean;
+        if (arrive(c, b, true, &clean)) finish(c, b, nq, n, plan, false);
+      }
       return;
     }
   }
@@ -266,370 +389,507 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   const half_t* v_res = reinterpret_cast<const half_t*>(c.v_res) + bh * c.R * kHeadDim;
   const half_t* k_src = k_new + bh * (long long)T * kHeadDim;
   const half_t* v_src = v_new + bh * (long long)T * kHeadDim;
-  const bool have_states = c.S16 != nullptr;
+  const bool states_live = c.S16 != nullptr;
   const bool have_master = c.S != nullptr;  // fp32 master copy of S; without it the state lives in its binary16 tiles
 
-  // Correction states of this (sequence, kv head) (Eq. 5).  The update runs on the matrix cores (4x4x4 blocks with a
-  // broadcast A operand): wave w owns the features 64 w .. 64 w + 63, i.e. 16 blocks of 4 rows of S, each as two
-  // accumulators (channel halves) whose lane 4 b + j holds channel 64 hh + 4 b + j.  Thread f = tid owns P[f].
-  const int blk = lane >> 2, jq = lane & 3;
-  const uint32_t perm_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
-  const int fwave = 64 * wave;
-  const bool states_live = have_states && plan.n_groups > 0;
-  float4_t sacc[16][2];
-  half4_t wop[32];  // W_k of this wave's features as B operands: step cs = channels 4 cs .. 4 cs + 3
-  float P_f = 0.0f;
+  // matrix-core roles of a lane: column l16 of a 16-wide tile, rows 4 kq .. 4 kq + 3 of the result, and the eight
+  // contraction indices 8 kq .. 8 kq + 7 of each 32-wide step (the same in both operands, so any order of them serves).
+  // Logits: wave w forms the features 16 w .. 16 w + 15 of the half.  S update: wave w holds the rows 16 (w % 4) .. of
+  // the part's 64 and the channels 64 (w / 4) .. 64 (w / 4) + 63, four tiles of 16.
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int hs = fp >> 1;  // half of phi this part belongs to; its own features are 64 (fp & 1) + 0..63 of that half
+  const int fw = 16 * (wave & 3), cw0 = 4 * (wave >> 2);
+  const int frow = 64 * fp + fw + 4 * kq;  // first of the 4 rows of S this lane holds in every accumulator
+  half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
+
+  half8_t wfrag[4];  // W_k[channel 32 kk + 8 kq + i][feature 16 wave + l16 of the half]
+  float4_t acc[4];   // S[frow + r][16 (cw0 + ct) + l16]
+  // softmax roles: the two halves of a wave take one token each, lane j of a half the features 4 j .. 4 j + 3 of the
+  // 128; the part's own features sit in the lanes of row (fp & 1) of each half
+  const int hw = lane >> 5, j4 = lane & 31;
+  const bool own_lane = ((j4 >> 4) == (fp & 1));
+  const int fo = 4 * (j4 & 15);  // first of this lane's 4 own features (of 64)
+  float Pacc[4] = {0.f, 0.f, 0.f, 0.f};  // sums of phi over the tokens this half-wave normalises
   if (states_live) {
-    const half_t* tiles_in = reinterpret_cast<const half_t*>(c.S16) + bh * kRank * kHeadDim;
+    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + hs) * kHeadDim * (kRank / 2);
 #pragma unroll
-    for (int fb = 0; fb < 16; ++fb)
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        if (have_master) {
+      for (int i = 0; i < 8; ++i) wfrag[kk][i] = W0[(long long)(32 * kk + 8 * kq + i) * (kRank / 2) + 16 * wave + l16];
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            sacc[fb][hh][i] = c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane];
-        } else {  // tile (wave, hh, fb) holds exactly this accumulator
-          const half4_t t16 = *reinterpret_cast<const half4_t*>(tiles_in + (((wave * 2 + hh) * 16 + fb) * 64 + lane) * 4);
+    for (int ct = 0; ct < 4; ++ct) {
+      const int cc = cw0 + ct;
+      if (have_master) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) sacc[fb][hh][i] = (float)t16[i];
-        }
+        for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * cc + l16];
+      } else {
+        const half4_t t16 = *reinterpret_cast<const half4_t*>(
+            tiles + ((((fp * 2 + (cc >> 2)) * 16 + (fw >> 2) + kq) * 64) + 16 * (cc & 3) + l16) * 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[ct][r] = (float)t16[r];
       }
-    P_f = c.P[bh * kRank + tid];
-    // a lane reads 4 features of one channel (natural order of W); the lane quad transposes
-    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) +
-                       ((long long)g * 2 + (wave >> 1)) * kHeadDim * (kRank / 2) + (long long)jq * (kRank / 2) +
-                       64 * (wave & 1) + 4 * blk;
-#pragma unroll
-    for (int cs = 0; cs < 32; ++cs) {
-      const uint2 w = *reinterpret_cast<const uint2*>(W0 + (long long)(4 * cs) * (kRank / 2));
-      wop[cs] = quad_transpose(w.x, w.y, perm_sel, lane);
     }
   }
   bool bad = false;
+  const int sub = tid & 15, tq = tid >> 4;  // quantizer roles: channels 8 sub .. 8 sub + 7; tq = 0 .. 31
 
   for (int j = 0; j < plan.n_groups; ++j) {
     const int valid = min(kGroup, plan.n_flush - j * kGroup);
     const long long grp = (long long)(nq / kGroup) + j;
+    uint32_t* rec = c.groups + (bh * c.max_groups + grp) * kRecordWords;
+    half_t* rec16 = reinterpret_cast<half_t*>(rec);
+    const int ubase = j * kGroup;                    // index of the group's first token in the stream [window, new]
+    const int nrg = min(max(nr - ubase, 0), valid);  // tokens of this group that come from the window (only if j == 0)
     // ---- 1. stage the group's raw keys and (raw or already rotated) values in LDS -------------------------
-    for (int ch = tid; ch < kGroup * 16; ch += kThreads) {  // 16-byte chunks: 16 per token row
-      const int t = ch >> 4, part = ch & 15;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (t < valid) {
-        const int u = j * kGroup + t;  // index in the stream [window tokens, new tokens]
-        if (u < nr) {
-          kv = *reinterpret_cast<const uint4*>(k_res + (long long)u * kHeadDim + part * 8);
-          // rotated values live 4 slots per channel: slot u, channel ch at [u/4][ch][u%4]
-          half_t tmp[8];
+    {
+      uint4 kv[4], vv[4];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) tmp[i] = v_res[((long long)(u >> 2) * kHeadDim + part * 8 + i) * 4 + (u & 3)];
-          vv = *reinterpret_cast<const uint4*>(tmp);
-        } else {
-          kv = *reinterpret_cast<const uint4*>(k_src + (long long)(u - nr) * kHeadDim + part * 8);
-          vv = *reinterpret_cast<const uint4*>(v_src + (long long)(u - nr) * kHeadDim + part * 8);
+      for (int i = 0; i < 4; ++i) {  // 16-byte pieces: 16 per token row; token tq + 32 i, piece sub
+        const int t = tq + 32 * i, u = ubase + t;
+        kv[i] = make_uint4(0, 0, 0, 0);
+        vv[i] = make_uint4(0, 0, 0, 0);
+        if (t < valid) {
+          if (u < nr) {
+            kv[i] = *reinterpret_cast<const uint4*>(k_res + (long long)u * kHeadDim + sub * 8);
+          } else {
+            kv[i] = *reinterpret_cast<const uint4*>(k_src + (long long)(u - nr) * kHeadDim + sub * 8);
+            vv[i] = *reinterpret_cast<const uint4*>(v_src + (long long)(u - nr) * kHeadDim + sub * 8);
+          }
         }
       }
-      uint32_t* dk = reinterpret_cast<uint32_t*>(&L.sK[t][part * 8]);
-      uint32_t* dv = reinterpret_cast<uint32_t*>(&L.sV[t][part * 8]);
-      dk[0] = kv.x; dk[1] = kv.y; dk[2] = kv.z; dk[3] = kv.w;
-      dv[0] = vv.x; dv[1] = vv.y; dv[2] = vv.z; dv[3] = vv.w;
+      // window values live 4 slots per channel: a 16-byte load brings 4 tokens of 2 channels
+      uint4 wv[4];
+      const int n_wv = ((nrg + 3) >> 2) * 64;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int it = tid + kThreads * i;
+        wv[i] = make_uint4(0, 0, 0, 0);
+        if (it < n_wv) wv[i] = *reinterpret_cast<const uint4*>(v_res + ((long long)(it >> 6) * kHeadDim + 2 * (it & 63)) * 4);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = tq + 32 * i;
+        *reinterpret_cast<uint4*>(&L.bK[t][sub * 8]) = kv[i];
+        if (t >= nrg) *reinterpret_cast<uint4*>(&L.bV[t][sub * 8]) = vv[i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int it = tid + kThreads * i, q = it >> 6, cp = it & 63;
+        if (it < n_wv) {
+          const uint4 w = wv[i];
+          const uint32_t lo[4] = {w.x & 0xffffu, w.x >> 16, w.y & 0xffffu, w.y >> 16};
+          const uint32_t hi[4] = {w.z & 0xffffu, w.z >> 16, w.w & 0xffffu, w.w >> 16};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (4 * q + e < nrg) *reinterpret_cast<uint32_t*>(&L.bV[4 * q + e][2 * cp]) = lo[e] | (hi[e] << 16);
+        }
+      }
     }
     __syncthreads();
     // rotate the rows that came from new tokens (window rows are rotated already)
-    for (int tb = wave; tb < valid; tb += 4 * (kThreads / 64)) {  // rows tb, tb + 4, tb + 8, tb + 12 together
-      float x0[4], x1[4];
-      bool act[4];
+    if (nrg < valid) {
+      for (int tb = wave; tb < valid; tb += 4 * kWaves) {  // rows tb, tb + 8, tb + 16, tb + 24 together
+        float x0[4], x1[4];
+        bool act[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int t = tb + 4 * u;
-        act[u] = t < valid && j * kGroup + t >= nr;
-        x0[u] = act[u] ? (float)L.sV[t][2 * lane] : 0.0f;
-        x1[u] = act[u] ? (float)L.sV[t][2 * lane + 1] : 0.0f;
-      }
-      if (!(act[0] || act[1] || act[2] || act[3])) continue;
-      fwht128_wave_multi<4>(x0, x1, lane);
+        for (int u = 0; u < 4; ++u) {
+          const int t = tb + kWaves * u;
+          act[u] = t < valid && t >= nrg;
+          x0[u] = act[u] ? (float)L.bV[t][2 * lane] : 0.0f;
+          x1[u] = act[u] ? (float)L.bV[t][2 * lane + 1] : 0.0f;
+        }
+        if (!(act[0] || act[1] || act[2] || act[3])) continue;
+        fwht128_wave_multi<4>(x0, x1, lane);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (act[u]) {
-          const int t = tb + 4 * u;
-          L.sV[t][2 * lane] = (half_t)x0[u];
-          L.sV[t][2 * lane + 1] = (half_t)x1[u];
+        for (int u = 0; u < 4; ++u) {
+          if (act[u]) {
+            const int t = tb + kWaves * u;
+            L.bV[t][2 * lane] = (half_t)x0[u];
+            L.bV[t][2 * lane + 1] = (half_t)x1[u];
+          }
         }
       }
+      __syncthreads();
     }
-    __syncthreads();
-    // ---- 2. Eq. 1: keys per channel over the group's tokens, rotated values per token over the channels ----
-    if (tid < kGroup) {
-      const int ch = tid;
-      float mn = INFINITY, mx = -INFINITY;
-#pragma unroll 8
-      for (int t = 0; t < valid; ++t) {
-        const half_t h = L.sK[t][ch];
-        bad |= nonfinite_bits(h);
-        const float x = (float)h;
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
-      }
-      const Q2 p = q2_params(mn, mx);
-#pragma unroll 8
-      for (int t = 0; t < kGroup; ++t) L.cK[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sK[t][ch], p) : 0;
-      L.kScale[ch] = p.s;
-      L.kZero[ch] = p.z;
-      half_t* rec16 = reinterpret_cast<half_t*>(c.groups + (bh * c.max_groups + grp) * kRecordWords);
-      rec16[2 * kRecKeyScale + ch] = p.s16;
-      rec16[2 * kRecKeyZero + ch] = p.z16;
-    } else {
-      const int t = tid - kGroup;
-      Q2 p;
-      p.z = p.s = 0.0f;
-      p.z16 = p.s16 = (half_t)0.0f;
-      if (t < valid) {
-        float mn = INFINITY, mx = -INFINITY;
-#pragma unroll 8
-        for (int ch = 0; ch < kHeadDim; ++ch) {
-          const half_t h = L.sV[t][ch];
-          bad |= nonfinite_bits(h);
-          const float x = (float)h;
-          mn = fminf(mn, x);
-          mx = fmaxf(mx, x);
-        }
-        p = q2_params(mn, mx);
-      }
-#pragma unroll 8
-      for (int ch = 0; ch < kHeadDim; ++ch) L.cV[t][ch] = t < valid ? (uint8_t)q2_code((float)L.sV[t][ch], p) : 0;
-      L.vScale[t] = p.s;
-      L.vZero[t] = p.z;
-      half_t* rec16 = reinterpret_cast<half_t*>(c.groups + (bh * c.max_groups + grp) * kRecordWords);
-      const int sz_word = kRecValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
-      rec16[2 * sz_word] = p.s16;
-      rec16[2 * sz_word + 1] = p.z16;
-    }
-    __syncthreads();
-    // ---- 3. pack the two 4 KB tiles ------------------------------------------------------------------------
+    // ---- 2. Eq. 1: rotated values per token over the channels, keys per channel over the group's tokens ----
+    // values: the 16 lanes of a row share the tokens 4 tq .. 4 tq + 3 (8 channels each); rows beyond `valid` are zero
+    // and quantize to scale 0, zero-point 0, codes 0
     {
-      uint32_t* k_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecKeyTile;
-      uint32_t* v_tile = c.groups + (bh * c.max_groups + grp) * kRecordWords + kRecValueTile;
-      for (int wi = tid; wi < kTileWords; wi += kThreads) {
-        // word wi = ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w of both tiles: block n of 16 rows, row j, quarter g of the
-        // contraction axis; code p of the word belongs to position k = 32 g + 16 w + 8 (p % 2) + p / 2 and is stored as the
-        // bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for the codes 0..3, hi in bit 4 (p / 2) + 3 - p % 2, lo two below.
-        // key tile: row = token 16 n + j, position k = channel k;
-        // value tile: row = channel 16 n + j, position k = token 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2.
-        const int w = wi & 1, n = 2 * (wi >> 8) + ((wi >> 1) & 1), l = (wi >> 2) & 63, jr = l & 15, gq4 = l >> 4;
-        const int row = 16 * n + jr, k0 = 32 * gq4 + 16 * w;
-        const int tok0 = 4 * ((k0 >> 4) & 3) + 2 * (k0 >> 6);  // token of position k0 + 8 e + i is 16 i + tok0 + e
-        uint32_t kw = 0, vw = 0;
+      float x[4][8], mn[4], mx[4];
 #pragma unroll
-        for (int pp = 0; pp < 16; ++pp) {
-          const int e = pp & 1, i = pp >> 1;
-          const uint32_t ck = L.cK[row][k0 + 8 * e + i], cv = L.cV[16 * i + tok0 + e][row];
-          // hi = not (c / 2), lo = not (c / 2 xor c % 2)
-          kw |= (((ck >> 1) ^ 1u) << (4 * i + 3 - e)) | ((((ck >> 1) ^ ck ^ 1u) & 1u) << (4 * i + 1 - e));
-          vw |= (((cv >> 1) ^ 1u) << (4 * i + 3 - e)) | ((((cv >> 1) ^ cv ^ 1u) & 1u) << (4 * i + 1 - e));
-        }
-        k_tile[wi] = kw;
-        v_tile[wi] = vw;
+      for (int i = 0; i < 4; ++i) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(&L.bV[4 * tq + i][8 * sub]);
+        bad |= nonfinite_any(raw);
+        unpack8(raw, x[i]);
+        mn[i] = fminf(fminf(fminf(x[i][0], x[i][1]), fminf(x[i][2], x[i][3])), fminf(fminf(x[i][4], x[i][5]), fminf(x[i][6], x[i][7])));
+        mx[i] = fmaxf(fmaxf(fmaxf(x[i][0], x[i][1]), fmaxf(x[i][2], x[i][3])), fmaxf(fmaxf(x[i][4], x[i][5]), fmaxf(x[i][6], x[i][7])));
       }
-    }
-    // ---- 4. S += phi_k(K - K_q)^T V_q, P += sum phi_k(K - K_q) over the group's valid tokens (Eq. 5, Eq. 6) ----
-    // With V_q[t][c] = z_t + s_t code[t][c]:  S[f][c] += sum_t (phi[t][f] s_t) code[t][c] + sum_t phi[t][f] z_t.
-    // Both contractions take binary16 operands whose products are exact: the codes are small integers, W_k is
-    // binary16, and the key error and phi s are split into two binary16 terms (hi + lo).
-    if (states_live) {
-      float Z_f = 0.0f;  // sum_t phi[t][f] z_t of this group, f = tid
-      for (int t0 = 0; t0 < valid; t0 += kChunk) {
-        __syncthreads();
-        for (int i = tid; i < kChunk * kHeadDim; i += kThreads) {
-          const int tt = i >> 7, ch = i & 127, t = t0 + tt;
-          float ke = 0.0f;
-          if (t < valid) ke = (float)L.sK[t][ch] - (L.kScale[ch] * (float)L.cK[t][ch] + L.kZero[ch]);
-          const half_t hi = (half_t)ke;
-          L.kErrH[tt][ch] = hi;
-          L.kErrL[tt][ch] = (half_t)(ke - (float)hi);
-          L.cVh[tt][ch] = (half_t)(float)L.cV[t][ch];
-        }
-        __syncthreads();
-        // logits[t][f] = sum_c kErr[t][c] W[c][f]: rows = 4 tokens, block = 4 features, k = 4 channels
-        {
-          float4_t dH[4], dL[4];
-          half4_t aH[4][2], aL[4][2];
-#pragma clang loop unroll(full)
-          for (int tb = 0; tb < 4; ++tb) {
-            dH[tb] = float4_t{0.f, 0.f, 0.f, 0.f};
-            dL[tb] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma clang loop unroll(full)
-            for (int pr = 0; pr < 2; ++pr) {
-              aH[tb][pr] = *reinterpret_cast<const half4_t*>(&L.kErrH[4 * tb + jq][64 * pr + 4 * blk]);
-              aL[tb][pr] = *reinterpret_cast<const half4_t*>(&L.kErrL[4 * tb + jq][64 * pr + 4 * blk]);
-            }
-          }
-#pragma clang loop unroll(full)
-          for (int cs = 0; cs < 32; ++cs)
-#pragma clang loop unroll(full)
-            for (int tb = 0; tb < 4; ++tb) {
-              dH[tb] = mfma_bcast(aH[tb][cs >> 4], wop[cs], dH[tb], cs & 15);
-              dL[tb] = mfma_bcast(aL[tb][cs >> 4], wop[cs], dL[tb], cs & 15);
-            }
-#pragma clang loop unroll(full)
-          for (int tb = 0; tb < 4; ++tb)
-#pragma clang loop unroll(full)
-            for (int i = 0; i < 4; ++i) L.phi[4 * tb + i][fwave + lane] = dH[tb][i] + dL[tb][i];
-        }
-        __syncthreads();
-        // softmax over each half (128 features) of each token row: 2*kChunk rows, a wave takes two rows at a time so
-        // that their cross-lane reductions overlap.  Besides phi (fp32, for P and the zero-point term) it leaves
-        // phi s_t as two binary16 terms, feature-major.
-        for (int row = 2 * wave; row < 2 * kChunk; row += 2 * (kThreads / 64)) {
-          float a0[2], a1[2], m[2], e0[2], e1[2], sum[2];
-#pragma clang loop unroll(full)
-          for (int u = 0; u < 2; ++u) {
-            const float* p = &L.phi[(row + u) >> 1][((row + u) & 1) * 128];
-            a0[u] = p[lane];
-            a1[u] = p[lane + 64];
-            m[u] = fmaxf(a0[u], a1[u]);
-          }
-#pragma clang loop unroll(full)
-          for (int u = 0; u < 2; ++u) m[u] = wave_allmax(m[u]);
-#pragma clang loop unroll(full)
-          for (int u = 0; u < 2; ++u) {
-            e0[u] = __expf(a0[u] - m[u]);
-            e1[u] = __expf(a1[u] - m[u]);
-            sum[u] = e0[u] + e1[u];
-          }
-#pragma clang loop unroll(full)
-          for (int u = 0; u < 2; ++u) sum[u] = wave_allsum(sum[u]);
-#pragma clang loop unroll(full)
-          for (int u = 0; u < 2; ++u) {
-            const int tt = (row + u) >> 1, hs = (row + u) & 1;
-            const bool live = t0 + tt < valid;
-            const float inv = live ? 1.0f / sum[u] : 0.0f;
-            const float sc_t = live ? L.vScale[t0 + tt] : 0.0f;
-            const float p0 = e0[u] * inv, p1 = e1[u] * inv;
-            L.phi[tt][hs * 128 + lane] = p0;
-            L.phi[tt][hs * 128 + lane + 64] = p1;
-            const float w0 = p0 * sc_t, w1 = p1 * sc_t;
-            const half_t h0 = (half_t)w0, h1 = (half_t)w1;
-            L.phTH[hs * 128 + lane][tt] = h0;
-            L.phTH[hs * 128 + lane + 64][tt] = h1;
-            L.phTL[hs * 128 + lane][tt] = (half_t)(w0 - (float)h0);
-            L.phTL[hs * 128 + lane + 64][tt] = (half_t)(w1 - (float)h1);
-          }
-        }
-        __syncthreads();
-#pragma clang loop unroll(full)
-        for (int tt = 0; tt < kChunk; ++tt) {
-          const float ph = L.phi[tt][tid];
-          P_f += ph;
-          Z_f += ph * L.vZero[min(t0 + tt, kGroup - 1)];
-        }
-        // S[f][c] += sum_t (phi s)[t][f] code[t][c]: rows = 4 features, block = 4 channels, k = 4 tokens
-        {
-          half4_t bop[4][2];
-#pragma clang loop unroll(full)
-          for (int ts = 0; ts < 4; ++ts)
-#pragma clang loop unroll(full)
-            for (int hh = 0; hh < 2; ++hh) {
-              half4_t v;
-#pragma clang loop unroll(full)
-              for (int k = 0; k < 4; ++k) v[k] = L.cVh[4 * ts + k][64 * hh + lane];
-              bop[ts][hh] = v;
-            }
-          const int ts_mine = blk & 3;  // the A operand of token step ts is taken from block ts
-#pragma clang loop unroll(full)
-          for (int fb0 = 0; fb0 < 16; fb0 += 4) {
-            half4_t aH[4], aL[4];
-#pragma clang loop unroll(full)
-            for (int u = 0; u < 4; ++u) {
-              const int f = fwave + 4 * (fb0 + u) + jq;
-              aH[u] = *reinterpret_cast<const half4_t*>(&L.phTH[f][4 * ts_mine]);
-              aL[u] = *reinterpret_cast<const half4_t*>(&L.phTL[f][4 * ts_mine]);
-            }
-#pragma clang loop unroll(full)
-            for (int ts = 0; ts < 4; ++ts)
-#pragma clang loop unroll(full)
-              for (int hh = 0; hh < 2; ++hh)
-#pragma clang loop unroll(full)
-                for (int u = 0; u < 4; ++u) {
-                  sacc[fb0 + u][hh] = mfma_bcast(aH[u], bop[ts][hh], sacc[fb0 + u][hh], ts);
-                  sacc[fb0 + u][hh] = mfma_bcast(aL[u], bop[ts][hh], sacc[fb0 + u][hh], ts);
-                }
-          }
-        }
-      }
-      // the zero-point term is the same for every channel of a row
-      __syncthreads();
-      L.zs[tid] = Z_f;
-      __syncthreads();
-#pragma clang loop unroll(full)
-      for (int fb = 0; fb < 16; ++fb) {
-        const float4 z4 = *reinterpret_cast<const float4*>(&L.zs[fwave + 4 * fb]);
-#pragma clang loop unroll(full)
-        for (int hh = 0; hh < 2; ++hh) {
-          sacc[fb][hh][0] += z4.x;
-          sacc[fb][hh][1] += z4.y;
-          sacc[fb][hh][2] += z4.z;
-          sacc[fb][hh][3] += z4.w;
-        }
-      }
-    }
-    __syncthreads();
-  }
-
-  // A fault seen only now (one kv head per sequence in a bulk append: this workgroup is the sequence's only one) leaves
-  // states, window and counters as they were; the records written above lie beyond n_quant and are dead storage.
-  if (__syncthreads_or(bad)) {
-    commit_sequence(c, b, nq, n, plan, KVLINC_ST_NONFINITE);
-    return;
-  }
-  if (states_live) {
-    // fp32 master copy (if the cache keeps one), row-major, and the binary16 tiles the decode kernel reads: tile (64-feature block = wave,
-    // channel half hh, feature step fb) holds S[64 wave + 4 fb + k][64 hh + l] at [l][k] -- exactly one accumulator.
-    // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
-    half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
-    bool out_of_range = false;
 #pragma unroll
-    for (int fb = 0; fb < 16; ++fb)
+      for (int i = 0; i < 4; ++i) {
+        mn[i] = row16_min(mn[i]);
+        mx[i] = row16_max(mx[i]);
+      }
+      Q2 pv[4];
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        half4_t t16;
+      for (int i = 0; i < 4; ++i) pv[i] = q2_params(mn[i], mx[i]);
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {  // two channels = 8 halfs = one 16-byte store
+        half8_t h;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float v = sacc[fb][hh][i];
-          if (have_master) c.S[(bh * kRank + fwave + 4 * fb + i) * kHeadDim + 64 * hh + lane] = v;
-          out_of_range |= !(fabsf(v) <= 65504.0f);
-          t16[i] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+          h[i] = (half_t)((float)q2_code(x[i][e], pv[i]) - 1.5f);
+          h[4 + i] = (half_t)((float)q2_code(x[i][e + 1], pv[i]) - 1.5f);
         }
-        *reinterpret_cast<half4_t*>(tiles + (((wave * 2 + hh) * 16 + fb) * 64 + lane) * 4) = t16;
+        *reinterpret_cast<half8_t*>(&L.cV[tq][8 * sub + e][0]) = h;
       }
-    c.P[bh * kRank + tid] = P_f;
-    if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 && lane == 0) atomicOr(c.status, KVLINC_ST_STATE_RANGE);
+      if (sub < 4) {  // lane sub of the row writes token 4 tq + sub
+        Q2 mine = pv[0];
+        if (sub == 1) mine = pv[1];
+        if (sub == 2) mine = pv[2];
+        if (sub == 3) mine = pv[3];
+        const int t = 4 * tq + sub;
+        L.vScale[t] = mine.s;
+        L.vCentre[t] = mine.z + 1.5f * mine.s;
+        if (fp == 0) {
+          const int sz_word = kRecValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
+          rec16[2 * sz_word] = mine.s16;
+          rec16[2 * sz_word + 1] = mine.z16;
+        }
+      }
+    }
+    // keys: minima / maxima of 8 channels over the tokens tq, tq + 32, ...
+    {
+      float kmn[8], kmx[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        kmn[e] = INFINITY;
+        kmx[e] = -INFINITY;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = tq + 32 * i;
+        if (t < valid) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(&L.bK[t][8 * sub]);
+          bad |= nonfinite_any(raw);
+          float x[8];
+          unpack8(raw, x);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            kmn[e] = fminf(kmn[e], x[e]);
+            kmx[e] = fmaxf(kmx[e], x[e]);
+          }
+        }
+      }
+      half8_t hmn, hmx;  // exact: the values are fp16 values or infinities
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        hmn[e] = (half_t)kmn[e];
+        hmx[e] = (half_t)kmx[e];
+      }
+      *reinterpret_cast<half8_t*>(&L.u.part.mn[tq][8 * sub]) = hmn;
+      *reinterpret_cast<half8_t*>(&L.u.part.mx[tq][8 * sub]) = hmx;
+    }
+    __syncthreads();
+    if (tid < 2 * kGroup) {  // threads 0..127 the minima, 128..255 the maxima (parked in the scale / zero-point slots)
+      const int ch = tid & (kGroup - 1);
+      const half_t(*src)[kGroup] = tid < kGroup ? L.u.part.mn : L.u.part.mx;
+      float v = (float)src[0][ch];
+#pragma unroll
+      for (int r = 1; r < kThreads / 16; ++r) v = tid < kGroup ? fminf(v, (float)src[r][ch]) : fmaxf(v, (float)src[r][ch]);
+      (tid < kGroup ? L.kZero : L.kScale)[ch] = v;
+    }
+    __syncthreads();
+    if (tid < kGroup) {
+      const Q2 pk = q2_params(L.kZero[tid], L.kScale[tid]);
+      L.kScale[tid] = pk.s;
+      L.kZero[tid] = pk.z;
+      if (fp == 0) {
+        rec16[2 * kRecKeyScale + tid] = pk.s16;
+        rec16[2 * kRecKeyZero + tid] = pk.z16;
+      }
+    }
+    __syncthreads();
+    // key codes -- this part's quarter of the key tile goes out from registers -- and K - K_q as two binary16 terms in
+    // place of the staged tiles.
+    // Tile word ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w holds, for the row 16 n + j, the positions
+    // k = 32 g + 16 w + 8 (p % 2) + p / 2, p = 0..15: code p as the bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for the
+    // codes 0..3, hi in bit 4 (p / 2) + 3 - p % 2, lo two below.  Key tile: row = token, position = channel: this
+    // thread's 8 channels are the p % 2 = sub % 2 half of the word of (g, w) = (sub / 4, (sub / 2) % 2), its neighbour
+    // in the lane pair has the other half.
+    {
+      Q2 pk[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pk[e].s = L.kScale[8 * sub + e];
+        pk[e].z = L.kZero[8 * sub + e];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = tq + 32 * i;
+        const uint4 raw = *reinterpret_cast<const uint4*>(&L.bK[t][8 * sub]);
+        float x[8];
+        unpack8(raw, x);
+        half8_t eh, el;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t code = t < valid ? q2_code(x[e], pk[e]) : 0u;
+          float ke = t < valid ? x[e] - (pk[e].s * (float)code + pk[e].z) : 0.0f;
+          asm volatile("" : "+v"(ke));  // the binary32 difference first, then its two binary16 terms
+          eh[e] = (half_t)ke;
+          el[e] = (half_t)(ke - (float)eh[e]);
+          // hi = not (code / 2), lo = not (code / 2 xor code % 2)
+          bits |= (((code >> 1) ^ 1u) << (4 * e + 3 - (sub & 1))) | ((((code >> 1) ^ code ^ 1u) & 1u) << (4 * e + 1 - (sub & 1)));
+        }
+        *reinterpret_cast<half8_t*>(&L.bK[t][8 * sub]) = eh;
+        *reinterpret_cast<half8_t*>(&L.bV[t][8 * sub]) = el;
+        bits |= dpp_u<kQuadSwap1>(bits);
+        if (i == fp && (sub & 1) == 0) {  // tokens 32 fp .. 32 fp + 31 are the blocks n = 2 fp, 2 fp + 1
+          const int nb = t >> 4, jr = t & 15;
+          rec[kRecKeyTile + ((nb >> 1) * 64 + jr + 16 * (sub >> 2)) * 4 + 2 * (nb & 1) + ((sub >> 1) & 1)] = bits;
+        }
+      }
+    }
+    // ---- 3. this part's quarter of the value tile: row = channel 16 n + j, position k = token
+    // 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2, the bit pairs read off the centred codes ----
+    if (tid < kTileWords / kParts) {
+      // (the centred codes of all tokens were stored before the last barrier)
+      const int wi = (kTileWords / kParts) * fp + tid;
+      const int w = wi & 1, nb = 2 * (wi >> 8) + ((wi >> 1) & 1), l = (wi >> 2) & 63, jr = l & 15, gq4 = l >> 4;
+      const int row = 16 * nb + jr, k0 = 32 * gq4 + 16 * w;
+      const int tok0 = 4 * ((k0 >> 4) & 3) + 2 * (k0 >> 6);  // token of position k0 + 8 e + i is 16 i + tok0 + e
+      uint32_t vw = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = 16 * i + tok0;  // even: t and t + 1 share a quad of tokens
+        const uint32_t two = *reinterpret_cast<const uint32_t*>(&L.cV[t >> 2][row][t & 3]);
+        const uint32_t h0 = two & 0xffffu, h1 = two >> 16;
+        vw |= (hi_of(h0) << (4 * i + 3)) | (lo_of(h0) << (4 * i + 1)) | (hi_of(h1) << (4 * i + 2)) | (lo_of(h1) << (4 * i));
+      }
+      rec[kRecValueTile + wi] = vw;
+    }
+    __syncthreads();
+    // ---- 4. the group's contribution to S and P (Eq. 5, Eq. 6), 32 tokens at a time --------------------------
+    if (states_live) {
+      float Zacc[4] = {0.f, 0.f, 0.f, 0.f};  // sums of phi (z_t + 1.5 s_t) over the tokens this half-wave normalises
+      for (int t0 = 0; t0 < valid; t0 += kChunk) {
+        // a. logits: this wave's 16 features of the half, two tiles of 16 tokens
+        {
+          float4_t d[2], dl[2];
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            d[tt] = dl[tt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            const int tr = t0 + 16 * tt + l16;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+              const half8_t aH = *reinterpret_cast<const half8_t*>(&L.bK[tr][32 * kk + 8 * kq]);
+              const half8_t aL = *reinterpret_cast<const half8_t*>(&L.bV[tr][32 * kk + 8 * kq]);
+              d[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, wfrag[kk], d[tt], 0, 0, 0);
+              dl[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, wfrag[kk], dl[tt], 0, 0, 0);
+            }
+          }
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) L.u.lg[16 * tt + 4 * kq + r][16 * wave + l16] = d[tt][r] + dl[tt][r];
+        }
+        __syncthreads();
+        // b. softmax over the half for 4 tokens per wave, one per half-wave and step; phi of the part's own 64
+        // features goes on as phi s_t in two binary16 terms, feature-major
+        {
+          float4 a[2];
+          float m[2], sum[2];
+          float e[2][4];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            a[u] = *reinterpret_cast<const float4*>(&L.u.lg[4 * wave + 2 * u + hw][4 * j4]);
+            m[u] = fmaxf(fmaxf(a[u].x, a[u].y), fmaxf(a[u].z, a[u].w));
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) m[u] = rowpair_max(m[u]);
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            e[u][0] = __expf(a[u].x - m[u]);
+            e[u][1] = __expf(a[u].y - m[u]);
+            e[u][2] = __expf(a[u].z - m[u]);
+            e[u][3] = __expf(a[u].w - m[u]);
+            sum[u] = (e[u][0] + e[u][1]) + (e[u][2] + e[u][3]);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) sum[u] = rowpair_sum(sum[u]);
+          if (own_lane) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+              const int tc = 4 * wave + 2 * u + hw, t = t0 + tc;
+              const bool live = t < valid;
+              const float inv = live ? 1.0f / sum[u] : 0.0f;
+              const float sc = L.vScale[t], ce = L.vCentre[t];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float ph = e[u][i] * inv;
+                Pacc[i] += ph;
+                Zacc[i] += ph * ce;
+                float ws = ph * sc;
+                // The two terms must add up to the binary32 product: keep its rounding apart from the conversion (a
+                // fused multiply-and-convert would round the exact product once, and the low term would then belong
+                // to another high term in the rare near-tie cases).
+                asm volatile("" : "+v"(ws));
+                const half_t h = (half_t)ws;
+                L.phH[fo + i][tc] = h;
+                L.phL[fo + i][tc] = (half_t)(ws - (float)h);
+              }
+            }
+          }
+        }
+        __syncthreads();
+        // c. S[f][c] += sum_t (phi s)[t][f] (code[t][c] - 1.5): this wave's 16 features, 4 tiles of 16 channels
+        {
+          const half8_t aH = *reinterpret_cast<const half8_t*>(&L.phH[fw + l16][8 * kq]);
+          const half8_t aL = *reinterpret_cast<const half8_t*>(&L.phL[fw + l16][8 * kq]);
+          const int q0 = (t0 >> 2) + 2 * kq;  // the lane's 8 tokens are two quads
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) {
+            const int ch = 16 * (cw0 + ct) + l16;
+            const half4_t b0 = *reinterpret_cast<const half4_t*>(&L.cV[q0][ch][0]);
+            const half4_t b1 = *reinterpret_cast<const half4_t*>(&L.cV[q0 + 1][ch][0]);
+            const half8_t bc = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+            float4_t d = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, bc, float4_t{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, bc, d, 0, 0, 0);
+            acc[ct] += d;
+          }
+        }
+      }
+      // the term of the code centres is the same for every channel of a row
+      __syncthreads();
+      if (own_lane) *reinterpret_cast<float4*>(&L.red[2 * wave + hw][fo]) = make_float4(Zacc[0], Zacc[1], Zacc[2], Zacc[3]);
+      __syncthreads();
+      {
+        float z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w2 = 0; w2 < 2 * kWaves; ++w2) {
+          const float4 zz = *reinterpret_cast<const float4*>(&L.red[w2][fw + 4 * kq]);
+          z[0] += zz.x; z[1] += zz.y; z[2] += zz.z; z[3] += zz.w;
+        }
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[ct][r] += z[r];
+      }
+    }
+    __syncthreads();
   }
 
-  // ---- 5. new tokens that stay in the window: raw key, rotated value ----------------------------------------
-  // Stream index u >= n_flush goes to slot u - n_flush.  Old window tokens either all left (n_flush >= nr) or
-  // none did (n_flush == 0, they keep their slots), so only new tokens are written here.
-  half_t* k_win = reinterpret_cast<half_t*>(c.k_res) + bh * c.R * kHeadDim;
-  half_t* v_win = reinterpret_cast<half_t*>(c.v_res) + bh * c.R * kHeadDim;
-  const int first_new = max(plan.n_flush, nr);
-  bool row_bad = false;  // only a one-token append that does not flush can still meet a non-finite row here
-  for (int u = first_new + wave; u < nr + n; u += kThreads / 64) {
-    const int slot = u - plan.n_flush;
-    const half_t* ks = k_src + (long long)(u - nr) * kHeadDim;
-    const half_t* vs = v_src + (long long)(u - nr) * kHeadDim;
-    const uint32_t kk = *reinterpret_cast<const uint32_t*>(ks + 2 * lane);
-    float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
-    fwht128_wave(x0, x1, lane);
-    const half_t r0 = (half_t)x0, r1 = (half_t)x1;
-    const bool mine = ((kk & 0x7C00u) == 0x7C00u) || ((kk & 0x7C000000u) == 0x7C000000u) || nonfinite_bits(r0) || nonfinite_bits(r1);
-    if (__builtin_amdgcn_ballot_w64(mine) != 0) {  // nothing of a faulty row reaches the window
-      row_bad = true;
-      continue;
+  // A fault seen only now (one kv head per sequence in a bulk append; every part sees it) leaves states, window and
+  // counters as they were; the records written above lie beyond n_quant and are dead storage.
+  const bool any_bad = __syncthreads_or(bad) != 0;
+  if (!any_bad && states_live) {
+    // fp32 master copy (if the cache keeps one), row-major, and the binary16 tiles the decode kernel reads: tile
+    // (64-feature block, channel half hh, feature step fb) holds S[64 block + 4 fb + k][64 hh + l] at [l][k].
+    // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
+    bool out_of_range = false;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const int cc = cw0 + ct;
+      half4_t t16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = acc[ct][r];
+        if (have_master) c.S[(bh * kRank + frow + r) * kHeadDim + 16 * cc + l16] = v;
+        out_of_range |= !(fabsf(v) <= 65504.0f);
+        t16[r] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+      }
+      *reinterpret_cast<half4_t*>(tiles + ((((fp * 2 + (cc >> 2)) * 16 + (fw >> 2) + kq) * 64) + 16 * (cc & 3) + l16) * 4) = t16;
     }
-    *reinterpret_cast<uint32_t*>(k_win + (long long)slot * kHeadDim + 2 * lane) = kk;
-    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = r0;
-    v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = r1;
+    if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 && lane == 0) atomicOr(c.status, KVLINC_ST_STATE_RANGE);
+    if (own_lane) *reinterpret_cast<float4*>(&L.red[2 * wave + hw][fo]) = make_float4(Pacc[0], Pacc[1], Pacc[2], Pacc[3]);
+    __syncthreads();
+    if (tid < 64) {
+      float* P = c.P + bh * kRank + 64 * fp;
+      float add = 0.0f;
+#pragma unroll
+      for (int w2 = 0; w2 < 2 * kWaves; ++w2) add += L.red[w2][tid];
+      P[tid] = P[tid] + add;
+    }
   }
-  commit_sequence(c, b, nq, n, plan, __syncthreads_or(row_bad) ? KVLINC_ST_NONFINITE : 0);
+
+  // count this part in; the arrival that completes the sequence stores the new rows that stay in the window -- raw
+  // key, rotated value -- for all its kv heads (only now have all parts staged the window's old rows) and commits.
+  // Stream index u >= n_flush goes to slot u - n_flush; old window tokens all left (n_flush >= n_res).
+  if (tid == 0) {
+    if (any_bad && fp == 0) atomicOr(c.status, KVLINC_ST_NONFINITE);
+    bool clean;
+    const bool last = arrive(c, b, any_bad, &clean);
+    L.last_flag = last ? (clean ? 2 : 1) : 0;
+  }
+  __syncthreads();
+  const int flag = L.last_flag;
+  if (flag == 2) {
+    const int first_new = max(plan.n_flush, nr), cnt = nr + n - first_new;
+    for (int r = wave; r < cnt * c.H_kv; r += kWaves) {
+      const int g2 = r / cnt, u = first_new + r % cnt;
+      const long long bh2 = (long long)b * c.H_kv + g2;
+      store_window_row(reinterpret_cast<half_t*>(c.k_res) + bh2 * c.R * kHeadDim,
+                       reinterpret_cast<half_t*>(c.v_res) + bh2 * c.R * kHeadDim, u - plan.n_flush,
+                       k_new + (bh2 * T + (u - nr)) * kHeadDim, v_new + (bh2 * T + (u - nr)) * kHeadDim, lane);
+    }
+  }
+  __syncthreads();
+  if (flag != 0 && tid == 0) finish(c, b, nq, n, plan, flag == 2);
+}
+
+// One launch serves every sequence: item it of the grid's list is part (it / 8) % kParts of the pair
+// (it / 32) * 8 + it % 8 of (sequence, kv head), and workgroup x owns the items x, x + G, x + 2 G, ...: the parts of a
+// pair sit on one XCD (workgroups are dealt to the 8 XCDs in turn, and G is a multiple of 8), whose L2 then serves
+// the rows that all of them stage.
+__global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
+                                                                 const half_t* __restrict__ v_new,
+                                                                 const int32_t* __restrict__ n_new, int T, int keep) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  Lds& L = *reinterpret_cast<Lds*>(lds_raw);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long n_pairs = (long long)c.B * c.H_kv;
+  const long long n_items = kParts * 8 * ((n_pairs + 7) / 8);
+  const long long G = gridDim.x;
+
+  for (long long k0 = 0; k0 * G < n_items; k0 += kListCap) {
+    if (tid == 0) {
+      L.n_light = 0;
+      L.n_heavy = 0;
+    }
+    __syncthreads();
+    // every thread looks at one item: what needs a wave or the workgroup is listed, the rest is counted in at once
+    const long long it = (k0 + tid) * G + blockIdx.x;
+    if (it < n_items) {
+      const int fp = (int)((it >> 3) & (kParts - 1));
+      const long long p = (it >> 5) * 8 + (it & 7);
+      if (p < n_pairs) {
+        const int b = (int)(p / c.H_kv);
+        const Counters s = read_counters(c, b, n_new, T, keep);
+        if (s.plan.err || s.n == 0) {
+          if (s.plan.err && fp == 0) atomicOr(c.status, s.plan.err);
+          bool clean;
+          if (arrive(c, b, s.plan.err != 0, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
+        } else if (s.plan.n_groups == 0) {
+          if (fp == 0) {
+            L.light[atomicAdd(&L.n_light, 1)] = (int)p;
+          } else {
+            bool clean;
+            if (arrive(c, b, false, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
+          }
+        } else {
+          L.heavy[atomicAdd(&L.n_heavy, 1)] = (int)p * kParts + fp;
+        }
+      }
+    }
+    __syncthreads();
+    const int n_light = L.n_light, n_heavy = L.n_heavy;
+    for (int i = wave; i < n_light; i += kThreads / 64) light_item(c, L.light[i], k_new, v_new, n_new, T, keep, lane);
+    for (int i = 0; i < n_heavy; ++i) {
+      flush_item(c, L, L.heavy[i], k_new, v_new, n_new, T, keep);
+      __syncthreads();
+    }
+    __syncthreads();
+  }
 }
 
 }  // namespace
@@ -644,7 +904,11 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
   if (T > 1 && c.H_kv > 1)
     hipLaunchKernelGGL(append_scan_kernel, dim3(c.B * c.H_kv, (T + kScanRows - 1) / kScanRows), dim3(kThreads), 0, stream, c,
                        reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T);
-  hipLaunchKernelGGL(append_flush_kernel, dim3(c.B * c.H_kv), dim3(kThreads), sizeof(Lds), stream, c,
+  // one workgroup per compute unit at most (the LDS tiles of a flush fill most of one); items beyond that are taken
+  // in further rounds by the same workgroups
+  const long long n_items = kParts * 8 * (((long long)c.B * c.H_kv + 7) / 8);
+  const int grid = (int)(n_items < 256 ? n_items : 256);
+  hipLaunchKernelGGL(append_flush_kernel, dim3(grid), dim3(kThreads), sizeof(Lds), stream, c,
                      reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   return KVLINC_OK;

@@ -19,28 +19,22 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kRowH = 136;     // halfs per LDS row of a 128-wide fp16 tile (rows stay 16-byte aligned)
-constexpr int kChunk = 32;     // tokens per step of the state update
-constexpr int kParts = 4;      // workgroups that share the flush of one (sequence, kv head): 64-feature blocks of S
+constexpr int kParts = 2;      // workgroups that share the flush of one (sequence, kv head): the two halves of phi
 constexpr int kListCap = kThreads;  // items one workgroup looks at per round (one per thread)
 
 struct Lds {
-  half_t bK[kGroup][kRowH];       // raw keys [token][channel]; after the quantizer the high term of K - K_q
-  half_t bV[kGroup][kRowH];       // rotated values [token][channel]; after the quantizer the low term of K - K_q
+  // raw keys / rotated values [token][channel]; after the quantizer the high / low term of K - K_q; after the logits
+  // the high / low term of phi s of the group for this workgroup's 128 features, [feature][token]
+  half_t bK[kGroup][kRowH];
+  half_t bV[kGroup][kRowH];
   // value codes as the binary16 numbers code - 1.5, [token / 4][channel][token % 4]: what the S update multiplies by,
   // and -- sign and the bit that tells 1.5 from 0.5 -- the bit pair the record stores
   half_t cV[kGroup / 4][kHeadDim][4];
   float kScale[kGroup], kZero[kGroup];
   float vScale[kGroup], vCentre[kGroup];  // vCentre: z + 1.5 s, the value of the centre of the code range
-  union {
-    struct {
-      half_t mn[kThreads / 16][kGroup], mx[kThreads / 16][kGroup];  // per-channel key minima / maxima of token subsets
-    } part;
-    float lg[kChunk][kHeadDim + 4];  // logits of one chunk of tokens for the 128 features of one half of phi
-  } u;
-  // phi s of the chunk for this workgroup's 64 features, feature-major, as two binary16 terms
-  half_t phH[64][kChunk + 8];
-  half_t phL[64][kChunk + 8];
-  float red[2 * kWaves][64];
+  half_t kmn[kWaves][kGroup], kmx[kWaves][kGroup];  // per-channel key minima / maxima of each wave's tokens
+  half_t Wt[kRank / 2][kRowH];  // W_k of the half of phi this workgroup belongs to, [feature][channel]
+  float red[kWaves][kRank / 2];
   int light[kListCap], heavy[kListCap];
   int n_light, n_heavy, last_flag;
 };
@@ -284,15 +278,33 @@ __device__ __forceinline__ void rowpair_exchange(float v, float& mine_or_other, 
   mine_or_other = __builtin_bit_cast(float, a0);
   other_or_mine = __builtin_bit_cast(float, a1);
 }
-__device__ __forceinline__ float rowpair_max(float v) {
-  float p, q;
-  rowpair_exchange(row16_max(v), p, q);
-  return fmaxf(p, q);
+// reductions over the lanes l, l ^ 16, l ^ 32, l ^ 48 (the four rows of a wave), result in every lane
+__device__ __forceinline__ void rows_exchange32(float v, float& p, float& q) {
+  uint32_t x = __builtin_bit_cast(uint32_t, v), y = x;
+  asm volatile("" : "+v"(y));
+  const auto a = __builtin_amdgcn_permlane32_swap(x, y, false, false);
+  uint32_t a0 = a[0], a1 = a[1];
+  asm volatile("" : "+v"(a0), "+v"(a1));
+  p = __builtin_bit_cast(float, a0);
+  q = __builtin_bit_cast(float, a1);
 }
-__device__ __forceinline__ float rowpair_sum(float v) {
+__device__ __forceinline__ float rows_sum(float v) {
   float p, q;
-  rowpair_exchange(row16_sum(v), p, q);
+  rowpair_exchange(v, p, q);
+  rows_exchange32(p + q, p, q);
   return p + q;
+}
+__device__ __forceinline__ float rows_min(float v) {
+  float p, q;
+  rowpair_exchange(v, p, q);
+  rows_exchange32(fminf(p, q), p, q);
+  return fminf(p, q);
+}
+__device__ __forceinline__ float rows_max(float v) {
+  float p, q;
+  rowpair_exchange(v, p, q);
+  rows_exchange32(fmaxf(p, q), p, q);
+  return fmaxf(p, q);
 }
 
 // bits of the binary16 number code - 1.5 that make the stored bit pair: hi = sign (codes 0, 1), lo = magnitude 1.5
@@ -300,19 +312,20 @@ __device__ __forceinline__ float rowpair_sum(float v) {
 __device__ __forceinline__ uint32_t hi_of(uint32_t h16) { return (h16 >> 15) & 1u; }
 __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u; }
 
-// One of the kParts workgroups that flush the groups of one (sequence, kv head).  All of them stage and quantize the
-// whole group (the quantizer's outputs feed every part of the state update); part fp writes a quarter of the record's
-// tile words (part 0 also the scales and zero-points) and owns the features 64 fp .. 64 fp + 63 of S and P.  The state
+// One of the two workgroups that flush the groups of one (sequence, kv head).  Both stage and quantize the whole group
+// (the quantizer's outputs feed both halves of the state update); part fp writes half of the record's tile words
+// (part 0 also the scales and zero-points) and owns the half fp of phi: the features 128 fp .. 128 fp + 127 of S and P
+// (Eq. 6 normalises each half by itself).  The state
 // update runs on the matrix cores (16x16x32, binary16 operands whose products are exact: the centred codes are
 // multiples of 0.5, W_k is binary16, the key error and phi s are carried as two binary16 terms):
-//   logits[t][f] = sum_c (K - K_q)[t][c] W_k[c][f]   for the 128 features of the half of phi the part belongs to,
+//   logits[t][f] = sum_c (K - K_q)[t][c] W_k[c][f]   for the 128 features of the part's half,
 //   phi = softmax over that half (Eq. 6),
 //   S[f][c] += sum_t (phi s_t)[t][f] (code[t][c] - 1.5) + sum_t phi[t][f] (z_t + 1.5 s_t),   P[f] += sum_t phi[t][f]   (Eq. 5)
 // with V_q[t][c] = z_t + s_t code[t][c].  S stays in registers for all groups of the call.  The matrix instruction lines
 // its 32 products and its addend up with the largest of them before it adds, so what it is given is kept small and of
-// both signs: every chunk's products start from a zero addend and are added to S by ordinary binary32 additions, the
-// codes are centred (the other part is the same for all channels of a row), and the two terms of the key error
-// are contracted separately.
+// both signs: the products of every 32 tokens start from a zero addend and are added to S by ordinary binary32
+// additions, the codes are centred (the other part is the same for all channels of a row), and of the two terms of the
+// key error the small one is contracted first.
 __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
                            const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -394,41 +407,47 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 
   // matrix-core roles of a lane: column l16 of a 16-wide tile, rows 4 kq .. 4 kq + 3 of the result, and the eight
   // contraction indices 8 kq .. 8 kq + 7 of each 32-wide step (the same in both operands, so any order of them serves).
-  // Logits: wave w forms the features 16 w .. 16 w + 15 of the half.  S update: wave w holds the rows 16 (w % 4) .. of
-  // the part's 64 and the channels 64 (w / 4) .. 64 (w / 4) + 63, four tiles of 16.
+  // Logits and softmax: wave w takes the tokens 16 w .. 16 w + 15 and all 128 features of the half (8 tiles), so a
+  // token's features sit in the 16 lanes of a row and in the lane's own registers.  S update: wave w holds the rows
+  // 16 w .. 16 w + 15 of the half and all 128 channels, eight tiles of 16.
   const int l16 = lane & 15, kq = lane >> 4;
-  const int hs = fp >> 1;  // half of phi this part belongs to; its own features are 64 (fp & 1) + 0..63 of that half
-  const int fw = 16 * (wave & 3), cw0 = 4 * (wave >> 2);
-  const int frow = 64 * fp + fw + 4 * kq;  // first of the 4 rows of S this lane holds in every accumulator
+  const int fw = 16 * wave;
+  const int frow = (kRank / 2) * fp + fw + 4 * kq;  // first of the 4 rows of S this lane holds in every accumulator
+  const int tile0 = ((frow >> 6) * 2) * 16 + ((frow & 63) >> 2);  // binary16 tile of these rows for the channels 0..63
   half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
 
-  half8_t wfrag[4];  // W_k[channel 32 kk + 8 kq + i][feature 16 wave + l16 of the half]
-  float4_t acc[4];   // S[frow + r][16 (cw0 + ct) + l16]
-  // softmax roles: the two halves of a wave take one token each, lane j of a half the features 4 j .. 4 j + 3 of the
-  // 128; the part's own features sit in the lanes of row (fp & 1) of each half
-  const int hw = lane >> 5, j4 = lane & 31;
-  const bool own_lane = ((j4 >> 4) == (fp & 1));
-  const int fo = 4 * (j4 & 15);  // first of this lane's 4 own features (of 64)
-  float Pacc[4] = {0.f, 0.f, 0.f, 0.f};  // sums of phi over the tokens this half-wave normalises
+  float4_t acc[8];  // S[frow + r][16 ct + l16]
+  float Pacc[8];    // sums of phi[t][16 fo + l16] over the tokens 4 kq .. 4 kq + 3 of this wave's tiles
+#pragma unroll
+  for (int fo = 0; fo < 8; ++fo) Pacc[fo] = 0.0f;
+  float P_old = 0.0f;
   if (states_live) {
-    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + hs) * kHeadDim * (kRank / 2);
+    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + fp) * kHeadDim * (kRank / 2);
+    {  // transposed into LDS: a lane's B operand (8 channels of one feature) is then one 16-byte read
+      uint4 w[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+      for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const uint4*>(W0 + (long long)(tid + kThreads * i) * 8);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) wfrag[kk][i] = W0[(long long)(32 * kk + 8 * kq + i) * (kRank / 2) + 16 * wave + l16];
+      for (int i = 0; i < 4; ++i) {
+        const int piece = tid + kThreads * i, ch = piece >> 4, f8 = 8 * (piece & 15);
+        const uint32_t ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-      const int cc = cw0 + ct;
+        for (int e = 0; e < 8; ++e)
+          L.Wt[f8 + e][ch] = __builtin_bit_cast(half_t, (unsigned short)((ww[e >> 1] >> (16 * (e & 1))) & 0xffffu));
+      }
+    }
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) {
       if (have_master) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * cc + l16];
+        for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * ct + l16];
       } else {
-        const half4_t t16 = *reinterpret_cast<const half4_t*>(
-            tiles + ((((fp * 2 + (cc >> 2)) * 16 + (fw >> 2) + kq) * 64) + 16 * (cc & 3) + l16) * 4);
+        const half4_t t16 = *reinterpret_cast<const half4_t*>(tiles + ((tile0 + 16 * (ct >> 2)) * 64 + 16 * (ct & 3) + l16) * 4);
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[ct][r] = (float)t16[r];
       }
     }
+    if (tid < kRank / 2) P_old = c.P[bh * kRank + (kRank / 2) * fp + tid];
   }
   bool bad = false;
   const int sub = tid & 15, tq = tid >> 4;  // quantizer roles: channels 8 sub .. 8 sub + 7; tq = 0 .. 31
@@ -580,27 +599,32 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
           }
         }
       }
-      half8_t hmn, hmx;  // exact: the values are fp16 values or infinities
+      // over the wave's four rows (token subsets), then one row of each wave leaves its minima / maxima
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        hmn[e] = (half_t)kmn[e];
-        hmx[e] = (half_t)kmx[e];
+        kmn[e] = rows_min(kmn[e]);
+        kmx[e] = rows_max(kmx[e]);
       }
-      *reinterpret_cast<half8_t*>(&L.u.part.mn[tq][8 * sub]) = hmn;
-      *reinterpret_cast<half8_t*>(&L.u.part.mx[tq][8 * sub]) = hmx;
-    }
-    __syncthreads();
-    if (tid < 2 * kGroup) {  // threads 0..127 the minima, 128..255 the maxima (parked in the scale / zero-point slots)
-      const int ch = tid & (kGroup - 1);
-      const half_t(*src)[kGroup] = tid < kGroup ? L.u.part.mn : L.u.part.mx;
-      float v = (float)src[0][ch];
+      if (kq == 0) {
+        half8_t hmn, hmx;  // exact: the values are fp16 values or infinities
 #pragma unroll
-      for (int r = 1; r < kThreads / 16; ++r) v = tid < kGroup ? fminf(v, (float)src[r][ch]) : fmaxf(v, (float)src[r][ch]);
-      (tid < kGroup ? L.kZero : L.kScale)[ch] = v;
+        for (int e = 0; e < 8; ++e) {
+          hmn[e] = (half_t)kmn[e];
+          hmx[e] = (half_t)kmx[e];
+        }
+        *reinterpret_cast<half8_t*>(&L.kmn[wave][8 * sub]) = hmn;
+        *reinterpret_cast<half8_t*>(&L.kmx[wave][8 * sub]) = hmx;
+      }
     }
     __syncthreads();
     if (tid < kGroup) {
-      const Q2 pk = q2_params(L.kZero[tid], L.kScale[tid]);
+      float mn = (float)L.kmn[0][tid], mx = (float)L.kmx[0][tid];
+#pragma unroll
+      for (int r = 1; r < kWaves; ++r) {
+        mn = fminf(mn, (float)L.kmn[r][tid]);
+        mx = fmaxf(mx, (float)L.kmx[r][tid]);
+      }
+      const Q2 pk = q2_params(mn, mx);
       L.kScale[tid] = pk.s;
       L.kZero[tid] = pk.z;
       if (fp == 0) {
@@ -609,7 +633,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       }
     }
     __syncthreads();
-    // key codes -- this part's quarter of the key tile goes out from registers -- and K - K_q as two binary16 terms in
+    // key codes -- this part's half of the key tile goes out from registers -- and K - K_q as two binary16 terms in
     // place of the staged tiles.
     // Tile word ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w holds, for the row 16 n + j, the positions
     // k = 32 g + 16 w + 8 (p % 2) + p / 2, p = 0..15: code p as the bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for the
@@ -644,15 +668,15 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         *reinterpret_cast<half8_t*>(&L.bK[t][8 * sub]) = eh;
         *reinterpret_cast<half8_t*>(&L.bV[t][8 * sub]) = el;
         bits |= dpp_u<kQuadSwap1>(bits);
-        if (i == fp && (sub & 1) == 0) {  // tokens 32 fp .. 32 fp + 31 are the blocks n = 2 fp, 2 fp + 1
+        if ((i >> 1) == fp && (sub & 1) == 0) {  // this part's half of the key tile: the tokens 64 fp .. 64 fp + 63
           const int nb = t >> 4, jr = t & 15;
           rec[kRecKeyTile + ((nb >> 1) * 64 + jr + 16 * (sub >> 2)) * 4 + 2 * (nb & 1) + ((sub >> 1) & 1)] = bits;
         }
       }
     }
-    // ---- 3. this part's quarter of the value tile: row = channel 16 n + j, position k = token
+    // ---- 3. this part's half of the value tile: row = channel 16 n + j, position k = token
     // 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2, the bit pairs read off the centred codes ----
-    if (tid < kTileWords / kParts) {
+    {
       // (the centred codes of all tokens were stored before the last barrier)
       const int wi = (kTileWords / kParts) * fp + tid;
       const int w = wi & 1, nb = 2 * (wi >> 8) + ((wi >> 1) & 1), l = (wi >> 2) & 63, jr = l & 15, gq4 = l >> 4;
@@ -669,109 +693,113 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       rec[kRecValueTile + wi] = vw;
     }
     __syncthreads();
-    // ---- 4. the group's contribution to S and P (Eq. 5, Eq. 6), 32 tokens at a time --------------------------
+    // ---- 4. the group's contribution to S and P (Eq. 5, Eq. 6) ----------------------------------------------
     if (states_live) {
-      float Zacc[4] = {0.f, 0.f, 0.f, 0.f};  // sums of phi (z_t + 1.5 s_t) over the tokens this half-wave normalises
-      for (int t0 = 0; t0 < valid; t0 += kChunk) {
-        // a. logits: this wave's 16 features of the half, two tiles of 16 tokens
-        {
-          float4_t d[2], dl[2];
+      float Zacc[8];  // as Pacc, of phi (z_t + 1.5 s_t)
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            d[tt] = dl[tt] = float4_t{0.f, 0.f, 0.f, 0.f};
-            const int tr = t0 + 16 * tt + l16;
+      for (int fo = 0; fo < 8; ++fo) Zacc[fo] = 0.0f;
+      // a. logits of this wave's 16 tokens for the 128 features of the half; the small products (low term) first
+      float4_t d[8];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-              const half8_t aH = *reinterpret_cast<const half8_t*>(&L.bK[tr][32 * kk + 8 * kq]);
-              const half8_t aL = *reinterpret_cast<const half8_t*>(&L.bV[tr][32 * kk + 8 * kq]);
-              d[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, wfrag[kk], d[tt], 0, 0, 0);
-              dl[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, wfrag[kk], dl[tt], 0, 0, 0);
-            }
-          }
+      for (int ft = 0; ft < 8; ++ft) d[ft] = float4_t{0.f, 0.f, 0.f, 0.f};
+      if (16 * wave < valid) {
+        const int tr = 16 * wave + l16;
+#pragma unroll 1
+        for (int kk = 0; kk < 4; ++kk) {
+          const half8_t aL = *reinterpret_cast<const half8_t*>(&L.bV[tr][32 * kk + 8 * kq]);
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) L.u.lg[16 * tt + 4 * kq + r][16 * wave + l16] = d[tt][r] + dl[tt][r];
+          for (int ft = 0; ft < 8; ++ft)
+            d[ft] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, *reinterpret_cast<const half8_t*>(&L.Wt[16 * ft + l16][32 * kk + 8 * kq]), d[ft], 0, 0, 0);
         }
-        __syncthreads();
-        // b. softmax over the half for 4 tokens per wave, one per half-wave and step; phi of the part's own 64
-        // features goes on as phi s_t in two binary16 terms, feature-major
-        {
-          float4 a[2];
-          float m[2], sum[2];
-          float e[2][4];
+#pragma unroll 1
+        for (int kk = 0; kk < 4; ++kk) {
+          const half8_t aH = *reinterpret_cast<const half8_t*>(&L.bK[tr][32 * kk + 8 * kq]);
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            a[u] = *reinterpret_cast<const float4*>(&L.u.lg[4 * wave + 2 * u + hw][4 * j4]);
-            m[u] = fmaxf(fmaxf(a[u].x, a[u].y), fmaxf(a[u].z, a[u].w));
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) m[u] = rowpair_max(m[u]);
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            e[u][0] = __expf(a[u].x - m[u]);
-            e[u][1] = __expf(a[u].y - m[u]);
-            e[u][2] = __expf(a[u].z - m[u]);
-            e[u][3] = __expf(a[u].w - m[u]);
-            sum[u] = (e[u][0] + e[u][1]) + (e[u][2] + e[u][3]);
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) sum[u] = rowpair_sum(sum[u]);
-          if (own_lane) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-              const int tc = 4 * wave + 2 * u + hw, t = t0 + tc;
-              const bool live = t < valid;
-              const float inv = live ? 1.0f / sum[u] : 0.0f;
-              const float sc = L.vScale[t], ce = L.vCentre[t];
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const float ph = e[u][i] * inv;
-                Pacc[i] += ph;
-                Zacc[i] += ph * ce;
-                float ws = ph * sc;
-                // The two terms must add up to the binary32 product: keep its rounding apart from the conversion (a
-                // fused multiply-and-convert would round the exact product once, and the low term would then belong
-                // to another high term in the rare near-tie cases).
-                asm volatile("" : "+v"(ws));
-                const half_t h = (half_t)ws;
-                L.phH[fo + i][tc] = h;
-                L.phL[fo + i][tc] = (half_t)(ws - (float)h);
-              }
-            }
-          }
-        }
-        __syncthreads();
-        // c. S[f][c] += sum_t (phi s)[t][f] (code[t][c] - 1.5): this wave's 16 features, 4 tiles of 16 channels
-        {
-          const half8_t aH = *reinterpret_cast<const half8_t*>(&L.phH[fw + l16][8 * kq]);
-          const half8_t aL = *reinterpret_cast<const half8_t*>(&L.phL[fw + l16][8 * kq]);
-          const int q0 = (t0 >> 2) + 2 * kq;  // the lane's 8 tokens are two quads
-#pragma unroll
-          for (int ct = 0; ct < 4; ++ct) {
-            const int ch = 16 * (cw0 + ct) + l16;
-            const half4_t b0 = *reinterpret_cast<const half4_t*>(&L.cV[q0][ch][0]);
-            const half4_t b1 = *reinterpret_cast<const half4_t*>(&L.cV[q0 + 1][ch][0]);
-            const half8_t bc = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
-            float4_t d = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, bc, float4_t{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, bc, d, 0, 0, 0);
-            acc[ct] += d;
-          }
+          for (int ft = 0; ft < 8; ++ft)
+            d[ft] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, *reinterpret_cast<const half8_t*>(&L.Wt[16 * ft + l16][32 * kk + 8 * kq]), d[ft], 0, 0, 0);
         }
       }
-      // the term of the code centres is the same for every channel of a row
+      __syncthreads();  // every wave has read its rows of the key error: their place now takes phi s
+      half_t(*phH)[kRowH] = L.bK;
+      half_t(*phL)[kRowH] = L.bV;
+      if (16 * wave < valid) {
+        // b. softmax over the half: register r of the lane belongs to token 16 wave + 4 kq + r, whose 128 features
+        // are the 8 tiles times the 16 lanes of the row.  phi goes on as phi s_t in two binary16 terms, feature-major.
+        const int tb = 16 * wave + 4 * kq;
+        const float4 sc4 = *reinterpret_cast<const float4*>(&L.vScale[tb]);
+        const float4 ce4 = *reinterpret_cast<const float4*>(&L.vCentre[tb]);
+        const float sc[4] = {sc4.x, sc4.y, sc4.z, sc4.w}, ce[4] = {ce4.x, ce4.y, ce4.z, ce4.w};
+        float m[4], sum[4], inv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          m[r] = fmaxf(fmaxf(fmaxf(d[0][r], d[1][r]), fmaxf(d[2][r], d[3][r])), fmaxf(fmaxf(d[4][r], d[5][r]), fmaxf(d[6][r], d[7][r])));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) m[r] = row16_max(m[r]);
+#pragma unroll
+        for (int ft = 0; ft < 8; ++ft)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) d[ft][r] = __expf(d[ft][r] - m[r]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum[r] = ((d[0][r] + d[1][r]) + (d[2][r] + d[3][r])) + ((d[4][r] + d[5][r]) + (d[6][r] + d[7][r]));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum[r] = row16_sum(sum[r]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) inv[r] = tb + r < valid ? 1.0f / sum[r] : 0.0f;
+#pragma unroll
+        for (int fo = 0; fo < 8; ++fo) {
+          const float4_t e = d[fo];
+          half4_t h4, l4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float ph = e[r] * inv[r];
+            Pacc[fo] += ph;
+            Zacc[fo] += ph * ce[r];
+            float ws = ph * sc[r];
+            // The two terms must add up to the binary32 product: keep its rounding apart from the conversion (a fused
+            // multiply-and-convert would round the exact product once, and the low term would then belong to another
+            // high term in the rare near-tie cases).
+            asm volatile("" : "+v"(ws));
+            h4[r] = (half_t)ws;
+            l4[r] = (half_t)(ws - (float)h4[r]);
+          }
+          *reinterpret_cast<half4_t*>(&phH[16 * fo + l16][tb]) = h4;
+          *reinterpret_cast<half4_t*>(&phL[16 * fo + l16][tb]) = l4;
+        }
+      }
+      // the term of the code centres is the same for every channel of a row: summed over the wave's tokens here
+#pragma unroll
+      for (int fo = 0; fo < 8; ++fo) Zacc[fo] = rows_sum(Zacc[fo]);
+      if (kq == 0) {
+#pragma unroll
+        for (int fo = 0; fo < 8; ++fo) L.red[wave][16 * fo + l16] = Zacc[fo];
+      }
       __syncthreads();
-      if (own_lane) *reinterpret_cast<float4*>(&L.red[2 * wave + hw][fo]) = make_float4(Zacc[0], Zacc[1], Zacc[2], Zacc[3]);
-      __syncthreads();
+      // c. S[f][c] += sum_t (phi s)[t][f] (code[t][c] - 1.5): this wave's 16 features, 8 tiles of 16 channels, 32 tokens
+      // per instruction
+      for (int t0 = 0; t0 < valid; t0 += 32) {
+        const half8_t aH = *reinterpret_cast<const half8_t*>(&phH[fw + l16][t0 + 8 * kq]);
+        const half8_t aL = *reinterpret_cast<const half8_t*>(&phL[fw + l16][t0 + 8 * kq]);
+        const int q0 = (t0 >> 2) + 2 * kq;  // the lane's 8 tokens are two quads
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) {
+          const int ch = 16 * ct + l16;
+          const half4_t b0 = *reinterpret_cast<const half4_t*>(&L.cV[q0][ch][0]);
+          const half4_t b1 = *reinterpret_cast<const half4_t*>(&L.cV[q0 + 1][ch][0]);
+          const half8_t bc = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+          float4_t dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, bc, float4_t{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, bc, dd, 0, 0, 0);
+          acc[ct] += dd;
+        }
+      }
       {
         float z[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w2 = 0; w2 < 2 * kWaves; ++w2) {
+        for (int w2 = 0; w2 < kWaves; ++w2) {
           const float4 zz = *reinterpret_cast<const float4*>(&L.red[w2][fw + 4 * kq]);
           z[0] += zz.x; z[1] += zz.y; z[2] += zz.z; z[3] += zz.w;
         }
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
           for (int r = 0; r < 4; ++r) acc[ct][r] += z[r];
       }
@@ -788,27 +816,30 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
     // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
     bool out_of_range = false;
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-      const int cc = cw0 + ct;
+    for (int ct = 0; ct < 8; ++ct) {
       half4_t t16;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float v = acc[ct][r];
-        if (have_master) c.S[(bh * kRank + frow + r) * kHeadDim + 16 * cc + l16] = v;
+        if (have_master) c.S[(bh * kRank + frow + r) * kHeadDim + 16 * ct + l16] = v;
         out_of_range |= !(fabsf(v) <= 65504.0f);
         t16[r] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
       }
-      *reinterpret_cast<half4_t*>(tiles + ((((fp * 2 + (cc >> 2)) * 16 + (fw >> 2) + kq) * 64) + 16 * (cc & 3) + l16) * 4) = t16;
+      *reinterpret_cast<half4_t*>(tiles + ((tile0 + 16 * (ct >> 2)) * 64 + 16 * (ct & 3) + l16) * 4) = t16;
     }
     if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 && lane == 0) atomicOr(c.status, KVLINC_ST_STATE_RANGE);
-    if (own_lane) *reinterpret_cast<float4*>(&L.red[2 * wave + hw][fo]) = make_float4(Pacc[0], Pacc[1], Pacc[2], Pacc[3]);
+#pragma unroll
+    for (int fo = 0; fo < 8; ++fo) Pacc[fo] = rows_sum(Pacc[fo]);
+    if (kq == 0) {
+#pragma unroll
+      for (int fo = 0; fo < 8; ++fo) L.red[wave][16 * fo + l16] = Pacc[fo];
+    }
     __syncthreads();
-    if (tid < 64) {
-      float* P = c.P + bh * kRank + 64 * fp;
+    if (tid < kRank / 2) {
       float add = 0.0f;
 #pragma unroll
-      for (int w2 = 0; w2 < 2 * kWaves; ++w2) add += L.red[w2][tid];
-      P[tid] = P[tid] + add;
+      for (int w2 = 0; w2 < kWaves; ++w2) add += L.red[w2][tid];
+      c.P[bh * kRank + (kRank / 2) * fp + tid] = P_old + add;
     }
   }
 
@@ -838,7 +869,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 }
 
 // One launch serves every sequence: item it of the grid's list is part (it / 8) % kParts of the pair
-// (it / 32) * 8 + it % 8 of (sequence, kv head), and workgroup x owns the items x, x + G, x + 2 G, ...: the parts of a
+// (it / (8 kParts)) * 8 + it % 8 of (sequence, kv head), and workgroup x owns the items x, x + G, x + 2 G, ...: the parts of a
 // pair sit on one XCD (workgroups are dealt to the 8 XCDs in turn, and G is a multiple of 8), whose L2 then serves
 // the rows that all of them stage.
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
@@ -861,7 +892,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     const long long it = (k0 + tid) * G + blockIdx.x;
     if (it < n_items) {
       const int fp = (int)((it >> 3) & (kParts - 1));
-      const long long p = (it >> 5) * 8 + (it & 7);
+      const long long p = (it / (8 * kParts)) * 8 + (it & 7);
       if (p < n_pairs) {
         const int b = (int)(p / c.H_kv);
         const Counters s = read_counters(c, b, n_new, T, keep);

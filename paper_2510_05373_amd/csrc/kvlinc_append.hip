@@ -336,6 +336,57 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
   const int nq = s.nq, nr = s.nr, n = s.n;
   const AppendPlan plan = s.plan;
 
+  // (The loads of W_k and of the state are issued before the new rows are looked at: they are wanted in any case but a
+  // refusal, and nothing is stored to global memory before the verdict.)
+  const half_t* k_res = reinterpret_cast<const half_t*>(c.k_res) + bh * c.R * kHeadDim;
+  const half_t* v_res = reinterpret_cast<const half_t*>(c.v_res) + bh * c.R * kHeadDim;
+  const half_t* k_src = k_new + bh * (long long)T * kHeadDim;
+  const half_t* v_src = v_new + bh * (long long)T * kHeadDim;
+  const bool states_live = c.S16 != nullptr;
+  const bool have_master = c.S != nullptr;  // fp32 master copy of S; without it the state lives in its binary16 tiles
+
+  // matrix-core roles of a lane: column l16 of a 16-wide tile, rows 4 kq .. 4 kq + 3 of the result, and the eight
+  // contraction indices 8 kq .. 8 kq + 7 of each 32-wide step (the same in both operands, so any order of them serves).
+  // Logits and softmax: wave w takes the tokens 16 w .. 16 w + 15 and all 128 features of the half (8 tiles), so a
+  // token's features sit in the 16 lanes of a row and in the lane's own registers.  S update: wave w holds the rows
+  // 16 w .. 16 w + 15 of the half and all 128 channels, eight tiles of 16.
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int fw = 16 * wave;
+  const int frow = (kRank / 2) * fp + fw + 4 * kq;  // first of the 4 rows of S this lane holds in every accumulator
+  const int tile0 = ((frow >> 6) * 2) * 16 + ((frow & 63) >> 2);  // binary16 tile of these rows for the channels 0..63
+  half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
+
+  float4_t acc[8];  // S[frow + r][16 ct + l16]
+  float Pacc[8];    // sums of phi[t][16 fo + l16] over the tokens 4 kq .. 4 kq + 3 of this wave's tiles
+#pragma unroll
+  for (int fo = 0; fo < 8; ++fo) Pacc[fo] = 0.0f;
+  float P_old = 0.0f;
+  if (states_live) {
+    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + fp) * kHeadDim * (kRank / 2);
+    {  // transposed into LDS: a lane's B operand (8 channels of one feature) is then one 16-byte read.  Thread: feature
+       // tid % 128 (consecutive lanes read consecutive halfs of a row of W), 8 channels per step.
+      const int f = tid & 127, c0 = 8 * (tid >> 7);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        half8_t w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = W0[(long long)(c0 + 32 * i + e) * (kRank / 2) + f];
+        *reinterpret_cast<half8_t*>(&L.Wt[f][c0 + 32 * i]) = w;
+      }
+    }
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) {
+      if (have_master) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * ct + l16];
+      } else {
+        const half4_t t16 = *reinterpret_cast<const half4_t*>(tiles + ((tile0 + 16 * (ct >> 2)) * 64 + 16 * (ct & 3) + l16) * 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[ct][r] = (float)t16[r];
+      }
+    }
+    if (tid < kRank / 2) P_old = c.P[bh * kRank + (kRank / 2) * fp + tid];
+  }
   {
     // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
     bool refuse = false;
@@ -398,57 +449,6 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
     }
   }
 
-  const half_t* k_res = reinterpret_cast<const half_t*>(c.k_res) + bh * c.R * kHeadDim;
-  const half_t* v_res = reinterpret_cast<const half_t*>(c.v_res) + bh * c.R * kHeadDim;
-  const half_t* k_src = k_new + bh * (long long)T * kHeadDim;
-  const half_t* v_src = v_new + bh * (long long)T * kHeadDim;
-  const bool states_live = c.S16 != nullptr;
-  const bool have_master = c.S != nullptr;  // fp32 master copy of S; without it the state lives in its binary16 tiles
-
-  // matrix-core roles of a lane: column l16 of a 16-wide tile, rows 4 kq .. 4 kq + 3 of the result, and the eight
-  // contraction indices 8 kq .. 8 kq + 7 of each 32-wide step (the same in both operands, so any order of them serves).
-  // Logits and softmax: wave w takes the tokens 16 w .. 16 w + 15 and all 128 features of the half (8 tiles), so a
-  // token's features sit in the 16 lanes of a row and in the lane's own registers.  S update: wave w holds the rows
-  // 16 w .. 16 w + 15 of the half and all 128 channels, eight tiles of 16.
-  const int l16 = lane & 15, kq = lane >> 4;
-  const int fw = 16 * wave;
-  const int frow = (kRank / 2) * fp + fw + 4 * kq;  // first of the 4 rows of S this lane holds in every accumulator
-  const int tile0 = ((frow >> 6) * 2) * 16 + ((frow & 63) >> 2);  // binary16 tile of these rows for the channels 0..63
-  half_t* tiles = reinterpret_cast<half_t*>(c.S16) + bh * kRank * kHeadDim;
-
-  float4_t acc[8];  // S[frow + r][16 ct + l16]
-  float Pacc[8];    // sums of phi[t][16 fo + l16] over the tokens 4 kq .. 4 kq + 3 of this wave's tiles
-#pragma unroll
-  for (int fo = 0; fo < 8; ++fo) Pacc[fo] = 0.0f;
-  float P_old = 0.0f;
-  if (states_live) {
-    const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + fp) * kHeadDim * (kRank / 2);
-    {  // transposed into LDS: a lane's B operand (8 channels of one feature) is then one 16-byte read
-      uint4 w[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const uint4*>(W0 + (long long)(tid + kThreads * i) * 8);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int piece = tid + kThreads * i, ch = piece >> 4, f8 = 8 * (piece & 15);
-        const uint32_t ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          L.Wt[f8 + e][ch] = __builtin_bit_cast(half_t, (unsigned short)((ww[e >> 1] >> (16 * (e & 1))) & 0xffffu));
-      }
-    }
-#pragma unroll
-    for (int ct = 0; ct < 8; ++ct) {
-      if (have_master) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * ct + l16];
-      } else {
-        const half4_t t16 = *reinterpret_cast<const half4_t*>(tiles + ((tile0 + 16 * (ct >> 2)) * 64 + 16 * (ct & 3) + l16) * 4);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[ct][r] = (float)t16[r];
-      }
-    }
-    if (tid < kRank / 2) P_old = c.P[bh * kRank + (kRank / 2) * fp + tid];
-  }
   bool bad = false;
   const int sub = tid & 15, tq = tid >> 4;  // quantizer roles: channels 8 sub .. 8 sub + 7; tq = 0 .. 31
 

@@ -604,12 +604,12 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
 // ---- merge the splits of one (sequence, query head), add the correction, rotate back (Alg. 1 lines 13-15; Eq. 5;
 // Sec. 3.1).  Run by one wave of the split that arrives last; lane l owns channels 2l and 2l+1. ----------------------
 
-// MB = splits whose partial results are requested together
-template <int MB>
-__device__ __forceinline__ void merge_row(const float* __restrict__ part, const float* __restrict__ corr,
-                                          int max_splits, int n_splits, int row, int lane, bool literal,
-                                          half_t* __restrict__ out) {
-  const float* p0 = part + (long long)row * max_splits * kPartStride;
+// MB = splits whose partial results are requested together; LOCAL: the partial results are this workgroup's own and
+// lie in LDS (plain loads), everything else alike
+template <int MB, bool LOCAL = false>
+__device__ __forceinline__ void merge_row(const float* __restrict__ p0, const float* __restrict__ corr, int n_splits,
+                                          int row, int lane, bool literal, half_t* __restrict__ out) {
+  // p0: the row's partial results, n_splits of kPartStride floats
   // correction parts first (their values are needed last): {Cd_r, m_r, Z_r, -, Cn_r[128]}
   float c_cd[kCorrParts], c_m[kCorrParts], c_z[kCorrParts], c_x[kCorrParts], c_y[kCorrParts];
   if (corr != nullptr) {
@@ -628,8 +628,13 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 #pragma unroll
     for (int k = 0; k < MB; ++k) {
       const float* pj = p0 + (long long)(j0 + k < n_splits ? j0 + k : n_splits - 1) * kPartStride;
-      mj[k] = ld_coherent(pj); lj[k] = ld_coherent(pj + 1);
-      ax[k] = ld_coherent(pj + 4 + 2 * lane); ay[k] = ld_coherent(pj + 5 + 2 * lane);
+      if (LOCAL) {
+        mj[k] = pj[0]; lj[k] = pj[1];
+        ax[k] = pj[4 + 2 * lane]; ay[k] = pj[5 + 2 * lane];
+      } else {
+        mj[k] = ld_coherent(pj); lj[k] = ld_coherent(pj + 1);
+        ax[k] = ld_coherent(pj + 4 + 2 * lane); ay[k] = ld_coherent(pj + 5 + 2 * lane);
+      }
     }
     float Mb = M;
 #pragma unroll
@@ -710,8 +715,9 @@ __device__ __forceinline__ void merge_row(const float* __restrict__ part, const 
 __device__ __forceinline__ void merge_rows(const float* __restrict__ part, const float* __restrict__ corr,
                                            int max_splits, int n_splits, int row, int lane, bool literal,
                                            half_t* __restrict__ out) {
-  if (n_splits <= 4) merge_row<4>(part, corr, max_splits, n_splits, row, lane, literal, out);
-  else merge_row<8>(part, corr, max_splits, n_splits, row, lane, literal, out);
+  const float* p0 = part + (long long)row * max_splits * kPartStride;
+  if (n_splits <= 4) merge_row<4>(p0, corr, n_splits, row, lane, literal, out);
+  else merge_row<8>(p0, corr, n_splits, row, lane, literal, out);
 }
 
 // Splits the groups of a sequence are cut into.  The host fixes the average over the batch (avg_splits) and the most
@@ -962,6 +968,17 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     }
   }
 
+  // A sequence with a single split whose correction parts have all arrived has nobody left to wait for: its one
+  // workgroup then merges what it holds, without the trip of its partial result through memory.  The look at the
+  // counter is taken here so that its latency passes during the combine; a look that comes too early only sends the
+  // workgroup down the ordinary way.
+  __shared__ int sDirect;
+  if (tid == 0) {
+    int direct = 0;
+    if (n_splits == 1)
+      direct = n_parts == 0 ? 1 : (__hip_atomic_load(c.split_done + bh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == n_parts);
+    sDirect = direct;
+  }
   // combine the four waves (Alg. 1 lines 13-14 restricted to this workgroup) and write (m, l, Y_s)
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -974,6 +991,8 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       sAcc[wave][h][16 * n + lr.jd] = ((st.acc[nb][n][0] + st.acc[nb][n][1]) + (st.acc[nb][n][2] + st.acc[nb][n][3])) + pz;
   }
   __syncthreads();
+  const bool direct = sDirect != 0;
+  float* own = reinterpret_cast<float*>(&ex[0][0]);  // [gq][kPartStride]: the exchange regions are free by now
   for (int i = tid; i < gq * kHeadDim; i += kThreads) {
     const int h = i >> 7, ch = i & 127;
     float M = -INFINITY;
@@ -988,9 +1007,23 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
         l = fmaf(f, sL[w][h], l);
       }
     }
-    float* dst = part + (((long long)b * c.H_q + g * gq + h) * max_splits + sp) * kPartStride;
-    if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
-    st_coherent(dst + 4 + ch, a);
+    if (direct) {
+      float* dst = own + h * kPartStride;
+      if (ch == 0) { dst[0] = M; dst[1] = l; }
+      dst[4 + ch] = a;
+    } else {
+      float* dst = part + (((long long)b * c.H_q + g * gq + h) * max_splits + sp) * kPartStride;
+      if (ch == 0) { st_coherent(dst, M); st_coherent(dst + 1, l); }
+      st_coherent(dst + 4 + ch, a);
+    }
+  }
+  if (direct) {
+    __syncthreads();
+    for (int h = wave; h < gq; h += kWaves)
+      merge_row<4, true>(own + h * kPartStride, corr, 1, b * c.H_q + g * gq + h, lane,
+                         (c.flags & KVLINC_FLAG_ALG1_LITERAL) != 0, out);
+    if (tid == 0 && n_parts != 0) c.split_done[bh] = 0;  // the arrivals of the correction workgroups
+    return;
   }
 
   // The workgroup that arrives last merges (Alg. 1 lines 13-15): it reads what the others wrote with coherent

@@ -315,9 +315,9 @@ __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u
 // One of the two workgroups that flush the groups of one (sequence, kv head).  Both stage and quantize the whole group
 // (the quantizer's outputs feed both halves of the state update); part fp writes half of the record's tile words
 // (part 0 also the scales and zero-points) and owns the half fp of phi: the features 128 fp .. 128 fp + 127 of S and P
-// (Eq. 6 normalises each half by itself).  The state
-// update runs on the matrix cores (16x16x32, binary16 operands whose products are exact: the centred codes are
-// multiples of 0.5, W_k is binary16, the key error and phi s are carried as two binary16 terms):
+// (Eq. 6 normalises each half by itself).  The state update runs on the matrix cores (16x16x32, binary16 operands
+// whose products are exact: the centred codes are multiples of 0.5, W_k is binary16, the key error and phi s are carried
+// as two binary16 terms):
 //   logits[t][f] = sum_c (K - K_q)[t][c] W_k[c][f]   for the 128 features of the part's half,
 //   phi = softmax over that half (Eq. 6),
 //   S[f][c] += sum_t (phi s_t)[t][f] (code[t][c] - 1.5) + sum_t phi[t][f] (z_t + 1.5 s_t),   P[f] += sum_t phi[t][f]   (Eq. 5)

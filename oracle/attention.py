@@ -10,6 +10,13 @@ The correction terms are added to the UNSHIFTED exponential sums, as Eq. 5 defin
 M = max_i score_i the same quotient is (num + e^{-M} C_n) / (den + e^{-M} C_d) for the shifted sums
 num, den; Alg. 1 prints C_n, C_d added to the shifted sums without that factor, which is kept
 here only as the switch ``literal_alg1`` so its distance from Eq. 5 can be reported.
+
+Value window (Sec. 4.1, setup: the most recent tokens stay in full precision).  Keys are quantized per channel over
+128 tokens, so they can only leave the window a block at a time; values are quantized per token, so they can leave
+one at a time.  ``value_window="block"``: values leave with the keys (the window holds the n_res newest tokens of
+both).  ``value_window="sliding"``: the values of the newest ``R`` tokens are always the fp16 ones, those of all older
+tokens the quantized ones, whatever the key window holds.  The states S, P are the same in both (they are sums over
+the key-quantized tokens of their quantized values).
 """
 import numpy as np
 
@@ -17,9 +24,16 @@ from . import hadamard
 from .kvcache import feature_map
 
 
-def _operands(cache):
+def _operands(cache, value_window="block", R=128):
     keys = np.concatenate([cache["K_hat"], cache["k_res"].astype(np.float64)], axis=0)
     vals = np.concatenate([cache["V_hat"], cache["v_res"].astype(np.float64)], axis=0)
+    if value_window == "sliding":
+        n, nq = cache["n"], cache["n_quant"]
+        assert n - nq <= R, "the key window is never longer than the value window"
+        first = max(0, n - R)  # the values of tokens first .. n-1 are the fp16 ones
+        vals[first:] = cache["v_rot"][first:].astype(np.float64)
+    else:
+        assert value_window == "block"
     return keys, vals
 
 
@@ -29,7 +43,7 @@ def correction_terms(q, cache, Wq):
     return phi_q @ cache["S"], float(phi_q @ cache["P"])
 
 
-def decode(q, cache, Wq=None, *, rotate=True, literal_alg1=False):
+def decode(q, cache, Wq=None, *, rotate=True, literal_alg1=False, value_window="block"):
     """Eq. 5 for one query row q [d]; returns y [d] in the original basis (fp64).
 
     Wq: [2, d, D/2] adapters of this query head, or None for plain quantized attention (Eq. 3 on
@@ -37,7 +51,7 @@ def decode(q, cache, Wq=None, *, rotate=True, literal_alg1=False):
     """
     q = np.asarray(q, dtype=np.float64)
     d = q.shape[0]
-    keys, vals = _operands(cache)
+    keys, vals = _operands(cache, value_window)
     score = keys @ q / np.sqrt(float(d))
     M = score.max()
     e = np.exp(score - M)

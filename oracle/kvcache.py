@@ -61,7 +61,8 @@ def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=
     possibly partial): k_codes, v_codes [n_groups, G, d] (token-in-group, channel; padding codes 0),
     k_scale, k_zero [n_groups, d] per channel, v_scale, v_zero [n_groups, G] per token (padding 0),
     the dequantized K_hat, V_hat [n_quant, d] (fp64); the window k_res (raw) and v_res (rotated)
-    [n_res, d]; and S [D, d], P [D] if adapters Wk [2, d, D/2] are given.
+    [n_res, d]; v_rot, the rotated values of ALL tokens as the window would hold them (for the sliding value window
+    of the decode oracle); and S [D, d], P [D] if adapters Wk [2, d, D/2] are given.
     mode: 'spec32' (GPU contract, fp16 storage), 'exact16' (fp64 arithmetic, fp16 storage),
     'real' (Eq. 1 in fp64 throughout, any bit width; for convergence checks only).
     state_rounding: None = S kept exactly (fp64).  Otherwise an iterable of quantized-token counts (multiples of G):
@@ -91,7 +92,7 @@ def build_cache(K, V, n_quant, *, G=128, bits=2, mode="spec32", rotate=True, Wk=
         "k_scale": np.zeros((n_groups, d), dtype=store), "k_zero": np.zeros((n_groups, d), dtype=store),
         "v_scale": np.zeros((n_groups, G), dtype=store), "v_zero": np.zeros((n_groups, G), dtype=store),
         "K_hat": np.zeros((n_quant, d)), "V_hat": np.zeros((n_quant, d)),
-        "k_res": K[n_quant:].copy(), "v_res": Vr[n_quant:].copy(),
+        "k_res": K[n_quant:].copy(), "v_res": Vr[n_quant:].copy(), "v_rot": np.asarray(Vr).copy(),
     }
     for g in range(n_groups):
         t0, t1 = g * G, min((g + 1) * G, n_quant)

@@ -179,6 +179,45 @@ def test_sixteen_bit_state_storage_rounds_at_the_stated_points():
     assert np.isfinite(big["S"]).all() and np.abs(big["S"]).max() <= 65504.0
 
 
+def test_sliding_value_window_uniform_attention_closed_form():
+    """Sec. 4.1 (setup): with a zero query every token weighs the same, so the rotated output is the plain mean of the
+    values the mode uses: fp16 values for the newest 128 tokens, dequantized ones for all older tokens -- whatever the key
+    window holds (here 44 tokens).  The block mode uses the fp16 values of the 44 window tokens only."""
+    _, K, V, _, _ = _case(n=300, seed=11)
+    c = kvcache.build_cache(K, V, 256)
+    q0 = np.zeros(128, dtype=np.float16)
+    vr = c["v_rot"].astype(np.float64)
+    want_sliding = (c["V_hat"][:300 - 128].sum(0) + vr[300 - 128:].sum(0)) / 300.0
+    want_block = (c["V_hat"].sum(0) + vr[256:].sum(0)) / 300.0
+    got_sliding = attention.decode(q0, c, None, rotate=False, value_window="sliding")
+    got_block = attention.decode(q0, c, None, rotate=False)
+    np.testing.assert_allclose(got_sliding, want_sliding, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(got_block, want_block, rtol=1e-12, atol=1e-14)
+    assert np.abs(want_sliding - want_block).max() > 1e-4  # the two modes are told apart by this case
+
+
+def test_sliding_value_window_equals_block_window_when_the_key_window_is_full():
+    """With 128 tokens in the key window the newest 128 tokens are the window tokens: both modes use the same values.
+    With fewer than 128 tokens in all nothing is quantized and again nothing differs."""
+    q, K, V, Wq, Wk = _case(n=384, seed=12)
+    c = kvcache.build_cache(K, V, 256, Wk=Wk)
+    np.testing.assert_array_equal(attention.decode(q, c, Wq, value_window="sliding"), attention.decode(q, c, Wq))
+    c = kvcache.build_cache(K[:100], V[:100], 0, Wk=Wk)
+    np.testing.assert_array_equal(attention.decode(q, c, Wq, value_window="sliding"), attention.decode(q, c, Wq))
+
+
+def test_sliding_value_window_is_closer_to_unquantized_values():
+    """More values in full precision: the error against attention over the quantized keys and exact values shrinks."""
+    q, K, V, _, _ = _case(n=300, seed=13)
+    c = kvcache.build_cache(K, V, 256)
+    exact_v = dict(c)
+    exact_v["V_hat"] = c["v_rot"][:256].astype(np.float64)
+    ref = attention.decode(q, exact_v, None)
+    e_block = np.linalg.norm(attention.decode(q, c, None) - ref)
+    e_sliding = np.linalg.norm(attention.decode(q, c, None, value_window="sliding") - ref)
+    assert e_sliding < e_block
+
+
 def test_partial_tail_group_uses_valid_tokens_only():
     _, K, V, _, _ = _case(n=256, seed=8)
     c = kvcache.build_cache(K, V, 224)  # one full group + 96 tokens

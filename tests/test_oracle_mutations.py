@@ -73,6 +73,13 @@ CASES = [
      'np.concatenate([cache["K_hat"], cache["k_res"].astype(np.float64)], axis=0)',
      'np.concatenate([cache["K_hat"], cache["k_res"][:0].astype(np.float64)], axis=0)',
      [pa.test_bits_to_16_converges_to_textbook_attention]),
+    ("sliding value window: the window is one token short", attention, "_operands", "first = max(0, n - R)",
+     "first = max(0, n - R + 1)", [pa.test_sliding_value_window_uniform_attention_closed_form]),
+    ("sliding value window: values leave with the keys after all", attention, "_operands", "first = max(0, n - R)",
+     "first = nq", [pa.test_sliding_value_window_uniform_attention_closed_form]),
+    ("sliding value window: window values taken unrotated-window order (from the start of the sequence)", attention,
+     "_operands", 'vals[first:] = cache["v_rot"][first:]', 'vals[first:] = cache["v_rot"][:n - first]',
+     [pa.test_sliding_value_window_uniform_attention_closed_form]),
     ("block merge weighted by exp(M - m) instead of exp(m - M)", attention, "decode_blocks", "w = np.exp(m - M)",
      "w = np.exp(M - m)", [(pa.test_block_merge_equals_single_softmax, False)]),
     ("C_d taken from S instead of P", attention, "correction_terms", 'float(phi_q @ cache["P"])',

@@ -127,8 +127,13 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run 4 plain device copies of 256 MiB, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
+    ap.add_argument("--variant", default="default", choices=["default", "sliding-values", "state16", "alg1-literal"],
+                    help="measure one of the variants of the path (descriptor flags / 16-bit state storage); the "
+                         "default line is the one the metric is quoted on")
     ap.add_argument("--no-events", action="store_true", help="diagnosis: no per-launch events (roofline is then void)")
     args = ap.parse_args()
+    if args.variant != "default":
+        args.no_cpu_baseline = True  # the oracle leg (timing and parity sample) belongs to the default path
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence / "
               "KV head without communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
@@ -186,7 +191,9 @@ def main():
         if wl != 5 and j % 4 == 0:
             short = min(n0 - 1, W // L + 3 + (j // 4) * 7)  # its window (full at n0) flushes at append `short`+1
         n_start = base_len - short
-        c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk)
+        c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk,
+                           state_storage="fp16" if args.variant == "state16" else "fp32",
+                           flags={"sliding-values": kv.KVLINC_FLAG_SLIDING_VALUES, "alg1-literal": kv.KVLINC_FLAG_ALG1_LITERAL}.get(args.variant, 0))
         t_max = int(n_start.max())
         c.append(Kd[:, :, :t_max].contiguous(), Vd[:, :, :t_max].contiguous(),
                  n_new=torch.from_numpy(n_start.astype(np.int32)).to(dev))
@@ -301,7 +308,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u2 codes, f16 operands, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": cfg["name"], "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
+        "config": {"workload": cfg["name"] + ("" if args.variant == "default" else " [variant: %s]" % args.variant), "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
                    "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0), "window": 128, "group": 128, "bits": 2, "correction_rank": 256,
                    "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
                    "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),

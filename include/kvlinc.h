@@ -22,8 +22,9 @@
  *   - Faults only the device can see (capacity exhausted, non-finite input, append to a cache whose
  *     last group is partial) set bits in *status and leave that sequence unchanged: its counters, its live group
  *     records and window rows, and its states S, P, S16 (in all KV heads) are bit for bit what they were.  Storage
- *     beyond the counters (group records from n_quant / 128 on, window slots from n_res on) is dead and may have
- *     been overwritten; a non-finite value is never stored into the window.
+ *     beyond the counters (group records from n_quant / 128 on, window slots from n_res on -- key slots only when
+ *     KVLINC_FLAG_SLIDING_VALUES is set, see flags) is dead and may have been overwritten; a non-finite value is never
+ *     stored into the window.
  *   - Magnitudes: the operands of the matrix products carry a block exponent per group and query head, so keys,
  *     queries and values of any finite binary16 magnitude keep the tolerance.  What can leave its range is the
  *     16-bit copy of the state: an entry of S beyond +-65504 is stored saturated and reported as
@@ -68,6 +69,15 @@
  *   flags             KVLINC_FLAG_* bits.  KVLINC_FLAG_ALG1_LITERAL: the merge adds C_n, C_d to the max-shifted sums
  *                     as the last lines of Alg. 1 print them, (num + C_n) / (den + C_d), instead of Eq. 5's
  *                     (num + e^-M C_n) / (den + e^-M C_d) (the two differ by the factor e^-M, M = largest score).
+ *                     KVLINC_FLAG_SLIDING_VALUES (Sec. 4.1, setup: the most recent 128 tokens in full precision):
+ *                     keys can only leave the fp16 window a group at a time (they are quantized per channel over 128
+ *                     tokens), values are quantized per token and leave one at a time: the decode step takes the
+ *                     fp16 rotated values of the newest 128 tokens and the quantized values of all older ones,
+ *                     whatever n_res is.  The value of token t lives in window slot t % 128: the slots n_res..127 of
+ *                     v_res then hold the values of the last 128 - n_res tokens of the newest group and are live (an
+ *                     incremental append leaves them there anyway; a bulk append stores them when the flag is set).
+ *                     The states and the records are the same with and without the flag.  Needs R = 128 and
+ *                     keep_residual = 0; set it when the cache is created and keep it.
  *   status            [1] int32, OR-ed KVLINC_ST_* bits.
  *   split_done        [B, H_kv] int32 scratch counters (arrival counts: of the workgroups of a (sequence, KV head)
  *                     in kvlinc_decode_attention, where the last one merges; of the workgroups of a sequence in
@@ -110,7 +120,8 @@ enum {
 };
 
 enum {
-  KVLINC_FLAG_ALG1_LITERAL = 1 /* correction added without the e^-M factor (Alg. 1 as printed) */
+  KVLINC_FLAG_ALG1_LITERAL = 1,  /* correction added without the e^-M factor (Alg. 1 as printed) */
+  KVLINC_FLAG_SLIDING_VALUES = 2 /* values leave the fp16 window one token at a time (Sec. 4.1, setup) */
 };
 
 typedef struct kvlinc_cache {

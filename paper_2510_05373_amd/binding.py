@@ -8,6 +8,7 @@ lib_path = os.path.join(HERE, "libkvlinc.so")
 KVLINC_OK, KVLINC_EINVAL, KVLINC_EWORKSPACE, KVLINC_EHIP, KVLINC_ESCRATCH = 0, -1, -2, -3, -4
 KVLINC_STATIC_SCRATCH_BYTES = 16 << 20
 KVLINC_FLAG_ALG1_LITERAL = 1
+KVLINC_FLAG_SLIDING_VALUES = 2
 KVLINC_ST_CAPACITY, KVLINC_ST_NONFINITE, KVLINC_ST_STATIC, KVLINC_ST_STATE_RANGE = 1, 2, 4, 8
 
 

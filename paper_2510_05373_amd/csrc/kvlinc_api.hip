@@ -66,7 +66,8 @@ int kvlinc_cache_validate(const kvlinc_cache* c) {
   if (n_corr == 4 && (!aligned(c->S, 16) || !aligned(c->S16, 16) || !aligned(c->P, 16) || !aligned(c->Wq, 16) ||
                       !aligned(c->Wk, 16)))
     return KVLINC_EINVAL;
-  if ((c->flags & ~KVLINC_FLAG_ALG1_LITERAL) != 0) return KVLINC_EINVAL;
+  if ((c->flags & ~(KVLINC_FLAG_ALG1_LITERAL | KVLINC_FLAG_SLIDING_VALUES)) != 0) return KVLINC_EINVAL;
+  if ((c->flags & KVLINC_FLAG_SLIDING_VALUES) != 0 && c->R != kvlinc::kGroup) return KVLINC_EINVAL;
   return KVLINC_OK;
 }
 
@@ -79,6 +80,7 @@ int kvlinc_append_quantize(const kvlinc_cache* cache, const kvlinc_half* k_new, 
   if (T < 1 || T > (1 << 24)) return KVLINC_EINVAL;
   if (keep_residual < 0 || keep_residual > cache->R) return KVLINC_EINVAL;
   if (keep_residual == 0 && cache->R != kvlinc::kGroup) return KVLINC_EINVAL;
+  if (keep_residual != 0 && (cache->flags & KVLINC_FLAG_SLIDING_VALUES) != 0) return KVLINC_EINVAL;
   return kvlinc::launch_append(*cache, k_new, v_new, n_new, T, keep_residual, static_cast<hipStream_t>(stream));
 }
 

@@ -169,6 +169,50 @@ __device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __re
   return false;
 }
 
+// One-token append: is the new row of any kv head of sequence b non-finite (key) or beyond fp16 once rotated (value)?
+// The caller's waves share the heads: wave `first` of `stride` takes the heads first, first + stride, ..., eight per
+// batch; the verdicts of the waves still have to be combined.  g: a head whose row may be read in place of a missing one.
+__device__ inline bool new_rows_of_all_heads_bad(const kvlinc_cache& c, int b, int g, const half_t* __restrict__ k_new,
+                                                 const half_t* __restrict__ v_new, int lane, int first, int stride) {
+  bool refuse = false;
+  for (int g0 = first; g0 < c.H_kv; g0 += stride * 8) {
+    uint32_t chk_k[8], chk_v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int g2 = g0 + stride * u;
+      const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
+      chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
+      chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
+    }
+    // A rotated value is at most sum_i |v_i| / sqrt(128): rows whose sum of magnitudes stays below
+    // 65504 sqrt(128) cannot overflow fp16 and need no rotation here (a non-finite v makes the sum non-finite).
+    float mag[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      refuse |= nonfinite_pair(chk_k[u]);
+      const half2_t h = as_h2(chk_v[u]);
+      mag[u] = fabsf((float)h[0]) + fabsf((float)h[1]);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) mag[u] = wave_allsum(mag[u]);
+#pragma unroll
+    for (int u0 = 0; u0 < 8; u0 += 4) {
+      if (mag[u0] < 741000.0f && mag[u0 + 1] < 741000.0f && mag[u0 + 2] < 741000.0f && mag[u0 + 3] < 741000.0f) continue;
+      float x0[4], x1[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const half2_t h = as_h2(chk_v[u0 + u]);
+        x0[u] = (float)h[0];
+        x1[u] = (float)h[1];
+      }
+      fwht128_wave_multi<4>(x0, x1, lane);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) refuse |= nonfinite_bits((half_t)x0[u]) || nonfinite_bits((half_t)x1[u]);
+    }
+  }
+  return refuse;
+}
+
 struct Counters {
   int nq, nr, n;
   AppendPlan plan;
@@ -186,6 +230,7 @@ __device__ inline Counters read_counters(const kvlinc_cache& c, int b, const int
 // An append that quantizes nothing: one wave stores the new rows of one (sequence, kv head) behind the window's
 // tokens.  The slots are dead storage until the counters advance, and they do not advance if any head of the sequence
 // votes against.
+template <bool SLIDING>
 __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __restrict__ k_new,
                                   const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
                                   int lane) {
@@ -196,7 +241,13 @@ __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __
   const half_t* k_src = k_new + (long long)p * T * kHeadDim;
   const half_t* v_src = v_new + (long long)p * T * kHeadDim;
   bool row_bad = false;
-  for (int i = 0; i < s.n; ++i)
+  // With the sliding value window the value slots behind the key window are live (the values of the newest group's
+  // last tokens): nothing may be written there before the new rows of ALL kv heads of the sequence have been looked at.
+  if (SLIDING && c.H_kv > 1) {
+    if (T == 1) row_bad = __builtin_amdgcn_ballot_w64(new_rows_of_all_heads_bad(c, b, p % c.H_kv, k_new, v_new, lane, 0, 1)) != 0;
+    else row_bad = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
+  }
+  for (int i = 0; i < s.n && !row_bad; ++i)
     row_bad |= store_window_row(k_win, v_win, s.nr + i, k_src + (long long)i * kHeadDim, v_src + (long long)i * kHeadDim, lane);
   if (lane == 0) {
     if (row_bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
@@ -326,6 +377,7 @@ __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u
 // both signs: the products of every 32 tokens start from a zero addend and are added to S by ordinary binary32
 // additions, the codes are centred (the other part is the same for all channels of a row), and of the two terms of the
 // key error the small one is contracted first.
+template <bool SLIDING>
 __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
                            const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -393,41 +445,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
     if (T == 1) {
       // A one-token append that flushes the window changes live state (S, P, the window's first slot) in every kv
       // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.
-      for (int g0 = wave; g0 < c.H_kv; g0 += kWaves * 8) {
-        uint32_t chk_k[8], chk_v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int g2 = g0 + kWaves * u;
-          const long long row = ((long long)b * c.H_kv + (g2 < c.H_kv ? g2 : g)) * kHeadDim + 2 * lane;
-          chk_k[u] = *reinterpret_cast<const uint32_t*>(k_new + row);
-          chk_v[u] = *reinterpret_cast<const uint32_t*>(v_new + row);
-        }
-        // A rotated value is at most sum_i |v_i| / sqrt(128): rows whose sum of magnitudes stays below
-        // 65504 sqrt(128) cannot overflow fp16 and need no rotation here (a non-finite v makes the sum non-finite).
-        float mag[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          refuse |= nonfinite_pair(chk_k[u]);
-          const half2_t h = as_h2(chk_v[u]);
-          mag[u] = fabsf((float)h[0]) + fabsf((float)h[1]);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) mag[u] = wave_allsum(mag[u]);
-#pragma unroll
-        for (int u0 = 0; u0 < 8; u0 += 4) {
-          if (mag[u0] < 741000.0f && mag[u0 + 1] < 741000.0f && mag[u0 + 2] < 741000.0f && mag[u0 + 3] < 741000.0f) continue;
-          float x0[4], x1[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const half2_t h = as_h2(chk_v[u0 + u]);
-            x0[u] = (float)h[0];
-            x1[u] = (float)h[1];
-          }
-          fwht128_wave_multi<4>(x0, x1, lane);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) refuse |= nonfinite_bits((half_t)x0[u]) || nonfinite_bits((half_t)x1[u]);
-        }
-      }
+      refuse = new_rows_of_all_heads_bad(c, b, g, k_new, v_new, lane, wave, kWaves);
     } else if (c.H_kv > 1) {
       refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
     } else {
@@ -864,6 +882,22 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
                        k_new + (bh2 * T + (u - nr)) * kHeadDim, v_new + (bh2 * T + (u - nr)) * kHeadDim, lane);
     }
   }
+  if (SLIDING && flag == 2 && T > 1) {
+    // Sliding value window after a bulk append: the newest 128 tokens keep their fp16 values, the value of stream
+    // index u in window slot u % 128 (n_quant is a multiple of 128).  Those among them that were quantized in this
+    // call and came in as new tokens are stored here (old window tokens lie in their slots already).
+    const int lo = max(nr, nr + n - kGroup), cnt2 = plan.n_flush - lo;
+    for (int r = wave; r < cnt2 * c.H_kv; r += kWaves) {
+      const int g2 = r / cnt2, u = lo + r % cnt2, slot = u % kGroup;
+      const long long bh2 = (long long)b * c.H_kv + g2;
+      const half_t* vs = v_new + (bh2 * T + (u - nr)) * kHeadDim;
+      half_t* v_win = reinterpret_cast<half_t*>(c.v_res) + bh2 * c.R * kHeadDim;
+      float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
+      fwht128_wave(x0, x1, lane);
+      v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = (half_t)x0;
+      v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = (half_t)x1;
+    }
+  }
   __syncthreads();
   if (flag != 0 && tid == 0) finish(c, b, nq, n, plan, flag == 2);
 }
@@ -872,6 +906,8 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 // (it / (8 kParts)) * 8 + it % 8 of (sequence, kv head), and workgroup x owns the items x, x + G, x + 2 G, ...: the parts of a
 // pair sit on one XCD (workgroups are dealt to the 8 XCDs in turn, and G is a multiple of 8), whose L2 then serves
 // the rows that all of them stage.
+// SLIDING: the variant for caches with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own.
+template <bool SLIDING>
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
                                                                  const int32_t* __restrict__ n_new, int T, int keep) {
@@ -914,9 +950,9 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     }
     __syncthreads();
     const int n_light = L.n_light, n_heavy = L.n_heavy;
-    for (int i = wave; i < n_light; i += kThreads / 64) light_item(c, L.light[i], k_new, v_new, n_new, T, keep, lane);
+    for (int i = wave; i < n_light; i += kThreads / 64) light_item<SLIDING>(c, L.light[i], k_new, v_new, n_new, T, keep, lane);
     for (int i = 0; i < n_heavy; ++i) {
-      flush_item(c, L, L.heavy[i], k_new, v_new, n_new, T, keep);
+      flush_item<SLIDING>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep);
       __syncthreads();
     }
     __syncthreads();
@@ -929,7 +965,9 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
                   int T, int keep, hipStream_t stream) {
   static_assert(sizeof(Lds) <= 160 * 1024, "LDS budget of one CU");
   // per device and cheap: set on every call rather than remembered in process state
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(append_flush_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+  void (*kernel)(kvlinc_cache, const half_t*, const half_t*, const int32_t*, int, int) =
+      (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0 ? append_flush_kernel<true> : append_flush_kernel<false>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sizeof(Lds)) != hipSuccess)
     return KVLINC_EHIP;
   if (T > 1 && c.H_kv > 1)
@@ -939,7 +977,7 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
   // in further rounds by the same workgroups
   const long long n_items = kParts * 8 * (((long long)c.B * c.H_kv + 7) / 8);
   const int grid = (int)(n_items < 256 ? n_items : 256);
-  hipLaunchKernelGGL(append_flush_kernel, dim3(grid), dim3(kThreads), sizeof(Lds), stream, c,
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), sizeof(Lds), stream, c,
                      reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   return KVLINC_OK;

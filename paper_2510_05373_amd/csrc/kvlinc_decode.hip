@@ -340,10 +340,11 @@ __device__ __forceinline__ void update_reference(const float (&sc)[NB][8], WaveS
   }
 }
 
-// p = 2^(x - m), its sums, and E V of one group (Alg. 1 lines 9-10).
-template <int NB>
+// p = 2^(x - m), its sums, and E V of one group (Alg. 1 lines 9-10).  MASKED: tokens from `fp16_from` on count in the
+// sums of p but not in E V: their values are taken from the fp16 window (pv_window_tail).
+template <int NB, bool MASKED = false>
 __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[NB][8], const Roles& lr,
-                                         WaveState<NB>& st) {
+                                         WaveState<NB>& st, int fp16_from = kGroup) {
   const uint32_t SZ[8] = {g.sz[0].x, g.sz[0].y, g.sz[0].z, g.sz[0].w, g.sz[1].x, g.sz[1].y, g.sz[1].z, g.sz[1].w};
   v8i_t A[NB];
   int scale_a[NB];
@@ -355,9 +356,10 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
       const float p = __builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]);
       const half2_t sz = as_h2(SZ[n]);
       st.l[nb] += p;
-      y[n] = fmaf(p, (float)sz[0], 0.0f);  // p * value scale: the weight of the token's codes
+      const bool coded = !MASKED || 16 * n + lr.jd < fp16_from;
+      y[n] = coded ? fmaf(p, (float)sz[0], 0.0f) : 0.0f;  // p * value scale: the weight of the token's codes
       // sum_t p_t (z_t + 1.5 s_t): the zero-points and the centring of the codes, the same for every channel
-      st.pz[nb] = fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb]));
+      st.pz[nb] = coded ? fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb])) : st.pz[nb];
       mx = fmaxf(mx, y[n]);
     }
     const uint32_t eb = block_exponent(row_umax(as_bits(mx)));  // over the 128 tokens of the head
@@ -379,6 +381,42 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
       for (int nb = 0; nb < NB; ++nb)
         st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick);
   }
+}
+
+// Sliding value window (Sec. 4.1, setup: the newest 128 tokens in full precision): the tokens j >= from of the newest
+// group still have their fp16 rotated values in the window slots j.  Their share of E V is formed here from those values
+// in plain binary32 arithmetic -- at most 127 tokens per (sequence, kv head) and step, by the one wave that has the
+// newest group -- and goes to the spare row of the accumulators.  Lane (head hd, column jd) takes the channels 16 n + jd.
+template <int NB>
+__device__ __forceinline__ void pv_window_tail(const half_t* __restrict__ v_win, const float (&sc)[NB][8], int from,
+                                               const Roles& lr, WaveState<NB>& st, int lane) {
+  float* pbuf = reinterpret_cast<float*>(lr.ex_pv);  // [4 heads][128 tokens]
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int j = 16 * n + lr.jd;
+      pbuf[kGroup * lr.hd + j] = j >= from ? __builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]) : 0.0f;
+    }
+    lds_order();
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int q = from >> 2; q < kGroup / 4; ++q) {  // 4 window slots per step: [slot / 4][channel][slot % 4]
+      const float4 p4 = *reinterpret_cast<const float4*>(pbuf + kGroup * lr.hd + 4 * q);
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const uint2 w = *reinterpret_cast<const uint2*>(v_win + ((long long)q * kHeadDim + 16 * n + lr.jd) * 4);
+        const half2_t lo = as_h2(w.x), hi = as_h2(w.y);
+        a[n] = fmaf(p4.x, (float)lo[0], fmaf(p4.y, (float)lo[1], fmaf(p4.z, (float)hi[0], fmaf(p4.w, (float)hi[1], a[n]))));
+      }
+    }
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.acc[nb][n][3] += a[n];
+    lds_order();
+  }
+  // the spare term row of every head of this exchange region reads as zero again
+  uint32_t* ex = reinterpret_cast<uint32_t*>(lr.ex_pv);
+  for (int i = lane; i < 4 * 32; i += 64) ex[(i >> 5) * kExHead + 96 + (i & 31)] = 0u;
+  lds_order();
 }
 
 // ---- half of the fp16 window as one more block of 64 tokens of one wave (raw keys, rotated values) ---------------
@@ -757,7 +795,9 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
 // sequence uses fewer splits; and, when the correction is on, the correction workgroups: after them (corr_first = 0)
 // or leading the first corr_first runs of 256 workgroups (1: all of them first -- they are long chains of dependent
 // steps and should start at once).  All of them count themselves in at split_done; the last arrival merges.
-template <int NB>
+// SLIDING: the variant with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own, so that the
+// default one carries none of its code.
+template <int NB, bool SLIDING = false>
 __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
                                                                    half_t* __restrict__ out, int max_splits,
@@ -955,7 +995,11 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
     // While a group is consumed the wave's next record is already requested: its key part right after the scores,
     // its value part right after E V.  Past the last group the current (cached) record is requested once more, so
     // that no branch joins between a request and its first use and the waits stay partial.
-    while (idx < count) {
+    // sliding value window: the newest group's tokens from n_res on take their values from the window
+    // (the newest group is left to the code below when its last tokens take their values from the window)
+    const bool sliding = SLIDING && nq % kGroup == 0 && nr < kGroup;
+    const int count_plain = sliding ? count - 1 : count;
+    while (idx < count_plain) {
       const int nxt = group_of_round(++rd);
       const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
       float sc[NB][8];
@@ -965,6 +1009,13 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       pv_phase<NB>(vr, sc, lr, st);
       load_values(vr, src, lr);
       idx = nxt;
+    }
+    if (SLIDING && idx < count) {  // sliding value window: the newest group, whose tokens from n_res on have fp16 values
+      float sc[NB][8];
+      qk_phase<NB>(kr, kGroup, qa, qh, lr, sc);
+      update_reference<NB>(sc, st);
+      pv_phase<NB, true>(vr, sc, lr, st, nr);
+      pv_window_tail<NB>(reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim, sc, nr, lr, st, lane);
     }
   }
 
@@ -1103,17 +1154,14 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const int n_corr = corr != nullptr ? c.H_kv * kCorrParts * ((c.B + kCorrSeqs - 1) / kCorrSeqs) : 0;
   const dim3 grid(BH * n_splits + n_corr), block(kThreads);
   const int corr_first = sp.corr_first;
-  if (start != nullptr) {  // timestamps of the dispatch itself, no extra packets on the stream
-    if (gq <= 4)
-      hipExtLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
-    else
-      hipExtLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
-  } else {
-    if (gq <= 4)
-      hipLaunchKernelGGL(decode_main_kernel<1>, grid, block, 0, stream, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
-    else
-      hipLaunchKernelGGL(decode_main_kernel<2>, grid, block, 0, stream, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
-  }
+  const bool sliding = (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0;
+  void (*kernel)(kvlinc_cache, const half_t*, float*, float*, half_t*, int, int, int, int) =
+      gq <= 4 ? (sliding ? decode_main_kernel<1, true> : decode_main_kernel<1, false>)
+              : (sliding ? decode_main_kernel<2, true> : decode_main_kernel<2, false>);
+  if (start != nullptr)  // timestamps of the dispatch itself, no extra packets on the stream
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
   return hipGetLastError() == hipSuccess ? KVLINC_OK : KVLINC_EHIP;
 }
 

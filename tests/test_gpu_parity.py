@@ -596,3 +596,87 @@ def test_timed_entry_point_gives_the_same_bits(kv):
     assert torch.equal(out, plain)
     hip.hipEventDestroy(e0)
     hip.hipEventDestroy(e1)
+
+
+def _sliding_reference(K, V, q, lengths, n_quant, H_q, H_kv, Wq, Wk):
+    want = {}
+    gq = H_q // H_kv
+    for b in range(len(lengths)):
+        for g in range(H_kv):
+            n = int(lengths[b])
+            ref = tl.o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=None if Wk is None else Wk[g])
+            for h in range(g * gq, (g + 1) * gq):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h], value_window="sliding")
+    return want
+
+
+@pytest.mark.parametrize("gq", [4, 7])
+@pytest.mark.parametrize("correction", [True, False])
+def test_sliding_value_window(kv, gq, correction):
+    """KVLINC_FLAG_SLIDING_VALUES (Sec. 4.1, setup): the values of the newest 128 tokens are the fp16 ones whatever the
+    key window holds.  A bulk build (which has to store the newest group's values into the window) and one-token appends
+    across a flush (which leave them there), decoded after every few appends, against the oracle's sliding mode; the
+    records, states and window rows are those of the block mode."""
+    import torch
+    B, H_kv = 3, 2
+    H_q = gq * H_kv
+    pre = [517, 128 + 77, 60]      # key windows of 5, 77 and 60 tokens; the last sequence has nothing quantized
+    extra = 140                    # every sequence crosses a flush
+    lengths = [p + extra for p in pre]
+    K, V = tl.gen_kv(36, B, H_kv, lengths)
+    Wq, Wk = (synth.adapters_q(36, H_q), synth.adapters_k(36, H_kv)) if correction else (None, None)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk),
+                           flags=kv.KVLINC_FLAG_SLIDING_VALUES)
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :max(pre)].contiguous(), Vd[:, :, :max(pre)].contiguous(), n_new=tl.to_dev(np.asarray(pre, dtype=np.int32)))
+    worst_gap = 0.0
+    for s in range(extra + 1):
+        cur = [p + s for p in pre]
+        if s in (0, 1, 50, 67, 68, 69, 123, 124, 139, 140):
+            q = tl.gen_q(36, B, H_q, step=s)
+            out = cache.decode(tl.to_dev(q)).cpu().numpy().astype(np.float64)
+            assert int(cache.status.item()) == 0
+            n_quant, n_res = tl.check_counters(cache, cur)
+            want = _sliding_reference(K, V, q, cur, n_quant, H_q, H_kv, Wq, Wk)
+            tl.check_outputs(out, want)
+            # the block mode's answer differs (so the comparison above tells the two apart)
+            blockw = tl.oracle_decode(K, V, q, cur, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+            worst_gap = max(worst_gap, max(np.abs(want[k] - blockw[k]).max() for k in want))
+        if s < extra:
+            kn = torch.stack([Kd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            cache.append(kn, vn)
+    assert worst_gap > 1e-3
+    # records, states and window rows are what the block mode stores
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    for b in range(B):
+        for g in range(H_kv):
+            tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), int(n_res[b]),
+                                         None if Wk is None else Wk[g], check_states=correction)
+
+
+def test_sliding_value_window_keeps_a_refused_append_out_of_the_live_value_slots(kv):
+    """With the sliding window the value slots behind the key window are live.  A one-token append with a non-finite
+    key in ONE kv head must leave them alone in ALL kv heads: the decode result after the refused append equals the one
+    before it, bit for bit."""
+    import torch
+    B, H_q, H_kv = 2, 8, 4
+    n0 = 128 + 40
+    K, V = tl.gen_kv(37, B, H_kv, [n0 + 1] * B)
+    cache = kv.KVLincCache(B, H_q, H_kv, 512, flags=kv.KVLINC_FLAG_SLIDING_VALUES)
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :n0].contiguous(), Vd[:, :, :n0].contiguous())
+    q = tl.to_dev(tl.gen_q(37, B, H_q))
+    before = cache.decode(q).clone()
+    v_before = cache.v_res.clone()
+    kn = Kd[:, :, n0:n0 + 1].clone()
+    kn[1, 2, 0, 5] = float("inf")
+    cache.append(kn, Vd[:, :, n0:n0 + 1].contiguous())
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) & kv.KVLINC_ST_NONFINITE
+    nr = cache.n_res.cpu().numpy()
+    assert list(nr) == [41, 40]
+    assert torch.equal(cache.v_res[1], v_before[1])
+    cache.status.zero_()
+    after = cache.decode(q)
+    assert torch.equal(after[1], before[1])

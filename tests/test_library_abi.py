@@ -76,7 +76,7 @@ def test_validate_accepts_and_rejects():
     bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=4), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
            dict(H_q=32, H_kv=2), dict(B=0), dict(max_groups=0), dict(groups=0), dict(groups=0x10004), dict(k_res=0),
            dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S16=0),
-           dict(S16=0x10008), dict(Wk=0), dict(P=0x10002), dict(S=0x10004), dict(flags=2), dict(flags=-1),
+           dict(S16=0x10008), dict(Wk=0), dict(P=0x10002), dict(S=0x10004), dict(flags=4), dict(flags=-1), dict(flags=kb.KVLINC_FLAG_SLIDING_VALUES, R=64),
            dict(S16=0, P=0, Wq=0, Wk=0)]  # (the last: an fp32 master copy without the rest of the correction)
     for over in bad:
         assert kb.kvlinc_cache_validate(fake_struct(**over)) == kb.KVLINC_EINVAL, over
@@ -84,6 +84,7 @@ def test_validate_accepts_and_rejects():
     assert kb.kvlinc_cache_validate(fake_struct(S=0, S16=0, P=0, Wq=0, Wk=0)) == kb.KVLINC_OK
     assert kb.kvlinc_cache_validate(fake_struct(S=0)) == kb.KVLINC_OK
     assert kb.kvlinc_cache_validate(fake_struct(flags=kb.KVLINC_FLAG_ALG1_LITERAL)) == kb.KVLINC_OK
+    assert kb.kvlinc_cache_validate(fake_struct(flags=kb.KVLINC_FLAG_SLIDING_VALUES | kb.KVLINC_FLAG_ALG1_LITERAL)) == kb.KVLINC_OK
     assert kb.lib.kvlinc_cache_validate(None) == kb.KVLINC_EINVAL
 
 

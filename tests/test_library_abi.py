@@ -99,6 +99,8 @@ def test_rejections_happen_before_any_launch():
     assert ap(ctypes.byref(ok), p, p, None, 1, 129, None) == kb.KVLINC_EINVAL
     assert ap(ctypes.byref(ok), p, p, None, 1, -1, None) == kb.KVLINC_EINVAL
     assert ap(ctypes.byref(fake_struct(R=32)), p, p, None, 1, 0, None) == kb.KVLINC_EINVAL  # lazy flush needs R == G
+    # the sliding value window maps token t to slot t % 128: no static cache with kept tokens
+    assert ap(ctypes.byref(fake_struct(flags=kb.KVLINC_FLAG_SLIDING_VALUES)), p, p, None, 64, 32, None) == kb.KVLINC_EINVAL
     de = kb.lib.kvlinc_decode_attention
     need = kb.kvlinc_decode_workspace_bytes(ok, 0)
     assert need > 0

@@ -127,27 +127,31 @@ __device__ inline uint32_t q2_code(float x, const Q2& p) {
   return p.s == 0.0f ? 0u : c;
 }
 
-// Every (sequence, kv head) has kParts owners in the grid, fixed by the launch shape alone.  Each owner reads the
-// sequence's counters once and counts itself in at the sequence's first split_done entry when it is done -- with a
-// vote in the upper half of the counter if it found a fault; the counters change only in the arrival that completes
-// the count (kParts H_kv), i.e. after every reader has read them, and only if nobody voted against.  That arrival
-// leaves the counter (and the sequence's fault flag of the scan launch, its second split_done entry) at zero, as the
-// decode kernel, which uses the same entries in the same way, expects.
+// Every (sequence, kv head) has kParts * n_chunks owners in the grid, fixed by the launch shape alone (n_chunks > 1
+// only in a bulk append of few sequences, whose groups are then shared out in chunks).  Each owner reads the sequence's
+// counters once and counts itself in at the sequence's first split_done entry when it is done -- with a vote in the
+// upper half of the counter if it found a fault; the counters change only in the arrival that completes the count
+// (kParts n_chunks H_kv), i.e. after every reader has read them, and only if nobody voted against.  The scan launch
+// that precedes a bulk append raises bit 30 of the same entry for a sequence with a non-finite new row: it reads as a
+// vote.  The completing arrival leaves the entry at zero, as the decode kernel, which uses the same entries in the
+// same way, expects.
 constexpr int kFaultVote = 1 << 16;
-__device__ inline bool arrive(const kvlinc_cache& c, int b, bool vote, bool* clean) {
+constexpr int kScanFlag = 1 << 30;
+__device__ inline bool arrive(const kvlinc_cache& c, int b, int n_chunks, bool vote, bool* clean) {
   int* counter = c.split_done + (long long)b * c.H_kv;
   const int before = __hip_atomic_fetch_add(counter, vote ? 1 + kFaultVote : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   *clean = !vote && before < kFaultVote;
-  return (before & (kFaultVote - 1)) == kParts * c.H_kv - 1;
+  return (before & (kFaultVote - 1)) == kParts * n_chunks * c.H_kv - 1;
 }
 __device__ inline void finish(const kvlinc_cache& c, int b, int nq, int n, const AppendPlan& plan, bool clean) {
-  int* counter = c.split_done + (long long)b * c.H_kv;
   if (clean && plan.err == 0 && n > 0) {
     c.n_quant[b] = nq + plan.n_flush;
     c.n_res[b] = plan.new_res;
   }
-  *counter = 0;
-  if (c.H_kv > 1) counter[1] = 0;
+  c.split_done[(long long)b * c.H_kv] = 0;
+}
+__device__ inline bool scan_flag(const kvlinc_cache& c, int b) {
+  return (__hip_atomic_load(c.split_done + (long long)b * c.H_kv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) & kScanFlag) != 0;
 }
 
 __device__ inline bool nonfinite_pair(uint32_t w) { return ((w & 0x7C00u) == 0x7C00u) || ((w & 0x7C000000u) == 0x7C000000u); }
@@ -233,7 +237,7 @@ __device__ inline Counters read_counters(const kvlinc_cache& c, int b, const int
 template <bool SLIDING>
 __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __restrict__ k_new,
                                   const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
-                                  int lane) {
+                                  int n_chunks, int lane) {
   const int b = p / c.H_kv;
   const Counters s = read_counters(c, b, n_new, T, keep);
   half_t* k_win = reinterpret_cast<half_t*>(c.k_res) + (long long)p * c.R * kHeadDim;
@@ -245,14 +249,14 @@ __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __
   // last tokens): nothing may be written there before the new rows of ALL kv heads of the sequence have been looked at.
   if (SLIDING && c.H_kv > 1) {
     if (T == 1) row_bad = __builtin_amdgcn_ballot_w64(new_rows_of_all_heads_bad(c, b, p % c.H_kv, k_new, v_new, lane, 0, 1)) != 0;
-    else row_bad = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
+    else row_bad = scan_flag(c, b);  // raised by the scan launch
   }
   for (int i = 0; i < s.n && !row_bad; ++i)
     row_bad |= store_window_row(k_win, v_win, s.nr + i, k_src + (long long)i * kHeadDim, v_src + (long long)i * kHeadDim, lane);
   if (lane == 0) {
     if (row_bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
     bool clean;
-    if (arrive(c, b, row_bad, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
+    if (arrive(c, b, n_chunks, row_bad, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
   }
 }
 
@@ -267,11 +271,12 @@ __device__ inline bool row_is_bad(const half_t* __restrict__ k_row, const half_t
   return bad || nonfinite_bits((half_t)x0) || nonfinite_bits((half_t)x1);
 }
 
-// Scan launch of a bulk append (T > 1) to a cache with more than one kv head: every new row of every (sequence, kv
-// head) is looked at once, and a fault raises the sequence's flag -- its second split_done entry -- so that ALL the
-// workgroups of that sequence in the append launch that follows refuse the append, whichever head the fault is in.
-// (With one kv head per sequence the append workgroup is alone and needs no flag; a one-token append looks at the
-// new rows of all heads itself.)  Grid: (B H_kv, chunks of kScanRows rows).
+// Scan launch of a bulk append (T > 1) to a cache with more than one kv head, or whose groups are shared out in
+// chunks: every new row of every (sequence, kv head) is looked at once, and a fault raises the sequence's flag (bit 30
+// of its first split_done entry) so that ALL the workgroups of that sequence in the append launch that follows refuse
+// the append, whichever head or chunk the fault is in.  (With one kv head and one chunk the two workgroups of the
+// sequence see all its rows themselves; a one-token append looks at the new rows of all heads itself.)
+// Grid: (B H_kv, chunks of kScanRows rows).
 constexpr int kScanRows = 256;
 __global__ __launch_bounds__(kThreads) void append_scan_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                 const half_t* __restrict__ v_new,
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void append_scan_kernel(kvlinc_cache c, c
   bool bad = false;
   for (int t = first + wave; t < last; t += kThreads / 64)
     bad |= row_is_bad(k_src + (long long)t * kHeadDim, v_src + (long long)t * kHeadDim, lane);
-  if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(c.split_done + (long long)b * c.H_kv + 1, 1);
+  if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(c.split_done + (long long)b * c.H_kv, kScanFlag);
 }
 
 __device__ inline void unpack8(const uint4& raw, float (&x)[8]) {
@@ -379,14 +384,24 @@ __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u
 // key error the small one is contracted first.
 template <bool SLIDING>
 __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
-                           const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep) {
+                           const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
+                           int n_chunks) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int p = item / kParts, fp = item % kParts;
+  const int ck = item % n_chunks, fp = (item / n_chunks) % kParts, p = item / (n_chunks * kParts);
   const int b = p / c.H_kv, g = p % c.H_kv;
   const long long bh = p;
   const Counters s = read_counters(c, b, n_new, T, keep);
   const int nq = s.nq, nr = s.nr, n = s.n;
   const AppendPlan plan = s.plan;
+  // Chunks (bulk append of few sequences): the groups of the call are shared out evenly among n_chunks owners per
+  // part, each of which forms the sum of its groups' contributions to S and P and adds it to the fp32 state in memory
+  // with atomic additions (the order of the additions, and with it the last bits of S, then differ from run to run);
+  // the arrival that completes the sequence rounds S to its binary16 tiles.  A call with one chunk in use -- every
+  // one-token append, every cache without an fp32 state -- keeps S in registers from load to store.
+  const int per_chunk = (plan.n_groups + n_chunks - 1) / n_chunks;
+  const int j_first = ck * per_chunk, j_last = min(plan.n_groups, j_first + per_chunk);
+  const bool chunked = plan.n_groups > per_chunk;  // more than one chunk has groups
+  const bool has_work = j_first < j_last;          // (without chunks: the owner of chunk 0 only)
 
   // (The loads of W_k and of the state are issued before the new rows are looked at: they are wanted in any case but a
   // refusal, and nothing is stored to global memory before the verdict.)
@@ -413,7 +428,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 #pragma unroll
   for (int fo = 0; fo < 8; ++fo) Pacc[fo] = 0.0f;
   float P_old = 0.0f;
-  if (states_live) {
+  if (states_live && has_work) {
     const half_t* W0 = reinterpret_cast<const half_t*>(c.Wk) + ((long long)g * 2 + fp) * kHeadDim * (kRank / 2);
     {  // transposed into LDS: a lane's B operand (8 channels of one feature) is then one 16-byte read.  Thread: feature
        // tid % 128 (consecutive lanes read consecutive halfs of a row of W), 8 channels per step.
@@ -428,7 +443,9 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
     }
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct) {
-      if (have_master) {
+      if (chunked) {
+        acc[ct] = float4_t{0.f, 0.f, 0.f, 0.f};
+      } else if (have_master) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[ct][r] = c.S[(bh * kRank + frow + r) * kHeadDim + 16 * ct + l16];
       } else {
@@ -437,7 +454,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         for (int r = 0; r < 4; ++r) acc[ct][r] = (float)t16[r];
       }
     }
-    if (tid < kRank / 2) P_old = c.P[bh * kRank + (kRank / 2) * fp + tid];
+    if (tid < kRank / 2 && !chunked) P_old = c.P[bh * kRank + (kRank / 2) * fp + tid];
   }
   {
     // non-finite new tokens: the verdict has to be the same in all workgroups of the sequence
@@ -446,8 +463,8 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       // A one-token append that flushes the window changes live state (S, P, the window's first slot) in every kv
       // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.
       refuse = new_rows_of_all_heads_bad(c, b, g, k_new, v_new, lane, wave, kWaves);
-    } else if (c.H_kv > 1) {
-      refuse = c.split_done[(long long)b * c.H_kv + 1] != 0;  // raised by the scan launch
+    } else if (c.H_kv > 1 || n_chunks > 1) {
+      refuse = scan_flag(c, b);  // raised by the scan launch
     } else {
       // bulk append, one kv head: the parts of this (sequence, kv head) are the sequence's only workgroups and see the
       // same rows.  The new rows that will stay in the window (at most R) are looked at here; those that get quantized
@@ -461,7 +478,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       if (tid == 0) {
         if (fp == 0) atomicOr(c.status, KVLINC_ST_NONFINITE);
         bool clean;
-        if (arrive(c, b, true, &clean)) finish(c, b, nq, n, plan, false);
+        if (arrive(c, b, n_chunks, true, &clean)) finish(c, b, nq, n, plan, false);
       }
       return;
     }
@@ -470,7 +487,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
   bool bad = false;
   const int sub = tid & 15, tq = tid >> 4;  // quantizer roles: channels 8 sub .. 8 sub + 7; tq = 0 .. 31
 
-  for (int j = 0; j < plan.n_groups; ++j) {
+  for (int j = j_first; j < j_last; ++j) {
     const int valid = min(kGroup, plan.n_flush - j * kGroup);
     const long long grp = (long long)(nq / kGroup) + j;
     uint32_t* rec = c.groups + (bh * c.max_groups + grp) * kRecordWords;
@@ -828,7 +845,31 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
   // A fault seen only now (one kv head per sequence in a bulk append; every part sees it) leaves states, window and
   // counters as they were; the records written above lie beyond n_quant and are dead storage.
   const bool any_bad = __syncthreads_or(bad) != 0;
-  if (!any_bad && states_live) {
+  if (!any_bad && states_live && chunked) {
+    if (has_work) {
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          __hip_atomic_fetch_add(c.S + (bh * kRank + frow + r) * kHeadDim + 16 * ct + l16, acc[ct][r], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_SYSTEM);
+#pragma unroll
+      for (int fo = 0; fo < 8; ++fo) Pacc[fo] = rows_sum(Pacc[fo]);
+      if (kq == 0) {
+#pragma unroll
+        for (int fo = 0; fo < 8; ++fo) L.red[wave][16 * fo + l16] = Pacc[fo];
+      }
+      __syncthreads();
+      if (tid < kRank / 2) {
+        float add = 0.0f;
+#pragma unroll
+        for (int w2 = 0; w2 < kWaves; ++w2) add += L.red[w2][tid];
+        __hip_atomic_fetch_add(c.P + bh * kRank + (kRank / 2) * fp + tid, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the additions of every wave are done before this owner
+    __syncthreads();                                  // counts itself in
+  } else if (!any_bad && states_live && has_work) {
     // fp32 master copy (if the cache keeps one), row-major, and the binary16 tiles the decode kernel reads: tile
     // (64-feature block, channel half hh, feature step fb) holds S[64 block + 4 fb + k][64 hh + l] at [l][k].
     // An entry beyond the binary16 range is stored as +-65504 and reported in the status word.
@@ -867,11 +908,30 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
   if (tid == 0) {
     if (any_bad && fp == 0) atomicOr(c.status, KVLINC_ST_NONFINITE);
     bool clean;
-    const bool last = arrive(c, b, any_bad, &clean);
+    const bool last = arrive(c, b, n_chunks, any_bad, &clean);
     L.last_flag = last ? (clean ? 2 : 1) : 0;
   }
   __syncthreads();
   const int flag = L.last_flag;
+  if (flag == 2 && chunked && states_live) {
+    // every chunk of every kv head has added its share: S of all kv heads of the sequence goes to the binary16 tiles
+    // (tile (64-feature block, channel half hh, feature step fb) holds S[64 block + 4 fb + k][64 hh + l] at [l][k])
+    bool out_of_range = false;
+    for (int i = tid; i < c.H_kv * 128 * 64; i += kThreads) {
+      const int g2 = i >> 13, t = (i >> 6) & 127, l = i & 63;
+      const long long bh2 = (long long)b * c.H_kv + g2;
+      const int f0 = 64 * (t >> 5) + 4 * (t & 15), ch = 64 * ((t >> 4) & 1) + l;
+      half4_t t16;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float v = __hip_atomic_load(c.S + (bh2 * kRank + f0 + k) * kHeadDim + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        out_of_range |= !(fabsf(v) <= 65504.0f);
+        t16[k] = (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+      }
+      *reinterpret_cast<half4_t*>(reinterpret_cast<half_t*>(c.S16) + bh2 * kRank * kHeadDim + ((long long)t * 64 + l) * 4) = t16;
+    }
+    if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 && lane == 0) atomicOr(c.status, KVLINC_ST_STATE_RANGE);
+  }
   if (flag == 2) {
     const int first_new = max(plan.n_flush, nr), cnt = nr + n - first_new;
     for (int r = wave; r < cnt * c.H_kv; r += kWaves) {
@@ -910,12 +970,14 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 template <bool SLIDING>
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
-                                                                 const int32_t* __restrict__ n_new, int T, int keep) {
+                                                                 const int32_t* __restrict__ n_new, int T, int keep,
+                                                                 int n_chunks) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   Lds& L = *reinterpret_cast<Lds*>(lds_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long n_pairs = (long long)c.B * c.H_kv;
-  const long long n_items = kParts * 8 * ((n_pairs + 7) / 8);
+  const int owners = kParts * n_chunks;  // per (sequence, kv head)
+  const long long n_items = (long long)owners * 8 * ((n_pairs + 7) / 8);
   const long long G = gridDim.x;
 
   for (long long k0 = 0; k0 * G < n_items; k0 += kListCap) {
@@ -927,32 +989,32 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     // every thread looks at one item: what needs a wave or the workgroup is listed, the rest is counted in at once
     const long long it = (k0 + tid) * G + blockIdx.x;
     if (it < n_items) {
-      const int fp = (int)((it >> 3) & (kParts - 1));
-      const long long p = (it / (8 * kParts)) * 8 + (it & 7);
+      const int own = (int)((it >> 3) % owners);  // (part, chunk): part = own / n_chunks, chunk = own % n_chunks
+      const long long p = (it / (8 * owners)) * 8 + (it & 7);
       if (p < n_pairs) {
         const int b = (int)(p / c.H_kv);
         const Counters s = read_counters(c, b, n_new, T, keep);
         if (s.plan.err || s.n == 0) {
-          if (s.plan.err && fp == 0) atomicOr(c.status, s.plan.err);
+          if (s.plan.err && own == 0) atomicOr(c.status, s.plan.err);
           bool clean;
-          if (arrive(c, b, s.plan.err != 0, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
+          if (arrive(c, b, n_chunks, s.plan.err != 0, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
         } else if (s.plan.n_groups == 0) {
-          if (fp == 0) {
+          if (own == 0) {
             L.light[atomicAdd(&L.n_light, 1)] = (int)p;
           } else {
             bool clean;
-            if (arrive(c, b, false, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
+            if (arrive(c, b, n_chunks, false, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
           }
         } else {
-          L.heavy[atomicAdd(&L.n_heavy, 1)] = (int)p * kParts + fp;
+          L.heavy[atomicAdd(&L.n_heavy, 1)] = (int)p * owners + own;
         }
       }
     }
     __syncthreads();
     const int n_light = L.n_light, n_heavy = L.n_heavy;
-    for (int i = wave; i < n_light; i += kThreads / 64) light_item<SLIDING>(c, L.light[i], k_new, v_new, n_new, T, keep, lane);
+    for (int i = wave; i < n_light; i += kThreads / 64) light_item<SLIDING>(c, L.light[i], k_new, v_new, n_new, T, keep, n_chunks, lane);
     for (int i = 0; i < n_heavy; ++i) {
-      flush_item<SLIDING>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep);
+      flush_item<SLIDING>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep, n_chunks);
       __syncthreads();
     }
     __syncthreads();
@@ -965,20 +1027,34 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
                   int T, int keep, hipStream_t stream) {
   static_assert(sizeof(Lds) <= 160 * 1024, "LDS budget of one CU");
   // per device and cheap: set on every call rather than remembered in process state
-  void (*kernel)(kvlinc_cache, const half_t*, const half_t*, const int32_t*, int, int) =
+  void (*kernel)(kvlinc_cache, const half_t*, const half_t*, const int32_t*, int, int, int) =
       (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0 ? append_flush_kernel<true> : append_flush_kernel<false>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sizeof(Lds)) != hipSuccess)
     return KVLINC_EHIP;
-  if (T > 1 && c.H_kv > 1)
+  // A bulk append of few sequences and many groups (a long prompt) would leave most of the chip idle with two
+  // workgroups per (sequence, kv head): from 64 groups on, its groups are shared out in chunks of at least 16, about one
+  // owner per compute unit.  The chunks add their shares of S and P to the fp32 state with atomic additions -- S and P
+  // are then reproducible up to the rounding order only -- so this needs a cache that keeps the fp32 state (or has no
+  // correction at all).
+  const long long pairs = (long long)c.B * c.H_kv;
+  int n_chunks = 1;
+  if (T > 1 && pairs * kParts < 128 && (c.S != nullptr || c.S16 == nullptr)) {
+    const long long groups_most = ((long long)T + c.R + kGroup - 1) / kGroup;
+    long long want = 256 / (pairs * kParts);
+    if (want > groups_most / 16) want = groups_most / 16;
+    if (want > 64) want = 64;
+    if (groups_most >= 64 && want > 1) n_chunks = (int)want;
+  }
+  if (T > 1 && (c.H_kv > 1 || n_chunks > 1))
     hipLaunchKernelGGL(append_scan_kernel, dim3(c.B * c.H_kv, (T + kScanRows - 1) / kScanRows), dim3(kThreads), 0, stream, c,
                        reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T);
   // one workgroup per compute unit at most (the LDS tiles of a flush fill most of one); items beyond that are taken
   // in further rounds by the same workgroups
-  const long long n_items = kParts * 8 * (((long long)c.B * c.H_kv + 7) / 8);
+  const long long n_items = (long long)kParts * n_chunks * 8 * ((pairs + 7) / 8);
   const int grid = (int)(n_items < 256 ? n_items : 256);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), sizeof(Lds), stream, c,
-                     reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep);
+                     reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T, keep, n_chunks);
   if (hipGetLastError() != hipSuccess) return KVLINC_EHIP;
   return KVLINC_OK;
 }

@@ -680,3 +680,69 @@ def test_sliding_value_window_keeps_a_refused_append_out_of_the_live_value_slots
     cache.status.zero_()
     after = cache.decode(q)
     assert torch.equal(after[1], before[1])
+
+
+@pytest.mark.parametrize("H_kv", [1, 2])
+def test_long_prompt_build_in_chunks(kv, H_kv):
+    """A bulk append of few sequences and many groups is shared out in chunks of groups over the chip (their shares of
+    S and P meet by atomic additions): records and window bit-exact, states within the element-wise bounds, for a long
+    sequence, and for a short one in the same call (whose single chunk keeps the state in registers); then the decode."""
+    B, H_q = 2, 4 * H_kv
+    lengths = [8192 + 77, 300]
+    K, V = tl.gen_kv(38, B, H_kv, lengths)
+    Wq, Wk = synth.adapters_q(38, H_q), synth.adapters_k(38, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 8192 + 512, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+    assert int(cache.status.item()) == 0
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    for b in range(B):
+        for g in range(H_kv):
+            tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), int(n_res[b]), Wk[g])
+    q = tl.gen_q(38, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy().astype(np.float64)
+    tl.check_outputs(out, tl.oracle_decode(K, V, q, lengths, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk))
+    # a second call on top (the chunks add to a state that is not zero): 8192 more tokens for sequence 0 only
+    more = [8192, 0]
+    K2, V2 = tl.gen_kv(39, B, H_kv, [8192, 8192])
+    cache2 = kv.KVLincCache(B, H_q, H_kv, 2 * 8192 + 512, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache2.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+    cache2.append(tl.to_dev(K2), tl.to_dev(V2), n_new=tl.to_dev(np.asarray(more, dtype=np.int32)))
+    assert int(cache2.status.item()) == 0
+    total = [lengths[0] + 8192, lengths[1]]
+    n_quant, n_res = tl.check_counters(cache2, total)
+    for g in range(H_kv):
+        Kall = np.concatenate([K[0, g, :lengths[0]], K2[0, g]]); Vall = np.concatenate([V[0, g, :lengths[0]], V2[0, g]])
+        tl.check_pair_against_oracle(cache2, 0, g, Kall, Vall, int(n_quant[0]), int(n_res[0]), Wk[g])
+        tl.check_pair_against_oracle(cache2, 1, g, K[1, g, :lengths[1]], V[1, g, :lengths[1]], int(n_quant[1]), int(n_res[1]), Wk[g])
+
+
+@pytest.mark.parametrize("H_kv", [1, 2])
+def test_long_prompt_build_in_chunks_refuses_as_a_whole(kv, H_kv):
+    """A non-finite value in a late group of one kv head: no chunk of any head may have touched the states."""
+    import torch
+    B, H_q = 1, 4 * H_kv
+    n0, n1 = 300, 8192
+    K, V = tl.gen_kv(40, B, H_kv, [n0 + n1])
+    Wq, Wk = synth.adapters_q(40, H_q), synth.adapters_k(40, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, n0 + n1 + 512, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :n0].contiguous(), Vd[:, :, :n0].contiguous())
+    before = {nm: getattr(cache, nm).clone() for nm in ("S", "P", "S16", "n_quant", "n_res", "k_res", "v_res")}
+    ng = int(cache.n_quant[0].item()) // 128
+    rec_before = cache.groups[:, :, :ng].clone()
+    vbad = Vd[:, :, n0:].clone()
+    vbad[0, H_kv - 1, 7000, 3] = float("nan")
+    cache.append(Kd[:, :, n0:].contiguous(), vbad)
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) & kv.KVLINC_ST_NONFINITE
+    for nm, t in before.items():
+        assert torch.equal(getattr(cache, nm), t), nm
+    assert torch.equal(cache.groups[:, :, :ng], rec_before)
+    assert not cache.split_done.any()
+    # and the same append without the fault goes through
+    cache.status.zero_()
+    cache.append(Kd[:, :, n0:].contiguous(), Vd[:, :, n0:].contiguous())
+    assert int(cache.status.item()) == 0
+    n_quant, n_res = tl.check_counters(cache, [n0 + n1])
+    for g in range(H_kv):
+        tl.check_pair_against_oracle(cache, 0, g, K[0, g], V[0, g], int(n_quant[0]), int(n_res[0]), Wk[g])

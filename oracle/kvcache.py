@@ -45,8 +45,7 @@ def feature_map(x, W):
 
 def _quantize_rows(x, bits, mode):
     if mode == "spec32":
-        assert bits == 2
-        return quantizer.quantize_spec32(x)
+        return quantizer.quantize_spec32(x, bits)
     if mode == "exact16":
         return quantizer.quantize_exact16(x, bits)
     if mode == "real":

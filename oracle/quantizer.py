@@ -43,20 +43,23 @@ def quantize_exact16(x16, bits=2):
     return codes.astype(np.int64), s16, z16
 
 
-def quantize_spec32(x16):
-    """The 2-bit quantizer the GPU is held to bit for bit (inputs fp16, one group per row).
+def quantize_spec32(x16, bits=2):
+    """The quantizer the GPU is held to bit for bit (inputs fp16, one group per row), N = ``bits`` in {2, 4}, L = 2^N - 1:
 
       mn, mx  = min, max of the group (exact); a zero of either sign counts as +0
       z16     = mn
       d32     = fl32(mx - mn)
-      s16     = fp16(fl32(d32 / 3))
+      s16     = fp16(fl32(d32 / L))
       t       = fl32(x - z16)
-      code    = (t > 0.5 s16) + (t >= 1.5 s16) + (t > 2.5 s16)       [s16 == 0 -> code 0]
+      code    = number of k in 0 .. L-1 with  t > (k + 0.5) s16  (k even)  or  t >= (k + 0.5) s16  (k odd)
+                [s16 == 0 -> code 0];  for N = 2:  (t > 0.5 s16) + (t >= 1.5 s16) + (t > 2.5 s16)
 
-    The three thresholds are exact in binary32, so ``code`` is round-half-to-even of the real
-    quotient t / s16 clamped to [0, 3]: Eq. 1 against the stored scale, without a division.
-    Returns (codes uint8, s16, z16).
+    The thresholds (k + 0.5) s16 are exact in binary32 (an 11-bit significand times an odd number below 32), so
+    ``code`` is round-half-to-even of the real quotient t / s16 clamped to [0, L]: Eq. 1 against the stored scale,
+    without a division.  Returns (codes uint8, s16, z16).
     """
+    assert bits in (2, 4)
+    L = 2 ** bits - 1
     x16 = np.asarray(x16, dtype=np.float16)
     f32 = np.float32
     x = x16.astype(f32)
@@ -66,11 +69,13 @@ def quantize_spec32(x16):
     mx = np.where(mx == 0, f32(0.0), mx).astype(f32)
     z16 = mn.astype(np.float16)  # exact: mn is an fp16 value
     d32 = (mx - mn).astype(f32)
-    s16 = (d32 / f32(3.0)).astype(f32).astype(np.float16)
+    s16 = (d32 / f32(L)).astype(f32).astype(np.float16)
     s = s16.astype(f32)[..., None]
     t = (x - mn[..., None]).astype(f32)
-    code = (t > f32(0.5) * s).astype(np.uint8) + (t >= f32(1.5) * s).astype(np.uint8) \
-        + (t > f32(2.5) * s).astype(np.uint8)
+    code = np.zeros(t.shape, dtype=np.uint8)
+    for k in range(L):
+        thr = (f32(k + 0.5) * s).astype(f32)
+        code += (t >= thr).astype(np.uint8) if k % 2 else (t > thr).astype(np.uint8)
     code = np.where(s == 0, np.uint8(0), code).astype(np.uint8)
     return code, s16, z16
 

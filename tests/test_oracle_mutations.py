@@ -85,20 +85,22 @@ CASES = [
     ("C_d taken from S instead of P", attention, "correction_terms", 'float(phi_q @ cache["P"])',
      'float((phi_q @ cache["S"]).sum())', [pa.test_zero_weights_closed_form]),
     # the functions the GPU is held to bit for bit
-    ("spec32: the middle threshold loses its tie rule", quantizer, "quantize_spec32", "(t >= f32(1.5) * s)",
-     "(t > f32(1.5) * s)", [pq.test_spec32_ties_literal, pq.test_spec32_is_eq1_against_stored_scale]),
+    ("spec32: the odd thresholds lose their tie rule", quantizer, "quantize_spec32", "(t >= thr)",
+     "(t > thr)", [pq.test_spec32_ties_literal, (pq.test_spec32_is_eq1_against_stored_scale, 2), (pq.test_spec32_is_eq1_against_stored_scale, 4)]),
+    ("spec32: the tie rule on the wrong thresholds", quantizer, "quantize_spec32", "if k % 2 else",
+     "if k % 2 == 0 else", [pq.test_spec32_ties_literal]),
     ("spec32: codes taken against the unrounded scale", quantizer, "quantize_spec32",
-     "s = s16.astype(f32)[..., None]", "s = (d32 / f32(3.0)).astype(f32)[..., None]",
-     [pq.test_spec32_is_eq1_against_stored_scale]),
+     "s = s16.astype(f32)[..., None]", "s = (d32 / f32(L)).astype(f32)[..., None]",
+     [(pq.test_spec32_is_eq1_against_stored_scale, 2), (pq.test_spec32_is_eq1_against_stored_scale, 4)]),
     ("spec32: a negative zero kept as zero-point", quantizer, "quantize_spec32",
      "mn = np.where(mn == 0, f32(0.0), mn).astype(f32)", "mn = mn.astype(f32)",
      [pq.test_spec32_negative_zero_is_canonical]),
-    ("spec32: scale over 4 levels", quantizer, "quantize_spec32", "d32 / f32(3.0)", "d32 / f32(4.0)",
-     [pq.test_spec32_is_eq1_against_stored_scale, pq.test_spec32_vs_exact16_mismatch_rate_is_tiny]),
+    ("spec32: scale over 2^N levels", quantizer, "quantize_spec32", "d32 / f32(L)", "d32 / f32(L + 1)",
+     [(pq.test_spec32_is_eq1_against_stored_scale, 2), (pq.test_spec32_vs_exact16_mismatch_rate_is_tiny, 4)]),
     ("exact16: codes against the unrounded zero-point", quantizer, "quantize_exact16",
      "codes = np.rint((x - z16.astype(np.float64)[..., None]) / safe[..., None])",
      "codes = np.rint((x - mn[..., None]) / (((mx - mn) / levels)[..., None] + 1e-300))",
-     [pq.test_spec32_is_eq1_against_stored_scale, pq.test_spec32_vs_exact16_mismatch_rate_is_tiny,
+     [(pq.test_spec32_is_eq1_against_stored_scale, 2), (pq.test_spec32_vs_exact16_mismatch_rate_is_tiny, 2),
       pq.test_constant_group_is_all_zero_codes]),
     ("fast transform: difference taken the other way round", hadamard, "fwht_spec32", "t = (a - b)", "t = (b - a)",
      [pq.test_fwht_spec32_equals_dense_product]),

@@ -61,16 +61,19 @@ def test_constant_group_is_all_zero_codes():
         assert np.all(quantizer.dequantize(codes, s, z) == 1.25)
 
 
-def test_spec32_is_eq1_against_stored_scale():
+@pytest.mark.parametrize("bits", [2, 4])
+def test_spec32_is_eq1_against_stored_scale(bits):
     """The binary32 threshold form must be round-half-even of the REAL quotient (x - z16) / s16, clamped."""
+    L = 2 ** bits - 1
     rng = np.random.default_rng(3)
     x16 = (rng.standard_normal((512, 128)) * rng.choice([1e-3, 1.0, 30.0], size=(512, 1))).astype(np.float16)
-    codes, s16, z16 = quantizer.quantize_spec32(x16)
+    x16[:64] = np.round(rng.standard_normal((64, 128)) * 4) / 4  # rows on a coarse grid: many exact ties
+    codes, s16, z16 = quantizer.quantize_spec32(x16, bits)
     # rebuild from exact rational arithmetic on the stored patterns (fp16 values are exact in fp64 and so are
     # their differences; the only binary32 rounding in the contract is t = fl32(x - z16))
     t = (x16.astype(np.float32) - z16.astype(np.float32)[:, None]).astype(np.float64)
     s = s16.astype(np.float64)[:, None]
-    ref = np.clip(np.rint(t / s), 0, 3)  # np.rint is half-to-even; t/s here is only inexact away from ties
+    ref = np.clip(np.rint(t / s), 0, L)  # np.rint is half-to-even; t/s here is only inexact away from ties
     frac = t / s - np.floor(t / s)
     far_from_tie = np.abs(frac - 0.5) > 1e-9
     assert np.all(codes[far_from_tie] == ref[far_from_tie])
@@ -78,15 +81,15 @@ def test_spec32_is_eq1_against_stored_scale():
     tie = ~far_from_tie
     if tie.any():
         k = np.floor(t / s)[tie]
-        want = np.clip(np.where(k % 2 == 0, k, k + 1), 0, 3)
+        want = np.clip(np.where(k % 2 == 0, k, k + 1), 0, L)
         assert np.all(codes[tie] == want)
     # stored pattern definition
     mn, mx = x16.astype(np.float32).min(1), x16.astype(np.float32).max(1)
     assert np.array_equal(z16.view(np.uint16), mn.astype(np.float16).view(np.uint16))
-    assert np.array_equal(s16.view(np.uint16), ((mx - mn) / np.float32(3)).astype(np.float16).view(np.uint16))
-    # self-consistent round trip against the stored scale (t >= 0; beyond 3.5 s can only come from fp16 rounding of s)
+    assert np.array_equal(s16.view(np.uint16), ((mx - mn) / np.float32(L)).astype(np.float16).view(np.uint16))
+    # self-consistent round trip against the stored scale (t >= 0; beyond (L + .5) s can only come from fp16 rounding of s)
     err = np.abs(quantizer.dequantize(codes, s16, z16) - x16.astype(np.float64))
-    assert np.all(err <= 0.5 * s + np.abs(mx.astype(np.float64) - mn - 3 * s[:, 0])[:, None] + 1e-12)
+    assert np.all(err <= 0.5 * s + np.abs(mx.astype(np.float64) - mn - L * s[:, 0])[:, None] + 1e-12)
 
 
 def test_spec32_ties_literal():
@@ -95,6 +98,13 @@ def test_spec32_ties_literal():
     codes, s16, z16 = quantizer.quantize_spec32(x)
     assert float(s16[0]) == 1.0 and float(z16[0]) == 0.0
     assert codes[0, :5].tolist() == [0, 0, 2, 2, 3]
+    # 4 bits, s16 = 1 exactly (range 0..15): every half goes to the even neighbour
+    halves = [k + 0.5 for k in range(15)]
+    x = np.array([[0.0, 15.0] + halves + [7.0] * 111], dtype=np.float16)
+    codes, s16, z16 = quantizer.quantize_spec32(x, 4)
+    assert float(s16[0]) == 1.0 and float(z16[0]) == 0.0
+    assert codes[0, :2].tolist() == [0, 15]
+    assert codes[0, 2:17].tolist() == [0, 2, 2, 4, 4, 6, 6, 8, 8, 10, 10, 12, 12, 14, 14]
 
 
 def test_spec32_negative_zero_is_canonical():
@@ -109,11 +119,12 @@ def test_spec32_negative_zero_is_canonical():
     assert float(s16[2]) == float(np.float16(np.float32(127 / 64.0) / np.float32(3.0))) and codes[2, 0] == 0
 
 
-def test_spec32_vs_exact16_mismatch_rate_is_tiny():
+@pytest.mark.parametrize("bits", [2, 4])
+def test_spec32_vs_exact16_mismatch_rate_is_tiny(bits):
     rng = np.random.default_rng(4)
     x16 = rng.standard_normal((4096, 128)).astype(np.float16)
-    c1, s1, z1 = quantizer.quantize_spec32(x16)
-    c2, s2, z2 = quantizer.quantize_exact16(x16)
+    c1, s1, z1 = quantizer.quantize_spec32(x16, bits)
+    c2, s2, z2 = quantizer.quantize_exact16(x16, bits)
     assert np.array_equal(z1.view(np.uint16), z2.view(np.uint16))
     assert (s1.view(np.uint16) != s2.view(np.uint16)).mean() < 1e-2  # fl16(fl32(d/3)) double rounding is rare
     same_scale = s1.view(np.uint16) == s2.view(np.uint16)

@@ -29,13 +29,12 @@ Group record, 2304 words (everything one decode step needs of a group, contiguou
 State tiles: the binary16 copy of S [256 features, 128 channels] that the decode step reads is stored as 128 tiles of
 64 x 4 halves; tile (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4 holds S[f][c] at [c % 64][f % 4].
 
-4-bit codes (Eq. 1 at N = 4; `bits` = 4 in the cache descriptor): a tile has 2048 words, a record 4352 (17408 bytes):
-key tile 0..2047, value tile 2048..4095, key scale 4096..4159, key zero-point 4160..4223, value (scale, zero-point)
-4224..4351 in the order above.  Rows, blocks and the position-to-token map of the value tile are those of the 2-bit
-tiles.  The four words w = 0..3 of (n, j, g) sit at word index (n * 64 + j + 16 * g) * 4 + w and hold the positions
-k = 64 (w // 2) + 16 g + 8 (w % 2) + o, o = 0..7: position offset o in nibble q = 2 (o % 4) + o // 4 (bits 4 q + 3 .. 4 q).
-A code c is stored as the nibble sign | m with c - 7.5 = (1 - 2 sign) (m + 0.5): sign = 1, m = 7 - c for c <= 7;
-sign = 0, m = c - 8 for c >= 8.
+4-bit codes (Eq. 1 at N = 4; `bits` = 4 in the cache descriptor): a code c = 4 c_hi + c_lo is stored as two 2-bit
+codes, c_hi = c // 4 and c_lo = c % 4, each in a 2-bit tile of its own ("plane") with the order and the bit pairs above.
+A record has 4352 words (17408 bytes): key tile high plane 0..1023, key tile low plane 1024..2047, value tile high
+plane 2048..3071, value tile low plane 3072..4095, key scale 4096..4159, key zero-point 4160..4223, value (scale,
+zero-point) 4224..4351 in the order above.  (c - 7.5 = 4 (c_hi - 1.5) + (c_lo - 1.5): a contraction with the codes is
+the sum of the contractions with the two planes, the high one weighted by 4.)
 
 Window of fp16 values: rotated values are stored 4 consecutive tokens per channel, v_res[slot // 4][channel][slot % 4],
 so that a lane owning a channel reads 4 tokens with one 8-byte load; keys stay row-major k_res[slot][channel].
@@ -134,75 +133,21 @@ def unpack_v_tile(tile):
 
 
 # ---- 4-bit codes ------------------------------------------------------------------------------------------------
-TILE_WORDS4 = 2048
 RECORD_WORDS4 = 4352
-
-
-def _position_maps4():
-    """For every (row r = 16 n + j, position k) of a 4-bit tile: word index and the nibble q of its code inside the word."""
-    r = np.arange(128)[:, None]
-    k = np.arange(128)[None, :]
-    n, j = r // 16, r % 16
-    g = (k % 64) // 16
-    w = 2 * (k // 64) + (k % 16) // 8
-    o = k % 8
-    q = 2 * (o % 4) + o // 4
-    word = (n * 64 + j + 16 * g) * 4 + w
-    return np.broadcast_to(word, (128, 128)), np.broadcast_to(q, (128, 128))
-
-
-def _v_index_maps4():
-    word_rk, q_rk = _position_maps4()
-    tok = _value_token_of_position()
-    word = np.empty((128, 128), dtype=np.int64)
-    q = np.empty((128, 128), dtype=np.int64)
-    word[tok[None, :], np.arange(128)[:, None]] = word_rk
-    q[tok[None, :], np.arange(128)[:, None]] = q_rk
-    return word, q
-
-
-_K_WORD4, _K_Q4 = _position_maps4()
-_V_WORD4, _V_Q4 = _v_index_maps4()
-
-
-def nibble_of_code4(c):
-    """code 0..15 -> stored nibble sign | m with c - 7.5 = (1 - 2 sign)(m + 0.5)."""
-    c = np.asarray(c, dtype=np.int64)
-    return np.where(c >= 8, c - 8, 8 | (7 - c)).astype(np.uint32)
-
-
-def code_of_nibble4(nib):
-    nib = np.asarray(nib, dtype=np.int64)
-    return np.where(nib & 8, 7 - (nib & 7), 8 + (nib & 7)).astype(np.uint8)
-
-
-def _pack4(codes, word, q):
-    codes = np.asarray(codes)
-    assert codes.shape[-2:] == (128, 128) and codes.min() >= 0 and codes.max() <= 15
-    lead = codes.shape[:-2]
-    nib = nibble_of_code4(codes.reshape((-1, 128 * 128)))
-    out = np.zeros((nib.shape[0], TILE_WORDS4), dtype=np.uint32)
-    wi = word.reshape(-1)
-    sh = (4 * q.reshape(-1)).astype(np.uint32)
-    for n in range(nib.shape[0]):
-        np.bitwise_or.at(out[n], wi, nib[n] << sh)
-    return out.reshape(lead + (TILE_WORDS4,))
-
-
-def _unpack4(tile, word, q):
-    tile = np.asarray(tile, dtype=np.uint32)
-    assert tile.shape[-1] == TILE_WORDS4
-    return code_of_nibble4((tile[..., word] >> (4 * q).astype(np.uint32)) & np.uint32(15))
 
 
 def pack_records4(k_codes, v_codes, k_scale, k_zero, v_scale, v_zero):
     """4-bit codes: per-group arrays ([n_groups, 128, 128] codes 0..15, [n_groups, 128] fp16 parameters) -> uint32 [n_groups, 4352]."""
-    n = np.asarray(k_codes).shape[0]
+    k_codes, v_codes = np.asarray(k_codes).astype(np.int64), np.asarray(v_codes).astype(np.int64)
+    n = k_codes.shape[0]
     rec = np.zeros((n, RECORD_WORDS4), dtype=np.uint32)
     if n == 0:
         return rec
-    rec[:, 0:2048] = _pack4(k_codes, _K_WORD4, _K_Q4)
-    rec[:, 2048:4096] = _pack4(v_codes, _V_WORD4, _V_Q4)
+    assert k_codes.min() >= 0 and k_codes.max() <= 15 and v_codes.min() >= 0 and v_codes.max() <= 15
+    rec[:, 0:1024] = pack_k_tile(k_codes // 4)
+    rec[:, 1024:2048] = pack_k_tile(k_codes % 4)
+    rec[:, 2048:3072] = pack_v_tile(v_codes // 4)
+    rec[:, 3072:4096] = pack_v_tile(v_codes % 4)
     rec[:, 4096:4160] = _halves_to_words(k_scale)
     rec[:, 4160:4224] = _halves_to_words(k_zero)
     vs = np.ascontiguousarray(v_scale, dtype=np.float16).view(np.uint16).astype(np.uint32)
@@ -220,7 +165,8 @@ def unpack_records4(rec):
         return np.stack([lo, hi], axis=-1).reshape(words.shape[:-1] + (-1,)).view(np.float16)
     sz = rec[:, 4224:4352][:, _SZ_WORD]
     return {
-        "k_codes": _unpack4(rec[:, 0:2048], _K_WORD4, _K_Q4), "v_codes": _unpack4(rec[:, 2048:4096], _V_WORD4, _V_Q4),
+        "k_codes": 4 * unpack_k_tile(rec[:, 0:1024]) + unpack_k_tile(rec[:, 1024:2048]),
+        "v_codes": 4 * unpack_v_tile(rec[:, 2048:3072]) + unpack_v_tile(rec[:, 3072:4096]),
         "k_scale": halves(rec[:, 4096:4160]), "k_zero": halves(rec[:, 4160:4224]),
         "v_scale": (sz & np.uint32(0xFFFF)).astype(np.uint16).view(np.float16),
         "v_zero": (sz >> np.uint32(16)).astype(np.uint16).view(np.float16),

@@ -161,49 +161,31 @@ def test_value_window_order():
     assert np.array_equal(layout.unpack_value_window(tiled, 5), rows)
 
 
-# ---- 4-bit records ----------------------------------------------------------------------------------------
+# ---- 4-bit records: two 2-bit planes per tile ----------------------------------------------------------------
 
-def _slot_of_position4(n, j, k):
-    """Word index and nibble q of position k of row (n, j), by search over the stated order: word
-    (n * 64 + j + 16 g) * 4 + w holds k = 64 (w // 2) + 16 g + 8 (w % 2) + o, offset o in nibble q = 2 (o % 4) + o // 4."""
-    for g in range(4):
-        for w in range(4):
-            for o in range(8):
-                if 64 * (w // 2) + 16 * g + 8 * (w % 2) + o == k:
-                    return (n * 64 + j + 16 * g) * 4 + w, 2 * (o % 4) + o // 4
-    raise AssertionError
-
-
-def _code_at4(word, q):
-    nib = (int(word) >> (4 * q)) & 15
-    sign, m = nib >> 3, nib & 7
-    value_times_2 = (1 - 2 * sign) * (2 * m + 1)  # 2 (c - 7.5)
-    return (value_times_2 + 15) // 2
-
-
-def test_four_bit_tiles_are_bijections_and_match_the_definition():
+def test_four_bit_record_is_two_planes_per_tile():
     rng = np.random.default_rng(5)
-    k_codes = rng.integers(0, 16, size=(1, 128, 128))
-    v_codes = rng.integers(0, 16, size=(1, 128, 128))
-    par = [rng.standard_normal((1, 128)).astype(np.float16) for _ in range(4)]
+    k_codes = rng.integers(0, 16, size=(2, 128, 128))
+    v_codes = rng.integers(0, 16, size=(2, 128, 128))
+    par = [rng.standard_normal((2, 128)).astype(np.float16) for _ in range(4)]
     rec = layout.pack_records4(k_codes, v_codes, *par)
-    assert rec.shape == (1, 4352) and rec.dtype == np.uint32
+    assert rec.shape == (2, 4352) and rec.dtype == np.uint32
     back = layout.unpack_records4(rec)
     assert np.array_equal(back["k_codes"], k_codes) and np.array_equal(back["v_codes"], v_codes)
     for got, want in zip((back["k_scale"], back["k_zero"], back["v_scale"], back["v_zero"]), par):
         assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
-    seen_k, seen_v = set(), set()
-    for t in range(0, 128, 5):
-        for c in range(128):
-            w, q = _slot_of_position4(t // 16, t % 16, c)  # key tile: row = token, position = channel
-            assert _code_at4(rec[0, w], q) == k_codes[0, t, c]
-            seen_k.add((w, q))
+    # every plane is a 2-bit tile (whose order the tests above pin) of one base-4 digit of the codes, read off here
+    # with the search over the stated order
+    for t in range(0, 128, 9):
+        for c in range(0, 128, 7):
+            w, p = _slot_of_position(t // 16, t % 16, c)
+            digits = (_code_at(rec[1, w], p), _code_at(rec[1, 1024 + w], p))
+            assert 4 * digits[0] + digits[1] == k_codes[1, t, c]
             kpos = [k for k in range(128) if 16 * (k % 8) + 4 * ((k // 16) % 4) + 2 * (k // 64) + (k // 8) % 2 == t][0]
-            w, q = _slot_of_position4(c // 16, c % 16, kpos)  # value tile: row = channel, position holds the token
-            assert _code_at4(rec[0, 2048 + w], q) == v_codes[0, t, c]
-            seen_v.add((w, q))
-    assert len(seen_k) == len(seen_v) == len(range(0, 128, 5)) * 128
-    # scales and zero-points sit where the 2-bit record has them, behind the two larger tiles
+            w, p = _slot_of_position(c // 16, c % 16, kpos)
+            digits = (_code_at(rec[1, 2048 + w], p), _code_at(rec[1, 3072 + w], p))
+            assert 4 * digits[0] + digits[1] == v_codes[1, t, c]
+    # scales and zero-points behind the four planes, in the order of the 2-bit record
     assert np.array_equal(rec[0, 4096:4160], layout._halves_to_words(par[0])[0])
     assert np.array_equal(rec[0, 4160:4224], layout._halves_to_words(par[1])[0])
     t = 16 * 3 + 5  # token 16 n + j, n = 3, j = 5 -> word 8 j + n of the field
@@ -212,24 +194,24 @@ def test_four_bit_tiles_are_bijections_and_match_the_definition():
 
 def test_four_bit_literal_corners():
     def one(t, c, code):
-        a = np.full((1, 128, 128), 8, dtype=np.int64)  # code 8 = +0.5 -> nibble 0: a tile of zeros
+        a = np.full((1, 128, 128), 10, dtype=np.int64)  # code 10 = digits (2, 2) -> bit pairs (0, 0): planes of zeros
         a[0, t, c] = code
         return a
     z = np.zeros((1, 128), dtype=np.float16)
-    k_of = lambda a: layout.pack_records4(a, np.full((1, 128, 128), 8), z, z, z, z)[0, :2048]
-    v_of = lambda a: layout.pack_records4(np.full((1, 128, 128), 8), a, z, z, z, z)[0, 2048:4096]
-    assert not k_of(np.full((1, 128, 128), 8)).any()
-    # the 16 levels: code 15 = +7.5 -> nibble 0111, code 0 = -7.5 -> nibble 1111, code 7 = -0.5 -> nibble 1000
-    assert k_of(one(0, 0, 15))[0] == 0x7 and k_of(one(0, 0, 0))[0] == 0xF and k_of(one(0, 0, 7))[0] == 0x8
-    # key: token 0, channel 1 -> offset 1 -> nibble 2; channel 4 -> offset 4 -> nibble 1; channel 8 -> word 1
-    assert k_of(one(0, 1, 9))[0] == 0x1 << 8
-    assert k_of(one(0, 4, 9))[0] == 0x1 << 4
-    assert k_of(one(0, 8, 9))[1] == 0x1
-    # channel 64 -> word 2; channel 16 -> quarter g = 1 -> word 16 * 4; token 17 -> block 1, row 1 -> (64 + 1) * 4
-    assert k_of(one(0, 64, 9))[2] == 0x1
-    assert k_of(one(0, 16, 9))[64] == 0x1
-    assert k_of(one(17, 0, 9))[(64 + 1) * 4] == 0x1
-    # value: channel 3 -> row 3; token 16 = position 1 -> nibble 2 of word 3 * 4
-    assert v_of(one(16, 3, 9))[12] == 0x1 << 8
-    # value: token 2 = position 64 -> word 2 of the row
-    assert v_of(one(2, 3, 9))[14] == 0x1
+    k_of = lambda a: layout.pack_records4(a, np.full((1, 128, 128), 10), z, z, z, z)[0, :2048]
+    v_of = lambda a: layout.pack_records4(np.full((1, 128, 128), 10), a, z, z, z, z)[0, 2048:4096]
+    assert not k_of(np.full((1, 128, 128), 10)).any()
+    # token 0, channel 0 -> code p = 0 of word 0 of a plane: hi in bit 3, lo in bit 1
+    # code 2 = digits (0, 2): high plane (1, 1), low plane untouched; code 8 = digits (2, 0): the other way round
+    t = k_of(one(0, 0, 2))
+    assert t[0] == 0b1010 and t[1024] == 0 and np.count_nonzero(t) == 1
+    t = k_of(one(0, 0, 8))
+    assert t[0] == 0 and t[1024] == 0b1010 and np.count_nonzero(t) == 1
+    # code 7 = digits (1, 3): high plane (1, 0), low plane (0, 1); code 15 = (3, 3): (0, 1) in both
+    t = k_of(one(0, 0, 7))
+    assert t[0] == 0b1000 and t[1024] == 0b0010
+    t = k_of(one(0, 0, 15))
+    assert t[0] == 0b0010 and t[1024] == 0b0010
+    # value tile: channel 3 = row 3, token 16 = position 1 -> p = 2 -> bits 7 and 5 of word 3 * 4 of each plane
+    t = v_of(one(16, 3, 1))  # digits (0, 1): (1, 1) high, (1, 0) low
+    assert t[12] == 0b1010 << 4 and t[1024 + 12] == 0b1000 << 4 and np.count_nonzero(t) == 2

@@ -155,14 +155,19 @@ LAYOUT_CASES = [
     ("state tiles: channel half before feature block", "pack_state_tiles",
      "tile = (f // 64 * 2 + c // 64) * 16 + (f % 64) // 4", "tile = (c // 64 * 4 + f // 64) * 16 + (f % 64) // 4",
      [pl.test_state_tiles_are_a_bijection]),
-    ("4-bit tile: the two halves of a word's eight positions exchanged", "_position_maps4", "q = 2 * (o % 4) + o // 4",
-     "q = 2 * (o % 4) + 1 - o // 4", [pl.test_four_bit_tiles_are_bijections_and_match_the_definition, pl.test_four_bit_literal_corners]),
-    ("4-bit tile: the upper 64 positions in words 1 and 3", "_position_maps4", "w = 2 * (k // 64) + (k % 16) // 8",
-     "w = (k // 64) + 2 * ((k % 16) // 8)", [pl.test_four_bit_literal_corners]),
-    ("4-bit code: stored as the plain number 0..15", "nibble_of_code4", "return np.where(c >= 8, c - 8, 8 | (7 - c)).astype(np.uint32)",
-     "return c.astype(np.uint32)", [pl.test_four_bit_literal_corners]),
+    ("4-bit record: the low plane of the key tile before the high plane", "pack_records4",
+     "rec[:, 0:1024] = pack_k_tile(k_codes // 4)\n    rec[:, 1024:2048] = pack_k_tile(k_codes % 4)",
+     "rec[:, 0:1024] = pack_k_tile(k_codes % 4)\n    rec[:, 1024:2048] = pack_k_tile(k_codes // 4)",
+     [pl.test_four_bit_literal_corners]),
+    ("4-bit record: the value planes hold the key tile's order", "pack_records4",
+     "rec[:, 2048:3072] = pack_v_tile(v_codes // 4)", "rec[:, 2048:3072] = pack_k_tile(v_codes // 4)",
+     [pl.test_four_bit_literal_corners, pl.test_four_bit_record_is_two_planes_per_tile]),
+    ("4-bit record: the planes are the digits in base 2 and 8", "pack_records4",
+     "rec[:, 0:1024] = pack_k_tile(k_codes // 4)\n    rec[:, 1024:2048] = pack_k_tile(k_codes % 4)",
+     "rec[:, 0:1024] = pack_k_tile(k_codes // 8 * 2 + k_codes % 2)\n    rec[:, 1024:2048] = pack_k_tile(k_codes // 2 % 4)",
+     [pl.test_four_bit_literal_corners]),
     ("4-bit record: the key zero-points before the key scales", "pack_records4", "rec[:, 4096:4160] = _halves_to_words(k_scale)\n    rec[:, 4160:4224] = _halves_to_words(k_zero)",
-     "rec[:, 4096:4160] = _halves_to_words(k_zero)\n    rec[:, 4160:4224] = _halves_to_words(k_scale)", [pl.test_four_bit_tiles_are_bijections_and_match_the_definition]),
+     "rec[:, 4096:4160] = _halves_to_words(k_zero)\n    rec[:, 4160:4224] = _halves_to_words(k_scale)", [pl.test_four_bit_record_is_two_planes_per_tile]),
 ]
 
 
@@ -177,13 +182,6 @@ def test_a_planted_layout_mistake_is_noticed(monkeypatch, case):
         word, shift = layout._v_index_maps()
         monkeypatch.setattr(layout, "_V_WORD", word)
         monkeypatch.setattr(layout, "_V_SHIFT", shift)
-    if name == "_position_maps4":
-        word, q = layout._position_maps4()
-        monkeypatch.setattr(layout, "_K_WORD4", word)
-        monkeypatch.setattr(layout, "_K_Q4", q)
-        word, q = layout._v_index_maps4()
-        monkeypatch.setattr(layout, "_V_WORD4", word)
-        monkeypatch.setattr(layout, "_V_Q4", q)
     _some_pin_fails(pins)
 
 

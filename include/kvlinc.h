@@ -4,7 +4,7 @@
  * The library implements, for one attention layer and one decode step, what Sec. 3 of the paper
  * (arxiv 2510.05373) defines:
  *   - keys quantized per channel, K_q = Q_C(K), values Hadamard-rotated and quantized per token,
- *     V_q = Q_T(V H), both at 2 bits with group size 128 (Sec. 3.1, Obs. 3; quantizer: Sec. 2, Eq. 1);
+ *     V_q = Q_T(V H), both at 2 bits (or at 4: `bits` of the cache descriptor) with group size 128 (Sec. 3.1, Obs. 3; quantizer: Sec. 2, Eq. 1);
  *   - the 128 most recent tokens kept in fp16 and quantized only after attention has used them
  *     (Sec. 4.1 "Setup"; Sec. 3.3, last sentence);
  *   - the linear correction states S, P of the key quantization error (Sec. 3.2, Eq. 4-6);
@@ -52,6 +52,14 @@
  *                     Value tile: row (n, j) = channel 16 n + j, position k = token
  *                                 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2.
  *                     A partial last group (bulk build only) has zero codes and zero (s, z) for its missing tokens.
+ *                     bits == 4 (Eq. 1 at N = 4, 16 levels): groups is [B, H_kv, max_groups, 4352] uint32, one 17408-byte
+ *                     record per group.  A code c = 4 c_hi + c_lo is stored as two 2-bit codes in two 2-bit tiles
+ *                     ("planes") of the order and bit pairs above:
+ *                       words    0..1023  key tile, high plane (c_hi)      words 1024..2047  key tile, low plane (c_lo)
+ *                       words 2048..3071  value tile, high plane           words 3072..4095  value tile, low plane
+ *                       words 4096..4159  key scale   words 4160..4223  key zero-point   words 4224..4351  value (s, z),
+ *                     the last three fields in the order of the 2-bit record.  (c - 7.5 = 4 (c_hi - 1.5) + (c_lo - 1.5):
+ *                     the decode step contracts with the two planes in turn, the high one under a block scale of 4.)
  *   k_res             [B, H_kv, R, 128] fp16: the window's raw keys, slot r = r-th oldest window token.
  *   v_res             [B, H_kv, R/4, 128, 4] fp16: the window's ROTATED values, 4 consecutive slots per channel:
  *                     slot r, channel c at [r/4][c][r%4].
@@ -130,7 +138,7 @@ typedef struct kvlinc_cache {
   int32_t G;    /* quantization group size, must be 128 */
   int32_t R;    /* window capacity in tokens, a multiple of 4 in 4..128; one-token appends need R == G */
   int32_t D;    /* rank of the correction feature maps, must be 256 */
-  int32_t bits; /* must be 2 */
+  int32_t bits; /* width of the codes: 2 or 4 (the layout of `groups` follows it) */
   int64_t max_groups; /* tile capacity per (sequence, KV head) */
   uint32_t* groups;
   kvlinc_half* k_res;

@@ -137,16 +137,18 @@ class KVLincCache:
     """Device buffers of one layer's cache plus the descriptor that points at them (allocation only)."""
 
     def __init__(self, B, H_q, H_kv, max_context, R=128, Wq=None, Wk=None, device="cuda", state_storage="fp32",
-                 flags=0):
+                 flags=0, bits=2):
         """state_storage: "fp32" keeps the fp32 master copy of S next to its binary16 tiles, "fp16" stores the state in
-        the binary16 tiles only; flags: KVLINC_FLAG_* bits."""
+        the binary16 tiles only; flags: KVLINC_FLAG_* bits; bits: width of the codes, 2 or 4 (group records of 2304 or
+        4352 words)."""
         import torch
-        self.B, self.H_q, self.H_kv, self.R = B, H_q, H_kv, R
+        assert bits in (2, 4)
+        self.B, self.H_q, self.H_kv, self.R, self.bits = B, H_q, H_kv, R, bits
         self.max_groups = max(1, -(-int(max_context) // 128))
         dev = torch.device(device)
         mg = self.max_groups
         z = lambda *s, dt: torch.zeros(*s, dtype=dt, device=dev)
-        self.groups = z(B, H_kv, mg, 2304, dt=torch.int32)
+        self.groups = z(B, H_kv, mg, 2304 if bits == 2 else 4352, dt=torch.int32)
         self.k_res = z(B, H_kv, R, 128, dt=torch.float16)
         self.v_res = z(B, H_kv, R // 4, 128, 4, dt=torch.float16)
         self.n_quant = z(B, dt=torch.int32)
@@ -164,7 +166,7 @@ class KVLincCache:
         else:
             self.S = self.S16 = self.P = None
         self.struct = CacheStruct(
-            B=B, H_q=H_q, H_kv=H_kv, d=128, G=128, R=R, D=256, bits=2, max_groups=mg,
+            B=B, H_q=H_q, H_kv=H_kv, d=128, G=128, R=R, D=256, bits=bits, max_groups=mg,
             groups=self.groups.data_ptr(),
             k_res=self.k_res.data_ptr(), v_res=self.v_res.data_ptr(),
             n_quant=self.n_quant.data_ptr(), n_res=self.n_res.data_ptr(),

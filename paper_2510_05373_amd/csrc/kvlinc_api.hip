@@ -51,7 +51,7 @@ const char* kvlinc_strerror(int code) {
 int kvlinc_cache_validate(const kvlinc_cache* c) {
   if (c == nullptr) return KVLINC_EINVAL;
   if (c->B < 1 || c->H_q < 1 || c->H_kv < 1) return KVLINC_EINVAL;
-  if (c->d != kvlinc::kHeadDim || c->G != kvlinc::kGroup || c->D != kvlinc::kRank || c->bits != 2) return KVLINC_EINVAL;
+  if (c->d != kvlinc::kHeadDim || c->G != kvlinc::kGroup || c->D != kvlinc::kRank || (c->bits != 2 && c->bits != 4)) return KVLINC_EINVAL;
   if (c->R < 4 || c->R > kvlinc::kGroup || c->R % 4 != 0) return KVLINC_EINVAL;
   if (c->H_q % c->H_kv != 0 || c->H_q / c->H_kv > kvlinc::kMaxGq) return KVLINC_EINVAL;
   if (c->max_groups < 1 || c->max_groups > (1ll << 24)) return KVLINC_EINVAL;

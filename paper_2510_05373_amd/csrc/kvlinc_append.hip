@@ -1,4 +1,4 @@
-// Append / flush path: Hadamard rotation of new values, 2-bit quantization of what leaves the fp16 window,
+// Append / flush path: Hadamard rotation of new values, 2-bit (or 4-bit) quantization of what leaves the fp16 window,
 // tile packing, and the update of the linear-correction states (Sec. 3.1, Obs. 3; Sec. 2, Eq. 1; Sec. 3.2, Eq. 5-6;
 // Sec. 3.3: the cache is quantized only after attention has used the new token).
 //
@@ -21,17 +21,18 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kRowH = 136;     // halfs per LDS row of a 128-wide fp16 tile (rows stay 16-byte aligned)
 constexpr int kParts = 2;      // workgroups that share the flush of one (sequence, kv head): the two halves of phi
 constexpr int kListCap = kThreads;  // items one workgroup looks at per round (one per thread)
+constexpr int kPlaneWords = 1024;   // a 128 x 128 tile of 2-bit codes; 4-bit codes take two such planes per tile
 
 struct Lds {
   // raw keys / rotated values [token][channel]; after the quantizer the high / low term of K - K_q; after the logits
   // the high / low term of phi s of the group for this workgroup's 128 features, [feature][token]
   half_t bK[kGroup][kRowH];
   half_t bV[kGroup][kRowH];
-  // value codes as the binary16 numbers code - 1.5, [token / 4][channel][token % 4]: what the S update multiplies by,
-  // and -- sign and the bit that tells 1.5 from 0.5 -- the bit pair the record stores
+  // value codes as the binary16 numbers code - centre (centre = 1.5 at 2 bits, 7.5 at 4), [token / 4][channel][token % 4]:
+  // what the S update multiplies by, and -- sign and magnitude -- what the record stores of a code
   half_t cV[kGroup / 4][kHeadDim][4];
   float kScale[kGroup], kZero[kGroup];
-  float vScale[kGroup], vCentre[kGroup];  // vCentre: z + 1.5 s, the value of the centre of the code range
+  float vScale[kGroup], vCentre[kGroup];  // vCentre: z + centre s, the value of the centre of the code range
   half_t kmn[kWaves][kGroup], kmx[kWaves][kGroup];  // per-channel key minima / maxima of each wave's tokens
   half_t Wt[kRank / 2][kRowH];  // W_k of the half of phi this workgroup belongs to, [feature][channel]
   float red[kWaves][kRank / 2];
@@ -101,30 +102,50 @@ __device__ inline void fwht128_wave_multi(float (&x0)[NV], float (&x1)[NV], int 
   }
 }
 
-// Eq. 1 at 2 bits against the stored fp16 scale / zero-point, decided in binary32 without a division.
-struct Q2 {
+// Eq. 1 at 2 or 4 bits against the stored fp16 scale / zero-point, decided in binary32 without a division.
+struct QP {
   float z;  // value of the stored fp16 zero-point
   float s;  // value of the stored fp16 scale
   half_t z16, s16;
 };
 
-__device__ inline Q2 q2_params(float mn, float mx) {
+template <int BITS>
+__device__ inline QP q_params(float mn, float mx) {
   mn = (mn == 0.0f) ? 0.0f : mn;  // a zero of either sign counts as +0
   mx = (mx == 0.0f) ? 0.0f : mx;
-  Q2 r;
+  QP r;
   r.z16 = (half_t)mn;  // exact: mn is an fp16 value
   r.z = mn;
   const float d32 = mx - mn;
-  const float q32 = d32 / 3.0f;  // IEEE-correct binary32 division
+  const float q32 = d32 / (float)Rec<BITS>::kLevels;  // IEEE-correct binary32 division
   r.s16 = (half_t)q32;
   r.s = (float)r.s16;
   return r;
 }
 
-__device__ inline uint32_t q2_code(float x, const Q2& p) {
+// The code is the number of thresholds (k + 0.5) s, k = 0 .. 2^BITS - 2, that t = x - z lies above -- strictly for even
+// k, or on for odd k: round-half-to-even of t / s, clamped.  The thresholds are exact in binary32 (s has 11 significant
+// bits, 2 k + 1 at most 5).
+template <int BITS>
+__device__ inline uint32_t q_code(float x, const QP& p) {
   const float t = x - p.z;
-  const uint32_t c = (uint32_t)(t > 0.5f * p.s) + (uint32_t)(t >= 1.5f * p.s) + (uint32_t)(t > 2.5f * p.s);
-  return p.s == 0.0f ? 0u : c;
+  if constexpr (BITS == 2) {
+    const uint32_t c = (uint32_t)(t > 0.5f * p.s) + (uint32_t)(t >= 1.5f * p.s) + (uint32_t)(t > 2.5f * p.s);
+    return p.s == 0.0f ? 0u : c;
+  } else {
+    // An estimate e of the code from an approximate quotient (off by one at most, and only next to a threshold), then
+    // the two thresholds around it decide: k = e - 1 (the code is at least e) and k = e (it is e + 1).  t is never
+    // negative, so threshold -1 always passes; a code beyond the last level can only come from a scale that was
+    // rounded down among the fp16 subnormals, and is clamped like the count of thresholds is.
+    constexpr float kTop = (float)Rec<BITS>::kLevels;
+    const float e = fminf(fmaxf(__builtin_rintf(t * __builtin_amdgcn_rcpf(p.s)), 0.0f), kTop);
+    const bool e_odd = ((int)e & 1) != 0;
+    const float lo = (e - 0.5f) * p.s, hi = (e + 0.5f) * p.s;
+    const bool at_least_e = e_odd ? t > lo : t >= lo;       // threshold k = e - 1 is even iff e is odd
+    const bool above_e = e_odd ? t >= hi : t > hi;
+    const float c = fminf(e - 1.0f + (at_least_e ? 1.0f : 0.0f) + (at_least_e && above_e ? 1.0f : 0.0f), kTop);
+    return p.s == 0.0f ? 0u : (uint32_t)c;
+  }
 }
 
 // Every (sequence, kv head) has kParts * n_chunks owners in the grid, fixed by the launch shape alone (n_chunks > 1
@@ -376,16 +397,18 @@ __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u
 // as two binary16 terms):
 //   logits[t][f] = sum_c (K - K_q)[t][c] W_k[c][f]   for the 128 features of the part's half,
 //   phi = softmax over that half (Eq. 6),
-//   S[f][c] += sum_t (phi s_t)[t][f] (code[t][c] - 1.5) + sum_t phi[t][f] (z_t + 1.5 s_t),   P[f] += sum_t phi[t][f]   (Eq. 5)
-// with V_q[t][c] = z_t + s_t code[t][c].  S stays in registers for all groups of the call.  The matrix instruction lines
+//   S[f][c] += sum_t (phi s_t)[t][f] (code[t][c] - ctr) + sum_t phi[t][f] (z_t + ctr s_t),   P[f] += sum_t phi[t][f]   (Eq. 5)
+// with V_q[t][c] = z_t + s_t code[t][c] and ctr = (2^BITS - 1) / 2 the centre of the code range.  S stays in registers for all groups of the call.  The matrix instruction lines
 // its 32 products and its addend up with the largest of them before it adds, so what it is given is kept small and of
 // both signs: the products of every 32 tokens start from a zero addend and are added to S by ordinary binary32
 // additions, the codes are centred (the other part is the same for all channels of a row), and of the two terms of the
 // key error the small one is contracted first.
-template <bool SLIDING>
+template <bool SLIDING, int BITS>
 __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
                            const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
                            int n_chunks) {
+  using R = Rec<BITS>;
+  constexpr float kCentre = R::kCentre;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ck = item % n_chunks, fp = (item / n_chunks) % kParts, p = item / (n_chunks * kParts);
   const int b = p / c.H_kv, g = p % c.H_kv;
@@ -490,7 +513,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
   for (int j = j_first; j < j_last; ++j) {
     const int valid = min(kGroup, plan.n_flush - j * kGroup);
     const long long grp = (long long)(nq / kGroup) + j;
-    uint32_t* rec = c.groups + (bh * c.max_groups + grp) * kRecordWords;
+    uint32_t* rec = c.groups + (bh * c.max_groups + grp) * R::kWords;
     half_t* rec16 = reinterpret_cast<half_t*>(rec);
     const int ubase = j * kGroup;                    // index of the group's first token in the stream [window, new]
     const int nrg = min(max(nr - ubase, 0), valid);  // tokens of this group that come from the window (only if j == 0)
@@ -583,29 +606,29 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         mn[i] = row16_min(mn[i]);
         mx[i] = row16_max(mx[i]);
       }
-      Q2 pv[4];
+      QP pv[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) pv[i] = q2_params(mn[i], mx[i]);
+      for (int i = 0; i < 4; ++i) pv[i] = q_params<BITS>(mn[i], mx[i]);
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {  // two channels = 8 halfs = one 16-byte store
         half8_t h;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          h[i] = (half_t)((float)q2_code(x[i][e], pv[i]) - 1.5f);
-          h[4 + i] = (half_t)((float)q2_code(x[i][e + 1], pv[i]) - 1.5f);
+          h[i] = (half_t)((float)q_code<BITS>(x[i][e], pv[i]) - kCentre);
+          h[4 + i] = (half_t)((float)q_code<BITS>(x[i][e + 1], pv[i]) - kCentre);
         }
         *reinterpret_cast<half8_t*>(&L.cV[tq][8 * sub + e][0]) = h;
       }
       if (sub < 4) {  // lane sub of the row writes token 4 tq + sub
-        Q2 mine = pv[0];
+        QP mine = pv[0];
         if (sub == 1) mine = pv[1];
         if (sub == 2) mine = pv[2];
         if (sub == 3) mine = pv[3];
         const int t = 4 * tq + sub;
         L.vScale[t] = mine.s;
-        L.vCentre[t] = mine.z + 1.5f * mine.s;
+        L.vCentre[t] = mine.z + kCentre * mine.s;
         if (fp == 0) {
-          const int sz_word = kRecValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
+          const int sz_word = R::kValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
           rec16[2 * sz_word] = mine.s16;
           rec16[2 * sz_word + 1] = mine.z16;
         }
@@ -659,24 +682,25 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         mn = fminf(mn, (float)L.kmn[r][tid]);
         mx = fmaxf(mx, (float)L.kmx[r][tid]);
       }
-      const Q2 pk = q2_params(mn, mx);
+      const QP pk = q_params<BITS>(mn, mx);
       L.kScale[tid] = pk.s;
       L.kZero[tid] = pk.z;
       if (fp == 0) {
-        rec16[2 * kRecKeyScale + tid] = pk.s16;
-        rec16[2 * kRecKeyZero + tid] = pk.z16;
+        rec16[2 * R::kKeyScale + tid] = pk.s16;
+        rec16[2 * R::kKeyZero + tid] = pk.z16;
       }
     }
     __syncthreads();
     // key codes -- this part's half of the key tile goes out from registers -- and K - K_q as two binary16 terms in
     // place of the staged tiles.
-    // Tile word ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w holds, for the row 16 n + j, the positions
+    // 2 bits: tile word ((n / 2) * 64 + j + 16 g) * 4 + 2 (n % 2) + w holds, for the row 16 n + j, the positions
     // k = 32 g + 16 w + 8 (p % 2) + p / 2, p = 0..15: code p as the bit pair (hi, lo) = (1,1), (1,0), (0,0), (0,1) for the
     // codes 0..3, hi in bit 4 (p / 2) + 3 - p % 2, lo two below.  Key tile: row = token, position = channel: this
     // thread's 8 channels are the p % 2 = sub % 2 half of the word of (g, w) = (sub / 4, (sub / 2) % 2), its neighbour
     // in the lane pair has the other half.
+    // 4 bits: the tile is two such planes of 1024 words, the first of the codes' high base-4 digits, the second of the low.
     {
-      Q2 pk[8];
+      QP pk[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         pk[e].s = L.kScale[8 * sub + e];
@@ -689,23 +713,31 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         float x[8];
         unpack8(raw, x);
         half8_t eh, el;
-        uint32_t bits = 0;
+        uint32_t bits = 0, bits_lo = 0;  // (bits_lo: the low plane of 4-bit codes)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const uint32_t code = t < valid ? q2_code(x[e], pk[e]) : 0u;
+          const uint32_t code = t < valid ? q_code<BITS>(x[e], pk[e]) : 0u;
           float ke = t < valid ? x[e] - (pk[e].s * (float)code + pk[e].z) : 0.0f;
           asm volatile("" : "+v"(ke));  // the binary32 difference first, then its two binary16 terms
           eh[e] = (half_t)ke;
           el[e] = (half_t)(ke - (float)eh[e]);
-          // hi = not (code / 2), lo = not (code / 2 xor code % 2)
-          bits |= (((code >> 1) ^ 1u) << (4 * e + 3 - (sub & 1))) | ((((code >> 1) ^ code ^ 1u) & 1u) << (4 * e + 1 - (sub & 1)));
+          // of a 2-bit code (digit) x: hi = not (x / 2), lo = not (x / 2 xor x % 2)
+          const uint32_t x = BITS == 2 ? code : code >> 2;
+          bits |= (((x >> 1) ^ 1u) << (4 * e + 3 - (sub & 1))) | ((((x >> 1) ^ x ^ 1u) & 1u) << (4 * e + 1 - (sub & 1)));
+          if constexpr (BITS == 4) {
+            const uint32_t y = code & 3u;
+            bits_lo |= (((y >> 1) ^ 1u) << (4 * e + 3 - (sub & 1))) | ((((y >> 1) ^ y ^ 1u) & 1u) << (4 * e + 1 - (sub & 1)));
+          }
         }
         *reinterpret_cast<half8_t*>(&L.bK[t][8 * sub]) = eh;
         *reinterpret_cast<half8_t*>(&L.bV[t][8 * sub]) = el;
         bits |= dpp_u<kQuadSwap1>(bits);
+        if constexpr (BITS == 4) bits_lo |= dpp_u<kQuadSwap1>(bits_lo);
         if ((i >> 1) == fp && (sub & 1) == 0) {  // this part's half of the key tile: the tokens 64 fp .. 64 fp + 63
           const int nb = t >> 4, jr = t & 15;
-          rec[kRecKeyTile + ((nb >> 1) * 64 + jr + 16 * (sub >> 2)) * 4 + 2 * (nb & 1) + ((sub >> 1) & 1)] = bits;
+          const int word = ((nb >> 1) * 64 + jr + 16 * (sub >> 2)) * 4 + 2 * (nb & 1) + ((sub >> 1) & 1);
+          rec[R::kKeyTile + word] = bits;
+          if constexpr (BITS == 4) rec[R::kKeyTile + kPlaneWords + word] = bits_lo;
         }
       }
     }
@@ -713,24 +745,35 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
     // 16 (k % 8) + 4 ((k / 16) % 4) + 2 (k / 64) + (k / 8) % 2, the bit pairs read off the centred codes ----
     {
       // (the centred codes of all tokens were stored before the last barrier)
-      const int wi = (kTileWords / kParts) * fp + tid;
+      const int wi = (kPlaneWords / kParts) * fp + tid;
       const int w = wi & 1, nb = 2 * (wi >> 8) + ((wi >> 1) & 1), l = (wi >> 2) & 63, jr = l & 15, gq4 = l >> 4;
       const int row = 16 * nb + jr, k0 = 32 * gq4 + 16 * w;
       const int tok0 = 4 * ((k0 >> 4) & 3) + 2 * (k0 >> 6);  // token of position k0 + 8 e + i is 16 i + tok0 + e
-      uint32_t vw = 0;
+      uint32_t vw = 0, vw_lo = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int t = 16 * i + tok0;  // even: t and t + 1 share a quad of tokens
         const uint32_t two = *reinterpret_cast<const uint32_t*>(&L.cV[t >> 2][row][t & 3]);
-        const uint32_t h0 = two & 0xffffu, h1 = two >> 16;
-        vw |= (hi_of(h0) << (4 * i + 3)) | (lo_of(h0) << (4 * i + 1)) | (hi_of(h1) << (4 * i + 2)) | (lo_of(h1) << (4 * i));
+        if constexpr (BITS == 2) {
+          const uint32_t h0 = two & 0xffffu, h1 = two >> 16;
+          vw |= (hi_of(h0) << (4 * i + 3)) | (lo_of(h0) << (4 * i + 1)) | (hi_of(h1) << (4 * i + 2)) | (lo_of(h1) << (4 * i));
+        } else {
+          const half2_t h = as_h2(two);
+          const uint32_t c0 = (uint32_t)((float)h[0] + kCentre), c1 = (uint32_t)((float)h[1] + kCentre);  // exact
+          const uint32_t x0 = c0 >> 2, x1 = c1 >> 2, y0 = c0 & 3u, y1 = c1 & 3u;
+          vw |= (((x0 >> 1) ^ 1u) << (4 * i + 3)) | ((((x0 >> 1) ^ x0 ^ 1u) & 1u) << (4 * i + 1)) |
+                (((x1 >> 1) ^ 1u) << (4 * i + 2)) | ((((x1 >> 1) ^ x1 ^ 1u) & 1u) << (4 * i));
+          vw_lo |= (((y0 >> 1) ^ 1u) << (4 * i + 3)) | ((((y0 >> 1) ^ y0 ^ 1u) & 1u) << (4 * i + 1)) |
+                   (((y1 >> 1) ^ 1u) << (4 * i + 2)) | ((((y1 >> 1) ^ y1 ^ 1u) & 1u) << (4 * i));
+        }
       }
-      rec[kRecValueTile + wi] = vw;
+      rec[R::kValueTile + wi] = vw;
+      if constexpr (BITS == 4) rec[R::kValueTile + kPlaneWords + wi] = vw_lo;
     }
     __syncthreads();
     // ---- 4. the group's contribution to S and P (Eq. 5, Eq. 6) ----------------------------------------------
     if (states_live) {
-      float Zacc[8];  // as Pacc, of phi (z_t + 1.5 s_t)
+      float Zacc[8];  // as Pacc, of phi (z_t + centre s_t)
 #pragma unroll
       for (int fo = 0; fo < 8; ++fo) Zacc[fo] = 0.0f;
       // a. logits of this wave's 16 tokens for the 128 features of the half; the small products (low term) first
@@ -809,7 +852,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         for (int fo = 0; fo < 8; ++fo) L.red[wave][16 * fo + l16] = Zacc[fo];
       }
       __syncthreads();
-      // c. S[f][c] += sum_t (phi s)[t][f] (code[t][c] - 1.5): this wave's 16 features, 8 tiles of 16 channels, 32 tokens
+      // c. S[f][c] += sum_t (phi s)[t][f] (code[t][c] - centre): this wave's 16 features, 8 tiles of 16 channels, 32 tokens
       // per instruction
       for (int t0 = 0; t0 < valid; t0 += 32) {
         const half8_t aH = *reinterpret_cast<const half8_t*>(&phH[fw + l16][t0 + 8 * kq]);
@@ -966,8 +1009,9 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
 // (it / (8 kParts)) * 8 + it % 8 of (sequence, kv head), and workgroup x owns the items x, x + G, x + 2 G, ...: the parts of a
 // pair sit on one XCD (workgroups are dealt to the 8 XCDs in turn, and G is a multiple of 8), whose L2 then serves
 // the rows that all of them stage.
-// SLIDING: the variant for caches with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own.
-template <bool SLIDING>
+// SLIDING: the variant for caches with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own;
+// BITS: so is the one for caches with 4-bit codes.
+template <bool SLIDING, int BITS>
 __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
                                                                  const half_t* __restrict__ v_new,
                                                                  const int32_t* __restrict__ n_new, int T, int keep,
@@ -1014,7 +1058,7 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
     const int n_light = L.n_light, n_heavy = L.n_heavy;
     for (int i = wave; i < n_light; i += kThreads / 64) light_item<SLIDING>(c, L.light[i], k_new, v_new, n_new, T, keep, n_chunks, lane);
     for (int i = 0; i < n_heavy; ++i) {
-      flush_item<SLIDING>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep, n_chunks);
+      flush_item<SLIDING, BITS>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep, n_chunks);
       __syncthreads();
     }
     __syncthreads();
@@ -1028,7 +1072,8 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
   static_assert(sizeof(Lds) <= 160 * 1024, "LDS budget of one CU");
   // per device and cheap: set on every call rather than remembered in process state
   void (*kernel)(kvlinc_cache, const half_t*, const half_t*, const int32_t*, int, int, int) =
-      (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0 ? append_flush_kernel<true> : append_flush_kernel<false>;
+      c.bits == 4 ? ((c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0 ? append_flush_kernel<true, 4> : append_flush_kernel<false, 4>)
+                  : ((c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0 ? append_flush_kernel<true, 2> : append_flush_kernel<false, 2>);
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sizeof(Lds)) != hipSuccess)
     return KVLINC_EHIP;

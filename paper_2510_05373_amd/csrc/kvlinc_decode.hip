@@ -210,39 +210,51 @@ __device__ __forceinline__ v8i_t get_operand(const uint32_t* ex, int at) {
   return v8i_t{(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
 }
 
-// D = A B + C with B = 32 centred codes per lane from two packed words (see centred_nibbles).
+// D = A B + C with B = 32 centred codes per lane from two packed words (see centred_nibbles); kScaleB: the block scale
+// byte of B (127 = 1, 129 = 4).
+template <int kScaleB = 127>
 __device__ __forceinline__ float4_t mfma_codes(v8i_t a, uint32_t w0, uint32_t w1, float4_t c, int scale_a, uint32_t pick) {
   const v8i_t b = {(int)centred_nibbles(w0, pick), (int)centred_nibbles(w0 << 1, pick), (int)centred_nibbles(w1, pick),
                    (int)centred_nibbles(w1 << 1, pick), 0, 0, 0, 0};
   return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /* A: FP8 E4M3 */, 4 /* B: FP4 E2M1 */, 0, scale_a,
-                                                         0, 127);
+                                                         0, kScaleB);
+}
+// 4-bit codes: a tile is two planes of 2-bit codes, the base-4 digits of the codes, and
+// code - 7.5 = 4 (high digit - 1.5) + (low digit - 1.5): the contraction with the codes is the contraction with the high
+// plane under a block scale of 4 plus the contraction with the low plane.
+__device__ __forceinline__ float4_t mfma_codes_high(v8i_t a, uint32_t w0, uint32_t w1, float4_t c, int scale_a, uint32_t pick) {
+  return mfma_codes<129>(a, w0, w1, c, scale_a, pick);
 }
 
-// Register image of one group.
+// Register image of one group; BITS / 2 planes per tile.
+template <int BITS>
 struct KeyRegs {
-  uint4 kw[4];  // key tile: kw[m] = the words of token blocks 2 m (x, y) and 2 m + 1 (z, w) for this lane's (column, quarter)
+  uint4 kw[2 * BITS];  // key tile: kw[4 plane + m] = the words of token blocks 2 m (x, y) and 2 m + 1 (z, w) for this lane's (column, quarter)
   uint4 ks, kz;  // key scale / zero-point of the 8 channels c0 .. c0 + 7 this lane builds operands for
 };
+template <int BITS>
 struct ValueRegs {
-  uint4 vw[4];  // value tile, channel blocks 2 m and 2 m + 1
+  uint4 vw[2 * BITS];  // value tile, channel blocks 2 m and 2 m + 1 of every plane
   uint4 sz[2];  // value (scale, zero-point) pairs of tokens 16 n + jd, n = 0..7
 };
 
 // A record is fetched in two parts so that each part can be requested again for the next group as soon as its
 // contraction has consumed it: the key part flies during E V, the value part during the next q K^T.
-__device__ __forceinline__ void load_keys(KeyRegs& r, const uint32_t* __restrict__ rec, const Roles& lr) {
-  const uint4* kt = reinterpret_cast<const uint4*>(rec + kRecKeyTile);
+template <int BITS>
+__device__ __forceinline__ void load_keys(KeyRegs<BITS>& r, const uint32_t* __restrict__ rec, const Roles& lr) {
+  const uint4* kt = reinterpret_cast<const uint4*>(rec + Rec<BITS>::kKeyTile);
 #pragma unroll
-  for (int m = 0; m < 4; ++m) r.kw[m] = kt[m * 64 + lr.lane];
-  r.ks = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + kRecKeyScale) + lr.c0);
-  r.kz = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + kRecKeyZero) + lr.c0);
+  for (int m = 0; m < 2 * BITS; ++m) r.kw[m] = kt[m * 64 + lr.lane];  // (the planes follow each other)
+  r.ks = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + Rec<BITS>::kKeyScale) + lr.c0);
+  r.kz = *reinterpret_cast<const uint4*>(reinterpret_cast<const half_t*>(rec + Rec<BITS>::kKeyZero) + lr.c0);
 }
 
-__device__ __forceinline__ void load_values(ValueRegs& r, const uint32_t* __restrict__ rec, const Roles& lr) {
-  const uint4* vt = reinterpret_cast<const uint4*>(rec + kRecValueTile);
+template <int BITS>
+__device__ __forceinline__ void load_values(ValueRegs<BITS>& r, const uint32_t* __restrict__ rec, const Roles& lr) {
+  const uint4* vt = reinterpret_cast<const uint4*>(rec + Rec<BITS>::kValueTile);
 #pragma unroll
-  for (int m = 0; m < 4; ++m) r.vw[m] = vt[m * 64 + lr.lane];
-  const uint4* sz = reinterpret_cast<const uint4*>(rec + kRecValueSZ) + 2 * lr.jd;
+  for (int m = 0; m < 2 * BITS; ++m) r.vw[m] = vt[m * 64 + lr.lane];
+  const uint4* sz = reinterpret_cast<const uint4*>(rec + Rec<BITS>::kValueSZ) + 2 * lr.jd;
   r.sz[0] = sz[0];
   r.sz[1] = sz[1];
 }
@@ -259,8 +271,8 @@ struct WaveState {
 
 // q K^T of one group for all heads (Alg. 1 line 7): scores in the log2 domain, sc[nb][n] = head 4 nb + hd, token 16 n + jd.
 // qa = this lane's 8 query values (head 4 nb + ha, channels c0 ..) times log2(e) / sqrt(d); qh = the same as binary16 pairs.
-template <int NB>
-__device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const float (&qa)[NB][8], const uint32_t (&qh)[NB][4],
+template <int NB, int BITS>
+__device__ __forceinline__ void qk_phase(const KeyRegs<BITS>& g, int valid, const float (&qa)[NB][8], const uint32_t (&qh)[NB][4],
                                          const Roles& lr, float (&sc)[NB][8]) {
   const uint32_t S[4] = {g.ks.x, g.ks.y, g.ks.z, g.ks.w};
   const uint32_t Z[4] = {g.kz.x, g.kz.y, g.kz.z, g.kz.w};
@@ -280,7 +292,7 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const floa
     // group's scores and small (keys are centred), its rounding (2^-12 of it) is of no account.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const half2_t mid = as_h2(S[i]) * half2_t{(half_t)1.5f, (half_t)1.5f} + as_h2(Z[i]);
+      const half2_t mid = as_h2(S[i]) * half2_t{(half_t)Rec<BITS>::kCentre, (half_t)Rec<BITS>::kCentre} + as_h2(Z[i]);
       bz = __builtin_amdgcn_fdot2(as_h2(qh[nb][i]), mid, bz, false);
     }
     const uint32_t eb = block_exponent(xrow_umax(quad_umax(as_bits(mx))));  // over the 128 channels of the head
@@ -300,13 +312,29 @@ __device__ __forceinline__ void qk_phase(const KeyRegs& g, int valid, const floa
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     const uint32_t w[4] = {g.kw[m].x, g.kw[m].y, g.kw[m].z, g.kw[m].w};
+    if constexpr (BITS == 2) {
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
+      for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const float4_t d = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb], lr.pick);
-        sc[nb][2 * m + hf] = (d[0] + d[1]) + d[2];
-      }
+        for (int nb = 0; nb < NB; ++nb) {
+          const float4_t d = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb], lr.pick);
+          sc[nb][2 * m + hf] = (d[0] + d[1]) + d[2];
+        }
+    } else {
+      const uint32_t wl[4] = {g.kw[4 + m].x, g.kw[4 + m].y, g.kw[4 + m].z, g.kw[4 + m].w};  // low plane
+      float4_t d[2][NB];
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) d[hf][nb] = mfma_codes_high(A[nb], w[2 * hf], w[2 * hf + 1], c0[nb], scale_a[nb], lr.pick);
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          d[hf][nb] = mfma_codes(A[nb], wl[2 * hf], wl[2 * hf + 1], d[hf][nb], scale_a[nb], lr.pick);
+          sc[nb][2 * m + hf] = (d[hf][nb][0] + d[hf][nb][1]) + d[hf][nb][2];
+        }
+    }
   }
   if (valid < kGroup) {  // partial last group: tokens >= valid do not exist
 #pragma unroll
@@ -342,8 +370,8 @@ __device__ __forceinline__ void update_reference(const float (&sc)[NB][8], WaveS
 
 // p = 2^(x - m), its sums, and E V of one group (Alg. 1 lines 9-10).  MASKED: tokens from `fp16_from` on count in the
 // sums of p but not in E V: their values are taken from the fp16 window (pv_window_tail).
-template <int NB, bool MASKED = false>
-__device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[NB][8], const Roles& lr,
+template <int NB, int BITS, bool MASKED = false>
+__device__ __forceinline__ void pv_phase(const ValueRegs<BITS>& g, const float (&sc)[NB][8], const Roles& lr,
                                          WaveState<NB>& st, int fp16_from = kGroup) {
   const uint32_t SZ[8] = {g.sz[0].x, g.sz[0].y, g.sz[0].z, g.sz[0].w, g.sz[1].x, g.sz[1].y, g.sz[1].z, g.sz[1].w};
   v8i_t A[NB];
@@ -359,7 +387,7 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
       const bool coded = !MASKED || 16 * n + lr.jd < fp16_from;
       y[n] = coded ? fmaf(p, (float)sz[0], 0.0f) : 0.0f;  // p * value scale: the weight of the token's codes
       // sum_t p_t (z_t + 1.5 s_t): the zero-points and the centring of the codes, the same for every channel
-      st.pz[nb] = coded ? fmaf(y[n], 1.5f, fmaf(p, (float)sz[1], st.pz[nb])) : st.pz[nb];
+      st.pz[nb] = coded ? fmaf(y[n], Rec<BITS>::kCentre, fmaf(p, (float)sz[1], st.pz[nb])) : st.pz[nb];
       mx = fmaxf(mx, y[n]);
     }
     const uint32_t eb = block_exponent(row_umax(as_bits(mx)));  // over the 128 tokens of the head
@@ -379,7 +407,19 @@ __device__ __forceinline__ void pv_phase(const ValueRegs& g, const float (&sc)[N
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick);
+        st.acc[nb][2 * m + hf] = BITS == 2 ? mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick)
+                                           : mfma_codes_high(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick);
+  }
+  if constexpr (BITS == 4) {  // the low plane
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uint32_t w[4] = {g.vw[4 + m].x, g.vw[4 + m].y, g.vw[4 + m].z, g.vw[4 + m].w};
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          st.acc[nb][2 * m + hf] = mfma_codes(A[nb], w[2 * hf], w[2 * hf + 1], st.acc[nb][2 * m + hf], scale_a[nb], lr.pick);
+    }
   }
 }
 
@@ -797,8 +837,9 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
 // steps and should start at once).  All of them count themselves in at split_done; the last arrival merges.
 // SLIDING: the variant with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own, so that the
 // default one carries none of its code.
-template <int NB, bool SLIDING = false>
-__global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
+// BITS: so is the one for caches with 4-bit codes (it holds twice the tile words in registers).
+template <int NB, bool SLIDING = false, int BITS = 2>
+__global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
                                                                    half_t* __restrict__ out, int max_splits,
                                                                    int avg_splits, int gq, int corr_first) {
@@ -910,10 +951,11 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
 
   // The first record is requested before the sequence length is known (any group index below the capacity is
   // readable memory); what it holds is used only if the group exists.
+  constexpr int kRecordWords = Rec<BITS>::kWords;
   const uint32_t* rec0 = c.groups + (long long)bh * c.max_groups * kRecordWords;
   const Roles lr = make_roles(lane, ex[wave]);
-  KeyRegs kr;
-  ValueRegs vr;
+  KeyRegs<BITS> kr;
+  ValueRegs<BITS> vr;
   if (sp < avg_splits) {
     const long long first = idx < c.max_groups ? idx : c.max_groups - 1;
     load_keys(kr, rec0 + first * kRecordWords, lr);
@@ -1003,18 +1045,18 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 3 : 2) void decode_main_kernel(
       const int nxt = group_of_round(++rd);
       const uint32_t* src = rec0 + (long long)(nxt < count ? nxt : idx) * kRecordWords;
       float sc[NB][8];
-      qk_phase<NB>(kr, min(kGroup, nq - idx * kGroup), qa, qh, lr, sc);
+      qk_phase<NB, BITS>(kr, min(kGroup, nq - idx * kGroup), qa, qh, lr, sc);
       load_keys(kr, src, lr);
       update_reference<NB>(sc, st);
-      pv_phase<NB>(vr, sc, lr, st);
+      pv_phase<NB, BITS>(vr, sc, lr, st);
       load_values(vr, src, lr);
       idx = nxt;
     }
     if (SLIDING && idx < count) {  // sliding value window: the newest group, whose tokens from n_res on have fp16 values
       float sc[NB][8];
-      qk_phase<NB>(kr, kGroup, qa, qh, lr, sc);
+      qk_phase<NB, BITS>(kr, kGroup, qa, qh, lr, sc);
       update_reference<NB>(sc, st);
-      pv_phase<NB, true>(vr, sc, lr, st, nr);
+      pv_phase<NB, BITS, true>(vr, sc, lr, st, nr);
       pv_window_tail<NB>(reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim, sc, nr, lr, st, lane);
     }
   }
@@ -1156,8 +1198,10 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const int corr_first = sp.corr_first;
   const bool sliding = (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0;
   void (*kernel)(kvlinc_cache, const half_t*, float*, float*, half_t*, int, int, int, int) =
-      gq <= 4 ? (sliding ? decode_main_kernel<1, true> : decode_main_kernel<1, false>)
-              : (sliding ? decode_main_kernel<2, true> : decode_main_kernel<2, false>);
+      c.bits == 4 ? (gq <= 4 ? (sliding ? decode_main_kernel<1, true, 4> : decode_main_kernel<1, false, 4>)
+                             : (sliding ? decode_main_kernel<2, true, 4> : decode_main_kernel<2, false, 4>))
+                  : (gq <= 4 ? (sliding ? decode_main_kernel<1, true> : decode_main_kernel<1, false>)
+                             : (sliding ? decode_main_kernel<2, true> : decode_main_kernel<2, false>));
   if (start != nullptr)  // timestamps of the dispatch itself, no extra packets on the stream
     hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
   else

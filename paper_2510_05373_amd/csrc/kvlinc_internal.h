@@ -11,10 +11,18 @@ namespace kvlinc {
 constexpr int kHeadDim = 128;   // d
 constexpr int kGroup = 128;     // G: tokens per key group = channels per value group
 constexpr int kRank = 256;      // D
-constexpr int kTileWords = 1024;
-// group record (words): key tile, value tile, key scale, key zero-point, value (scale, zero-point) per token
-constexpr int kRecordWords = 2304;
-constexpr int kRecKeyTile = 0, kRecValueTile = 1024, kRecKeyScale = 2048, kRecKeyZero = 2112, kRecValueSZ = 2176;
+// Group record of a cache with BITS-bit codes (words): key tile, value tile, key scale, key zero-point, value
+// (scale, zero-point) per token; a tile holds 128 x 128 codes.  kCentre: the middle of the code range, (2^BITS - 1) / 2 --
+// the tiles hold the codes as the numbers code - kCentre.
+template <int BITS>
+struct Rec {
+  static_assert(BITS == 2 || BITS == 4, "code widths of the record layout");
+  static constexpr int kTile = kGroup * kHeadDim * BITS / 32;
+  static constexpr int kKeyTile = 0, kValueTile = kTile, kKeyScale = 2 * kTile, kKeyZero = 2 * kTile + 64,
+                       kValueSZ = 2 * kTile + 128, kWords = 2 * kTile + 256;
+  static constexpr int kLevels = (1 << BITS) - 1;
+  static constexpr float kCentre = 0.5f * kLevels;
+};
 constexpr int kMaxGq = 8;       // query heads per KV head supported by the decode kernels
 
 // Partial result of one block of tokens for one query head (Alg. 1: m^j, l^j, Y_s^j), log2 domain:

@@ -90,18 +90,19 @@ def check_states_against(cache, b, g, S_ref, P_ref, quiet=False):
 def check_pair_against_oracle(cache, b, g, k_rows, v_rows, nq, nr, Wk_g=None, check_states=True):
     """Bit-exact comparison of everything the append path stores for one (sequence, kv head) whose token history is
     k_rows, v_rows [n, 128]; returns the oracle's cache."""
-    ref = o_cache.build_cache(k_rows, v_rows, nq, Wk=Wk_g)
+    bits = getattr(cache, "bits", 2)
+    pack, unpack = (o_layout.pack_records, o_layout.unpack_records) if bits == 2 else (o_layout.pack_records4, o_layout.unpack_records4)
+    ref = o_cache.build_cache(k_rows, v_rows, nq, Wk=Wk_g, bits=bits)
     ng = -(-nq // 128)
     rec = cache.groups[b, g, :ng].cpu().numpy().view(np.uint32)
     if ng:
         # logical fields first (clearer failure), then the physical record bytes
-        got = o_layout.unpack_records(rec)
+        got = unpack(rec)
         assert np.array_equal(got["k_codes"], ref["k_codes"]), ("k codes", b, g)
         assert np.array_equal(got["v_codes"], ref["v_codes"]), ("v codes", b, g)
         for name in ("k_scale", "k_zero", "v_scale", "v_zero"):
             assert np.array_equal(u16(got[name]), u16(ref[name])), (name, b, g)
-        want = o_layout.pack_records(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"],
-                                     ref["v_scale"], ref["v_zero"])
+        want = pack(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"], ref["v_scale"], ref["v_zero"])
         assert np.array_equal(rec, want), ("records", b, g)
     assert np.array_equal(u16(cache.k_res[b, g, :nr].cpu().numpy()), u16(ref["k_res"])), ("k_res", b, g)
     v_win = o_layout.unpack_value_window(cache.v_res[b, g].cpu().numpy(), nr)
@@ -120,13 +121,13 @@ def check_cache_against_oracle(cache, K, V, lengths, pairs, Wk=None, keep=None, 
                                   None if Wk is None else Wk[g], check_states)
 
 
-def oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq=None, Wk=None):
+def oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq=None, Wk=None, bits=2):
     """{(b, h): y fp64[128]} for every query head of the listed (sequence, kv head) pairs."""
     gq = H_q // H_kv
     out = {}
     for (b, g) in pairs:
         n = int(lengths[b])
-        ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=None if Wk is None else Wk[g])
+        ref = o_cache.build_cache(K[b, g, :n], V[b, g, :n], int(n_quant[b]), Wk=None if Wk is None else Wk[g], bits=bits)
         for h in range(g * gq, (g + 1) * gq):
             out[(b, h)] = o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h])
     return out

@@ -16,12 +16,13 @@ def kv():
     return kvmod
 
 
-def _build(kv, cfg, B, H_q, H_kv, lengths, R=128, keep=None, correction=True, capacity=None):
+def _build(kv, cfg, B, H_q, H_kv, lengths, R=128, keep=None, correction=True, capacity=None, bits=2, flags=0):
     K, V = tl.gen_kv(cfg, B, H_kv, lengths)
     Wq = synth.adapters_q(cfg, H_q) if correction else None
     Wk = synth.adapters_k(cfg, H_kv) if correction else None
     cache = kv.KVLincCache(B, H_q, H_kv, capacity or int(max(lengths)) + 512, R=R,
-                           Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk))
+                           Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk),
+                           bits=bits, flags=flags)
     n_new = tl.to_dev(np.asarray(lengths, dtype=np.int32))
     cache.append(tl.to_dev(K), tl.to_dev(V), n_new=n_new, keep_residual=0 if keep is None else keep)
     return cache, K, V, Wq, Wk
@@ -746,3 +747,111 @@ def test_long_prompt_build_in_chunks_refuses_as_a_whole(kv, H_kv):
     n_quant, n_res = tl.check_counters(cache, [n0 + n1])
     for g in range(H_kv):
         tl.check_pair_against_oracle(cache, 0, g, K[0, g], V[0, g], int(n_quant[0]), int(n_res[0]), Wk[g])
+
+
+# ---- 4-bit codes (Eq. 1 at N = 4) ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gq,H_kv,correction", [(4, 2, True), (4, 2, False), (8, 1, True), (1, 3, True), (7, 2, True)])
+def test_four_bit_codes_bulk_and_decode(kv, gq, H_kv, correction):
+    """A cache with 4-bit codes: records (two 2-bit planes per tile), window, states and counters bit for bit / within
+    the state bounds against the oracle at bits = 4, and the decode output within the output tolerance; ragged lengths
+    with a sequence below one group, an exact multiple and several groups per wave."""
+    import torch
+    B, H_q = 4, gq * H_kv
+    lengths = [700, 128, 57, 2300]
+    cache, K, V, Wq, Wk = _build(kv, 41, B, H_q, H_kv, lengths, correction=correction, bits=4)
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == 0 and cache.groups.shape[-1] == 4352
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)
+    q = tl.gen_q(41, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    n_quant = cache.n_quant.cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk, bits=4)
+    tl.check_outputs(out, want)
+    # the 2-bit answer on the same inputs differs by more than the tolerance, so the comparison tells the widths apart
+    two = tl.oracle_decode(K, V, q, lengths, n_quant, [(0, 0)], H_q, H_kv, Wq, Wk, bits=2)
+    assert max(np.abs(two[k] - want[k]).max() for k in two) > 2 * tl.OUT_MAX_ABS
+
+
+def test_four_bit_codes_one_token_appends_cross_a_flush(kv):
+    """One-token appends through a window flush with 4-bit codes, a partial tail group from a static window, and a
+    refused append that leaves the sequence as it was."""
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    start, steps = [250, 127], 140
+    total = [s + steps for s in start]
+    K, V = tl.gen_kv(42, B, H_kv, total)
+    Wq, Wk = synth.adapters_q(42, H_q), synth.adapters_k(42, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), bits=4)
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :max(start)].contiguous(), Vd[:, :, :max(start)].contiguous(),
+                 n_new=tl.to_dev(np.asarray(start, dtype=np.int32)))
+    lengths = list(start)
+    for step in range(steps):
+        kn = torch.stack([Kd[b, :, lengths[b]:lengths[b] + 1] for b in range(B)]).contiguous()
+        vn = torch.stack([Vd[b, :, lengths[b]:lengths[b] + 1] for b in range(B)]).contiguous()
+        cache.append(kn, vn)
+        lengths = [n + 1 for n in lengths]
+        if step in (0, 5, 6, 7, 133, 134, steps - 1):
+            tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)
+            q = tl.gen_q(42, B, H_q, step)
+            out = cache.decode(tl.to_dev(q)).cpu().numpy()
+            want = tl.oracle_decode(K, V, q, lengths, cache.n_quant.cpu().numpy(), _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk, bits=4)
+            tl.check_outputs(out, want)
+    assert int(cache.status.item()) == 0
+    # a non-finite key in one head: refused, nothing of the sequence changes
+    before = [t.clone() for t in (cache.groups, cache.k_res, cache.v_res, cache.S, cache.P, cache.S16, cache.n_quant, cache.n_res)]
+    kn = torch.zeros(B, H_kv, 1, 128, dtype=torch.float16, device="cuda")
+    kn[1, 1, 0, 5] = float("inf")
+    cache.append(kn, torch.zeros_like(kn), n_new=tl.to_dev(np.asarray([0, 1], dtype=np.int32)))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == kv.KVLINC_ST_NONFINITE
+    nq, nr = cache.n_quant.cpu().tolist(), cache.n_res.cpu().tolist()
+    for old, new in zip(before[4:], (cache.P, cache.S16, cache.n_quant, cache.n_res)):
+        assert torch.equal(old, new)
+    assert torch.equal(before[3], cache.S)
+    for b in range(B):
+        assert torch.equal(before[0][b, :, :nq[b] // 128], cache.groups[b, :, :nq[b] // 128])
+        assert torch.equal(before[1][b, :, :nr[b]], cache.k_res[b, :, :nr[b]])
+
+
+def test_four_bit_codes_static_window_and_sliding_values(kv):
+    """4-bit codes with the static 32-token window of workload 1 (a partial tail group) and with the sliding value
+    window."""
+    c = synth.CONFIGS[1]
+    lengths = [c["n"]]
+    cache, K, V, Wq, Wk = _build(kv, 1, c["B"], c["H_q"], c["H_kv"], lengths, R=c["R"], keep=c["keep"], capacity=1024, bits=4)
+    assert cache.n_quant.cpu().tolist() == [992] and cache.n_res.cpu().tolist() == [32]
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(1, 8), Wk=Wk, keep=32)
+    q = tl.gen_q(1, 1, 32)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = tl.oracle_decode(K, V, q, lengths, [992], _all_pairs(1, 8), 32, 8, Wq, Wk, bits=4)
+    tl.check_outputs(out, want)
+    # sliding value window: bulk build, then appends; the newest group's last tokens take their values from the window
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    pre, extra = [517, 205], 30
+    lengths = [p + extra for p in pre]
+    K, V = tl.gen_kv(43, B, H_kv, lengths)
+    Wq, Wk = synth.adapters_q(43, H_q), synth.adapters_k(43, H_kv)
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), flags=kv.KVLINC_FLAG_SLIDING_VALUES, bits=4)
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :max(pre)].contiguous(), Vd[:, :, :max(pre)].contiguous(), n_new=tl.to_dev(np.asarray(pre, dtype=np.int32)))
+    for s in range(extra + 1):
+        cur = [p + s for p in pre]
+        if s in (0, 1, 29, 30):
+            q = tl.gen_q(43, B, H_q, step=s)
+            out = cache.decode(tl.to_dev(q)).cpu().numpy().astype(np.float64)
+            n_quant, n_res = tl.check_counters(cache, cur)
+            want = {}
+            for b in range(B):
+                for g in range(H_kv):
+                    ref = tl.o_cache.build_cache(K[b, g, :cur[b]], V[b, g, :cur[b]], int(n_quant[b]), Wk=Wk[g], bits=4)
+                    for h in range(4 * g, 4 * g + 4):
+                        want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h], value_window="sliding")
+            tl.check_outputs(out, want)
+        if s < extra:
+            kn = torch.stack([Kd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            cache.append(kn, vn)
+    assert int(cache.status.item()) == 0

@@ -73,7 +73,7 @@ def test_version_and_messages():
 def test_validate_accepts_and_rejects():
     ok = fake_struct()
     assert kb.kvlinc_cache_validate(ok) == kb.KVLINC_OK
-    bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=4), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
+    bad = [dict(d=64), dict(G=64), dict(D=128), dict(bits=3), dict(bits=8), dict(R=0), dict(R=130), dict(R=30), dict(H_q=9),
            dict(H_q=32, H_kv=2), dict(B=0), dict(max_groups=0), dict(groups=0), dict(groups=0x10004), dict(k_res=0),
            dict(v_res=8), dict(n_quant=0), dict(n_res=2), dict(status=0), dict(split_done=0), dict(S16=0),
            dict(S16=0x10008), dict(Wk=0), dict(P=0x10002), dict(S=0x10004), dict(flags=4), dict(flags=-1), dict(flags=kb.KVLINC_FLAG_SLIDING_VALUES, R=64),
@@ -137,6 +137,11 @@ def test_cache_bytes_reproduce_the_average_bit_figures():
     assert abs(bits16 - 2.71) < 0.01
     c32 = kb.KVLincCache(B, H_q, H_kv, n - 128, Wq=W, Wk=W[:H_kv], device="cpu")  # with the fp32 master copy of S
     assert abs(c32.bytes() * 8 / elements - (bits16 + 256 * 128 * 32 / (2 * n * 128))) < 1e-12
+    # 4-bit codes: 4 + 32 / 128 bits per quantized element (Sec. 2: a scale and a zero-point of 16 bits per group of 128)
+    four = kb.KVLincCache(B, H_q, H_kv, n - 128, device="cpu", bits=4)
+    assert four.struct.bits == 4 and four.groups.shape[-1] == 4352
+    assert kb.kvlinc_cache_validate(four) == kb.KVLINC_OK
+    assert abs(four.bytes() * 8 / elements - accounting.average_bits(n, bits=4)) < 1e-12
 
 
 def test_noalloc_entry_rejects_on_the_host():

@@ -71,7 +71,8 @@ def read_only_ceiling(caches, B, H_kv, H_q, counts, n_res, reps, hip, new_event)
     args = []
     total = 0
     for c in caches:
-        segs = [(c.groups, counts * 9216, c.max_groups * 9216, B * H_kv),
+        rec_bytes = c.groups.shape[-1] * 4  # one group record
+        segs = [(c.groups, counts * rec_bytes, c.max_groups * rec_bytes, B * H_kv),
                 (c.k_res, n_res * 256, c.R * 256, B * H_kv), (c.v_res, -(-n_res // 4) * 1024, c.R * 256, B * H_kv),
                 (c.S16, B * H_kv * 65536, 0, 1), (c.P, B * H_kv * 1024, 0, 1), (c.Wq, H_q * 65536, 0, 1)]
         n = len(segs)
@@ -100,12 +101,12 @@ def read_only_ceiling(caches, B, H_kv, H_q, counts, n_res, reps, hip, new_event)
     return float(np.mean(ms)) * 1e-3, total
 
 
-def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True):
-    """Bytes one decode call must move: 2-bit codes (64 B per token and KV head), fp16 scale + zero-point (8 B),
+def algorithmic_bytes(B, H_q, H_kv, n_quant, n_res, correction=True, bits=2):
+    """Bytes one decode call must move: 2-bit codes (64 B per token and KV head; twice that at 4 bits), fp16 scale + zero-point (8 B),
     the fp16 window (512 B per window token and KV head), the 16-bit state S and the fp32 P once per (sequence, KV
     head), W_q once, q and out.  Split partials are an implementation choice and are not counted."""
     groups = sum(-(-int(n) // 128) for n in n_quant)
-    total = groups * H_kv * (2 * 4096 + 2 * 512)
+    total = groups * H_kv * (2 * 2048 * bits + 2 * 512)
     total += int(sum(n_res)) * H_kv * 512
     if correction:
         total += B * H_kv * (256 * 128 * 2 + 256 * 4) + H_q * 2 * 128 * 128 * 2
@@ -127,8 +128,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run 4 plain device copies of 256 MiB, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
-    ap.add_argument("--variant", default="default", choices=["default", "sliding-values", "state16", "alg1-literal"],
-                    help="measure one of the variants of the path (descriptor flags / 16-bit state storage); the "
+    ap.add_argument("--variant", default="default", choices=["default", "sliding-values", "state16", "alg1-literal", "bits4"],
+                    help="measure one of the variants of the path (descriptor flags / 16-bit state storage / 4-bit codes); the "
                          "default line is the one the metric is quoted on")
     ap.add_argument("--no-events", action="store_true", help="diagnosis: no per-launch events (roofline is then void)")
     args = ap.parse_args()
@@ -147,6 +148,7 @@ def main():
     import paper_2510_05373_amd as kv
 
     wl = args.workload
+    bits = 4 if args.variant == "bits4" else 2
     cfg = synth.CONFIGS[wl]
     B, H_q, H_kv = cfg["B"], cfg["H_q"], cfg["H_kv"]
     L = args.layers if args.layers else (4 if wl in (4, 5) else 8)
@@ -193,7 +195,8 @@ def main():
         n_start = base_len - short
         c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk,
                            state_storage="fp16" if args.variant == "state16" else "fp32",
-                           flags={"sliding-values": kv.KVLINC_FLAG_SLIDING_VALUES, "alg1-literal": kv.KVLINC_FLAG_ALG1_LITERAL}.get(args.variant, 0))
+                           flags={"sliding-values": kv.KVLINC_FLAG_SLIDING_VALUES, "alg1-literal": kv.KVLINC_FLAG_ALG1_LITERAL}.get(args.variant, 0),
+                           bits=bits)
         t_max = int(n_start.max())
         c.append(Kd[:, :, :t_max].contiguous(), Vd[:, :, :t_max].contiguous(),
                  n_new=torch.from_numpy(n_start.astype(np.int32)).to(dev))
@@ -275,7 +278,7 @@ def main():
         n = lens[j]
         tokens += int(n.sum())
         n_res = (n - 1) % 128 + 1
-        alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, n - n_res, n_res))
+        alg_bytes.append(algorithmic_bytes(B, H_q, H_kv, n - n_res, n_res, bits=bits))
     if use_events:
         decode_ms = np.empty(len(timed))
         for k, s in enumerate(timed):
@@ -289,7 +292,7 @@ def main():
         decode_ms = np.array([float("nan")])
     decode_avg_s = float(decode_ms.mean()) * 1e-3
     achieved = float(np.mean(alg_bytes)) / decode_avg_s / 1e9
-    traffic, traffic_file, traffic_note = measured_traffic(cfg["name"])
+    traffic, traffic_file, traffic_note = measured_traffic(cfg["name"]) if args.variant == "default" else (None, None, "not collected for variants")
     # the practical ceiling: a launch that only reads the same bytes (windows full, as in most steps)
     ceiling = None
     if wl != 5 and not args.no_events:
@@ -306,10 +309,10 @@ def main():
         "n_gpus": 1, "steps": K_steps, "warmup": W,
         "ms_per_step": elapsed / K_steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u2 codes, f16 operands, f32 accumulate",
+        "dtype": "u%d codes, f16 operands, f32 accumulate" % bits,
         "data": "synthetic",
         "config": {"workload": cfg["name"] + ("" if args.variant == "default" else " [variant: %s]" % args.variant), "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
-                   "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0), "window": 128, "group": 128, "bits": 2, "correction_rank": 256,
+                   "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0), "window": 128, "group": 128, "bits": bits, "correction_rank": 256,
                    "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
                    "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),
                    "launch_loop_cpu_ms_per_step": (t_cpu_done - t_start) / K_steps * 1e3, "setup_s": setup_s},

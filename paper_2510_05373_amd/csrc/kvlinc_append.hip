@@ -28,11 +28,16 @@ struct Lds {
   // the high / low term of phi s of the group for this workgroup's 128 features, [feature][token]
   half_t bK[kGroup][kRowH];
   half_t bV[kGroup][kRowH];
-  // value codes as the binary16 numbers code - centre (centre = 1.5 at 2 bits, 7.5 at 4), [token / 4][channel][token % 4]:
-  // what the S update multiplies by, and -- sign and magnitude -- what the record stores of a code
+  // value codes as the binary16 numbers (code - centre) / f_t (centre = 1.5 at 2 bits, 7.5 at 4; f_t a power of two per
+  // token, see vFactor), [token / 4][channel][token % 4]: what the S update multiplies by, and -- sign and magnitude --
+  // what the record stores of a code
   half_t cV[kGroup / 4][kHeadDim][4];
   float kScale[kGroup], kZero[kGroup];
-  float vScale[kGroup], vCentre[kGroup];  // vCentre: z + centre s, the value of the centre of the code range
+  // vScale: the value scale s_t times f_t, the power of two that brings it to [2^13, 2^14) (or as near as the exponent
+  // range of the codes' binary16 form allows): phi s_t f_t then fills binary16's range from the top, and the two binary16
+  // terms it is carried in leave 2^-38 of the largest entry rather than 2^-25 of one.  vCentre: z + centre s, the value
+  // of the centre of the code range.
+  float vScale[kGroup], vCentre[kGroup], vFactor[kGroup];
   half_t kmn[kWaves][kGroup], kmx[kWaves][kGroup];  // per-channel key minima / maxima of each wave's tokens
   half_t Wt[kRank / 2][kRowH];  // W_k of the half of phi this workgroup belongs to, [feature][channel]
   float red[kWaves][kRank / 2];
@@ -384,8 +389,8 @@ __device__ __forceinline__ float rows_max(float v) {
   return fmaxf(p, q);
 }
 
-// bits of the binary16 number code - 1.5 that make the stored bit pair: hi = sign (codes 0, 1), lo = magnitude 1.5
-// rather than 0.5 (codes 0, 3)
+// bits of the binary16 number (code - 1.5) times a power of two that make the stored bit pair: hi = sign (codes 0, 1),
+// lo = magnitude 1.5 rather than 0.5 (codes 0, 3), the leading fraction bit
 __device__ __forceinline__ uint32_t hi_of(uint32_t h16) { return (h16 >> 15) & 1u; }
 __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u; }
 
@@ -607,25 +612,35 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
         mx[i] = row16_max(mx[i]);
       }
       QP pv[4];
+      float fac[4], inv_fac[4];  // f_t and 1 / f_t: 2^k with k = 13 - (exponent of s_t), kept inside -2 .. 13 so that
+                                 // (code - centre) / f_t stays a normal binary16 number (0.5 * 2^-13 .. 7.5 * 4)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) pv[i] = q_params<BITS>(mn[i], mx[i]);
+      for (int i = 0; i < 4; ++i) {
+        pv[i] = q_params<BITS>(mn[i], mx[i]);
+        const int e = (int)(__builtin_bit_cast(uint32_t, pv[i].s) >> 23) - 127;
+        const int k = pv[i].s == 0.0f ? 0 : min(max(13 - e, -2), 13);
+        fac[i] = __builtin_bit_cast(float, (uint32_t)(127 + k) << 23);
+        inv_fac[i] = __builtin_bit_cast(float, (uint32_t)(127 - k) << 23);
+      }
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {  // two channels = 8 halfs = one 16-byte store
         half8_t h;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          h[i] = (half_t)((float)q_code<BITS>(x[i][e], pv[i]) - kCentre);
-          h[4 + i] = (half_t)((float)q_code<BITS>(x[i][e + 1], pv[i]) - kCentre);
+        for (int i = 0; i < 4; ++i) {  // (exact: a multiple of 0.5 times a power of two)
+          h[i] = (half_t)(((float)q_code<BITS>(x[i][e], pv[i]) - kCentre) * inv_fac[i]);
+          h[4 + i] = (half_t)(((float)q_code<BITS>(x[i][e + 1], pv[i]) - kCentre) * inv_fac[i]);
         }
         *reinterpret_cast<half8_t*>(&L.cV[tq][8 * sub + e][0]) = h;
       }
       if (sub < 4) {  // lane sub of the row writes token 4 tq + sub
         QP mine = pv[0];
-        if (sub == 1) mine = pv[1];
-        if (sub == 2) mine = pv[2];
-        if (sub == 3) mine = pv[3];
+        float my_fac = fac[0];
+        if (sub == 1) { mine = pv[1]; my_fac = fac[1]; }
+        if (sub == 2) { mine = pv[2]; my_fac = fac[2]; }
+        if (sub == 3) { mine = pv[3]; my_fac = fac[3]; }
         const int t = 4 * tq + sub;
-        L.vScale[t] = mine.s;
+        L.vScale[t] = mine.s * my_fac;
+        L.vFactor[t] = my_fac;
         L.vCentre[t] = mine.z + kCentre * mine.s;
         if (fp == 0) {
           const int sz_word = R::kValueSZ + 8 * (t & 15) + (t >> 4);  // token 16 n + j at word 8 j + n of the field
@@ -759,7 +774,8 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
           vw |= (hi_of(h0) << (4 * i + 3)) | (lo_of(h0) << (4 * i + 1)) | (hi_of(h1) << (4 * i + 2)) | (lo_of(h1) << (4 * i));
         } else {
           const half2_t h = as_h2(two);
-          const uint32_t c0 = (uint32_t)((float)h[0] + kCentre), c1 = (uint32_t)((float)h[1] + kCentre);  // exact
+          const float2 f2 = *reinterpret_cast<const float2*>(&L.vFactor[t]);
+          const uint32_t c0 = (uint32_t)((float)h[0] * f2.x + kCentre), c1 = (uint32_t)((float)h[1] * f2.y + kCentre);  // exact
           const uint32_t x0 = c0 >> 2, x1 = c1 >> 2, y0 = c0 & 3u, y1 = c1 & 3u;
           vw |= (((x0 >> 1) ^ 1u) << (4 * i + 3)) | ((((x0 >> 1) ^ x0 ^ 1u) & 1u) << (4 * i + 1)) |
                 (((x1 >> 1) ^ 1u) << (4 * i + 2)) | ((((x1 >> 1) ^ x1 ^ 1u) & 1u) << (4 * i));

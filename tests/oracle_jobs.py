@@ -25,7 +25,7 @@ def sha(a):
 
 
 def run_job(job):
-    """job: dict(cfg, b, g, n, nq, H_q, H_kv, step, R) -> dict of references (see the module docstring)."""
+    """job: dict(cfg, b, g, n, nq, H_q, H_kv, step, R[, bits]) -> dict of references (see the module docstring)."""
     if ROOT not in sys.path:
         sys.path.insert(0, ROOT)
     import kvlinc_synth as synth
@@ -38,8 +38,9 @@ def run_job(job):
     K, V = synth.keys(cfg, b, g, n), synth.values(cfg, b, g, n)
     Wk, Wq = synth.adapters_k(cfg, H_kv)[g], synth.adapters_q(cfg, H_q)
     q = synth.queries(cfg, b, H_q, job["step"])
-    ref = o_cache.build_cache(K, V, nq, Wk=Wk)
-    rec = o_layout.pack_records(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"], ref["v_scale"], ref["v_zero"])
+    bits = job.get("bits", 2)
+    ref = o_cache.build_cache(K, V, nq, Wk=Wk, bits=bits)
+    rec = (o_layout.pack_records if bits == 2 else o_layout.pack_records4)(ref["k_codes"], ref["v_codes"], ref["k_scale"], ref["k_zero"], ref["v_scale"], ref["v_zero"])
     y = np.stack([o_attn.decode(q[h], ref, Wq[h]) for h in range(g * gq, (g + 1) * gq)])
     return dict(rec_sha=sha(rec), kres_sha=sha(ref["k_res"].view(np.uint16)),
                 vres_sha=sha(ref["v_res"].view(np.uint16)),  # the live window rows [n_res, 128], oldest first

@@ -61,8 +61,8 @@ def _fill(cfg_id, B, H_kv, T, lengths, pairs, seed):
     return Kd, Vd
 
 
-def _jobs(cfg_id, pairs, lengths, n_quant, H_q, H_kv, step, R=128):
-    return [dict(cfg=cfg_id, b=int(b), g=int(g), n=int(lengths[b]), nq=int(n_quant[b]), H_q=H_q, H_kv=H_kv, step=step, R=R)
+def _jobs(cfg_id, pairs, lengths, n_quant, H_q, H_kv, step, R=128, bits=2):
+    return [dict(cfg=cfg_id, b=int(b), g=int(g), n=int(lengths[b]), nq=int(n_quant[b]), H_q=H_q, H_kv=H_kv, step=step, R=R, bits=bits)
             for (b, g) in pairs]
 
 
@@ -92,7 +92,7 @@ def _compare(cache, pairs, refs, lengths, n_quant, n_res, out, cfg_id, H_q, H_kv
     return tl.check_outputs(out, want)
 
 
-def _run_bulk_config(kv, cfg_id, pairs):
+def _run_bulk_config(kv, cfg_id, pairs, bits=2):
     import torch
     cfg = synth.CONFIGS[cfg_id]
     B, H_q, H_kv, n = cfg["B"], cfg["H_q"], cfg["H_kv"], cfg["n"]
@@ -100,10 +100,10 @@ def _run_bulk_config(kv, cfg_id, pairs):
     print("  [case] config %d %s B=%d heads %d/%d context %d, %d of %d pairs compared"
           % (cfg_id, cfg["name"], B, H_q, H_kv, n, len(pairs), B * H_kv), flush=True)
     t0 = time.time()
-    jobs = _jobs(cfg_id, pairs, lengths, [n - 128] * B, H_q, H_kv, 0)
+    jobs = _jobs(cfg_id, pairs, lengths, [n - 128] * B, H_q, H_kv, 0, bits=bits)
     Wq, Wk = synth.adapters_q(cfg_id, H_q), synth.adapters_k(cfg_id, H_kv)
     Kd, Vd = _fill(cfg_id, B, H_kv, n, lengths, pairs, seed=cfg_id)
-    cache = kv.KVLincCache(B, H_q, H_kv, n + 256, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache = kv.KVLincCache(B, H_q, H_kv, n + 256, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), bits=bits)
     cache.append(Kd, Vd)
     del Kd, Vd
     q = tl.gen_q(cfg_id, B, H_q)
@@ -130,6 +130,12 @@ def _all_pairs(B, H_kv):
 
 def test_config2_llama3_8b_batch16_ctx8k(kv):
     _run_bulk_config(kv, 2, _all_pairs(16, 8))
+
+
+def test_config2_with_four_bit_codes(kv):
+    """The workload the metric is quoted on, with 4-bit codes (Eq. 1 at N = 4), in the launch configuration the
+    benchmark's 4-bit variant times; a quarter of the (sequence, kv head) pairs against the oracle."""
+    _run_bulk_config(kv, 2, [(b, g) for b in range(16) for g in range(8) if (b + g) % 4 == 0], bits=4)
 
 
 def test_config3_single_sequence_ctx128k(kv):

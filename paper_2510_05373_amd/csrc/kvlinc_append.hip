@@ -43,6 +43,9 @@ struct Lds {
   float red[kWaves][kRank / 2];
   int light[kListCap], heavy[kListCap];
   int n_light, n_heavy, last_flag;
+  // one-token append: the item that thread w looked at is a light one whose new row wave w has read ahead; the
+  // sequence's counters as that thread read them
+  int ahead[kWaves], ahead_nq[kWaves], ahead_nr[kWaves], ahead_n[kWaves];
 };
 
 __device__ inline bool nonfinite_bits(half_t x) {
@@ -185,10 +188,11 @@ __device__ inline bool nonfinite_pair(uint32_t w) { return ((w & 0x7C00u) == 0x7
 // One wave: raw key and rotated value of one new token into its window slot (values live 4 slots per channel: slot u,
 // channel ch at [u / 4][ch][u % 4]).  Nothing of a row with a non-finite key or rotated value is stored; returns
 // whether the row was such a row.
-__device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __restrict__ v_win, int slot,
-                                        const half_t* __restrict__ ks, const half_t* __restrict__ vs, int lane) {
-  const uint32_t kk = *reinterpret_cast<const uint32_t*>(ks + 2 * lane);
-  float x0 = (float)vs[2 * lane], x1 = (float)vs[2 * lane + 1];
+// (kk, vv: the lane's two elements of the new key and value row)
+__device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __restrict__ v_win, int slot, uint32_t kk,
+                                        uint32_t vv, int lane) {
+  const half2_t v2 = as_h2(vv);
+  float x0 = (float)v2[0], x1 = (float)v2[1];
   fwht128_wave(x0, x1, lane);
   const half_t r0 = (half_t)x0, r1 = (half_t)x1;
   const bool mine = nonfinite_pair(kk) || nonfinite_bits(r0) || nonfinite_bits(r1);
@@ -197,6 +201,11 @@ __device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __re
   v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane) * 4 + (slot & 3)] = r0;
   v_win[((long long)(slot >> 2) * kHeadDim + 2 * lane + 1) * 4 + (slot & 3)] = r1;
   return false;
+}
+__device__ inline bool store_window_row(half_t* __restrict__ k_win, half_t* __restrict__ v_win, int slot,
+                                        const half_t* __restrict__ ks, const half_t* __restrict__ vs, int lane) {
+  return store_window_row(k_win, v_win, slot, *reinterpret_cast<const uint32_t*>(ks + 2 * lane),
+                          *reinterpret_cast<const uint32_t*>(vs + 2 * lane), lane);
 }
 
 // One-token append: is the new row of any kv head of sequence b non-finite (key) or beyond fp16 once rotated (value)?
@@ -260,12 +269,16 @@ __device__ inline Counters read_counters(const kvlinc_cache& c, int b, const int
 // An append that quantizes nothing: one wave stores the new rows of one (sequence, kv head) behind the window's
 // tokens.  The slots are dead storage until the counters advance, and they do not advance if any head of the sequence
 // votes against.
+// known: the sequence's counters as read before, and the lane's elements of the pair's (only) new row, read ahead into
+// row_k, row_v (one-token append).
 template <bool SLIDING>
 __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __restrict__ k_new,
                                   const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
-                                  int n_chunks, int lane) {
+                                  int n_chunks, int lane, const Counters* known = nullptr, uint32_t row_k = 0,
+                                  uint32_t row_v = 0) {
   const int b = p / c.H_kv;
-  const Counters s = read_counters(c, b, n_new, T, keep);
+  const bool have_row = known != nullptr;
+  const Counters s = have_row ? *known : read_counters(c, b, n_new, T, keep);
   half_t* k_win = reinterpret_cast<half_t*>(c.k_res) + (long long)p * c.R * kHeadDim;
   half_t* v_win = reinterpret_cast<half_t*>(c.v_res) + (long long)p * c.R * kHeadDim;
   const half_t* k_src = k_new + (long long)p * T * kHeadDim;
@@ -277,8 +290,12 @@ __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __
     if (T == 1) row_bad = __builtin_amdgcn_ballot_w64(new_rows_of_all_heads_bad(c, b, p % c.H_kv, k_new, v_new, lane, 0, 1)) != 0;
     else row_bad = scan_flag(c, b);  // raised by the scan launch
   }
-  for (int i = 0; i < s.n && !row_bad; ++i)
-    row_bad |= store_window_row(k_win, v_win, s.nr + i, k_src + (long long)i * kHeadDim, v_src + (long long)i * kHeadDim, lane);
+  if (have_row) {
+    if (s.n > 0 && !row_bad) row_bad = store_window_row(k_win, v_win, s.nr, row_k, row_v, lane);
+  } else {
+    for (int i = 0; i < s.n && !row_bad; ++i)
+      row_bad |= store_window_row(k_win, v_win, s.nr + i, k_src + (long long)i * kHeadDim, v_src + (long long)i * kHeadDim, lane);
+  }
   if (lane == 0) {
     if (row_bad) atomicOr(c.status, KVLINC_ST_NONFINITE);
     bool clean;
@@ -411,10 +428,10 @@ __device__ __forceinline__ uint32_t lo_of(uint32_t h16) { return (h16 >> 9) & 1u
 template <bool SLIDING, int BITS>
 __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t* __restrict__ k_new,
                            const half_t* __restrict__ v_new, const int32_t* __restrict__ n_new, int T, int keep,
-                           int n_chunks) {
+                           int n_chunks, int tid) {
   using R = Rec<BITS>;
   constexpr float kCentre = R::kCentre;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = tid >> 6;
   const int ck = item % n_chunks, fp = (item / n_chunks) % kParts, p = item / (n_chunks * kParts);
   const int b = p / c.H_kv, g = p % c.H_kv;
   const long long bh = p;
@@ -1035,24 +1052,40 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
   extern __shared__ __align__(16) unsigned char lds_raw[];
   Lds& L = *reinterpret_cast<Lds*>(lds_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long long n_pairs = (long long)c.B * c.H_kv;
-  const int owners = kParts * n_chunks;  // per (sequence, kv head)
-  const long long n_items = (long long)owners * 8 * ((n_pairs + 7) / 8);
-  const long long G = gridDim.x;
+  // (32-bit item arithmetic: at most 2^24 pairs, and more than two owners per pair only below 64 pairs)
+  const uint32_t n_pairs = (uint32_t)c.B * (uint32_t)c.H_kv;
+  const uint32_t owners = kParts * n_chunks;  // per (sequence, kv head)
+  const uint32_t n_items = owners * 8u * ((n_pairs + 7u) / 8u);
+  const uint32_t G = gridDim.x;
 
-  for (long long k0 = 0; k0 * G < n_items; k0 += kListCap) {
+  for (uint32_t k0 = 0; k0 * G < n_items; k0 += kListCap) {
     if (tid == 0) {
       L.n_light = 0;
       L.n_heavy = 0;
     }
+    if (tid < kWaves) L.ahead[tid] = 0;
     __syncthreads();
+    // One-token append: wave w requests the new row of the pair of the item that thread w looks at in the first round
+    // while the sequence's counters are on their way (most such appends only store that row into the window).  The row
+    // goes straight to LDS (this wave's row of the reduction buffer, unused at this point), 4 bytes per lane.  (A
+    // one-token append has two owners per pair and at most 2^25 items.)
+    int pre_p = -1;
+    if (T == 1 && k0 == 0 && (uint32_t)wave * G + blockIdx.x < n_items) {
+      const uint32_t it = (uint32_t)wave * G + blockIdx.x;
+      const uint32_t p = (it >> 4) * 8u + (it & 7u);
+      if (((it >> 3) & 1u) == 0u && p < n_pairs) {
+        pre_p = (int)p;
+        __builtin_amdgcn_global_load_lds(k_new + (long long)p * kHeadDim + 2 * lane, &L.red[wave][0], 4, 0, 0);
+        __builtin_amdgcn_global_load_lds(v_new + (long long)p * kHeadDim + 2 * lane, &L.red[wave][64], 4, 0, 0);
+      }
+    }
     // every thread looks at one item: what needs a wave or the workgroup is listed, the rest is counted in at once
-    const long long it = (k0 + tid) * G + blockIdx.x;
+    const uint32_t it = (k0 + tid) * G + blockIdx.x;
     if (it < n_items) {
       const int own = (int)((it >> 3) % owners);  // (part, chunk): part = own / n_chunks, chunk = own % n_chunks
-      const long long p = (it / (8 * owners)) * 8 + (it & 7);
+      const uint32_t p = (it / (8u * owners)) * 8u + (it & 7u);
       if (p < n_pairs) {
-        const int b = (int)(p / c.H_kv);
+        const int b = (int)(p / (uint32_t)c.H_kv);
         const Counters s = read_counters(c, b, n_new, T, keep);
         if (s.plan.err || s.n == 0) {
           if (s.plan.err && own == 0) atomicOr(c.status, s.plan.err);
@@ -1060,21 +1093,41 @@ __global__ __launch_bounds__(kThreads) void append_flush_kernel(kvlinc_cache c, 
           if (arrive(c, b, n_chunks, s.plan.err != 0, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
         } else if (s.plan.n_groups == 0) {
           if (own == 0) {
-            L.light[atomicAdd(&L.n_light, 1)] = (int)p;
+            if (T == 1 && k0 == 0 && tid < kWaves) {  // wave `tid` holds the row
+              L.ahead[tid] = 1;
+              L.ahead_nq[tid] = s.nq;
+              L.ahead_nr[tid] = s.nr;
+              L.ahead_n[tid] = s.n;
+            } else {
+              L.light[atomicAdd(&L.n_light, 1)] = (int)p;
+            }
           } else {
             bool clean;
             if (arrive(c, b, n_chunks, false, &clean)) finish(c, b, s.nq, s.n, s.plan, clean);
           }
         } else {
-          L.heavy[atomicAdd(&L.n_heavy, 1)] = (int)p * owners + own;
+          L.heavy[atomicAdd(&L.n_heavy, 1)] = (int)(p * owners) + own;
         }
       }
     }
     __syncthreads();
     const int n_light = L.n_light, n_heavy = L.n_heavy;
+    if (L.ahead[wave] != 0) {  // (the barrier has waited for the row)
+      Counters s;
+      s.nq = L.ahead_nq[wave];
+      s.nr = L.ahead_nr[wave];
+      s.n = L.ahead_n[wave];
+      s.plan = plan_append(s.nq, s.nr, s.n, c.R, keep, c.max_groups);
+      light_item<SLIDING>(c, pre_p, k_new, v_new, n_new, T, keep, n_chunks, lane, &s,
+                          __builtin_bit_cast(uint32_t, L.red[wave][lane]), __builtin_bit_cast(uint32_t, L.red[wave][64 + lane]));
+    }
     for (int i = wave; i < n_light; i += kThreads / 64) light_item<SLIDING>(c, L.light[i], k_new, v_new, n_new, T, keep, n_chunks, lane);
     for (int i = 0; i < n_heavy; ++i) {
-      flush_item<SLIDING, BITS>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep, n_chunks);
+      // (the thread index is made opaque here so that none of the flush's address arithmetic is hoisted to the top of
+      // the kernel, where every launch -- most of them flush nothing -- would pay for it)
+      int tid_here = tid;
+      asm volatile("" : "+v"(tid_here));
+      flush_item<SLIDING, BITS>(c, L, L.heavy[i], k_new, v_new, n_new, T, keep, n_chunks, tid_here);
       __syncthreads();
     }
     __syncthreads();

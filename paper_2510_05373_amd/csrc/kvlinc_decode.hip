@@ -616,10 +616,11 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
       sreg[hh][fs] = *reinterpret_cast<const uint2*>(tiles + state_tile(r64, hh, fs0 + fs) + 4 * lane);
   const float4 p4 = *reinterpret_cast<const float4*>(c.P + (long long)bh_mine * kRank + 128 * hs + fpart + 4 * fblk);
   for (int hb = 0; hb < n_head_blocks; ++hb) {
-    // ---- phase 1: this wave's head, all sequences ----
-    {
+    // ---- phase 1: this wave's head, all sequences (a wave whose head does not exist leaves its logits as they are:
+    // phase 2 forms that head's row from them, isolated from the others, and stores nothing of it) ----
+    if (hb * 4 + wave < gq) {
       const int h = hb * 4 + wave;
-      const int hc = h < gq ? h : gq - 1;
+      const int hc = h;
       const int b_row = b_first + (j < n_seq ? j : n_seq - 1);  // row j of A = sequence j
       const half_t* qrow = q + ((long long)b_row * c.H_q + g * gq + hc) * kHeadDim + 4 * blk;
       const half_t* W0 = Wq + (((long long)g * gq + hc) * 2 + hs) * kHeadDim * (kRank / 2) + (long long)j * (kRank / 2) +

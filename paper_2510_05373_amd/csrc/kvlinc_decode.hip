@@ -594,6 +594,12 @@ __device__ __forceinline__ float quadgroup_allsum(float v) {
 }
 
 // sLogit: [kCorrSeqs][4][kPartFeat] floats of LDS.
+// FEW_HEADS: fewer than 4 query heads per kv head (one head block).  The waves whose head does not exist then skip
+// phase 1 and leave their logits as they are: phase 2 forms that head's row from them, isolated from the others, and
+// stores nothing of it.  (A variant of its own, down to the kernel: with the test in the common code the compiler no
+// longer staggers the loads of the two phases, and a second copy of this function in one kernel costs that kernel
+// registers; either way the launches with 4 or more heads lose 3 to 4 % of their time.)
+template <bool FEW_HEADS>
 __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, const half_t* __restrict__ q,
                                                      float* __restrict__ corr, int gq, int g, int r, int b_first,
                                                      int n_seq, int n_head_blocks, int lane, int wave, float* sLogit) {
@@ -616,11 +622,10 @@ __device__ __forceinline__ void correction_workgroup(const kvlinc_cache& c, cons
       sreg[hh][fs] = *reinterpret_cast<const uint2*>(tiles + state_tile(r64, hh, fs0 + fs) + 4 * lane);
   const float4 p4 = *reinterpret_cast<const float4*>(c.P + (long long)bh_mine * kRank + 128 * hs + fpart + 4 * fblk);
   for (int hb = 0; hb < n_head_blocks; ++hb) {
-    // ---- phase 1: this wave's head, all sequences (a wave whose head does not exist leaves its logits as they are:
-    // phase 2 forms that head's row from them, isolated from the others, and stores nothing of it) ----
-    if (hb * 4 + wave < gq) {
+    // ---- phase 1: this wave's head, all sequences ----
+    if (!FEW_HEADS || wave < gq) {
       const int h = hb * 4 + wave;
-      const int hc = h;
+      const int hc = h < gq ? h : gq - 1;
       const int b_row = b_first + (j < n_seq ? j : n_seq - 1);  // row j of A = sequence j
       const half_t* qrow = q + ((long long)b_row * c.H_q + g * gq + hc) * kHeadDim + 4 * blk;
       const half_t* W0 = Wq + (((long long)g * gq + hc) * 2 + hs) * kHeadDim * (kRank / 2) + (long long)j * (kRank / 2) +
@@ -839,7 +844,8 @@ __device__ __forceinline__ bool arrive(int* counter, int expected, int* sFlag) {
 // SLIDING: the variant with the sliding value window (KVLINC_FLAG_SLIDING_VALUES) is a kernel of its own, so that the
 // default one carries none of its code.
 // BITS: so is the one for caches with 4-bit codes (it holds twice the tile words in registers).
-template <int NB, bool SLIDING = false, int BITS = 2>
+// FEW_HEADS: and the one for fewer than 4 query heads per kv head (see correction_workgroup).
+template <int NB, bool SLIDING = false, int BITS = 2, bool FEW_HEADS = false>
 __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void decode_main_kernel(kvlinc_cache c, const half_t* __restrict__ q,
                                                                    float* __restrict__ part, float* __restrict__ corr,
                                                                    half_t* __restrict__ out, int max_splits,
@@ -890,7 +896,7 @@ __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void d
     const int n_seq = min(kCorrSeqs, c.B - b_first);
     // A sequence without quantized tokens has S = P = 0 (the states only change at a flush), so its parts come out
     // as zero without looking at n_quant.
-    correction_workgroup(c, q, corr, gq, g, r, b_first, n_seq, NB, lane, wave, lds);
+    correction_workgroup<FEW_HEADS>(c, q, corr, gq, g, r, b_first, n_seq, NB, lane, wave, lds);
     // count this workgroup in at each of its sequences; merge those it completes
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -1199,10 +1205,12 @@ int launch_decode(const kvlinc_cache& c, const kvlinc_half* q, kvlinc_half* out,
   const int corr_first = sp.corr_first;
   const bool sliding = (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0;
   void (*kernel)(kvlinc_cache, const half_t*, float*, float*, half_t*, int, int, int, int) =
-      c.bits == 4 ? (gq <= 4 ? (sliding ? decode_main_kernel<1, true, 4> : decode_main_kernel<1, false, 4>)
-                             : (sliding ? decode_main_kernel<2, true, 4> : decode_main_kernel<2, false, 4>))
-                  : (gq <= 4 ? (sliding ? decode_main_kernel<1, true> : decode_main_kernel<1, false>)
-                             : (sliding ? decode_main_kernel<2, true> : decode_main_kernel<2, false>));
+      c.bits == 4 ? (gq > 4   ? (sliding ? decode_main_kernel<2, true, 4> : decode_main_kernel<2, false, 4>)
+                     : gq < 4 ? (sliding ? decode_main_kernel<1, true, 4, true> : decode_main_kernel<1, false, 4, true>)
+                              : (sliding ? decode_main_kernel<1, true, 4> : decode_main_kernel<1, false, 4>))
+                  : (gq > 4   ? (sliding ? decode_main_kernel<2, true> : decode_main_kernel<2, false>)
+                     : gq < 4 ? (sliding ? decode_main_kernel<1, true, 2, true> : decode_main_kernel<1, false, 2, true>)
+                              : (sliding ? decode_main_kernel<1, true> : decode_main_kernel<1, false>));
   if (start != nullptr)  // timestamps of the dispatch itself, no extra packets on the stream
     hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, start, stop, 0, c, qq, part, corr, oo, sp.most, sp.avg, gq, corr_first);
   else

@@ -1,5 +1,5 @@
 """GPU parity on seeded random shapes: batch, head counts, lengths (with the window boundaries mixed in), a bulk
-prefix followed by a few one-token appends, correction on or off, and the three kinds of launch bound.  Records, window,
+prefix followed by a few one-token appends, correction on or off, 2-bit and 4-bit codes, and the three kinds of launch bound.  Records, window,
 states and outputs of two random (sequence, KV head) pairs per case are compared with the oracle."""
 import numpy as np
 import pytest
@@ -18,8 +18,8 @@ def kv():
     return kvmod
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2])
-def test_random_shapes(kv, seed):
+@pytest.mark.parametrize("seed,bits", [(0, 2), (1, 2), (2, 2), (3, 4), (4, 4)])
+def test_random_shapes(kv, seed, bits):
     import torch
     rng = np.random.default_rng(1000 + seed)
     for it in range(12):
@@ -40,7 +40,7 @@ def test_random_shapes(kv, seed):
         Wq = synth.adapters_q(cfg, H_q) if corr else None
         Wk = synth.adapters_k(cfg, H_kv) if corr else None
         cache = kv.KVLincCache(B, H_q, H_kv, max(lengths) + int(rng.integers(1, 600)),
-                               Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk))
+                               Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk), bits=bits)
         tail = int(rng.integers(0, 4))  # the last `tail` tokens arrive one at a time
         pre = [max(0, n - tail) for n in lengths]
         Kd, Vd = tl.to_dev(K), tl.to_dev(V)
@@ -69,6 +69,6 @@ def test_random_shapes(kv, seed):
             tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]),
                                          int(n_res[b]), None if Wk is None else Wk[g])
         if pairs:
-            want = tl.oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq, Wk)
+            want = tl.oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq, Wk, bits=bits)
             tl.check_outputs(out, want)
         assert int(cache.split_done.abs().sum().item()) == 0

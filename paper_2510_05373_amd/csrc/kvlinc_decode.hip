@@ -425,34 +425,66 @@ __device__ __forceinline__ void pv_phase(const ValueRegs<BITS>& g, const float (
 
 // Sliding value window (Sec. 4.1, setup: the newest 128 tokens in full precision): the tokens j >= from of the newest
 // group still have their fp16 rotated values in the window slots j.  Their share of E V is formed here from those values
-// in plain binary32 arithmetic -- at most 127 tokens per (sequence, kv head) and step, by the one wave that has the
-// newest group -- and goes to the spare row of the accumulators.  Lane (head hd, column jd) takes the channels 16 n + jd.
+// by the one wave that has the newest group, on v_mfma_f32_4x4x4_16B_f16 as in window_half: rows = the 4 heads of a head
+// block, columns = 64 channels (lane = channel), k = 4 window slots, the probabilities (binary16, through LDS) broadcast
+// from one lane quad per block of 4 slots.  The result goes to the spare row of the accumulators through `out`, this
+// wave's [NB * 4][128] slice of the combine buffer.
 template <int NB>
 __device__ __forceinline__ void pv_window_tail(const half_t* __restrict__ v_win, const float (&sc)[NB][8], int from,
-                                               const Roles& lr, WaveState<NB>& st, int lane) {
-  float* pbuf = reinterpret_cast<float*>(lr.ex_pv);  // [4 heads][128 tokens]
+                                               const Roles& lr, WaveState<NB>& st, int lane, float (*out)[kHeadDim]) {
+  half_t* pb = reinterpret_cast<half_t*>(lr.ex_pv);  // [NB * 4 heads][128 tokens]
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int j = 16 * n + lr.jd;
-      pbuf[kGroup * lr.hd + j] = j >= from ? __builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]) : 0.0f;
+      pb[(nb * 4 + lr.hd) * kGroup + j] = j >= from ? (half_t)__builtin_amdgcn_exp2f(sc[nb][n] - st.m[nb]) : (half_t)0.0f;
     }
-    lds_order();
-    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int q = from >> 2; q < kGroup / 4; ++q) {  // 4 window slots per step: [slot / 4][channel][slot % 4]
-      const float4 p4 = *reinterpret_cast<const float4*>(pbuf + kGroup * lr.hd + 4 * q);
+  lds_order();
+  const int quad = lane >> 2, hrow = lane & 3;
+  half4_t A[NB][2];
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
-        const uint2 w = *reinterpret_cast<const uint2*>(v_win + ((long long)q * kHeadDim + 16 * n + lr.jd) * 4);
-        const half2_t lo = as_h2(w.x), hi = as_h2(w.y);
-        a[n] = fmaf(p4.x, (float)lo[0], fmaf(p4.y, (float)lo[1], fmaf(p4.z, (float)hi[0], fmaf(p4.w, (float)hi[1], a[n]))));
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) A[nb][hf] = *reinterpret_cast<const half4_t*>(pb + (nb * 4 + hrow) * kGroup + 64 * hf + 4 * quad);
+  const uint2* vb = reinterpret_cast<const uint2*>(v_win);  // [slot / 4][channel] -> 4 slots
+  const int first = from >> 2;                              // blocks of 4 slots below it hold no such token
+  float4_t acc[NB][2];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) acc[nb][0] = acc[nb][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    uint2 vx[2][16];
+#pragma unroll
+    for (int bq = 0; bq < 16; ++bq)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const int blk = 16 * hf + bq;
+        vx[ch][bq] = blk >= first ? vb[(long long)blk * kHeadDim + 64 * ch + lane] : make_uint2(0, 0);
       }
-    }
 #pragma unroll
-    for (int n = 0; n < 8; ++n) st.acc[nb][n][3] += a[n];
-    lds_order();
+    for (int bq = 0; bq < 16; ++bq)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const half4_t bop = as_h4(vx[ch][bq].x, vx[ch][bq].y);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb][ch] = mfma_bcast(A[nb][hf], bop, acc[nb][ch], bq);
+      }
   }
+  // (lane = channel, registers = heads) -> (row = head, lane = channel % 16, channel block n)
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      out[nb * 4 + h][lane] = acc[nb][0][h];
+      out[nb * 4 + h][64 + lane] = acc[nb][1][h];
+    }
+  lds_order();
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.acc[nb][n][3] += out[nb * 4 + lr.hd][16 * n + lr.jd];
+  lds_order();
   // the spare term row of every head of this exchange region reads as zero again
   uint32_t* ex = reinterpret_cast<uint32_t*>(lr.ex_pv);
   for (int i = lane; i < 4 * 32; i += 64) ex[(i >> 5) * kExHead + 96 + (i & 31)] = 0u;
@@ -1064,7 +1096,7 @@ __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void d
       qk_phase<NB, BITS>(kr, kGroup, qa, qh, lr, sc);
       update_reference<NB>(sc, st);
       pv_phase<NB, BITS, true>(vr, sc, lr, st, nr);
-      pv_window_tail<NB>(reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim, sc, nr, lr, st, lane);
+      pv_window_tail<NB>(reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim, sc, nr, lr, st, lane, sAcc[wave]);
     }
   }
 

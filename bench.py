@@ -137,7 +137,7 @@ def main():
         args.no_cpu_baseline = True  # the oracle leg (timing and parity sample) belongs to the default path
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence / "
-              "KV head without communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "KV head without communication)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -855,3 +855,58 @@ def test_four_bit_codes_static_window_and_sliding_values(kv):
             vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
             cache.append(kn, vn)
     assert int(cache.status.item()) == 0
+
+
+def test_a_step_replayed_from_a_hip_graph(kv):
+    """One step -- kvlinc_append_quantize (one token) + kvlinc_decode_attention_noalloc -- captured into a HIP graph and
+    replayed 140 times across a window flush, with the program's own eager copies and synchronisations between the
+    replays; every replay gives the bits of an eager twin cache that takes the same tokens through the workspace entry
+    point.  (The library records kernels only: no memset nodes, no allocation.)"""
+    import torch
+    B, H_q, H_kv = 3, 8, 2
+    pre = [300, 127, 64]
+    steps = 140
+    total = [p + steps for p in pre]
+    K, V = tl.gen_kv(51, B, H_kv, total)
+    Wq, Wk = tl.to_dev(synth.adapters_q(51, H_q)), tl.to_dev(synth.adapters_k(51, H_kv))
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    n0 = tl.to_dev(np.asarray(pre, dtype=np.int32))
+    caches = [kv.KVLincCache(B, H_q, H_kv, 1024, Wq=Wq, Wk=Wk) for _ in range(2)]
+    for c in caches:
+        c.append(Kd[:, :, :max(pre)].contiguous(), Vd[:, :, :max(pre)].contiguous(), n_new=n0)
+    graphed, eager = caches
+    k_in = torch.zeros(B, H_kv, 1, 128, dtype=torch.float16, device="cuda")
+    v_in = torch.zeros_like(k_in)
+    q_in = torch.zeros(B, H_q, 128, dtype=torch.float16, device="cuda")
+    out_g = torch.zeros_like(q_in)
+    # the static buffer's address is looked up on the first call on a device: not inside a capture
+    assert kv.kvlinc_decode_attention_noalloc(graphed, q_in, out_g, max_context=1024) == kv.KVLINC_OK
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            assert kv.kvlinc_append_quantize(graphed, k_in, v_in, stream=side) == kv.KVLINC_OK
+            assert kv.kvlinc_decode_attention_noalloc(graphed, q_in, out_g, max_context=1024, stream=side) == kv.KVLINC_OK
+    torch.cuda.synchronize()
+    # the capture itself ran nothing: the caches still agree
+    assert torch.equal(graphed.n_res, eager.n_res) and torch.equal(graphed.n_quant, eager.n_quant)
+    q_all = tl.to_dev(np.stack([tl.gen_q(51, B, H_q, step=s) for s in range(steps)]))
+    for s in range(steps):
+        kn = torch.stack([Kd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+        vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+        k_in.copy_(kn); v_in.copy_(vn); q_in.copy_(q_all[s])
+        torch.cuda.synchronize()
+        g.replay()
+        eager.append(kn, vn)
+        want = eager.decode(q_all[s], max_context=1024)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, want), s
+    assert int(graphed.status.item()) == 0 and int(graphed.split_done.abs().sum().item()) == 0
+    for name in ("groups", "k_res", "n_quant", "n_res", "S", "P", "S16"):
+        assert torch.equal(getattr(graphed, name), getattr(eager, name)), name
+    lengths = [p + steps for p in pre]
+    want = tl.oracle_decode(K, V, q_all[steps - 1].cpu().numpy(), lengths, graphed.n_quant.cpu().numpy(), [(0, 1), (2, 0)], H_q, H_kv,
+                            synth.adapters_q(51, H_q), synth.adapters_k(51, H_kv))
+    tl.check_outputs(out_g.cpu().numpy(), want)

@@ -138,6 +138,12 @@ def test_config2_with_four_bit_codes(kv):
     _run_bulk_config(kv, 2, [(b, g) for b in range(16) for g in range(8) if (b + g) % 4 == 0], bits=4)
 
 
+def test_config4_with_four_bit_codes(kv):
+    """Seven query heads per KV head (two head blocks per wave) at 4 bits and context 32768: 6 pairs spread over the
+    batch against the oracle."""
+    _run_bulk_config(kv, 4, [(0, 0), (3, 1), (4, 2), (17, 3), (30, 0), (31, 3)], bits=4)
+
+
 def test_config3_single_sequence_ctx128k(kv):
     _run_bulk_config(kv, 3, _all_pairs(1, 8))
 

@@ -24,7 +24,11 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 WORKLOAD = 2  # index into kvlinc_synth.CONFIGS
-EVENT_STRIDE = 4  # every 4th decode launch of the timed region is timed with dispatch events
+# Decode launches of the timed region that carry dispatch events: 4 to 16 of them, evenly spaced.  (A launch with
+# events costs the stream about 10 us over a plain one, so timing every 4th launch of 256 took 8 % off the throughput.)
+def timed_steps(K):
+    n = max(4, min(16, K // 16))
+    return sorted(set(min(K - 1, int((i + 0.5) * K / n)) for i in range(n))) if K > 0 else []
 KERNEL_SOURCES = ("kvlinc_decode.hip", "kvlinc_mfma.h", "kvlinc_internal.h")  # what the decode kernel is compiled from
 
 
@@ -160,6 +164,8 @@ def main():
     else:
         base_len = np.full(B, cfg["n"], dtype=np.int64)
     n0 = int(base_len.max())
+    pad = 0 if wl == 5 else 128  # equal lengths: the layers start between n0 and n0 + 127 tokens (see below)
+    n_hist = n0 + pad
 
     # ---- inputs: one seeded K/V history copied into L distinct caches.  For the default workload it is generated
     # on the host (the oracle leg needs it); the other workloads take device-generated N(0, 1) data.
@@ -167,33 +173,37 @@ def main():
     Wq_h, Wk_h = synth.adapters_q(wl, H_q), synth.adapters_k(wl, H_kv)
     Wq, Wk = torch.from_numpy(Wq_h).to(dev), torch.from_numpy(Wk_h).to(dev)
     if wl == WORKLOAD:
-        Kh = np.empty((B, H_kv, n0, 128), dtype=np.float16)
+        Kh = np.empty((B, H_kv, n_hist, 128), dtype=np.float16)
         Vh = np.empty_like(Kh)
         for b in range(B):
             for g in range(H_kv):
-                Kh[b, g] = synth.keys(wl, b, g, n0)
-                Vh[b, g] = synth.values(wl, b, g, n0)
+                Kh[b, g] = synth.keys(wl, b, g, n_hist)
+                Vh[b, g] = synth.values(wl, b, g, n_hist)
         Kd, Vd = torch.from_numpy(Kh).to(dev), torch.from_numpy(Vh).to(dev)
     else:
         g0 = torch.Generator(device=dev)
         g0.manual_seed(synth.BASE_SEED + wl)
-        Kd = torch.empty(B, H_kv, n0, 128, dtype=torch.float16, device=dev)
+        Kd = torch.empty(B, H_kv, n_hist, 128, dtype=torch.float16, device=dev)
         Vd = torch.empty_like(Kd)
         for b in range(B):  # per sequence, to bound the fp32 temporaries
-            Kd[b] = torch.randn(H_kv, n0, 128, device=dev, generator=g0).half()
-            Vd[b] = torch.randn(H_kv, n0, 128, device=dev, generator=g0).half()
+            Kd[b] = torch.randn(H_kv, n_hist, 128, device=dev, generator=g0).half()
+            Vd[b] = torch.randn(H_kv, n_hist, 128, device=dev, generator=g0).half()
     total_steps = W + K_steps
     per_layer = -(-total_steps // L)
-    # Windows flush once per 128 appends.  With equal lengths the layers start a few tokens short of the nominal
-    # context, staggered so that flush steps fall inside the timed region at about their natural rate (here 2 layers
-    # out of 8); ragged lengths are staggered by themselves.
+    # Windows flush once per 128 appends of a layer, i.e. with L layers taking turns some layer flushes every 128
+    # steps on average.  With equal lengths the layers start between the nominal context and 127 tokens above it, with
+    # windows that fill up at evenly spaced steps (128 / L appends apart, in the layer order 0, 4, 1, 5, ...), the
+    # first of them a few steps into the timed region whatever the warm-up: a run of 256 steps has 2 steps with a
+    # flush (its natural rate), a short run has one.  Ragged lengths are staggered by themselves.
     caches, start_len = [], []
     for j in range(L):
-        short = 0
-        if wl != 5 and j % 4 == 0:
-            short = min(n0 - 1, W // L + 3 + (j // 4) * 7)  # its window (full at n0) flushes at append `short`+1
-        n_start = base_len - short
-        c = kv.KVLincCache(B, H_q, H_kv, n0 + per_layer + 256, Wq=Wq, Wk=Wk,
+        if wl != 5:
+            pos = (j % 4) * ((L + 3) // 4) + j // 4                # place of the layer in the order of the flushes
+            short = (W // L + 3 + (128 // L) * pos) % 128          # its window fills up after `short` appends and the
+            n_start = base_len + pad - max(short, 1)               # next append flushes it
+        else:
+            n_start = base_len
+        c = kv.KVLincCache(B, H_q, H_kv, n_hist + per_layer + 256, Wq=Wq, Wk=Wk,
                            state_storage="fp16" if args.variant == "state16" else "fp32",
                            flags={"sliding-values": kv.KVLINC_FLAG_SLIDING_VALUES, "alg1-literal": kv.KVLINC_FLAG_ALG1_LITERAL}.get(args.variant, 0),
                            bits=bits)
@@ -210,7 +220,7 @@ def main():
     v_new = torch.randn(total_steps, B, H_kv, 1, 128, device=dev, generator=gen).half()
     q_all = torch.randn(total_steps, B, H_q, 128, device=dev, generator=gen).half()
     out = torch.empty(B, H_q, 128, dtype=torch.float16, device=dev)
-    max_ctx = n0 + per_layer + 1
+    max_ctx = n_hist + per_layer + 1
     for c in caches:
         c.workspace(max_ctx)
     torch.cuda.synchronize()
@@ -234,7 +244,7 @@ def main():
     torch.cuda.synchronize()
     lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]  # per layer: [B] lengths
 
-    # ---- timed region: exactly K steps.  Every EVENT_STRIDE-th decode launch carries a start and a stop event
+    # ---- timed region: exactly K steps.  A few evenly spaced decode launches (timed_steps) carry a start and a stop event
     # attached to its own dispatch on the launch stream (kvlinc_decode_attention_timed), so the kernel's duration is
     # measured inside the timed region without extra packets between the kernels (such a launch costs the host
     # about 25 us, so timing every launch would make the loop host-bound).
@@ -249,7 +259,7 @@ def main():
         return e
 
     use_events = not args.no_events
-    timed = [s for s in range(K_steps) if s % EVENT_STRIDE == 0] if use_events else []
+    timed = timed_steps(K_steps) if use_events else []
     ev_b = {s: new_event() for s in timed}
     ev_c = {s: new_event() for s in timed}
     f_dec_t = kb.lib.kvlinc_decode_attention_timed
@@ -272,8 +282,10 @@ def main():
     elapsed = t_end - t_start
     tokens = 0
     alg_bytes = []
+    flush_steps = 0  # steps of the timed region whose append flushed the window of at least one sequence
     for s in range(K_steps):
         j = (W + s) % L
+        flush_steps += int(((lens[j] >= 128) & (lens[j] % 128 == 0)).any())
         lens[j] = lens[j] + 1
         n = lens[j]
         tokens += int(n.sum())
@@ -312,8 +324,10 @@ def main():
         "dtype": "u%d codes, f16 operands, f32 accumulate" % bits,
         "data": "synthetic",
         "config": {"workload": cfg["name"] + ("" if args.variant == "default" else " [variant: %s]" % args.variant), "batch": B, "q_heads": H_q, "kv_heads": H_kv, "head_dim": 128,
-                   "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0), "window": 128, "group": 128, "bits": bits, "correction_rank": 256,
+                   "context": n0 if wl != 5 else "%d..%d" % (int(base_len.min()), n0),
+                   "context_of_the_layer_caches": "%d..%d" % (min(int(x.min()) for x in lens), max(int(x.max()) for x in lens)), "window": 128, "group": 128, "bits": bits, "correction_rank": 256,
                    "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
+                   "steps_with_a_window_flush": flush_steps,
                    "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),
                    "launch_loop_cpu_ms_per_step": (t_cpu_done - t_start) / K_steps * 1e3, "setup_s": setup_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",

@@ -347,16 +347,18 @@ __device__ __forceinline__ void qk_phase(const KeyRegs<BITS>& g, int valid, cons
 
 // Reference maximum (Alg. 1 line 8).  Any reference m works as long as 2^(x - m) stays moderate, so the reference of a
 // head is only raised -- with a maximum over the row and a rescale of the accumulated state -- when some score of the
-// group exceeds it by more than kSlack; most groups pay one comparison per register.
+// group exceeds it by more than `slack`; most groups pay one comparison per register.  (The literal form of Alg. 1's
+// last lines adds the correction to sums that are shifted by the TRUE maximum: there the slack is 0, which makes the
+// reference the running maximum itself.)
 constexpr float kSlack = 5.0f;
 template <int NB>
-__device__ __forceinline__ void update_reference(const float (&sc)[NB][8], WaveState<NB>& st) {
+__device__ __forceinline__ void update_reference(const float (&sc)[NB][8], WaveState<NB>& st, float slack) {
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     float mloc = sc[nb][0];
 #pragma unroll
     for (int n = 1; n < 8; ++n) mloc = fmaxf(mloc, sc[nb][n]);
-    if (__builtin_amdgcn_ballot_w64(mloc > st.m[nb] + kSlack) != 0) {
+    if (__builtin_amdgcn_ballot_w64(mloc > st.m[nb] + slack) != 0) {
       const float mnew = fmaxf(st.m[nb], row_allmax(mloc));
       const float f = mnew == -INFINITY ? 1.0f : exp2f(st.m[nb] - mnew);  // 0 when the old reference is -inf
       st.l[nb] *= f;
@@ -1078,6 +1080,7 @@ __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void d
     // that no branch joins between a request and its first use and the waits stay partial.
     // sliding value window: the newest group's tokens from n_res on take their values from the window
     // (the newest group is left to the code below when its last tokens take their values from the window)
+    const float slack = (c.flags & KVLINC_FLAG_ALG1_LITERAL) != 0 ? 0.0f : kSlack;
     const bool sliding = SLIDING && nq % kGroup == 0 && nr < kGroup;
     const int count_plain = sliding ? count - 1 : count;
     while (idx < count_plain) {
@@ -1086,7 +1089,7 @@ __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void d
       float sc[NB][8];
       qk_phase<NB, BITS>(kr, min(kGroup, nq - idx * kGroup), qa, qh, lr, sc);
       load_keys(kr, src, lr);
-      update_reference<NB>(sc, st);
+      update_reference<NB>(sc, st, slack);
       pv_phase<NB, BITS>(vr, sc, lr, st);
       load_values(vr, src, lr);
       idx = nxt;
@@ -1094,7 +1097,7 @@ __global__ __launch_bounds__(kThreads, BITS == 4 ? 2 : (NB == 1 ? 3 : 2)) void d
     if (SLIDING && idx < count) {  // sliding value window: the newest group, whose tokens from n_res on have fp16 values
       float sc[NB][8];
       qk_phase<NB, BITS>(kr, kGroup, qa, qh, lr, sc);
-      update_reference<NB>(sc, st);
+      update_reference<NB>(sc, st, slack);
       pv_phase<NB, BITS, true>(vr, sc, lr, st, nr);
       pv_window_tail<NB>(reinterpret_cast<const half_t*>(c.v_res) + (long long)bh * c.R * kHeadDim, sc, nr, lr, st, lane, sAcc[wave]);
     }

@@ -910,3 +910,46 @@ def test_a_step_replayed_from_a_hip_graph(kv):
     want = tl.oracle_decode(K, V, q_all[steps - 1].cpu().numpy(), lengths, graphed.n_quant.cpu().numpy(), [(0, 1), (2, 0)], H_q, H_kv,
                             synth.adapters_q(51, H_q), synth.adapters_k(51, H_kv))
     tl.check_outputs(out_g.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_all_variants_together(kv, bits):
+    """State stored in 16 bits only, the literal last lines of Alg. 1 and the sliding value window in one cache, at both
+    code widths: a bulk build, then one-token appends across a flush, decoded against the oracle with all three switches
+    (the variants are separate descriptor fields and kernel instantiations; this is the case where they all meet)."""
+    import torch
+    B, H_q, H_kv = 2, 8, 2
+    pre, extra = [390, 140], 140
+    lengths = [p + extra for p in pre]
+    K, V = tl.gen_kv(61, B, H_kv, lengths)
+    Wq, Wk = synth.adapters_q(61, H_q), synth.adapters_k(61, H_kv)
+    flags = kv.KVLINC_FLAG_ALG1_LITERAL | kv.KVLINC_FLAG_SLIDING_VALUES
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), state_storage="fp16", flags=flags, bits=bits)
+    Kd, Vd = tl.to_dev(K), tl.to_dev(V)
+    cache.append(Kd[:, :, :max(pre)].contiguous(), Vd[:, :, :max(pre)].contiguous(), n_new=tl.to_dev(np.asarray(pre, dtype=np.int32)))
+    gq = H_q // H_kv
+    for s in range(extra + 1):
+        cur = [p + s for p in pre]
+        if s in (0, 3, 119, 120, 140):
+            q = tl.gen_q(61, B, H_q, step=s)
+            out = cache.decode(tl.to_dev(q)).cpu().numpy()
+            assert int(cache.status.item()) == 0
+            n_quant, n_res = tl.check_counters(cache, cur)
+            want = {}
+            for b in range(B):
+                first = tl.o_cache.window_split(pre[b])[0]
+                points = list(range(first, int(n_quant[b]) + 1, 128))  # the state was rounded after the build and every flush
+                for g in range(H_kv):
+                    ref = tl.o_cache.build_cache(K[b, g, :cur[b]], V[b, g, :cur[b]], int(n_quant[b]), Wk=Wk[g], bits=bits,
+                                                 state_rounding=points)
+                    for h in range(g * gq, (g + 1) * gq):
+                        want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h], literal_alg1=True, value_window="sliding")
+            tl.check_outputs(out, want)
+        if s < extra:
+            kn = torch.stack([Kd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            vn = torch.stack([Vd[b, :, pre[b] + s] for b in range(B)]).unsqueeze(2).contiguous()
+            cache.append(kn, vn)
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    for b in range(B):
+        for g in range(H_kv):
+            tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), int(n_res[b]), None)

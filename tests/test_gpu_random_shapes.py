@@ -1,5 +1,5 @@
 """GPU parity on seeded random shapes: batch, head counts, lengths (with the window boundaries mixed in), a bulk
-prefix followed by a few one-token appends, correction on or off, 2-bit and 4-bit codes, and the three kinds of launch bound.  Records, window,
+prefix followed by a few one-token appends, correction on or off, 2-bit and 4-bit codes, the variants of the path (literal Alg. 1, sliding value window, 16-bit state) drawn at random, and the three kinds of launch bound.  Records, window,
 states and outputs of two random (sequence, KV head) pairs per case are compared with the oracle."""
 import numpy as np
 import pytest
@@ -18,10 +18,11 @@ def kv():
     return kvmod
 
 
-@pytest.mark.parametrize("seed,bits", [(0, 2), (1, 2), (2, 2), (3, 4), (4, 4)])
+@pytest.mark.parametrize("seed,bits", [(0, 2), (1, 2), (2, 2), (3, 4), (4, 4), (5, 2), (6, 4), (7, 2), (8, 4), (9, 2)])
 def test_random_shapes(kv, seed, bits):
     import torch
     rng = np.random.default_rng(1000 + seed)
+    vrng = np.random.default_rng(5000 + seed)  # the variants of the path, drawn apart from the shapes
     for it in range(12):
         B = int(rng.integers(1, 7))
         H_kv = int(rng.choice([1, 2, 3]))
@@ -34,13 +35,17 @@ def test_random_shapes(kv, seed, bits):
         if max(lengths) == 0:
             lengths[0] = 1
         cfg = 100 * (seed + 1) + it
-        print("  [case] seed %d #%d B=%d heads %d/%d lengths %s" % (seed, it, B, H_q, H_kv, lengths), flush=True)
+        literal, sliding, state16 = (bool(vrng.random() < 0.3) for _ in range(3))
+        flags = (kv.KVLINC_FLAG_ALG1_LITERAL if literal else 0) | (kv.KVLINC_FLAG_SLIDING_VALUES if sliding else 0)
+        print("  [case] seed %d #%d B=%d heads %d/%d lengths %s literal %d sliding %d state16 %d"
+              % (seed, it, B, H_q, H_kv, lengths, literal, sliding, state16), flush=True)
         K, V = tl.gen_kv(cfg, B, H_kv, lengths)
         corr = rng.random() < 0.8
         Wq = synth.adapters_q(cfg, H_q) if corr else None
         Wk = synth.adapters_k(cfg, H_kv) if corr else None
         cache = kv.KVLincCache(B, H_q, H_kv, max(lengths) + int(rng.integers(1, 600)),
-                               Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk), bits=bits)
+                               Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk), bits=bits,
+                               flags=flags, state_storage="fp16" if state16 else "fp32")
         tail = int(rng.integers(0, 4))  # the last `tail` tokens arrive one at a time
         pre = [max(0, n - tail) for n in lengths]
         Kd, Vd = tl.to_dev(K), tl.to_dev(V)
@@ -65,10 +70,19 @@ def test_random_shapes(kv, seed, bits):
                 assert not out[b].any()
         pairs = {(int(rng.integers(0, B)), int(rng.integers(0, H_kv))) for _ in range(2)}
         pairs = [p for p in pairs if lengths[p[0]] > 0]
+        want = {}
         for (b, g) in pairs:
+            # (with the state stored in 16 bits only there is no fp32 S to compare: the output comparison covers it)
             tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]),
-                                         int(n_res[b]), None if Wk is None else Wk[g])
+                                         int(n_res[b]), None if (Wk is None or state16) else Wk[g])
+            # the 16-bit state was rounded at the end of every call that flushed: after the bulk build and after each flush since
+            first = tl.o_cache.window_split(pre[b])[0]
+            points = list(range(first, int(n_quant[b]) + 1, 128)) if (state16 and corr) else None
+            ref = tl.o_cache.build_cache(K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), Wk=None if Wk is None else Wk[g],
+                                         bits=bits, state_rounding=points)
+            for h in range(g * gq, (g + 1) * gq):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h], literal_alg1=literal,
+                                                value_window="sliding" if sliding else "block")
         if pairs:
-            want = tl.oracle_decode(K, V, q, lengths, n_quant, pairs, H_q, H_kv, Wq, Wk, bits=bits)
             tl.check_outputs(out, want)
         assert int(cache.split_done.abs().sum().item()) == 0

@@ -953,3 +953,29 @@ def test_all_variants_together(kv, bits):
     for b in range(B):
         for g in range(H_kv):
             tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), int(n_res[b]), None)
+
+
+@pytest.mark.parametrize("bits,sliding,correction", [(4, True, True), (2, True, False), (4, False, False)])
+def test_long_prompt_build_in_chunks_variants(kv, bits, sliding, correction):
+    """The chunked build of a long prompt (groups shared out over the chip) at 4-bit codes, with the sliding value window
+    (the last arrival stores the newest group's fp16 values) and for a cache without correction states."""
+    B, H_q, H_kv = 2, 8, 2
+    lengths = [8192 + 513, 8192 - 31]
+    K, V = tl.gen_kv(62, B, H_kv, lengths)
+    Wq, Wk = (synth.adapters_q(62, H_q), synth.adapters_k(62, H_kv)) if correction else (None, None)
+    cache = kv.KVLincCache(B, H_q, H_kv, 8192 + 1024, Wq=None if Wq is None else tl.to_dev(Wq), Wk=None if Wk is None else tl.to_dev(Wk),
+                           bits=bits, flags=kv.KVLINC_FLAG_SLIDING_VALUES if sliding else 0)
+    cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
+    assert int(cache.status.item()) == 0
+    n_quant, n_res = tl.check_counters(cache, lengths)
+    q = tl.gen_q(62, B, H_q)
+    out = cache.decode(tl.to_dev(q)).cpu().numpy()
+    want = {}
+    for b in range(B):
+        for g in range(H_kv):
+            ref = tl.check_pair_against_oracle(cache, b, g, K[b, g, :lengths[b]], V[b, g, :lengths[b]], int(n_quant[b]), int(n_res[b]),
+                                               None if Wk is None else Wk[g])
+            for h in range(4 * g, 4 * g + 4):
+                want[(b, h)] = tl.o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h], value_window="sliding" if sliding else "block")
+    tl.check_outputs(out, want)
+    assert int(cache.split_done.abs().sum().item()) == 0

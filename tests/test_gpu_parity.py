@@ -356,9 +356,10 @@ def test_rejected_append_leaves_the_sequence_unchanged(kv, H_kv, bad_head):
     tl.check_outputs(out, want)
 
 
+@pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("log2_gain", [-8, -4, 4, 8])
 @pytest.mark.parametrize("which", ["values", "keys"])
-def test_magnitudes_far_from_one_keep_the_tolerance(kv, which, log2_gain):
+def test_magnitudes_far_from_one_keep_the_tolerance(kv, which, log2_gain, bits):
     """Values (resp. keys) scaled by 2^-8 .. 2^8: the operands of the matrix products carry block exponents, so the
     output stays inside the tolerance whatever the magnitude (relative to the output's own size)."""
     B, H_q, H_kv = 2, 8, 2
@@ -370,13 +371,14 @@ def test_magnitudes_far_from_one_keep_the_tolerance(kv, which, log2_gain):
     else:
         K = (K.astype(np.float32) * gain).astype(np.float16)
     Wq, Wk = synth.adapters_q(33, H_q), synth.adapters_k(33, H_kv)
-    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk))
+    cache = kv.KVLincCache(B, H_q, H_kv, 1024, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), bits=bits)
     cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray(lengths, dtype=np.int32)))
     q = tl.gen_q(33, B, H_q)
     out = cache.decode(tl.to_dev(q)).cpu().numpy().astype(np.float64)
     assert int(cache.status.item()) == 0
     n_quant, n_res = tl.check_counters(cache, lengths)
-    want = tl.oracle_decode(K, V, q, lengths, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk)
+    tl.check_cache_against_oracle(cache, K, V, lengths, _all_pairs(B, H_kv), Wk=Wk)  # (records, window, states at that magnitude)
+    want = tl.oracle_decode(K, V, q, lengths, n_quant, _all_pairs(B, H_kv), H_q, H_kv, Wq, Wk, bits=bits)
     # the tolerance is stated for outputs of order one: compare at the values' own scale
     unit = float(gain) if which == "values" else 1.0
     scaled = {k: v / unit for k, v in want.items()}

@@ -285,10 +285,12 @@ __device__ inline void light_item(const kvlinc_cache& c, int p, const half_t* __
   const half_t* v_src = v_new + (long long)p * T * kHeadDim;
   bool row_bad = false;
   // With the sliding value window the value slots behind the key window are live (the values of the newest group's
-  // last tokens): nothing may be written there before the new rows of ALL kv heads of the sequence have been looked at.
-  if (SLIDING && c.H_kv > 1) {
-    if (T == 1) row_bad = __builtin_amdgcn_ballot_w64(new_rows_of_all_heads_bad(c, b, p % c.H_kv, k_new, v_new, lane, 0, 1)) != 0;
-    else row_bad = scan_flag(c, b);  // raised by the scan launch
+  // last tokens): nothing may be written there before ALL new rows of ALL kv heads of the sequence have been looked at
+  // (several rows: by the scan launch, which precedes every bulk append to such a cache; one row and one kv head: the
+  // row is looked at before it is stored anyway).
+  if (SLIDING) {
+    if (T > 1) row_bad = scan_flag(c, b);
+    else if (c.H_kv > 1) row_bad = __builtin_amdgcn_ballot_w64(new_rows_of_all_heads_bad(c, b, p % c.H_kv, k_new, v_new, lane, 0, 1)) != 0;
   }
   if (have_row) {
     if (s.n > 0 && !row_bad) row_bad = store_window_row(k_win, v_win, s.nr, row_k, row_v, lane);
@@ -318,7 +320,9 @@ __device__ inline bool row_is_bad(const half_t* __restrict__ k_row, const half_t
 // chunks: every new row of every (sequence, kv head) is looked at once, and a fault raises the sequence's flag (bit 30
 // of its first split_done entry) so that ALL the workgroups of that sequence in the append launch that follows refuse
 // the append, whichever head or chunk the fault is in.  (With one kv head and one chunk the two workgroups of the
-// sequence see all its rows themselves; a one-token append looks at the new rows of all heads itself.)
+// sequence see all its rows themselves; a one-token append looks at the new rows of all heads itself.)  It also
+// precedes every bulk append to a cache with the sliding value window, whose value slots behind the key window are live:
+// there not even the rows ahead of a faulty one may be stored.
 // Grid: (B H_kv, chunks of kScanRows rows).
 constexpr int kScanRows = 256;
 __global__ __launch_bounds__(kThreads) void append_scan_kernel(kvlinc_cache c, const half_t* __restrict__ k_new,
@@ -508,7 +512,7 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       // A one-token append that flushes the window changes live state (S, P, the window's first slot) in every kv
       // head: the new row of every kv head of this sequence is looked at first, eight heads per wave and batch.
       refuse = new_rows_of_all_heads_bad(c, b, g, k_new, v_new, lane, wave, kWaves);
-    } else if (c.H_kv > 1 || n_chunks > 1) {
+    } else if (c.H_kv > 1 || n_chunks > 1 || SLIDING) {
       refuse = scan_flag(c, b);  // raised by the scan launch
     } else {
       // bulk append, one kv head: the parts of this (sequence, kv head) are the sequence's only workgroups and see the
@@ -1160,7 +1164,7 @@ int launch_append(const kvlinc_cache& c, const kvlinc_half* k_new, const kvlinc_
     if (want > 64) want = 64;
     if (groups_most >= 64 && want > 1) n_chunks = (int)want;
   }
-  if (T > 1 && (c.H_kv > 1 || n_chunks > 1))
+  if (T > 1 && (c.H_kv > 1 || n_chunks > 1 || (c.flags & KVLINC_FLAG_SLIDING_VALUES) != 0))
     hipLaunchKernelGGL(append_scan_kernel, dim3(c.B * c.H_kv, (T + kScanRows - 1) / kScanRows), dim3(kThreads), 0, stream, c,
                        reinterpret_cast<const half_t*>(k_new), reinterpret_cast<const half_t*>(v_new), n_new, T);
   // one workgroup per compute unit at most (the LDS tiles of a flush fill most of one); items beyond that are taken

@@ -981,3 +981,28 @@ def test_long_prompt_build_in_chunks_variants(kv, bits, sliding, correction):
                 want[(b, h)] = tl.o_attn.decode(q[b, h], ref, None if Wq is None else Wq[h], value_window="sliding" if sliding else "block")
     tl.check_outputs(out, want)
     assert int(cache.split_done.abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("H_kv", [1, 2])
+def test_sliding_value_window_refuses_a_bulk_append_before_any_row_is_stored(kv, H_kv):
+    """Sliding value window, a bulk append that flushes nothing, a non-finite value in its 6th row: not even the five
+    rows ahead of it may be stored, because the value slots behind the key window hold the newest group's fp16 values
+    (with one kv head no other head's workgroup could have warned: every bulk append to such a cache is scanned first)."""
+    import torch
+    B, H_q = 2, 4 * H_kv
+    lengths = [512 + 92, 300]
+    cache, K, V, Wq, Wk = _build(kv, 63, B, H_q, H_kv, lengths, flags=kv.KVLINC_FLAG_SLIDING_VALUES)
+    q = tl.to_dev(tl.gen_q(63, B, H_q))
+    before_out = cache.decode(q).clone()
+    before = {nm: getattr(cache, nm).clone() for nm in ("v_res", "n_quant", "n_res", "S", "P", "S16")}
+    rng = np.random.default_rng(9)
+    kn = rng.standard_normal((B, H_kv, 18, 128)).astype(np.float16)
+    vn = rng.standard_normal((B, H_kv, 18, 128)).astype(np.float16)
+    vn[0, H_kv - 1, 5, 77] = np.float16("nan")
+    cache.append(tl.to_dev(kn), tl.to_dev(vn), n_new=tl.to_dev(np.asarray([18, 0], dtype=np.int32)))
+    torch.cuda.synchronize()
+    assert int(cache.status.item()) == kv.KVLINC_ST_NONFINITE
+    for nm, t in before.items():
+        assert torch.equal(getattr(cache, nm), t), nm  # (all of v_res: live slots and window rows alike)
+    assert torch.equal(cache.decode(q), before_out)
+    assert not cache.split_done.any()

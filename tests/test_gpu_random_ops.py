@@ -21,7 +21,8 @@ def kv():
     return kvmod
 
 
-@pytest.mark.parametrize("seed,bits,sliding", [(0, 2, False), (1, 2, True), (2, 4, False), (3, 2, False), (4, 4, True), (5, 2, False)])
+@pytest.mark.parametrize("seed,bits,sliding", [(0, 2, False), (1, 2, True), (2, 4, False), (3, 2, False), (4, 4, True), (5, 2, False),
+                                                 (35, 2, True), (36, 4, True), (38, 2, True)])
 def test_random_call_sequences(kv, seed, bits, sliding):
     import torch
     rng = np.random.default_rng(7000 + seed)

@@ -33,8 +33,11 @@ def test_random_call_sequences(kv, seed, bits, sliding):
     capacity = int(rng.choice([1024, 1536]))  # tokens the group records hold per sequence (+ the window)
     cfg = 700 + seed
     Wq, Wk = synth.adapters_q(cfg, H_q), synth.adapters_k(cfg, H_kv)
+    literal, state16 = seed % 3 == 1, seed % 4 == 2  # the other variants of the path, by the seed
     cache = kv.KVLincCache(B, H_q, H_kv, capacity, Wq=tl.to_dev(Wq), Wk=tl.to_dev(Wk), bits=bits,
-                           flags=kv.KVLINC_FLAG_SLIDING_VALUES if sliding else 0)
+                           flags=(kv.KVLINC_FLAG_SLIDING_VALUES if sliding else 0) | (kv.KVLINC_FLAG_ALG1_LITERAL if literal else 0),
+                           state_storage="fp16" if state16 else "fp32")
+    rounded_at = [[] for _ in range(B)]  # 16-bit state: the quantized-token counts at which a call ended that had flushed
     hist_k = [np.zeros((H_kv, 0, 128), dtype=np.float16) for _ in range(B)]
     hist_v = [np.zeros((H_kv, 0, 128), dtype=np.float16) for _ in range(B)]
 
@@ -58,10 +61,13 @@ def test_random_call_sequences(kv, seed, bits, sliding):
                 if decode:
                     assert not out[b].any()
                 continue
-            ref = tl.check_pair_against_oracle(cache, b, g, hist_k[b][g], hist_v[b][g], int(n_quant[b]), int(n_res[b]), Wk[g])
+            ref = tl.check_pair_against_oracle(cache, b, g, hist_k[b][g], hist_v[b][g], int(n_quant[b]), int(n_res[b]),
+                                               None if state16 else Wk[g])
+            if state16:  # (no fp32 S to compare; the states enter through the output)
+                ref = tl.o_cache.build_cache(hist_k[b][g], hist_v[b][g], int(n_quant[b]), Wk=Wk[g], bits=bits, state_rounding=rounded_at[b])
             if decode:
                 for h in range(g * gq, (g + 1) * gq):
-                    want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h], value_window="sliding" if sliding else "block")
+                    want[(b, h)] = tl.o_attn.decode(q[b, h], ref, Wq[h], literal_alg1=literal, value_window="sliding" if sliding else "block")
         if want:
             tl.check_outputs(out, want)
         assert int(cache.split_done.abs().sum().item()) == 0
@@ -113,8 +119,12 @@ def test_random_call_sequences(kv, seed, bits, sliding):
                 assert got == expect, (kind, got, expect)
             for b in taken:
                 n = int(n_new[b])
+                nq_before = tl.o_cache.window_split(hist_k[b].shape[1])[0]
                 hist_k[b] = np.concatenate([hist_k[b], k[b, :, :n]], axis=1)
                 hist_v[b] = np.concatenate([hist_v[b], v[b, :, :n]], axis=1)
+                nq_after = tl.o_cache.window_split(hist_k[b].shape[1])[0]
+                if nq_after != nq_before:
+                    rounded_at[b].append(nq_after)
         if rng.random() < 0.35 or kind == "poison":
             pairs = [(int(rng.integers(0, B)), int(rng.integers(0, H_kv))) for _ in range(2)]
             if bad_b >= 0:

@@ -54,7 +54,16 @@ def test_random_call_sequences(kv, seed, bits, sliding):
         lengths = [h.shape[1] for h in hist_k]
         n_quant, n_res = tl.check_counters(cache, lengths)
         q = tl.gen_q(cfg, B, H_q, step=int(rng.integers(0, 1000)))
-        out = cache.decode(tl.to_dev(q)).cpu().numpy() if decode else None
+        out = None
+        if decode:  # through one of the entry points, with one of the kinds of launch bound
+            qd = tl.to_dev(q)
+            bound = [0, max(lengths), max(lengths) + 700][int(rng.integers(0, 3))]
+            if rng.random() < 0.3:
+                od = torch.empty_like(qd)
+                assert kv.kvlinc_decode_attention_noalloc(cache, qd, od, max_context=bound) == kv.KVLINC_OK
+            else:
+                od = cache.decode(qd, max_context=bound)
+            out = od.cpu().numpy()
         want = {}
         for (b, g) in pairs:
             if lengths[b] == 0:

@@ -837,9 +837,11 @@ __device__ void flush_item(const kvlinc_cache& c, Lds& L, int item, const half_t
       __syncthreads();  // every wave has read its rows of the key error: their place now takes phi s
       half_t(*phH)[kRowH] = L.bK;
       half_t(*phL)[kRowH] = L.bV;
-      if (16 * wave < valid) {
+      if (16 * wave < ((valid + 31) & ~31)) {
         // b. softmax over the half: register r of the lane belongs to token 16 wave + 4 kq + r, whose 128 features
         // are the 8 tiles times the 16 lanes of the row.  phi goes on as phi s_t in two binary16 terms, feature-major.
+        // (Step c reads tokens in blocks of 32: a wave whose 16 tokens all lie beyond `valid` inside the last such
+        // block writes its zeros -- inv = 0 -- over what the key error left there.)
         const int tb = 16 * wave + 4 * kq;
         const float4 sc4 = *reinterpret_cast<const float4*>(&L.vScale[tb]);
         const float4 ce4 = *reinterpret_cast<const float4*>(&L.vCentre[tb]);

@@ -181,9 +181,9 @@ int kvlinc_cache_validate(const kvlinc_cache* cache);
  * Per flushed group: key scale / zero-point / codes per channel, value scale / zero-point / codes per token
  * of the rotated value, S += phi_k(K - K_q)^T V_q and P += sum phi_k(K - K_q) when the adapters are given.
  * New tokens that stay in the window are stored as raw key and rotated fp16 value.  One kernel launch (a bulk
- * append, T > 1, to a cache with more than one KV head or with KVLINC_FLAG_SLIDING_VALUES, or of a long prompt as below, is preceded by a short launch
- * that looks for non-finite input): the workgroup of a sequence that finishes last updates n_quant / n_res, after all
- * of them have read the old values, and only if none of them found a fault.
+ * append, T > 1, to a cache with more than one KV head or with KVLINC_FLAG_SLIDING_VALUES, or of a long prompt as
+ * below, is preceded by a short launch that looks for non-finite input): the workgroup of a sequence that finishes
+ * last updates n_quant / n_res, after all of them have read the old values, and only if none of them found a fault.
  *
  * Reproducibility: records, window rows and counters are the same bits in every run.  So are S, P and S16, except
  * after a bulk append of a long prompt to few sequences (T + R >= 64 groups, B * H_kv < 64, and a cache that keeps the

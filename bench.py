@@ -239,15 +239,6 @@ def main():
                  max_ctx, s_ptr) for i in range(total_steps)]
     f_app, f_dec = kb.lib.kvlinc_append_quantize, kb.lib.kvlinc_decode_attention
 
-    for i in range(W):
-        assert f_app(*app_args[i]) == 0 and f_dec(*dec_args[i]) == 0
-    torch.cuda.synchronize()
-    lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]  # per layer: [B] lengths
-
-    # ---- timed region: exactly K steps.  A few evenly spaced decode launches (timed_steps) carry a start and a stop event
-    # attached to its own dispatch on the launch stream (kvlinc_decode_attention_timed), so the kernel's duration is
-    # measured inside the timed region without extra packets between the kernels (such a launch costs the host
-    # about 25 us, so timing every launch would make the loop host-bound).
     hip = ctypes.CDLL("libamdhip64.so")  # the copy torch has already loaded
     hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
@@ -259,10 +250,30 @@ def main():
         return e
 
     use_events = not args.no_events
+    f_dec_t = kb.lib.kvlinc_decode_attention_timed
+
+    for i in range(W):
+        assert f_app(*app_args[i]) == 0
+        if i == 0 and use_events:  # the single cold call: the first decode launch of the process
+            cold_b, cold_c = new_event(), new_event()
+            assert f_dec_t(*dec_args[i], cold_b, cold_c) == 0
+        else:
+            assert f_dec(*dec_args[i]) == 0
+    torch.cuda.synchronize()
+    first_call_ms = None
+    if W > 0 and use_events:
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), cold_b, cold_c) == 0
+        first_call_ms = ms.value
+    lens = [start_len[j] + sum(1 for i in range(W) if i % L == j) for j in range(L)]  # per layer: [B] lengths
+
+    # ---- timed region: exactly K steps.  A few evenly spaced decode launches (timed_steps) carry a start and a stop event
+    # attached to its own dispatch on the launch stream (kvlinc_decode_attention_timed), so the kernel's duration is
+    # measured inside the timed region without extra packets between the kernels (such a launch costs the host
+    # about 25 us, so timing every launch would make the loop host-bound).
     timed = timed_steps(K_steps) if use_events else []
     ev_b = {s: new_event() for s in timed}
     ev_c = {s: new_event() for s in timed}
-    f_dec_t = kb.lib.kvlinc_decode_attention_timed
     rc = 0
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -329,6 +340,7 @@ def main():
                    "layer_caches_cycled": L, "step": "append 1 token/sequence + decode attention",
                    "steps_with_a_window_flush": flush_steps,
                    "decode_ms_median": float(np.median(decode_ms)), "decode_ms_mean": float(decode_ms.mean()),
+                   "decode_ms_first_call": first_call_ms,
                    "launch_loop_cpu_ms_per_step": (t_cpu_done - t_start) / K_steps * 1e3, "setup_s": setup_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,

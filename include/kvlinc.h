@@ -170,6 +170,7 @@ int kvlinc_cache_validate(const kvlinc_cache* cache);
  *
  *   k_new, v_new   [B, H_kv, T, 128] fp16, raw keys and raw (unrotated) values of the new tokens.
  *   n_new          [B] int32 on the device: sequence b appends its first n_new[b] (0..T) rows; NULL = T for all.
+ *                  (A value below 0 is read as 0, one above T as T: the kernels never read beyond the T rows.)
  *   T              rows per (sequence, head) in k_new / v_new, >= 1.
  *   keep_residual  0: lazy block flush -- the window is quantized as whole groups of 128 tokens only when a
  *                     token arrives and the window is already full (needs R == 128); after the call

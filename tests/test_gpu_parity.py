@@ -244,6 +244,22 @@ def test_status_bits_and_rejections(kv):
     assert kv.kvlinc_append_quantize(cache, k, k, None, 600, 200) == kv.KVLINC_EINVAL
 
 
+def test_row_limits_outside_0_T_are_clamped(kv):
+    """n_new below 0 reads as 0, above T as T (the kernels never read beyond the T rows that were passed), in a
+    one-token append, a bulk append that stays in the window and one that flushes."""
+    import torch
+    B, H_q, H_kv = 3, 4, 2
+    for T in (1, 40, 300):
+        lengths = [0, T, T]
+        K, V = tl.gen_kv(21, B, H_kv, [T, T, T])
+        cache = kv.KVLincCache(B, H_q, H_kv, 1024)
+        cache.append(tl.to_dev(K), tl.to_dev(V), n_new=tl.to_dev(np.asarray([-7, T + 1000, T], dtype=np.int32)))
+        torch.cuda.synchronize()
+        assert int(cache.status.item()) == 0
+        tl.check_cache_against_oracle(cache, K, V, lengths, [(1, 0), (1, 1), (2, 0)], check_states=False)
+        assert cache.n_quant.cpu().tolist()[0] == 0 and cache.n_res.cpu().tolist()[0] == 0
+
+
 def _live_state(cache):
     """Everything a sequence's state consists of, as host arrays: counters, live group records and window rows, states."""
     nq, nr = cache.n_quant.cpu().numpy().copy(), cache.n_res.cpu().numpy().copy()

@@ -26,8 +26,13 @@
  *     KVLINC_FLAG_SLIDING_VALUES is set, see flags) is dead and may have been overwritten; a non-finite value is never
  *     stored into the window.
  *   - Magnitudes: the operands of the matrix products carry a block exponent per group and query head, so keys,
- *     queries and values of any finite binary16 magnitude keep the tolerance.  What can leave its range is the
- *     16-bit copy of the state: an entry of S beyond +-65504 is stored saturated and reported as
+ *     queries and values of any finite binary16 magnitude neither overflow nor flush; each operand keeps 2^-12 of
+ *     the group's largest one.  A logit is therefore off by up to about 1e-3 of the group's largest |logit|: the
+ *     output tolerance holds for logits of a few tens (the paper's workloads) whatever the scale of K, V and q
+ *     taken alone, and for any scale of the values; when keys and queries are scaled up together so that logits
+ *     reach the hundreds while several tokens stay nearly tied for the maximum, the softmax itself is
+ *     ill-conditioned and single rows have come out at 3e-3 relative (tolerance 2e-3).  What can leave its range is
+ *     the 16-bit copy of the state: an entry of S beyond +-65504 is stored saturated and reported as
  *     KVLINC_ST_STATE_RANGE (S grows with the context when the rotated values have a common sign).
  *   - Query head h reads KV head h / (H_q / H_kv).  The softmax scale is 1/sqrt(d) (Eq. 3).
  *

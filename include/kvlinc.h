@@ -96,7 +96,7 @@
  *                     in kvlinc_decode_attention, where the last one merges; of the workgroups of a sequence in
  *                     kvlinc_append_quantize, where the last one updates n_quant / n_res).  Zero them once after
  *                     allocation; every call leaves them at zero.  Two calls on the same cache must not overlap in
- *                     time.
+ *                     time; calls on different caches (each with a workspace of its own) may, on different streams.
  *   All cache buffers must be zero-initialised before their first use.
  *
  * Quantizer contract (bit exact; Eq. 1 taken against the stored fp16 scale and zero-point):

@@ -260,6 +260,46 @@ def test_row_limits_outside_0_T_are_clamped(kv):
         assert cache.n_quant.cpu().tolist()[0] == 0 and cache.n_res.cpu().tolist()[0] == 0
 
 
+def test_two_caches_stepped_on_two_streams_give_the_same_bits(kv):
+    """Calls on different caches may overlap in time: two caches (2-bit and 4-bit codes) stepped through appends, a
+    window flush and decodes on two streams at once end with the bits of the same steps taken one after the other."""
+    import torch
+    dev = torch.device("cuda:0")
+
+    def run(concurrent):
+        g = torch.Generator(device=dev)
+        g.manual_seed(77)
+        B, H_q, H_kv, n0, steps = 3, 8, 2, 600, 150
+        Wq = (torch.randn(H_q, 2, 128, 128, device=dev, generator=g) / 128 ** 0.5).half()
+        Wk = (torch.randn(H_kv, 2, 128, 128, device=dev, generator=g) / 128 ** 0.5).half()
+        caches, data, outs = [], [], []
+        for j in range(2):
+            c = kv.KVLincCache(B, H_q, H_kv, n0 + steps + 200, Wq=Wq, Wk=Wk, bits=2 + 2 * j)
+            K = torch.randn(B, H_kv, n0, 128, device=dev, generator=g).half()
+            V = torch.randn(B, H_kv, n0, 128, device=dev, generator=g).half()
+            c.append(K, V)
+            data.append(tuple(torch.randn(steps, B, h, n, 128, device=dev, generator=g).half().squeeze(3)
+                              for h, n in ((H_kv, 1), (H_kv, 1), (H_q, 1))))
+            caches.append(c)
+            outs.append(torch.empty(steps, B, H_q, 128, dtype=torch.float16, device=dev))
+            c.workspace(n0 + steps + 1)
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()] if concurrent else [torch.cuda.current_stream()] * 2
+        for s in range(steps):
+            for j in range(2):
+                kn, vn, qq = data[j]
+                caches[j].append(kn[s].unsqueeze(2), vn[s].unsqueeze(2), stream=streams[j])
+                caches[j].decode(qq[s], out=outs[j][s], max_context=n0 + steps + 1, stream=streams[j])
+        torch.cuda.synchronize()
+        for c in caches:
+            assert int(c.status.item()) == 0 and not c.split_done.any()
+        return ([o.cpu().numpy().view(np.uint16) for o in outs] + [c.groups.cpu().numpy() for c in caches]
+                + [c.S16.cpu().numpy().view(np.uint16) for c in caches] + [c.n_quant.cpu().numpy() for c in caches])
+
+    for x, y in zip(run(False), run(True)):
+        assert np.array_equal(x, y)
+
+
 def _live_state(cache):
     """Everything a sequence's state consists of, as host arrays: counters, live group records and window rows, states."""
     nq, nr = cache.n_quant.cpu().numpy().copy(), cache.n_res.cpu().numpy().copy()

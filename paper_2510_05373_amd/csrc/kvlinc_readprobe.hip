@@ -11,6 +11,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSegments = 8;
 constexpr int kUnroll = 4;  // 16-byte loads in flight per thread
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 struct Segments {
   const uint4* ptr[kSegments];   // 16-byte aligned device pointers
@@ -40,7 +41,10 @@ __global__ __launch_bounds__(kThreads) void read_only_kernel(Segments s, uint32_
         for (int u = 0; u < kUnroll; ++u) {
           const int i = (it * kUnroll + u) * kThreads + threadIdx.x;
           v[u] = make_uint4(0, 0, 0, 0);
-          if (i < left) v[u] = base[i];
+          if (i < left) {  // read once: non-temporal, as the decode kernel reads its records
+            const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + i));
+            v[u] = make_uint4(t[0], t[1], t[2], t[3]);
+          }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;

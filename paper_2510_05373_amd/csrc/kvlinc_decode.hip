@@ -305,15 +305,24 @@ __device__ __forceinline__ void qk_phase(const KeyRegs<BITS>& g, int valid, cons
     bz = xrow_allsum(quad_allsum(bz));
     uint32_t t[3][2];
     split_fp8x3(x, block_scale_bits(eb), t);
-    put_terms(lr.ex_qk, lr.wq, t);
-    lds_order();
-    A[nb] = get_operand(lr.ex_qk, lr.rd);
-    lds_order();
+    // (two head blocks: the second one goes through the other exchange region, so that one hand-over serves both)
+    put_terms(nb == 0 ? lr.ex_qk : lr.ex_pv, lr.wq, t);
+    if (NB == 1) {
+      lds_order();
+      A[nb] = get_operand(lr.ex_qk, lr.rd);
+      lds_order();
+    }
     scale_a[nb] = (int)eb - 7 - 4 * lr.ua;
     // the head's zero-point term enters as the C operand of its first term row: fetch it from a lane that holds head hd
     // in the operand role (lane 4 hd)
     c0[nb] = float4_t{__builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(16 * lr.hd, __builtin_bit_cast(int, bz))), 0.f,
                       0.f, 0.f};
+  }
+  if (NB == 2) {
+    lds_order();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) A[nb] = get_operand(nb == 0 ? lr.ex_qk : lr.ex_pv, lr.rd);
+    lds_order();
   }
   if constexpr (BITS == 2 && NB == 1) {
     // All eight matrix instructions first, each into registers of its own, then the sums of the term rows: written
@@ -416,11 +425,24 @@ __device__ __forceinline__ void pv_phase(const ValueRegs<BITS>& g, const float (
     const uint32_t eb = block_exponent(row_umax(as_bits(mx)));  // over the 128 tokens of the head
     uint32_t t[3][2];
     split_fp8x3(y, block_scale_bits(eb), t);
-    put_terms(lr.ex_pv, lr.wp, t);
-    lr.ex_pv[kExHead * lr.hd + kExExp] = eb;  // the same value from the 16 lanes of the row
+    uint32_t* region = nb == 0 ? lr.ex_pv : lr.ex_qk;
+    put_terms(region, lr.wp, t);
+    region[kExHead * lr.hd + kExExp] = eb;  // the same value from the 16 lanes of the row
+    if (NB == 1) {
+      lds_order();
+      A[nb] = get_operand(lr.ex_pv, lr.rd);
+      scale_a[nb] = (int)lr.ex_pv[kExHead * lr.ha + kExExp] - 7 - 4 * lr.ua;
+      lds_order();
+    }
+  }
+  if (NB == 2) {
     lds_order();
-    A[nb] = get_operand(lr.ex_pv, lr.rd);
-    scale_a[nb] = (int)lr.ex_pv[kExHead * lr.ha + kExExp] - 7 - 4 * lr.ua;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const uint32_t* region = nb == 0 ? lr.ex_pv : lr.ex_qk;
+      A[nb] = get_operand(region, lr.rd);
+      scale_a[nb] = (int)region[kExHead * lr.ha + kExExp] - 7 - 4 * lr.ua;
+    }
     lds_order();
   }
 #pragma unroll
